@@ -1,0 +1,50 @@
+"""Shared test helpers: seeded parameter sets (numbers only, no layer arithmetic)."""
+import numpy as np
+
+from paper_2605_18710_amd import synth
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    nb = np.sqrt((b * b).sum())
+    if nb == 0.0:
+        return float(np.sqrt(((a - b) ** 2).sum()))
+    return float(np.sqrt(((a - b) ** 2).sum()) / nb)
+
+
+def layer_params(cfg, seed, perturb=True):
+    """N(0,0.02) matrices; norm gains 1 and biases 0, perturbed by N(0,0.02) when asked
+    so that their gradients are exercised."""
+    h, f = cfg["hidden"], cfg["mlp"]
+    s = iter(range(seed, seed + 64))
+    n = lambda shape: synth.normal(next(s), shape, 0.0, 0.02)
+    one = lambda k: 1.0 + (n((k,)) if perturb else 0.0)
+    zero = lambda k: (n((k,)) if perturb else np.zeros(k))
+    if cfg["kind"] == "encoder":
+        return dict(ln1_g=one(h), ln1_b=zero(h), w_qkv=n((h, 3 * h)), b_qkv=zero(3 * h),
+                    w_o=n((h, h)), b_o=zero(h), ln2_g=one(h), ln2_b=zero(h),
+                    w_1=n((h, f)), b_1=zero(f), w_2=n((f, h)), b_2=zero(h))
+    return dict(rms1_g=one(h), w_qkv=n((h, 3 * h)), w_o=n((h, h)), rms2_g=one(h),
+                w_gate=n((h, f)), w_up=n((h, f)), w_down=n((f, h)))
+
+
+def projector_params(din, dout, seed, perturb=True):
+    s = iter(range(seed, seed + 8))
+    n = lambda shape: synth.normal(next(s), shape, 0.0, 0.02)
+    zero = lambda k: (n((k,)) if perturb else np.zeros(k))
+    return dict(w_1=n((din, dout)), b_1=zero(dout), w_2=n((dout, dout)), b_2=zero(dout))
+
+
+def stem_params(din, h, N, seed, perturb=True):
+    s = iter(range(seed, seed + 8))
+    n = lambda shape: synth.normal(next(s), shape, 0.0, 0.02)
+    return dict(w_stem=n((din, h)), b_stem=(n((h,)) if perturb else np.zeros(h)), pos=n((N, h)))
+
+
+def small_cfg(kind, B=2, N=8, h=16, H=2, f=24):
+    if kind == "encoder":
+        return dict(kind="encoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=1,
+                    norm="layernorm", act="gelu", causal=0, bias=1, eps=1e-5)
+    return dict(kind="decoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=1,
+                norm="rmsnorm", act="swiglu", causal=1, bias=0, eps=1e-5)
