@@ -1,0 +1,142 @@
+// C-ABI wrappers of the single operations, and the dispatch between the MFMA attention
+// kernels and the plain FMA ones.
+#include "kernels.h"
+
+mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+                                          int causal, const void* qkv, void* O, float* lse);
+mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+                                          int causal, const void* qkv, const void* O, const float* lse,
+                                          const void* dO, void* dqkv, float* delta);
+
+static mosaic_status check_attn(int B, int N, int H, int d) {
+  if (B <= 0 || N <= 0 || H <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "attention sizes must be positive");
+  if (d > 128) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "head size %d > 128", d);
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int causal,
+                                   const void* qkv, void* O, float* lse) {
+  MOSAIC_TRY(check_attn(B, N, H, d));
+  return launch_attention_fwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse);
+}
+
+mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int causal,
+                                   const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+                                   float* delta) {
+  MOSAIC_TRY(check_attn(B, N, H, d));
+  return launch_attention_bwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta);
+}
+
+static mosaic_status check_common(int32_t quota, int32_t dtype) {
+  if (dtype != MOSAIC_F32 && dtype != MOSAIC_BF16) MOSAIC_FAIL(MOSAIC_EINVAL, "bad dtype %d", dtype);
+  DeviceInfo di;
+  MOSAIC_TRY(mosaic_device_info(&di));
+  if (quota <= 0 || quota > di.cu_count) MOSAIC_FAIL(MOSAIC_EQUOTA, "quota %d outside [1, %d]", quota, di.cu_count);
+  return MOSAIC_OK;
+}
+
+#define NONNULL(p) if (!(p)) MOSAIC_FAIL(MOSAIC_EINVAL, "null pointer: " #p)
+
+extern "C" {
+
+mosaic_status mosaic_op_linear_fwd(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t k, int64_t n,
+                                   const void* X, const void* W, const void* bias, const void* R, void* Y) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(X); NONNULL(W); NONNULL(Y);
+  if (T < 0 || k <= 0 || n <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad linear sizes");
+  return launch_gemm((hipStream_t)stream, quota, dtype, true, false, T, n, k, X, k, W, n, Y, n, bias, R);
+}
+
+mosaic_status mosaic_op_linear_dgrad(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t k, int64_t n,
+                                     const void* dY, const void* W, const void* R, void* dX) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(dY); NONNULL(W); NONNULL(dX);
+  if (T < 0 || k <= 0 || n <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad linear sizes");
+  return launch_gemm((hipStream_t)stream, quota, dtype, true, true, T, k, n, dY, n, W, n, dX, k, nullptr, R);
+}
+
+size_t mosaic_op_colsum_scratch_bytes(int64_t n) { return colsum_scratch_bytes(n); }
+
+mosaic_status mosaic_op_linear_wgrad(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t k, int64_t n,
+                                     const void* X, const void* dY, void* dW, void* db, void* scratch) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(X); NONNULL(dY); NONNULL(dW);
+  if (T < 0 || k <= 0 || n <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad linear sizes");
+  if (db && !scratch) MOSAIC_FAIL(MOSAIC_EINVAL, "bias gradient needs scratch");
+  if (T == 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "weight gradient over zero tokens");
+  MOSAIC_TRY(launch_gemm((hipStream_t)stream, quota, dtype, false, false, k, n, T, X, k, dY, n, dW, n, nullptr, nullptr));
+  if (db) MOSAIC_TRY(launch_colsum((hipStream_t)stream, quota, dtype, T, n, dY, db, scratch));
+  return MOSAIC_OK;
+}
+
+mosaic_status mosaic_op_attention_fwd(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H,
+                                      int32_t d, int32_t causal, const void* qkv, void* O, float* lse) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(qkv); NONNULL(O); NONNULL(lse);
+  return launch_attention_fwd((hipStream_t)stream, quota, dtype, B, N, H, d, causal, qkv, O, lse);
+}
+
+mosaic_status mosaic_op_attention_bwd(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H,
+                                      int32_t d, int32_t causal, const void* qkv, const void* O, const float* lse,
+                                      const void* dO, void* dqkv, float* delta) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(qkv); NONNULL(O); NONNULL(lse); NONNULL(dO); NONNULL(dqkv); NONNULL(delta);
+  return launch_attention_bwd((hipStream_t)stream, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta);
+}
+
+mosaic_status mosaic_op_norm_fwd(void* stream, int32_t quota, int32_t dtype, int32_t norm, int64_t T, int64_t h,
+                                 float eps, const void* x, const void* gamma, const void* beta, void* y, float* stats) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(x); NONNULL(gamma); NONNULL(y); NONNULL(stats);
+  if (norm == MOSAIC_LAYERNORM) NONNULL(beta);
+  if (T < 0 || h <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm sizes");
+  return launch_norm_fwd((hipStream_t)stream, quota, dtype, norm, T, h, eps, x, gamma, beta, y, stats);
+}
+
+size_t mosaic_op_norm_bwd_scratch_bytes(int64_t h) { return norm_bwd_scratch_bytes(h); }
+
+mosaic_status mosaic_op_norm_bwd(void* stream, int32_t quota, int32_t dtype, int32_t norm, int64_t T, int64_t h,
+                                 const void* x, const void* gamma, const float* stats, const void* dy, const void* R,
+                                 void* dx, void* dgamma, void* dbeta, void* scratch) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(x); NONNULL(gamma); NONNULL(stats); NONNULL(dy); NONNULL(dx); NONNULL(dgamma); NONNULL(scratch);
+  if (norm == MOSAIC_LAYERNORM) NONNULL(dbeta);
+  if (T < 0 || h <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm sizes");
+  return launch_norm_bwd((hipStream_t)stream, quota, dtype, norm, T, h, x, gamma, stats, dy, R, dx, dgamma, dbeta, scratch);
+}
+
+mosaic_status mosaic_op_gelu_fwd(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* z, void* a) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(z); NONNULL(a);
+  return launch_gelu_fwd((hipStream_t)stream, quota, dtype, n, z, a);
+}
+
+mosaic_status mosaic_op_gelu_bwd(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* z, const void* da, void* dz) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(z); NONNULL(da); NONNULL(dz);
+  return launch_gelu_bwd((hipStream_t)stream, quota, dtype, n, z, da, dz);
+}
+
+mosaic_status mosaic_op_swiglu_fwd(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t f, const void* gu, void* a) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(gu); NONNULL(a);
+  return launch_swiglu_fwd((hipStream_t)stream, quota, dtype, T, f, gu, a);
+}
+
+mosaic_status mosaic_op_swiglu_bwd(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t f, const void* gu,
+                                   const void* da, void* dgu) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(gu); NONNULL(da); NONNULL(dgu);
+  return launch_swiglu_bwd((hipStream_t)stream, quota, dtype, T, f, gu, da, dgu);
+}
+
+size_t mosaic_op_mse_scratch_bytes(void) { return mse_scratch_bytes(); }
+
+mosaic_status mosaic_op_mse(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* y, const void* target,
+                            void* dy, float* loss, void* scratch) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(y); NONNULL(target); NONNULL(dy); NONNULL(loss); NONNULL(scratch);
+  return launch_mse((hipStream_t)stream, quota, dtype, n, y, target, dy, loss, scratch);
+}
+
+}  // extern "C"

@@ -1,0 +1,677 @@
+// Bandwidth-bound kernels of the module step: LayerNorm / RMSNorm forward and backward
+// (with fused residual add and fixed-order column reductions), GELU / SwiGLU forward and
+// backward, MSE loss and gradient, column sums for bias gradients, and the stem kernels
+// (patch unfold, position table, embedding gather / owner-computes scatter).
+//
+// All reductions run in an order fixed by the problem shape alone: persistent grids only
+// decide which workgroup handles a work item, so results are bit-identical for any quota.
+#include "kernels.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+// ------------------------------------------------------------------------ norm forward
+// One wave per row; the row lives in registers (NV 16-byte vectors per lane), so x is
+// read from HBM once.  LayerNorm: biased variance around the mean; RMSNorm: mean square.
+template <typename T, int NORM, int NV>
+__global__ __launch_bounds__(kThreads) void norm_fwd_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+    T* __restrict__ y, float* __restrict__ stats, int64_t rows, int h, float eps) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_h = 1.0f / (float)h;
+  for (int64_t row = (int64_t)blockIdx.x * kWaves + wave; row < rows;
+       row += (int64_t)gridDim.x * kWaves) {
+    Vec16<T> v[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * VN;
+      if (c < h) {
+        v[j].load(x + row * h + c);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) s += (NORM == MOSAIC_LAYERNORM) ? v[j].get(i) : v[j].get(i) * v[j].get(i);
+      }
+    }
+    s = wave_sum(s);
+    float mean = 0.f, rstd;
+    if (NORM == MOSAIC_LAYERNORM) {
+      mean = s * inv_h;
+      float q = 0.f;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) { const float dlt = v[j].get(i) - mean; q += dlt * dlt; }
+        }
+      }
+      q = wave_sum(q);
+      rstd = 1.0f / sqrtf(q * inv_h + eps);
+    } else {
+      rstd = 1.0f / sqrtf(s * inv_h + eps);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * VN;
+      if (c < h) {
+        Vec16<T> g, b, o;
+        g.load(gamma + c);
+        if (NORM == MOSAIC_LAYERNORM) b.load(beta + c);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          float r = (v[j].get(i) - mean) * rstd * g.get(i);
+          if (NORM == MOSAIC_LAYERNORM) r += b.get(i);
+          o.set(i, r);
+        }
+        o.store(y + row * h + c);
+      }
+    }
+    if (lane == 0) { stats[row * 2] = mean; stats[row * 2 + 1] = rstd; }
+  }
+}
+
+// ----------------------------------------------------------------------- norm backward
+// Work item = a contiguous partition of `rp` rows handled by one wave, rows in ascending
+// order; partial column sums for dgamma / dbeta stay in registers and are written once
+// per partition to scratch[p][2][h]; a second kernel adds the partitions in ascending p.
+template <typename T, int NORM, int NV>
+__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
+    const T* __restrict__ dy, const T* __restrict__ R, T* __restrict__ dx,
+    float* __restrict__ scratch, int64_t rows, int h, int rp, int np) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_h = 1.0f / (float)h;
+  for (int p = blockIdx.x * kWaves + wave; p < np; p += gridDim.x * kWaves) {
+    float pg[NV][VN], pb[NV][VN];
+    Vec16<T> g[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * VN;
+      if (c < h) g[j].load(gamma + c);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) { pg[j][i] = 0.f; pb[j][i] = 0.f; }
+    }
+    const int64_t r0 = (int64_t)p * rp;
+    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
+    for (int64_t row = r0; row < r1; ++row) {
+      const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+      Vec16<T> xv[NV], dv[NV];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+          xv[j].load(x + row * h + c);
+          dv[j].load(dy + row * h + c);
+#pragma unroll
+          for (int i = 0; i < VN; ++i) {
+            const float t = dv[j].get(i) * g[j].get(i);
+            if (NORM == MOSAIC_LAYERNORM) {
+              const float xh = (xv[j].get(i) - mean) * rstd;
+              s1 += t; s2 += t * xh;
+            } else {
+              s2 += t * xv[j].get(i);
+            }
+          }
+        }
+      }
+      if (NORM == MOSAIC_LAYERNORM) s1 = wave_sum(s1) * inv_h;
+      s2 = wave_sum(s2) * inv_h;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+          Vec16<T> o, rv;
+          if (R) rv.load(R + row * h + c);
+#pragma unroll
+          for (int i = 0; i < VN; ++i) {
+            const float d = dv[j].get(i), xr = xv[j].get(i);
+            const float t = d * g[j].get(i);
+            float r;
+            if (NORM == MOSAIC_LAYERNORM) {
+              const float xh = (xr - mean) * rstd;
+              r = (t - s1 - xh * s2) * rstd;
+              pg[j][i] += d * xh;
+              pb[j][i] += d;
+            } else {
+              r = rstd * t - rstd * rstd * rstd * xr * s2;
+              pg[j][i] += d * xr * rstd;
+            }
+            if (R) r += rv.get(i);
+            o.set(i, r);
+          }
+          o.store(dx + row * h + c);
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * VN;
+      if (c < h) {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          scratch[((int64_t)p * 2 + 0) * h + c + i] = pg[j][i];
+          if (NORM == MOSAIC_LAYERNORM) scratch[((int64_t)p * 2 + 1) * h + c + i] = pb[j][i];
+        }
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void norm_bwd_reduce_kernel(
+    const float* __restrict__ scratch, T* __restrict__ dgamma, T* __restrict__ dbeta, int h, int np) {
+  for (int c = blockIdx.x * kThreads + threadIdx.x; c < 2 * h; c += gridDim.x * kThreads) {
+    const int which = c / h, col = c - which * h;
+    if (which == 1 && dbeta == nullptr) continue;
+    float acc = 0.f;
+    for (int p = 0; p < np; ++p) acc += scratch[((int64_t)p * 2 + which) * h + col];
+    if (which == 0) dgamma[col] = from_f32<T>(acc); else dbeta[col] = from_f32<T>(acc);
+  }
+}
+
+// -------------------------------------------------------------------------- activations
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * expf(-0.5f * z * z) * 0.39894228040143268f;
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const T* __restrict__ z, T* __restrict__ a, int64_t nvec) {
+  constexpr int VN = Vec16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+    Vec16<T> v, o;
+    v.load(z + i * VN);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) o.set(k, gelu_f(v.get(k)));
+    o.store(a + i * VN);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const T* __restrict__ z, const T* __restrict__ da,
+                                                            T* __restrict__ dz, int64_t nvec) {
+  constexpr int VN = Vec16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+    Vec16<T> v, d, o;
+    v.load(z + i * VN);
+    d.load(da + i * VN);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) o.set(k, d.get(k) * gelu_grad_f(v.get(k)));
+    o.store(dz + i * VN);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ a,
+                                                              int64_t rows, int fv) {
+  constexpr int VN = Vec16<T>::N;
+  const int64_t nvec = rows * fv;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+    const int64_t r = i / fv;
+    const int64_t c = (i - r * fv) * VN;
+    const int64_t f = (int64_t)fv * VN;
+    Vec16<T> g, u, o;
+    g.load(gu + r * 2 * f + c);
+    u.load(gu + r * 2 * f + f + c);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) { const float z = g.get(k); o.set(k, z * sigmoid_f(z) * u.get(k)); }
+    o.store(a + r * f + c);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void swiglu_bwd_kernel(const T* __restrict__ gu, const T* __restrict__ da,
+                                                              T* __restrict__ dgu, int64_t rows, int fv) {
+  constexpr int VN = Vec16<T>::N;
+  const int64_t nvec = rows * fv;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+    const int64_t r = i / fv;
+    const int64_t c = (i - r * fv) * VN;
+    const int64_t f = (int64_t)fv * VN;
+    Vec16<T> g, u, d, og, ou;
+    g.load(gu + r * 2 * f + c);
+    u.load(gu + r * 2 * f + f + c);
+    d.load(da + r * f + c);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) {
+      const float z = g.get(k), s = sigmoid_f(z);
+      og.set(k, d.get(k) * u.get(k) * (s * (1.0f + z * (1.0f - s))));
+      ou.set(k, d.get(k) * (z * s));
+    }
+    og.store(dgu + r * 2 * f + c);
+    ou.store(dgu + r * 2 * f + f + c);
+  }
+}
+
+// ---------------------------------------------------------------------------------- MSE
+constexpr int kMsePartials = 1024;
+
+__device__ __forceinline__ float block_sum_fixed(float v, float* red) {
+  // fixed-shape reduction: butterfly inside each wave, then waves added in index order
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int w = 0; w < kWaves; ++w) t += red[w];
+  __syncthreads();
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void mse_kernel(const T* __restrict__ y, const T* __restrict__ tg,
+                                                       T* __restrict__ dy, float* __restrict__ partial,
+                                                       int64_t nvec, int64_t chunk, float scale) {
+  constexpr int VN = Vec16<T>::N;
+  __shared__ float red[kWaves];
+  for (int p = blockIdx.x; p < kMsePartials; p += gridDim.x) {
+    const int64_t v0 = (int64_t)p * chunk;
+    const int64_t v1 = (v0 + chunk < nvec) ? v0 + chunk : nvec;
+    float acc = 0.f;
+    for (int64_t i = v0 + threadIdx.x; i < v1; i += kThreads) {
+      Vec16<T> a, b, o;
+      a.load(y + i * VN);
+      b.load(tg + i * VN);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) {
+        const float dlt = a.get(k) - b.get(k);
+        acc += dlt * dlt;
+        o.set(k, dlt * scale);
+      }
+      o.store(dy + i * VN);
+    }
+    const float t = block_sum_fixed(acc, red);
+    if (threadIdx.x == 0) partial[p] = t;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void mse_final_kernel(const float* __restrict__ partial,
+                                                             float* __restrict__ loss, float inv_n) {
+  __shared__ float red[kWaves];
+  float acc = 0.f;
+  for (int p = threadIdx.x; p < kMsePartials; p += kThreads) acc += partial[p];
+  const float t = block_sum_fixed(acc, red);
+  if (threadIdx.x == 0) *loss = t * inv_n;
+}
+
+// ------------------------------------------------------------------------------ colsum
+constexpr int kColsumMaxParts = 256;
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __restrict__ X, float* __restrict__ partial,
+                                                                  int64_t rows, int64_t n, int rp, int np, int ctiles) {
+  constexpr int VN = Vec16<T>::N;
+  const int64_t items = (int64_t)np * ctiles;
+  for (int64_t it = blockIdx.x; it < items; it += gridDim.x) {
+    const int p = (int)(it / ctiles), ct = (int)(it - (int64_t)p * ctiles);
+    const int64_t c = ((int64_t)ct * kThreads + threadIdx.x) * VN;
+    if (c >= n) continue;
+    float acc[VN];
+#pragma unroll
+    for (int k = 0; k < VN; ++k) acc[k] = 0.f;
+    const int64_t r0 = (int64_t)p * rp;
+    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
+    for (int64_t r = r0; r < r1; ++r) {
+      Vec16<T> v;
+      v.load(X + r * n + c);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) acc[k] += v.get(k);
+    }
+#pragma unroll
+    for (int k = 0; k < VN; ++k) partial[(int64_t)p * n + c + k] = acc[k];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_final_kernel(const float* __restrict__ partial, T* __restrict__ out,
+                                                                int64_t n, int np) {
+  for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < n; c += (int64_t)gridDim.x * kThreads) {
+    float acc = 0.f;
+    for (int p = 0; p < np; ++p) acc += partial[(int64_t)p * n + c];
+    out[c] = from_f32<T>(acc);
+  }
+}
+
+// ------------------------------------------------------------------------------- stems
+// Patch vector index = (c*p + i)*p + j; patches row-major over the image.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void unfold_kernel(const T* __restrict__ img, T* __restrict__ out,
+                                                          int B, int side, int patch) {
+  const int g = side / patch, pd = 3 * patch * patch;
+  const int64_t total = (int64_t)B * g * g * pd;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    const int e = (int)(i % pd);
+    const int64_t tok = i / pd;
+    const int px = (int)(tok % g), py = (int)((tok / g) % g), b = (int)(tok / ((int64_t)g * g));
+    const int jj = e % patch, ii = (e / patch) % patch, c = e / (patch * patch);
+    out[i] = img[(((int64_t)b * 3 + c) * side + (py * patch + ii)) * side + (px * patch + jj)];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void add_pos_kernel(const T* __restrict__ pos, T* __restrict__ y,
+                                                           int B, int N, int h) {
+  const int64_t total = (int64_t)B * N * h, per = (int64_t)N * h;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads)
+    y[i] = from_f32<T>(to_f32(y[i]) + to_f32(pos[i % per]));
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pos_grad_kernel(const T* __restrict__ dy, T* __restrict__ dpos,
+                                                            int B, int N, int h) {
+  const int64_t per = (int64_t)N * h;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < per; i += (int64_t)gridDim.x * kThreads) {
+    float acc = 0.f;
+    for (int b = 0; b < B; ++b) acc += to_f32(dy[(int64_t)b * per + i]);
+    dpos[i] = from_f32<T>(acc);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void text_stem_fwd_kernel(const T* __restrict__ img_tok, const int32_t* __restrict__ ids,
+                                                                 const T* __restrict__ table, T* __restrict__ out,
+                                                                 int B, int N, int n_img, int h, int vocab) {
+  const int64_t total = (int64_t)B * N * h;
+  const int n_txt = N - n_img;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    const int c = (int)(i % h);
+    const int64_t row = i / h;
+    const int t = (int)(row % N), b = (int)(row / N);
+    if (t < n_img) out[i] = img_tok[((int64_t)b * n_img + t) * h + c];
+    else {
+      // an id outside the table is clamped rather than followed out of bounds
+      int id = ids[(int64_t)b * n_txt + (t - n_img)];
+      id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+      out[i] = table[(int64_t)id * h + c];
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void split_img_kernel(const T* __restrict__ dy, T* __restrict__ d_img,
+                                                             int B, int N, int n_img, int h) {
+  const int64_t total = (int64_t)B * n_img * h;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    const int c = (int)(i % h);
+    const int64_t row = i / h;
+    const int t = (int)(row % n_img), b = (int)(row / n_img);
+    d_img[i] = dy[((int64_t)b * N + t) * h + c];
+  }
+}
+
+// Owner-computes embedding gradient: a workgroup owns table row v and adds the upstream
+// rows of every occurrence of v in ascending position, so repeated ids need no atomics.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void embed_grad_kernel(const T* __restrict__ dy, const int32_t* __restrict__ ids,
+                                                              T* __restrict__ dtable, int B, int N, int n_img, int h, int vocab) {
+  const int n_txt = N - n_img;
+  const int total = B * n_txt;
+  for (int v = blockIdx.x; v < vocab; v += gridDim.x) {
+    for (int c0 = 0; c0 < h; c0 += kThreads) {
+      const int c = c0 + threadIdx.x;
+      float acc = 0.f;
+      for (int r = 0; r < total; ++r) {
+        if (ids[r] == v && c < h) {
+          const int b = r / n_txt, t = r - b * n_txt;
+          acc += to_f32(dy[((int64_t)b * N + n_img + t) * h + c]);
+        }
+      }
+      if (c < h) dtable[(int64_t)v * h + c] = from_f32<T>(acc);
+    }
+  }
+}
+
+int pick_nv(int need) {
+  const int opts[] = {1, 2, 3, 4, 5, 6, 8, 10};
+  for (int o : opts) if (o >= need) return o;
+  return -1;
+}
+
+}  // namespace
+
+// =================================================================== host launchers
+#define DISPATCH_NV(NVV, MACRO) \
+  switch (NVV) {                \
+    case 1: MACRO(1); break;    \
+    case 2: MACRO(2); break;    \
+    case 3: MACRO(3); break;    \
+    case 4: MACRO(4); break;    \
+    case 5: MACRO(5); break;    \
+    case 6: MACRO(6); break;    \
+    case 8: MACRO(8); break;    \
+    default: MACRO(10); break;  \
+  }
+
+template <typename T>
+static mosaic_status norm_fwd_t(hipStream_t s, int quota, int norm, int64_t rows, int64_t h, float eps,
+                                const T* x, const T* gamma, const T* beta, T* y, float* stats) {
+  constexpr int VN = Vec16<T>::N;
+  if (h % VN) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld is not a multiple of %d", (long long)h, VN);
+  const int nv = pick_nv((int)ceil_div(h, 64 * VN));
+  if (nv < 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld too large", (long long)h);
+  if (rows == 0) return MOSAIC_OK;
+  const int grid = grid_for(quota, 8, ceil_div(rows, kWaves));
+#define L(NVC)                                                                                         \
+  if (norm == MOSAIC_LAYERNORM)                                                                        \
+    norm_fwd_kernel<T, MOSAIC_LAYERNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, beta, y, stats, rows, (int)h, eps); \
+  else                                                                                                 \
+    norm_fwd_kernel<T, MOSAIC_RMSNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, beta, y, stats, rows, (int)h, eps)
+  DISPATCH_NV(nv, L);
+#undef L
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_norm_fwd(hipStream_t s, int quota, int dtype, int norm, int64_t T, int64_t h, float eps,
+                              const void* x, const void* gamma, const void* beta, void* y, float* stats) {
+  if (norm != MOSAIC_LAYERNORM && norm != MOSAIC_RMSNORM) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm kind %d", norm);
+  if (dtype == MOSAIC_BF16)
+    return norm_fwd_t<bf16>(s, quota, norm, T, h, eps, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta, (bf16*)y, stats);
+  return norm_fwd_t<float>(s, quota, norm, T, h, eps, (const float*)x, (const float*)gamma, (const float*)beta, (float*)y, stats);
+}
+
+static inline void norm_partition(int64_t T, int* rp, int* np) {
+  int64_t r = ceil_div(T, 1024);
+  if (r < 4) r = 4;
+  *rp = (int)r;
+  *np = (int)ceil_div(T, r);
+}
+
+size_t norm_bwd_scratch_bytes(int64_t h) { return (size_t)1024 * 2 * (size_t)h * sizeof(float); }
+
+template <typename T>
+static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows, int64_t h, const T* x,
+                                const T* gamma, const float* stats, const T* dy, const T* R, T* dx,
+                                T* dgamma, T* dbeta, float* scratch) {
+  constexpr int VN = Vec16<T>::N;
+  if (h % VN) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld is not a multiple of %d", (long long)h, VN);
+  const int nv = pick_nv((int)ceil_div(h, 64 * VN));
+  if (nv < 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld too large", (long long)h);
+  if (rows == 0) return MOSAIC_OK;
+  int rp, np;
+  norm_partition(rows, &rp, &np);
+  const int grid = grid_for(quota, 4, ceil_div(np, kWaves));
+#define L(NVC)                                                                                        \
+  if (norm == MOSAIC_LAYERNORM)                                                                       \
+    norm_bwd_kernel<T, MOSAIC_LAYERNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np); \
+  else                                                                                                \
+    norm_bwd_kernel<T, MOSAIC_RMSNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np)
+  DISPATCH_NV(nv, L);
+#undef L
+  MOSAIC_LAUNCH_CHECK();
+  const int g2 = grid_for(quota, 8, ceil_div(2 * h, kThreads));
+  norm_bwd_reduce_kernel<T><<<g2, kThreads, 0, s>>>(scratch, dgamma, norm == MOSAIC_LAYERNORM ? dbeta : nullptr, (int)h, np);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_norm_bwd(hipStream_t s, int quota, int dtype, int norm, int64_t T, int64_t h, const void* x,
+                              const void* gamma, const float* stats, const void* dy, const void* R, void* dx,
+                              void* dgamma, void* dbeta, void* scratch) {
+  if (norm != MOSAIC_LAYERNORM && norm != MOSAIC_RMSNORM) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm kind %d", norm);
+  if (dtype == MOSAIC_BF16)
+    return norm_bwd_t<bf16>(s, quota, norm, T, h, (const bf16*)x, (const bf16*)gamma, stats, (const bf16*)dy,
+                            (const bf16*)R, (bf16*)dx, (bf16*)dgamma, (bf16*)dbeta, (float*)scratch);
+  return norm_bwd_t<float>(s, quota, norm, T, h, (const float*)x, (const float*)gamma, stats, (const float*)dy,
+                           (const float*)R, (float*)dx, (float*)dgamma, (float*)dbeta, (float*)scratch);
+}
+
+#define EW_CHECK_VEC(n, dtype)                                                               \
+  const int vn__ = (dtype == MOSAIC_BF16) ? 8 : 4;                                           \
+  if ((n) % vn__) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "element count %lld is not a multiple of %d", (long long)(n), vn__)
+
+mosaic_status launch_gelu_fwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, void* a) {
+  EW_CHECK_VEC(n, dtype);
+  if (n == 0) return MOSAIC_OK;
+  const int64_t nvec = n / vn__;
+  const int grid = grid_for(quota, 8, ceil_div(nvec, kThreads));
+  if (dtype == MOSAIC_BF16) gelu_fwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)z, (bf16*)a, nvec);
+  else gelu_fwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)z, (float*)a, nvec);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_gelu_bwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, const void* da, void* dz) {
+  EW_CHECK_VEC(n, dtype);
+  if (n == 0) return MOSAIC_OK;
+  const int64_t nvec = n / vn__;
+  const int grid = grid_for(quota, 8, ceil_div(nvec, kThreads));
+  if (dtype == MOSAIC_BF16) gelu_bwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)z, (const bf16*)da, (bf16*)dz, nvec);
+  else gelu_bwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)z, (const float*)da, (float*)dz, nvec);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_swiglu_fwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f, const void* gu, void* a) {
+  EW_CHECK_VEC(f, dtype);
+  if (T * f == 0) return MOSAIC_OK;
+  const int fv = (int)(f / vn__);
+  const int grid = grid_for(quota, 8, ceil_div(T * fv, kThreads));
+  if (dtype == MOSAIC_BF16) swiglu_fwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)gu, (bf16*)a, T, fv);
+  else swiglu_fwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)gu, (float*)a, T, fv);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_swiglu_bwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f, const void* gu,
+                                const void* da, void* dgu) {
+  EW_CHECK_VEC(f, dtype);
+  if (T * f == 0) return MOSAIC_OK;
+  const int fv = (int)(f / vn__);
+  const int grid = grid_for(quota, 8, ceil_div(T * fv, kThreads));
+  if (dtype == MOSAIC_BF16) swiglu_bwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)gu, (const bf16*)da, (bf16*)dgu, T, fv);
+  else swiglu_bwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)gu, (const float*)da, (float*)dgu, T, fv);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+size_t mse_scratch_bytes() { return kMsePartials * sizeof(float); }
+
+mosaic_status launch_mse(hipStream_t s, int quota, int dtype, int64_t n, const void* y, const void* target,
+                         void* dy, float* loss, void* scratch) {
+  EW_CHECK_VEC(n, dtype);
+  if (n == 0) MOSAIC_FAIL(MOSAIC_EINVAL, "mse over zero elements");
+  const int64_t nvec = n / vn__;
+  const int64_t chunk = ceil_div(nvec, kMsePartials);
+  const int grid = grid_for(quota, 8, kMsePartials);
+  const float scale = (float)(2.0 / (double)n);
+  if (dtype == MOSAIC_BF16)
+    mse_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)y, (const bf16*)target, (bf16*)dy, (float*)scratch, nvec, chunk, scale);
+  else
+    mse_kernel<float><<<grid, kThreads, 0, s>>>((const float*)y, (const float*)target, (float*)dy, (float*)scratch, nvec, chunk, scale);
+  MOSAIC_LAUNCH_CHECK();
+  mse_final_kernel<<<1, kThreads, 0, s>>>((const float*)scratch, loss, (float)(1.0 / (double)n));
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+size_t colsum_scratch_bytes(int64_t n) { return (size_t)kColsumMaxParts * (size_t)n * sizeof(float); }
+
+mosaic_status launch_colsum(hipStream_t s, int quota, int dtype, int64_t T, int64_t n, const void* X, void* out,
+                            void* scratch) {
+  EW_CHECK_VEC(n, dtype);
+  if (n == 0) return MOSAIC_OK;
+  int64_t rp = ceil_div(T, kColsumMaxParts);
+  if (rp < 8) rp = 8;
+  const int np = (int)ceil_div(T, rp);
+  const int ctiles = (int)ceil_div(n, (int64_t)kThreads * vn__);
+  if (np > 0) {
+    const int grid = grid_for(quota, 8, (int64_t)np * ctiles);
+    if (dtype == MOSAIC_BF16)
+      colsum_partial_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)X, (float*)scratch, T, n, (int)rp, np, ctiles);
+    else
+      colsum_partial_kernel<float><<<grid, kThreads, 0, s>>>((const float*)X, (float*)scratch, T, n, (int)rp, np, ctiles);
+    MOSAIC_LAUNCH_CHECK();
+  }
+  const int g2 = grid_for(quota, 8, ceil_div(n, kThreads));
+  if (dtype == MOSAIC_BF16) colsum_final_kernel<bf16><<<g2, kThreads, 0, s>>>((const float*)scratch, (bf16*)out, n, np);
+  else colsum_final_kernel<float><<<g2, kThreads, 0, s>>>((const float*)scratch, (float*)out, n, np);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+#define EW_LAUNCH(KERNEL, total, ...)                                                        \
+  do {                                                                                       \
+    if ((total) == 0) return MOSAIC_OK;                                                      \
+    const int grid = grid_for(quota, 8, ceil_div((total), kThreads));                        \
+    if (dtype == MOSAIC_BF16) KERNEL<bf16><<<grid, kThreads, 0, s>>> __VA_ARGS__(bf16);      \
+    else KERNEL<float><<<grid, kThreads, 0, s>>> __VA_ARGS__(float);                         \
+    MOSAIC_LAUNCH_CHECK();                                                                   \
+    return MOSAIC_OK;                                                                        \
+  } while (0)
+
+mosaic_status launch_unfold(hipStream_t s, int quota, int dtype, int B, int side, int patch, const void* img, void* out) {
+  if (patch <= 0 || side % patch) MOSAIC_FAIL(MOSAIC_EINVAL, "image side %d is not a multiple of patch %d", side, patch);
+  const int64_t total = (int64_t)B * 3 * side * side;
+#define ARGS(TT) ((const TT*)img, (TT*)out, B, side, patch)
+  EW_LAUNCH(unfold_kernel, total, ARGS);
+#undef ARGS
+}
+
+mosaic_status launch_add_pos(hipStream_t s, int quota, int dtype, int B, int N, int h, const void* pos, void* y) {
+  const int64_t total = (int64_t)B * N * h;
+#define ARGS(TT) ((const TT*)pos, (TT*)y, B, N, h)
+  EW_LAUNCH(add_pos_kernel, total, ARGS);
+#undef ARGS
+}
+
+mosaic_status launch_pos_grad(hipStream_t s, int quota, int dtype, int B, int N, int h, const void* dy, void* dpos) {
+  const int64_t total = (int64_t)N * h;
+#define ARGS(TT) ((const TT*)dy, (TT*)dpos, B, N, h)
+  EW_LAUNCH(pos_grad_kernel, total, ARGS);
+#undef ARGS
+}
+
+mosaic_status launch_text_stem_fwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img, int h, int vocab,
+                                   const void* img_tok, const int32_t* ids, const void* table, void* out) {
+  const int64_t total = (int64_t)B * N * h;
+#define ARGS(TT) ((const TT*)img_tok, ids, (const TT*)table, (TT*)out, B, N, n_img, h, vocab)
+  EW_LAUNCH(text_stem_fwd_kernel, total, ARGS);
+#undef ARGS
+}
+
+mosaic_status launch_text_stem_bwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img, int h, int vocab,
+                                   const void* dy, const int32_t* ids, void* d_img, void* dtable) {
+  if (d_img != nullptr && n_img > 0) {
+    const int64_t total = (int64_t)B * n_img * h;
+    const int grid = grid_for(quota, 8, ceil_div(total, kThreads));
+    if (dtype == MOSAIC_BF16) split_img_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, (bf16*)d_img, B, N, n_img, h);
+    else split_img_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, (float*)d_img, B, N, n_img, h);
+    MOSAIC_LAUNCH_CHECK();
+  }
+  if (vocab > 0) {
+    const int grid = grid_for(quota, 8, vocab);
+    if (dtype == MOSAIC_BF16)
+      embed_grad_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, ids, (bf16*)dtable, B, N, n_img, h, vocab);
+    else
+      embed_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, ids, (float*)dtable, B, N, n_img, h, vocab);
+    MOSAIC_LAUNCH_CHECK();
+  }
+  return MOSAIC_OK;
+}

@@ -1,0 +1,65 @@
+// Internal launch interface between the kernel files and the module / C-ABI layer.
+// Every function enqueues on `s` and returns without synchronising.  `quota` is the CU
+// count the persistent grid is sized for.
+#pragma once
+#include "common.h"
+
+// ------------------------------------------------------------------------------ GEMM
+// C[M,N] = op(A) op(B) (+ bias[N]) (+ R[M,N]), fp32 accumulation in ascending k.
+//   a_kc: A is stored [M,K] (K contiguous) else [K,M];  b_kc: B is stored [N,K] else [K,N].
+// fprop  Y = X W      : A = X  [T,k] a_kc=1, B = W  [k,n] b_kc=0
+// dgrad  dX = dY W^T  : A = dY [T,n] a_kc=1, B = W  [k,n] b_kc=1 (contraction over n)
+// wgrad  dW = X^T dY  : A = X  [T,k] a_kc=0, B = dY [T,n] b_kc=0 (contraction over T)
+mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc,
+                          int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                          const void* B, int64_t ldb, void* C, int64_t ldc,
+                          const void* bias, const void* R);
+
+// ------------------------------------------------------------------------- attention
+mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H,
+                                   int d, int causal, const void* qkv, void* O, float* lse);
+mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H,
+                                   int d, int causal, const void* qkv, const void* O,
+                                   const float* lse, const void* dO, void* dqkv, float* delta);
+
+// ----------------------------------------------------------- norms and elementwise
+mosaic_status launch_norm_fwd(hipStream_t s, int quota, int dtype, int norm, int64_t T,
+                              int64_t h, float eps, const void* x, const void* gamma,
+                              const void* beta, void* y, float* stats);
+size_t norm_bwd_scratch_bytes(int64_t h);
+mosaic_status launch_norm_bwd(hipStream_t s, int quota, int dtype, int norm, int64_t T,
+                              int64_t h, const void* x, const void* gamma, const float* stats,
+                              const void* dy, const void* R, void* dx, void* dgamma,
+                              void* dbeta, void* scratch);
+mosaic_status launch_gelu_fwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, void* a);
+mosaic_status launch_gelu_bwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z,
+                              const void* da, void* dz);
+mosaic_status launch_swiglu_fwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f,
+                                const void* gu, void* a);
+mosaic_status launch_swiglu_bwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f,
+                                const void* gu, const void* da, void* dgu);
+size_t mse_scratch_bytes();
+mosaic_status launch_mse(hipStream_t s, int quota, int dtype, int64_t n, const void* y,
+                         const void* target, void* dy, float* loss, void* scratch);
+size_t colsum_scratch_bytes(int64_t n);
+// out[n] = sum over T rows of X[T,n] in a fixed two-level order.
+mosaic_status launch_colsum(hipStream_t s, int quota, int dtype, int64_t T, int64_t n,
+                            const void* X, void* out, void* scratch);
+
+// ----------------------------------------------------------------------------- stems
+mosaic_status launch_unfold(hipStream_t s, int quota, int dtype, int B, int side, int patch,
+                            const void* img, void* out);
+// y[b*N+t, :] += pos[t, :]
+mosaic_status launch_add_pos(hipStream_t s, int quota, int dtype, int B, int N, int h,
+                             const void* pos, void* y);
+// dpos[t,:] = sum_b dy[b*N+t,:] in ascending b
+mosaic_status launch_pos_grad(hipStream_t s, int quota, int dtype, int B, int N, int h,
+                              const void* dy, void* dpos);
+// out rows: per sample b, [0,n_img) from img_tok, [n_img,N) from table[ids]
+mosaic_status launch_text_stem_fwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img,
+                                   int h, int vocab, const void* img_tok, const int32_t* ids,
+                                   const void* table, void* out);
+// d_img rows from dy; dtable[v] = sum over occurrences of v (ascending position)
+mosaic_status launch_text_stem_bwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img,
+                                   int h, int vocab, const void* dy, const int32_t* ids,
+                                   void* d_img, void* dtable);

@@ -48,3 +48,71 @@ def small_cfg(kind, B=2, N=8, h=16, H=2, f=24):
                     norm="layernorm", act="gelu", causal=0, bias=1, eps=1e-5)
     return dict(kind="decoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=1,
                 norm="rmsnorm", act="swiglu", causal=1, bias=0, eps=1e-5)
+
+
+# ------------------------------------------------------------------ GPU-side helpers
+def quantize(a, dtype):
+    """What the GPU will see: values rounded to the storage dtype, as float64."""
+    if dtype == "bf16":
+        return synth.round_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+    return np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+def quantize_tree(t, dtype):
+    if isinstance(t, dict):
+        return {k: quantize_tree(v, dtype) for k, v in t.items()}
+    if isinstance(t, list):
+        return [quantize_tree(v, dtype) for v in t]
+    return quantize(t, dtype)
+
+
+def to_dev(a, dtype):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda().contiguous()
+
+
+def from_dev(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def tol(dtype):
+    """Relative L2 bound: 1e-5 on the fp32 path, 2e-2 for bf16 storage with fp32
+    accumulation (the workload's stated tolerances)."""
+    return 2e-2 if dtype == "bf16" else 1e-5
+
+
+def load_layer_params(module, layers):
+    """Copy oracle-style per-layer dicts into a module's flat parameter buffer."""
+    for l, p in enumerate(layers):
+        for k, v in p.items():
+            if k in ("w_gate", "w_up"):
+                continue
+            module.set_tensor(f"L{l}.{k}", v)
+        if "w_gate" in p:
+            module.set_tensor(f"L{l}.w_gu", np.concatenate([p["w_gate"], p["w_up"]], axis=1))
+
+
+def read_layer_grads(module, layers):
+    out = []
+    for l, p in enumerate(layers):
+        g = {}
+        for k in p:
+            if k in ("w_gate", "w_up"):
+                continue
+            g[k] = module.get_tensor(f"L{l}.{k}", grads=True).reshape(np.shape(p[k]))
+        if "w_gate" in p:
+            gu = module.get_tensor(f"L{l}.w_gu", grads=True)
+            f = p["w_gate"].shape[1]
+            g["w_gate"], g["w_up"] = gu[:, :f], gu[:, f:]
+        out.append(g)
+    return out
+
+
+def load_flat_params(module, p):
+    for k, v in p.items():
+        module.set_tensor(k, v)
+
+
+def read_flat_grads(module, p):
+    return {k: module.get_tensor(k, grads=True).reshape(np.shape(v)) for k, v in p.items()}

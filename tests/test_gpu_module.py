@@ -1,0 +1,180 @@
+"""Module-level parity through the C ABI: forward output, input gradient and every
+parameter gradient of encoder / decoder / projector / stem modules against the CPU
+checker, bit-identity across quotas, and the chained config-1 stage end to end."""
+import numpy as np
+import pytest
+
+from oracle import layers as O
+from paper_2605_18710_amd import synth
+from helpers import (rel_l2, quantize, quantize_tree, to_dev, from_dev, tol, layer_params, projector_params,
+                     stem_params, load_layer_params, read_layer_grads, load_flat_params, read_flat_grads)
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_18710_amd import binding
+    binding.lib()
+    return binding
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy().copy()
+
+
+def enc(B, N, h, H, f, L):
+    return dict(kind="encoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=L,
+                norm="layernorm", act="gelu", causal=0, bias=1, eps=1e-5)
+
+
+def dec(B, N, h, H, f, L):
+    return dict(kind="decoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=L,
+                norm="rmsnorm", act="swiglu", causal=1, bias=0, eps=1e-5)
+
+
+STACKS = [
+    ("f32", enc(2, 16, 128, 4, 512, 1)),        # config-1 vision layer
+    ("f32", dec(2, 128, 128, 4, 384, 1)),       # config-1 decoder layer
+    ("f32", dec(1, 24, 64, 2, 96, 3)),
+    ("bf16", enc(2, 196, 256, 4, 1024, 2)),     # ragged T = 392, head 64
+    ("bf16", dec(2, 160, 512, 4, 768, 2)),      # head 128, causal
+]
+
+
+@pytest.mark.parametrize("dtype,cfg", STACKS)
+def test_stack_step_matches_oracle_and_is_quota_invariant(mb, dtype, cfg):
+    T, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    layers = quantize_tree([layer_params(cfg, 1000 + 100 * l) for l in range(cfg["layers"])], dtype)
+    x = quantize(synth.normal(2000, (T, h)), dtype)
+    target = quantize(synth.normal(2001, (T, h)), dtype)
+    y_ref, saved = O.stack_fwd(x, layers, cfg)
+    loss_ref = O.mse_fwd(y_ref, target)
+    dx_ref, g_ref = O.stack_bwd(O.mse_bwd(y_ref, target), layers, saved, cfg)
+
+    m = mb.Module(cfg, dtype)
+    load_layer_params(m, layers)
+    x_, t_ = to_dev(x, dtype), to_dev(target, dtype)
+    first = None
+    for q in (256, 96, 17):
+        y = torch.empty_like(x_); dx = torch.empty_like(x_)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        m.grads.zero_()
+        m.step(q, None, x_, y, target=t_, dx=dx, loss=loss)
+        torch.cuda.synchronize()
+        snap = [bits(y), bits(dx), bits(m.grads), bits(loss)]
+        if first is None:
+            first = snap
+            assert rel_l2(from_dev(y), y_ref) <= tol(dtype)
+            assert abs(loss.item() - loss_ref) <= tol(dtype) * loss_ref
+            assert rel_l2(from_dev(dx), dx_ref) <= tol(dtype)
+            g = read_layer_grads(m, layers)
+            for l in range(cfg["layers"]):
+                for k in g_ref[l]:
+                    assert rel_l2(g[l][k], g_ref[l][k]) <= tol(dtype), (l, k)
+        else:
+            for a, b in zip(snap, first):
+                assert np.array_equal(a, b), "module step depends on the quota"
+    m.destroy()
+
+
+def test_given_upstream_gradient_instead_of_target(mb):
+    cfg = dec(1, 32, 64, 2, 96, 1)
+    layers = quantize_tree([layer_params(cfg, 3000)], "f32")
+    x = quantize(synth.normal(3001, (32, 64)), "f32"); dy = quantize(synth.normal(3002, (32, 64)), "f32")
+    y_ref, saved = O.stack_fwd(x, layers, cfg)
+    dx_ref, g_ref = O.stack_bwd(dy, layers, saved, cfg)
+    m = mb.Module(cfg, "f32")
+    load_layer_params(m, layers)
+    x_, dy_ = to_dev(x, "f32"), to_dev(dy, "f32")
+    y = torch.empty_like(x_); dx = torch.empty_like(x_)
+    m.step(256, None, x_, y, dy=dy_, dx=dx)
+    torch.cuda.synchronize()
+    assert rel_l2(from_dev(dx), dx_ref) <= 1e-5
+    assert rel_l2(read_layer_grads(m, layers)[0]["w_qkv"], g_ref[0]["w_qkv"]) <= 1e-5
+    with pytest.raises(mb.MosaicError):
+        m.step(256, None, x_, y, dx=dx)                 # neither dy nor target
+    with pytest.raises(mb.MosaicError):
+        m.step(300, None, x_, y, dy=dy_, dx=dx)         # quota beyond the device
+    m.destroy()
+
+
+@pytest.mark.parametrize("dtype,T,din,dout", [("f32", 32, 128, 128), ("bf16", 392, 256, 512)])
+def test_projector(mb, dtype, T, din, dout):
+    cfg = dict(kind="projector", batch=1, seq=T, in_dim=din, out_dim=dout)
+    p = quantize_tree(projector_params(din, dout, 4000), dtype)
+    x = quantize(synth.normal(4001, (T, din)), dtype); dy = quantize(synth.normal(4002, (T, dout)), dtype)
+    y_ref, s = O.projector_fwd(x, p)
+    dx_ref, g_ref = O.projector_bwd(dy, p, s)
+    m = mb.Module(cfg, dtype)
+    load_flat_params(m, p)
+    x_, dy_ = to_dev(x, dtype), to_dev(dy, dtype)
+    y = torch.empty((T, dout), dtype=x_.dtype, device="cuda"); dx = torch.empty_like(x_)
+    m.step(256, None, x_, y, dy=dy_, dx=dx)
+    torch.cuda.synchronize()
+    assert rel_l2(from_dev(y), y_ref) <= tol(dtype)
+    assert rel_l2(from_dev(dx), dx_ref) <= tol(dtype)
+    g = read_flat_grads(m, p)
+    for k in g_ref:
+        assert rel_l2(g[k], g_ref[k]) <= tol(dtype), k
+    m.destroy()
+
+
+def build_config1(mb, dtype="f32"):
+    """The tiny 2-module stage as a chain of five library modules."""
+    wl = synth.WORKLOADS[0]
+    cv, cp, cl = wl["modules"]
+    B, n_img, hv, hl = cv["batch"], cv["seq"], cv["hidden"], cl["hidden"]
+    n_txt = cl["seq"] - n_img
+    seed = synth.tensor_seed(0, 0)
+    P = dict(stem=stem_params(cv["in_dim"], hv, n_img, seed + 100),
+             vit=[layer_params(cv, seed + 200)], proj=projector_params(hv, hl, seed + 300),
+             table=synth.normal(seed + 400, (cl["vocab"], hl), 0, 0.02), llm=[layer_params(cl, seed + 500)])
+    P = quantize_tree(P, dtype)
+    img = quantize(synth.uniform(seed + 1, wl["image"]), dtype)
+    ids = synth.integers(seed + 2, (B, n_txt), 0, cl["vocab"])
+    target = quantize(synth.normal(seed + 3, (B * cl["seq"], hl)), dtype)
+    mods = [
+        mb.Module(dict(kind="patch_stem", batch=B, seq=n_img, hidden=hv, in_dim=cv["in_dim"], patch=wl["patch"]), dtype),
+        mb.Module(cv, dtype),
+        mb.Module(dict(cp), dtype),
+        mb.Module(dict(kind="text_stem", batch=B, seq=cl["seq"], hidden=hl, vocab=cl["vocab"], n_img=n_img), dtype),
+        mb.Module(cl, dtype),
+    ]
+    load_flat_params(mods[0], P["stem"]); load_layer_params(mods[1], P["vit"]); load_flat_params(mods[2], P["proj"])
+    mods[3].set_tensor("table", P["table"]); load_layer_params(mods[4], P["llm"])
+    ids_ = torch.from_numpy(ids.reshape(-1)).cuda()
+    mods[3].bind_ids(ids_)
+    return wl, P, img, ids, target, mods, ids_
+
+
+def test_config1_chain_end_to_end(mb):
+    dtype = "f32"
+    wl, P, img, ids, target, mods, ids_ = build_config1(mb, dtype)
+    cv, cp, cl = wl["modules"]
+    loss_ref, y_ref, G = O.chain_fwd_bwd(img, ids, target, P, dict(vit=cv, llm=cl), wl["patch"])
+    td = torch.float32
+    x0 = to_dev(img, dtype)
+    ys = [torch.empty(m.out_elems, dtype=td, device="cuda") for m in mods]
+    dxs = [None] + [torch.empty(m.in_elems, dtype=td, device="cuda") for m in mods[1:]]
+    xs = [x0] + ys[:-1]
+    dys = dxs[1:] + [None]
+    t_ = to_dev(target, dtype)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mb.pool_reserve(256, 0, mb.STRIPED)
+    r = mb.stage_run(mods, xs, ys, [256] * 5, [0] * 5, mb.STRIPED, mb.CHAINED, dy=dys,
+                     target=[None] * 4 + [t_], dx=dxs, loss=[None] * 4 + [loss])
+    assert r["stage_ms"] > 0
+    assert rel_l2(from_dev(ys[-1]).reshape(y_ref.shape), y_ref) <= 1e-5
+    assert abs(loss.item() - loss_ref) <= 1e-5 * loss_ref
+    checks = [(read_flat_grads(mods[0], P["stem"]), G["stem"]), (read_layer_grads(mods[1], P["vit"])[0], G["vit"][0]),
+              (read_flat_grads(mods[2], P["proj"]), G["proj"]), (read_layer_grads(mods[4], P["llm"])[0], G["llm"][0])]
+    for got, ref in checks:
+        for k in ref:
+            assert rel_l2(got[k], ref[k]) <= 1e-5, k
+    assert rel_l2(mods[3].get_tensor("table", grads=True), G["table"]) <= 1e-5
+    for m in mods:
+        m.destroy()

@@ -1,0 +1,200 @@
+"""Kernel-level parity: each operation called through the C ABI against the CPU checker
+on the same seeded inputs, at sizes that span several tiles and a ragged tail, plus
+bit-identity of the outputs across CU quotas."""
+import numpy as np
+import pytest
+
+from oracle import layers as O
+from paper_2605_18710_amd import synth
+from helpers import rel_l2, quantize, to_dev, from_dev, tol
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+QUOTAS = [256, 64, 24]
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_18710_amd import binding
+    binding.lib()
+    return binding
+
+
+def empty(shape, dtype):
+    return torch.empty(shape, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy().copy()
+
+
+LINEAR_SHAPES = [
+    ("f32", 77, 40, 52), ("f32", 256, 128, 384),
+    ("bf16", 333, 264, 392),          # ragged in every dimension, several 128-tiles
+    ("bf16", 1568, 768, 2304),        # ViT QKV projection of the CLIP-B-scale workload
+    ("bf16", 4096, 512, 8192),        # enough tiles for the 256x256 configuration
+    ("bf16", 40, 24, 16), ("bf16", 129, 600, 136),
+]
+
+
+@pytest.mark.parametrize("dtype,T,k,n", LINEAR_SHAPES)
+def test_linear_fwd_dgrad_wgrad(mb, dtype, T, k, n):
+    X = quantize(synth.normal(1, (T, k)), dtype); W = quantize(synth.normal(2, (k, n), 0, 0.05), dtype)
+    b = quantize(synth.normal(3, (n,), 0, 0.1), dtype); R = quantize(synth.normal(4, (T, n)), dtype)
+    dY = quantize(synth.normal(5, (T, n)), dtype); Rk = quantize(synth.normal(6, (T, k)), dtype)
+    dX_, W_, b_, R_, dY_, Rk_ = [to_dev(a, dtype) for a in (X, W, b, R, dY, Rk)]
+    ref_y = O.linear_fwd(X, W, b) + R
+    ref_dx, ref_dw, ref_db = O.linear_bwd(X, W, dY)
+    ref_dx = ref_dx + Rk
+    outs = []
+    for q in QUOTAS:
+        Y = empty((T, n), dtype); dX = empty((T, k), dtype); dW = empty((k, n), dtype); db = empty((n,), dtype)
+        scratch = torch.empty(mb.colsum_scratch_bytes(n), dtype=torch.uint8, device="cuda")
+        mb.op_linear_fwd(None, q, dtype, T, k, n, dX_, W_, b_, R_, Y)
+        mb.op_linear_dgrad(None, q, dtype, T, k, n, dY_, W_, Rk_, dX)
+        mb.op_linear_wgrad(None, q, dtype, T, k, n, dX_, dY_, dW, db, scratch)
+        torch.cuda.synchronize()
+        outs.append([bits(t) for t in (Y, dX, dW, db)])
+        if q == QUOTAS[0]:
+            assert rel_l2(from_dev(Y), ref_y) <= tol(dtype)
+            assert rel_l2(from_dev(dX), ref_dx) <= tol(dtype)
+            assert rel_l2(from_dev(dW), ref_dw) <= tol(dtype)
+            assert rel_l2(from_dev(db), ref_db) <= tol(dtype)
+    for o in outs[1:]:
+        for a, b0 in zip(o, outs[0]):
+            assert np.array_equal(a, b0), "result depends on the quota"
+
+
+def test_linear_without_bias_and_residual_and_empty(mb):
+    T, k, n = 70, 64, 72
+    X = quantize(synth.normal(7, (T, k)), "bf16"); W = quantize(synth.normal(8, (k, n), 0, 0.05), "bf16")
+    Y = empty((T, n), "bf16")
+    mb.op_linear_fwd(None, 256, "bf16", T, k, n, to_dev(X, "bf16"), to_dev(W, "bf16"), None, None, Y)
+    torch.cuda.synchronize()
+    assert rel_l2(from_dev(Y), X @ W) <= 2e-2
+    mb.op_linear_fwd(None, 256, "bf16", 0, k, n, to_dev(X, "bf16"), to_dev(W, "bf16"), None, None, Y)   # no tokens: no-op
+    with pytest.raises(mb.MosaicError) as e:
+        mb.op_linear_fwd(None, 0, "bf16", T, k, n, Y, Y, None, None, Y)
+    assert e.value.status == mb.EQUOTA
+    with pytest.raises(mb.MosaicError) as e:
+        mb.op_linear_fwd(None, 64, "bf16", T, k, n, None, Y, None, None, Y)
+    assert e.value.status == mb.EINVAL
+
+
+ATTN_SHAPES = [("f32", 2, 16, 4, 32, 0), ("f32", 2, 128, 4, 32, 1), ("f32", 1, 37, 2, 24, 1),
+               ("bf16", 2, 196, 3, 64, 0), ("bf16", 1, 300, 2, 128, 1), ("bf16", 2, 1, 2, 64, 1)]
+
+
+@pytest.mark.parametrize("dtype,B,N,H,d,causal", ATTN_SHAPES)
+def test_attention_fwd_bwd(mb, dtype, B, N, H, d, causal):
+    h = H * d
+    qkv = quantize(synth.normal(10, (B * N, 3 * h)), dtype)
+    dO = quantize(synth.normal(11, (B * N, h)), dtype)
+    ref_o = O.attention_fwd(qkv, B, N, H, causal)
+    ref_lse = O.attention_lse(qkv, B, N, H, causal)
+    ref_d = O.attention_bwd(qkv, dO, B, N, H, causal)
+    qkv_, dO_ = to_dev(qkv, dtype), to_dev(dO, dtype)
+    outs = []
+    for q in QUOTAS:
+        Oo = empty((B * N, h), dtype); lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        dqkv = empty((B * N, 3 * h), dtype); delta = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        mb.op_attention_fwd(None, q, dtype, B, N, H, d, causal, qkv_, Oo, lse)
+        mb.op_attention_bwd(None, q, dtype, B, N, H, d, causal, qkv_, Oo, lse, dO_, dqkv, delta)
+        torch.cuda.synchronize()
+        outs.append([bits(Oo), bits(lse), bits(dqkv)])
+        if q == QUOTAS[0]:
+            assert rel_l2(from_dev(Oo), ref_o) <= tol(dtype)
+            assert rel_l2(from_dev(lse), ref_lse) <= (1e-5 if dtype == "f32" else 1e-2)
+            got = from_dev(dqkv)
+            for part in range(3):      # dq, dk, dv separately
+                assert rel_l2(got[:, part * h:(part + 1) * h], ref_d[:, part * h:(part + 1) * h]) <= tol(dtype), part
+    for o in outs[1:]:
+        for a, b0 in zip(o, outs[0]):
+            assert np.array_equal(a, b0)
+
+
+NORM_SHAPES = [("f32", "layernorm", 32, 128), ("f32", "rmsnorm", 256, 128), ("bf16", "layernorm", 1568, 768),
+               ("bf16", "rmsnorm", 1000, 2048), ("bf16", "rmsnorm", 130, 5120), ("bf16", "layernorm", 3, 3200),
+               ("f32", "layernorm", 5, 24)]
+
+
+@pytest.mark.parametrize("dtype,norm,T,h", NORM_SHAPES)
+def test_norm_fwd_bwd(mb, dtype, norm, T, h):
+    eps = 1e-5
+    x = quantize(synth.normal(20, (T, h), 0.3, 1.7), dtype)
+    g = quantize(1 + synth.normal(21, (h,), 0, 0.1), dtype); b = quantize(synth.normal(22, (h,), 0, 0.1), dtype)
+    dy = quantize(synth.normal(23, (T, h)), dtype); R = quantize(synth.normal(24, (T, h)), dtype)
+    if norm == "layernorm":
+        ref_y = O.layernorm_fwd(x, g, b, eps)
+        ref_dx, ref_dg, ref_db = O.layernorm_bwd(x, g, dy, eps)
+    else:
+        ref_y = O.rmsnorm_fwd(x, g, eps)
+        ref_dx, ref_dg = O.rmsnorm_bwd(x, g, dy, eps)
+        ref_db = None
+    ref_dx = ref_dx + R
+    x_, g_, b_, dy_, R_ = [to_dev(a, dtype) for a in (x, g, b, dy, R)]
+    outs = []
+    for q in QUOTAS:
+        y = empty((T, h), dtype); stats = torch.empty((T, 2), dtype=torch.float32, device="cuda")
+        dx = empty((T, h), dtype); dg = empty((h,), dtype); db = empty((h,), dtype)
+        scratch = torch.empty(mb.norm_bwd_scratch_bytes(h), dtype=torch.uint8, device="cuda")
+        mb.op_norm_fwd(None, q, dtype, norm, T, h, eps, x_, g_, b_, y, stats)
+        mb.op_norm_bwd(None, q, dtype, norm, T, h, x_, g_, stats, dy_, R_, dx, dg, db, scratch)
+        torch.cuda.synchronize()
+        outs.append([bits(y), bits(dx), bits(dg)] + ([bits(db)] if ref_db is not None else []))
+        if q == QUOTAS[0]:
+            assert rel_l2(from_dev(y), ref_y) <= tol(dtype)
+            assert rel_l2(from_dev(dx), ref_dx) <= tol(dtype)
+            assert rel_l2(from_dev(dg), ref_dg) <= tol(dtype)
+            if ref_db is not None:
+                assert rel_l2(from_dev(db), ref_db) <= tol(dtype)
+    for o in outs[1:]:
+        for a, b0 in zip(o, outs[0]):
+            assert np.array_equal(a, b0)
+
+
+@pytest.mark.parametrize("dtype,T,f", [("f32", 32, 512), ("bf16", 1568, 3072), ("bf16", 77, 88), ("f32", 256, 384)])
+def test_activations(mb, dtype, T, f):
+    z = quantize(synth.normal(30, (T, f), 0, 2.0), dtype); da = quantize(synth.normal(31, (T, f)), dtype)
+    gu = quantize(synth.normal(32, (T, 2 * f), 0, 2.0), dtype)
+    z_, da_, gu_ = to_dev(z, dtype), to_dev(da, dtype), to_dev(gu, dtype)
+    outs = []
+    for q in QUOTAS:
+        a = empty((T, f), dtype); dz = empty((T, f), dtype); s = empty((T, f), dtype); dgu = empty((T, 2 * f), dtype)
+        mb.op_gelu_fwd(None, q, dtype, T * f, z_, a)
+        mb.op_gelu_bwd(None, q, dtype, T * f, z_, da_, dz)
+        mb.op_swiglu_fwd(None, q, dtype, T, f, gu_, s)
+        mb.op_swiglu_bwd(None, q, dtype, T, f, gu_, da_, dgu)
+        torch.cuda.synchronize()
+        outs.append([bits(t) for t in (a, dz, s, dgu)])
+        if q == QUOTAS[0]:
+            assert rel_l2(from_dev(a), O.gelu(z)) <= tol(dtype)
+            assert rel_l2(from_dev(dz), da * O.gelu_grad(z)) <= tol(dtype)
+            assert rel_l2(from_dev(s), O.swiglu_fwd(gu[:, :f], gu[:, f:])) <= tol(dtype)
+            dg, du = O.swiglu_bwd(gu[:, :f], gu[:, f:], da)
+            assert rel_l2(from_dev(dgu), np.concatenate([dg, du], 1)) <= tol(dtype)
+    for o in outs[1:]:
+        for a0, b0 in zip(o, outs[0]):
+            assert np.array_equal(a0, b0)
+
+
+@pytest.mark.parametrize("dtype,n", [("f32", 2 * 128 * 128), ("bf16", 8192 * 2048), ("bf16", 8), ("f32", 4 * 1031)])
+def test_mse(mb, dtype, n):
+    y = quantize(synth.normal(40, (n,)), dtype); t = quantize(synth.normal(41, (n,)), dtype)
+    y_, t_ = to_dev(y, dtype), to_dev(t, dtype)
+    outs = []
+    for q in QUOTAS:
+        dy = empty((n,), dtype); loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        scratch = torch.empty(mb.mse_scratch_bytes(), dtype=torch.uint8, device="cuda")
+        mb.op_mse(None, q, dtype, n, y_, t_, dy, loss, scratch)
+        torch.cuda.synchronize()
+        outs.append([bits(dy), bits(loss)])
+        if q == QUOTAS[0]:
+            assert abs(float(loss.item()) - O.mse_fwd(y, t)) <= 1e-5 * O.mse_fwd(y, t)
+            assert rel_l2(from_dev(dy), O.mse_bwd(y, t)) <= tol(dtype)
+    for o in outs[1:]:
+        for a0, b0 in zip(o, outs[0]):
+            assert np.array_equal(a0, b0)

@@ -1,0 +1,102 @@
+"""Launcher tests on the GPU: CU masks confine work, the pool removes stream creation
+from the stage path, and colocated / time-sliced execution give identical bits."""
+import numpy as np
+import pytest
+
+from paper_2605_18710_amd import synth
+from helpers import quantize, quantize_tree, to_dev, layer_params, load_layer_params
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_18710_amd import binding
+    binding.lib()
+    return binding
+
+
+def test_device_shape(mb):
+    assert mb.device_cu_count() == 256
+    assert mb.device_xcd_count() == 8
+
+
+def placement(mb, stream, n=2048):
+    out = torch.full((n, 3), -1, dtype=torch.int32, device="cuda")
+    mb.probe_placement(stream, n, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def test_masks_confine_workgroups(mb):
+    full = placement(mb, None)
+    all_cus = {tuple(r) for r in full}
+    assert len({r[0] for r in full}) == 8            # eight XCDs seen without a mask
+    s_al = mb.Stream(64, 64, mb.XCD_ALIGNED)
+    got = placement(mb, s_al)
+    assert {r[0] for r in got} <= {2, 3} and len({tuple(r) for r in got}) <= 64
+    s_st = mb.Stream(64, 0, mb.STRIPED)
+    got2 = placement(mb, s_st)
+    cus2 = {tuple(r) for r in got2}
+    assert len(cus2) <= 64 and len({r[0] for r in got2}) == 8
+    per_xcd = [len({tuple(r) for r in got2 if r[0] == x}) for x in range(8)]
+    assert max(per_xcd) <= 8
+    s_b = mb.Stream(192, 64, mb.STRIPED)
+    cus3 = {tuple(r) for r in placement(mb, s_b, 8192)}
+    assert not (cus2 & cus3), "disjoint quotas landed on a common CU"
+    assert len(all_cus) <= 256
+    for s in (s_al, s_st, s_b):
+        s.destroy()
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy().copy()
+
+
+def test_stage_modes_agree_and_pool_is_used(mb):
+    dtype = "bf16"
+    cfgs = [dict(kind="encoder", batch=2, seq=196, hidden=256, heads=4, mlp=1024, layers=2, norm="layernorm",
+                 act="gelu", causal=0, bias=1, eps=1e-5),
+            dict(kind="decoder", batch=2, seq=256, hidden=512, heads=4, mlp=768, layers=2, norm="rmsnorm",
+                 act="swiglu", causal=1, bias=0, eps=1e-5)]
+    mods, xs, ys, dxs, tg, losses = [], [], [], [], [], []
+    for i, cfg in enumerate(cfgs):
+        m = mb.Module(cfg, dtype)
+        load_layer_params(m, quantize_tree([layer_params(cfg, 5000 + 1000 * i + 100 * l) for l in range(cfg["layers"])], dtype))
+        T, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+        mods.append(m)
+        xs.append(to_dev(quantize(synth.normal(6000 + i, (T, h)), dtype), dtype))
+        tg.append(to_dev(quantize(synth.normal(6100 + i, (T, h)), dtype), dtype))
+        ys.append(torch.empty_like(xs[-1])); dxs.append(torch.empty_like(xs[-1]))
+        losses.append(torch.zeros(1, dtype=torch.float32, device="cuda"))
+    with pytest.raises(mb.MosaicError) as e:      # nothing reserved yet for this split
+        mb.stage_run(mods, xs, ys, [40, 216], [0, 40], mb.STRIPED, mb.COLOCATED, target=tg, dx=dxs, loss=losses)
+    assert e.value.status == mb.EQUOTA
+    for q, o, lay in ((256, 0, mb.STRIPED), (64, 0, mb.STRIPED), (192, 64, mb.STRIPED), (64, 0, mb.XCD_ALIGNED), (192, 64, mb.XCD_ALIGNED)):
+        mb.pool_reserve(q, o, lay)
+    created = mb.pool_creations()
+    snaps = []
+    runs = [([256, 256], [0, 0], mb.STRIPED, mb.TIME_SLICED), ([64, 192], [0, 64], mb.STRIPED, mb.COLOCATED),
+            ([64, 192], [0, 64], mb.XCD_ALIGNED, mb.COLOCATED)]
+    for quotas, offs, lay, mode in runs:
+        for m in mods:
+            m.grads.zero_()
+        r = mb.stage_run(mods, xs, ys, quotas, offs, lay, mode, target=tg, dx=dxs, loss=losses)
+        assert r["stage_ms"] > 0 and all(t > 0 for t in r["module_ms"])
+        if mode == mb.TIME_SLICED:
+            assert r["stage_ms"] >= sum(r["module_ms"]) * 0.999          # Eq. 1
+        else:
+            assert r["stage_ms"] >= max(r["module_ms"]) * 0.999          # Eq. 4
+        snaps.append([bits(t) for t in ys + dxs + losses] + [bits(m.grads) for m in mods])
+    assert mb.pool_creations() == created, "a stream was created on the stage path"
+    for s in snaps[1:]:
+        for a, b in zip(s, snaps[0]):
+            assert np.array_equal(a, b), "colocated and time-sliced runs differ"
+    with pytest.raises(mb.MosaicError) as e:
+        mb.stage_run(mods, xs, ys, [128, 192], [0, 64], mb.STRIPED, mb.COLOCATED, target=tg, dx=dxs, loss=losses)
+    assert e.value.status == mb.EQUOTA
+    for m in mods:
+        m.destroy()
