@@ -51,9 +51,12 @@ enum { MOSAIC_ENCODER = 0, MOSAIC_DECODER = 1, MOSAIC_PROJECTOR = 2,
 enum { MOSAIC_NORM_NONE = 0, MOSAIC_LAYERNORM = 1, MOSAIC_RMSNORM = 2 };
 enum { MOSAIC_GELU = 0, MOSAIC_SWIGLU = 1 };
 /* How a quota's CUs are chosen.  STRIPED takes the same share of every XCD (keeps
- * workgroup dispatch balanced over XCDs); XCD_ALIGNED fills whole XCDs first (keeps a
- * module's L2 private).  Quota and offset are in CUs; with XCD_ALIGNED both must be
- * multiples of the CUs per XCD. */
+ * workgroup dispatch balanced over XCDs).  XCD_ALIGNED fills whole XCDs first (would keep
+ * a module's L2 private); quota and offset must then be multiples of the CUs per XCD.
+ * On MI355X in its default partition mode one queue spans all XCDs and the driver
+ * refuses a mask that leaves an XCD empty, so mosaic_stream_create returns
+ * MOSAIC_EUNSUPPORTED for an XCD_ALIGNED quota below the whole device and MOSAIC_EQUOTA
+ * for a STRIPED quota below one CU per XCD; mosaic_cu_mask_build computes both. */
 enum { MOSAIC_STRIPED = 0, MOSAIC_XCD_ALIGNED = 1 };
 enum { MOSAIC_COLOCATED = 0, MOSAIC_TIME_SLICED = 1, MOSAIC_CHAINED = 2 };
 

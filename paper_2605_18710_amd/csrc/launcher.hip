@@ -99,6 +99,19 @@ extern "C" mosaic_status mosaic_stream_create(int32_t cu_quota, int32_t cu_offse
   MOSAIC_TRY(mosaic_device_info(&di));
   std::vector<uint32_t> mask((di.cu_count + 31) / 32);
   MOSAIC_TRY(mosaic_cu_mask_build(di.cu_count, di.xcd_count, cu_quota, cu_offset, layout, mask.data(), (int)mask.size()));
+  // One queue spans every XCD and its workgroups are dealt round-robin over them, so the
+  // driver refuses a mask that leaves an XCD without a CU (and the runtime's failure path
+  // is not safe to enter): reject such masks here.
+  for (int x = 0; x < di.xcd_count; ++x) {
+    bool any = false;
+    for (int i = x; i < di.cu_count; i += di.xcd_count) any |= (mask[i >> 5] >> (i & 31)) & 1u;
+    if (!any) {
+      if (layout == MOSAIC_XCD_ALIGNED)
+        MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "XCD-aligned quota %d at offset %d leaves XCD %d without CUs; this device "
+                    "spreads every queue over all %d XCDs, use MOSAIC_STRIPED", cu_quota, cu_offset, x, di.xcd_count);
+      MOSAIC_FAIL(MOSAIC_EQUOTA, "quota %d leaves XCD %d without CUs; the smallest quota is %d", cu_quota, x, di.xcd_count);
+    }
+  }
   mosaic_stream* st = new (std::nothrow) mosaic_stream();
   if (!st) MOSAIC_FAIL(MOSAIC_ENOMEM, "host allocation failed");
   hipError_t e;

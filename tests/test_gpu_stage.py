@@ -35,9 +35,13 @@ def test_masks_confine_workgroups(mb):
     full = placement(mb, None)
     all_cus = {tuple(r) for r in full}
     assert len({r[0] for r in full}) == 8            # eight XCDs seen without a mask
-    s_al = mb.Stream(64, 64, mb.XCD_ALIGNED)
-    got = placement(mb, s_al)
-    assert {r[0] for r in got} <= {2, 3} and len({tuple(r) for r in got}) <= 64
+    # one queue spans all XCDs: a mask that empties an XCD is refused before HIP sees it
+    with pytest.raises(mb.MosaicError) as e:
+        mb.Stream(64, 64, mb.XCD_ALIGNED)
+    assert e.value.status == mb.EUNSUPPORTED
+    with pytest.raises(mb.MosaicError) as e:
+        mb.Stream(4, 0, mb.STRIPED)
+    assert e.value.status == mb.EQUOTA
     s_st = mb.Stream(64, 0, mb.STRIPED)
     got2 = placement(mb, s_st)
     cus2 = {tuple(r) for r in got2}
@@ -48,7 +52,10 @@ def test_masks_confine_workgroups(mb):
     cus3 = {tuple(r) for r in placement(mb, s_b, 8192)}
     assert not (cus2 & cus3), "disjoint quotas landed on a common CU"
     assert len(all_cus) <= 256
-    for s in (s_al, s_st, s_b):
+    s_c = mb.Stream(8, 0, mb.STRIPED)          # smallest legal quota: one CU per XCD
+    cus4 = {tuple(r) for r in placement(mb, s_c, 512)}
+    assert len(cus4) <= 8 and len({c[0] for c in cus4}) == 8
+    for s in (s_st, s_b, s_c):
         s.destroy()
 
 
@@ -75,12 +82,12 @@ def test_stage_modes_agree_and_pool_is_used(mb):
     with pytest.raises(mb.MosaicError) as e:      # nothing reserved yet for this split
         mb.stage_run(mods, xs, ys, [40, 216], [0, 40], mb.STRIPED, mb.COLOCATED, target=tg, dx=dxs, loss=losses)
     assert e.value.status == mb.EQUOTA
-    for q, o, lay in ((256, 0, mb.STRIPED), (64, 0, mb.STRIPED), (192, 64, mb.STRIPED), (64, 0, mb.XCD_ALIGNED), (192, 64, mb.XCD_ALIGNED)):
+    for q, o, lay in ((256, 0, mb.STRIPED), (64, 0, mb.STRIPED), (192, 64, mb.STRIPED), (128, 0, mb.STRIPED), (128, 128, mb.STRIPED)):
         mb.pool_reserve(q, o, lay)
     created = mb.pool_creations()
     snaps = []
     runs = [([256, 256], [0, 0], mb.STRIPED, mb.TIME_SLICED), ([64, 192], [0, 64], mb.STRIPED, mb.COLOCATED),
-            ([64, 192], [0, 64], mb.XCD_ALIGNED, mb.COLOCATED)]
+            ([128, 128], [0, 128], mb.STRIPED, mb.COLOCATED)]
     for quotas, offs, lay, mode in runs:
         for m in mods:
             m.grads.zero_()
