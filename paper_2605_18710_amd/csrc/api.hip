@@ -8,6 +8,17 @@ mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, i
                                           int causal, const void* qkv, const void* O, const float* lse,
                                           const void* dO, void* dqkv, float* delta);
 
+mosaic_status launch_attention_delta(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+                                     const void* O, const void* dO, float* delta);
+bool attention_mfma_supported(int dtype, int d);
+mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+                                        const void* qkv, void* O, float* lse);
+mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+                                        const void* qkv, const float* lse, const void* dO, void* dqkv,
+                                        const float* delta);
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
 static mosaic_status check_attn(int B, int N, int H, int d) {
   if (B <= 0 || N <= 0 || H <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "attention sizes must be positive");
   if (d > 128) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "head size %d > 128", d);
@@ -17,6 +28,8 @@ static mosaic_status check_attn(int B, int N, int H, int d) {
 mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int causal,
                                    const void* qkv, void* O, float* lse) {
   MOSAIC_TRY(check_attn(B, N, H, d));
+  if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(O))
+    return launch_attention_fwd_mfma(s, quota, B, N, H, d, causal, qkv, O, lse);
   return launch_attention_fwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse);
 }
 
@@ -24,6 +37,10 @@ mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, i
                                    const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
                                    float* delta) {
   MOSAIC_TRY(check_attn(B, N, H, d));
+  if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(dO) && aligned16(dqkv)) {
+    MOSAIC_TRY(launch_attention_delta(s, quota, dtype, B, N, H, d, O, dO, delta));
+    return launch_attention_bwd_mfma(s, quota, B, N, H, d, causal, qkv, lse, dO, dqkv, delta);
+  }
   return launch_attention_bwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta);
 }
 

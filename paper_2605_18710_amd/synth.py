@@ -29,10 +29,10 @@ def _splitmix64(x: np.ndarray) -> np.ndarray:
         return z ^ (z >> np.uint64(31))
 
 
-def _bits(seed: int, n: int, stream: int = 0) -> np.ndarray:
+def _bits(seed: int, n: int, stream: int = 0, start: int = 0) -> np.ndarray:
     with np.errstate(over="ignore"):
         base = _splitmix64(np.array([seed], dtype=np.uint64) * np.uint64(2) + np.uint64(stream))[0]
-        ctr = np.arange(n, dtype=np.uint64) + base
+        ctr = np.arange(start, start + n, dtype=np.uint64) + base
     return _splitmix64(ctr)
 
 
@@ -50,6 +50,14 @@ def normal(seed: int, shape, mean: float = 0.0, std: float = 1.0) -> np.ndarray:
     u2 = (_bits(seed, n, 1) >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
     z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
     return (mean + std * z).reshape(shape)
+
+
+def normal_range(seed: int, start: int, end: int, mean: float = 0.0, std: float = 1.0) -> np.ndarray:
+    """Elements [start, end) of the flat stream that normal(seed, ...) draws from."""
+    n = end - start
+    u1 = ((_bits(seed, n, 0, start) >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / (1 << 53))
+    u2 = (_bits(seed, n, 1, start) >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
+    return mean + std * (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2))
 
 
 def integers(seed: int, shape, lo: int, hi: int) -> np.ndarray:
