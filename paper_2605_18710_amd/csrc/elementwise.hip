@@ -74,103 +74,133 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(
 }
 
 // ----------------------------------------------------------------------- norm backward
-// Work item = a contiguous partition of `rp` rows handled by one wave, rows in ascending
-// order; partial column sums for dgamma / dbeta stay in registers and are written once
-// per partition to scratch[p][2][h]; a second kernel adds the partitions in ascending p.
+// dx: one wave per row, the row of x and dy held in registers (read once), optional
+// residual added on the way out.
 template <typename T, int NORM, int NV>
-__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
+__global__ __launch_bounds__(kThreads) void norm_bwd_dx_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
-    const T* __restrict__ dy, const T* __restrict__ R, T* __restrict__ dx,
-    float* __restrict__ scratch, int64_t rows, int h, int rp, int np) {
+    const T* __restrict__ dy, const T* __restrict__ R, T* __restrict__ dx, int64_t rows, int h) {
   constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float inv_h = 1.0f / (float)h;
-  for (int p = blockIdx.x * kWaves + wave; p < np; p += gridDim.x * kWaves) {
-    float pg[NV][VN], pb[NV][VN];
-    Vec16<T> g[NV];
+  Vec16<T> g[NV];
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int c = (j * 64 + lane) * VN;
-      if (c < h) g[j].load(gamma + c);
-#pragma unroll
-      for (int i = 0; i < VN; ++i) { pg[j][i] = 0.f; pb[j][i] = 0.f; }
-    }
-    const int64_t r0 = (int64_t)p * rp;
-    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
-    for (int64_t row = r0; row < r1; ++row) {
-      const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
-      Vec16<T> xv[NV], dv[NV];
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int c = (j * 64 + lane) * VN;
-        if (c < h) {
-          xv[j].load(x + row * h + c);
-          dv[j].load(dy + row * h + c);
-#pragma unroll
-          for (int i = 0; i < VN; ++i) {
-            const float t = dv[j].get(i) * g[j].get(i);
-            if (NORM == MOSAIC_LAYERNORM) {
-              const float xh = (xv[j].get(i) - mean) * rstd;
-              s1 += t; s2 += t * xh;
-            } else {
-              s2 += t * xv[j].get(i);
-            }
-          }
-        }
-      }
-      if (NORM == MOSAIC_LAYERNORM) s1 = wave_sum(s1) * inv_h;
-      s2 = wave_sum(s2) * inv_h;
-#pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int c = (j * 64 + lane) * VN;
-        if (c < h) {
-          Vec16<T> o, rv;
-          if (R) rv.load(R + row * h + c);
-#pragma unroll
-          for (int i = 0; i < VN; ++i) {
-            const float d = dv[j].get(i), xr = xv[j].get(i);
-            const float t = d * g[j].get(i);
-            float r;
-            if (NORM == MOSAIC_LAYERNORM) {
-              const float xh = (xr - mean) * rstd;
-              r = (t - s1 - xh * s2) * rstd;
-              pg[j][i] += d * xh;
-              pb[j][i] += d;
-            } else {
-              r = rstd * t - rstd * rstd * rstd * xr * s2;
-              pg[j][i] += d * xr * rstd;
-            }
-            if (R) r += rv.get(i);
-            o.set(i, r);
-          }
-          o.store(dx + row * h + c);
-        }
-      }
-    }
+  for (int j = 0; j < NV; ++j) {
+    const int c = (j * 64 + lane) * VN;
+    if (c < h) g[j].load(gamma + c);
+  }
+  for (int64_t row = (int64_t)blockIdx.x * kWaves + wave; row < rows; row += (int64_t)gridDim.x * kWaves) {
+    const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+    Vec16<T> xv[NV], dv[NV];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int c = (j * 64 + lane) * VN;
       if (c < h) {
+        xv[j].load(x + row * h + c);
+        dv[j].load(dy + row * h + c);
 #pragma unroll
         for (int i = 0; i < VN; ++i) {
-          scratch[((int64_t)p * 2 + 0) * h + c + i] = pg[j][i];
-          if (NORM == MOSAIC_LAYERNORM) scratch[((int64_t)p * 2 + 1) * h + c + i] = pb[j][i];
+          const float t = dv[j].get(i) * g[j].get(i);
+          if (NORM == MOSAIC_LAYERNORM) {
+            const float xh = (xv[j].get(i) - mean) * rstd;
+            s1 += t; s2 += t * xh;
+          } else {
+            s2 += t * xv[j].get(i);
+          }
         }
+      }
+    }
+    if (NORM == MOSAIC_LAYERNORM) s1 = wave_sum(s1) * inv_h;
+    s2 = wave_sum(s2) * inv_h;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * VN;
+      if (c < h) {
+        Vec16<T> o, rv;
+        if (R) rv.load(R + row * h + c);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          const float xr = xv[j].get(i);
+          const float t = dv[j].get(i) * g[j].get(i);
+          float r;
+          if (NORM == MOSAIC_LAYERNORM) r = (t - s1 - (xr - mean) * rstd * s2) * rstd;
+          else r = rstd * t - rstd * rstd * rstd * xr * s2;
+          if (R) r += rv.get(i);
+          o.set(i, r);
+        }
+        o.store(dx + row * h + c);
       }
     }
   }
 }
 
+// dgamma / dbeta partial column sums: work item = (row partition p, tile of 256 column
+// vectors); a thread owns VN columns and walks the partition's rows in ascending order.
+// scratch[p][2][h]; the partitions are added in a fixed order by reduce_partials_kernel.
+template <typename T, int NORM>
+__global__ __launch_bounds__(kThreads) void norm_colgrad_partial_kernel(
+    const T* __restrict__ x, const float* __restrict__ stats, const T* __restrict__ dy,
+    float* __restrict__ scratch, int64_t rows, int h, int rp, int np, int ctiles) {
+  constexpr int VN = Vec16<T>::N;
+  const int64_t items = (int64_t)np * ctiles;
+  for (int64_t it = blockIdx.x; it < items; it += gridDim.x) {
+    const int p = (int)(it / ctiles), ct = (int)(it - (int64_t)p * ctiles);
+    const int c = (ct * kThreads + threadIdx.x) * VN;
+    if (c >= h) continue;
+    float ag[VN], ab[VN];
+#pragma unroll
+    for (int i = 0; i < VN; ++i) { ag[i] = 0.f; ab[i] = 0.f; }
+    const int64_t r0 = (int64_t)p * rp;
+    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
+    for (int64_t row = r0; row < r1; ++row) {
+      const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+      Vec16<T> xv, dv;
+      xv.load(x + row * h + c);
+      dv.load(dy + row * h + c);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) {
+        const float d = dv.get(i);
+        if (NORM == MOSAIC_LAYERNORM) { ag[i] += d * ((xv.get(i) - mean) * rstd); ab[i] += d; }
+        else ag[i] += d * xv.get(i) * rstd;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      scratch[((int64_t)p * 2 + 0) * h + c + i] = ag[i];
+      scratch[((int64_t)p * 2 + 1) * h + c + i] = ab[i];
+    }
+  }
+}
+
+// out[col] = sum_p partial[p*ld + col], partitions taken in 8 contiguous slices that are
+// added in slice order: a fixed tree that depends on np only.  Columns [0, split) go to
+// out0, columns [split, ncols) to out1 (skipped when out1 is null).
 template <typename T>
-__global__ __launch_bounds__(kThreads) void norm_bwd_reduce_kernel(
-    const float* __restrict__ scratch, T* __restrict__ dgamma, T* __restrict__ dbeta, int h, int np) {
-  for (int c = blockIdx.x * kThreads + threadIdx.x; c < 2 * h; c += gridDim.x * kThreads) {
-    const int which = c / h, col = c - which * h;
-    if (which == 1 && dbeta == nullptr) continue;
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
+    const float* __restrict__ partial, int np, int64_t ld, int64_t ncols, int64_t split,
+    T* __restrict__ out0, T* __restrict__ out1) {
+  __shared__ float red[8][32];
+  const int cl = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int per = (np + 7) / 8;
+  const int64_t groups = (ncols + 31) / 32;
+  for (int64_t gidx = blockIdx.x; gidx < groups; gidx += gridDim.x) {
+    const int64_t col = gidx * 32 + cl;
     float acc = 0.f;
-    for (int p = 0; p < np; ++p) acc += scratch[((int64_t)p * 2 + which) * h + col];
-    if (which == 0) dgamma[col] = from_f32<T>(acc); else dbeta[col] = from_f32<T>(acc);
+    if (col < ncols && !(col >= split && out1 == nullptr)) {
+      const int p1 = (sl + 1) * per < np ? (sl + 1) * per : np;
+      for (int p = sl * per; p < p1; ++p) acc += partial[(int64_t)p * ld + col];
+    }
+    red[sl][cl] = acc;
+    __syncthreads();
+    if (sl == 0 && col < ncols) {
+      float t = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) t += red[q][cl];
+      if (col < split) out0[col] = from_f32<T>(t);
+      else if (out1) out1[col - split] = from_f32<T>(t);
+    }
+    __syncthreads();
   }
 }
 
@@ -328,16 +358,6 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __res
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void colsum_final_kernel(const float* __restrict__ partial, T* __restrict__ out,
-                                                                int64_t n, int np) {
-  for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < n; c += (int64_t)gridDim.x * kThreads) {
-    float acc = 0.f;
-    for (int p = 0; p < np; ++p) acc += partial[(int64_t)p * n + c];
-    out[c] = from_f32<T>(acc);
-  }
-}
-
 // ------------------------------------------------------------------------------- stems
 // Patch vector index = (c*p + i)*p + j; patches row-major over the image.
 template <typename T>
@@ -476,14 +496,14 @@ mosaic_status launch_norm_fwd(hipStream_t s, int quota, int dtype, int norm, int
   return norm_fwd_t<float>(s, quota, norm, T, h, eps, (const float*)x, (const float*)gamma, (const float*)beta, (float*)y, stats);
 }
 
-static inline void norm_partition(int64_t T, int* rp, int* np) {
-  int64_t r = ceil_div(T, 1024);
-  if (r < 4) r = 4;
+static inline void col_partition(int64_t T, int* rp, int* np) {
+  int64_t r = ceil_div(T, kColsumMaxParts);
+  if (r < 8) r = 8;
   *rp = (int)r;
   *np = (int)ceil_div(T, r);
 }
 
-size_t norm_bwd_scratch_bytes(int64_t h) { return (size_t)1024 * 2 * (size_t)h * sizeof(float); }
+size_t norm_bwd_scratch_bytes(int64_t h) { return (size_t)kColsumMaxParts * 2 * (size_t)h * sizeof(float); }
 
 template <typename T>
 static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows, int64_t h, const T* x,
@@ -494,19 +514,27 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   const int nv = pick_nv((int)ceil_div(h, 64 * VN));
   if (nv < 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld too large", (long long)h);
   if (rows == 0) return MOSAIC_OK;
-  int rp, np;
-  norm_partition(rows, &rp, &np);
-  const int grid = grid_for(quota, 4, ceil_div(np, kWaves));
+  const int grid = grid_for(quota, 8, ceil_div(rows, kWaves));
 #define L(NVC)                                                                                        \
   if (norm == MOSAIC_LAYERNORM)                                                                       \
-    norm_bwd_kernel<T, MOSAIC_LAYERNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np); \
+    norm_bwd_dx_kernel<T, MOSAIC_LAYERNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, rows, (int)h); \
   else                                                                                                \
-    norm_bwd_kernel<T, MOSAIC_RMSNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np)
+    norm_bwd_dx_kernel<T, MOSAIC_RMSNORM, NVC><<<grid, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, rows, (int)h)
   DISPATCH_NV(nv, L);
 #undef L
   MOSAIC_LAUNCH_CHECK();
-  const int g2 = grid_for(quota, 8, ceil_div(2 * h, kThreads));
-  norm_bwd_reduce_kernel<T><<<g2, kThreads, 0, s>>>(scratch, dgamma, norm == MOSAIC_LAYERNORM ? dbeta : nullptr, (int)h, np);
+  int rp, np;
+  col_partition(rows, &rp, &np);
+  const int ctiles = (int)ceil_div(h, (int64_t)kThreads * VN);
+  const int g1 = grid_for(quota, 8, (int64_t)np * ctiles);
+  if (norm == MOSAIC_LAYERNORM)
+    norm_colgrad_partial_kernel<T, MOSAIC_LAYERNORM><<<g1, kThreads, 0, s>>>(x, stats, dy, scratch, rows, (int)h, rp, np, ctiles);
+  else
+    norm_colgrad_partial_kernel<T, MOSAIC_RMSNORM><<<g1, kThreads, 0, s>>>(x, stats, dy, scratch, rows, (int)h, rp, np, ctiles);
+  MOSAIC_LAUNCH_CHECK();
+  const int g2 = grid_for(quota, 8, ceil_div(2 * h, 32));
+  reduce_partials_kernel<T><<<g2, kThreads, 0, s>>>(scratch, np, 2 * h, 2 * h, h, dgamma,
+                                                    norm == MOSAIC_LAYERNORM ? dbeta : (T*)nullptr);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
@@ -597,21 +625,22 @@ mosaic_status launch_colsum(hipStream_t s, int quota, int dtype, int64_t T, int6
                             void* scratch) {
   EW_CHECK_VEC(n, dtype);
   if (n == 0) return MOSAIC_OK;
-  int64_t rp = ceil_div(T, kColsumMaxParts);
-  if (rp < 8) rp = 8;
-  const int np = (int)ceil_div(T, rp);
+  int rp, np;
+  col_partition(T, &rp, &np);
   const int ctiles = (int)ceil_div(n, (int64_t)kThreads * vn__);
   if (np > 0) {
     const int grid = grid_for(quota, 8, (int64_t)np * ctiles);
     if (dtype == MOSAIC_BF16)
-      colsum_partial_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)X, (float*)scratch, T, n, (int)rp, np, ctiles);
+      colsum_partial_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)X, (float*)scratch, T, n, rp, np, ctiles);
     else
-      colsum_partial_kernel<float><<<grid, kThreads, 0, s>>>((const float*)X, (float*)scratch, T, n, (int)rp, np, ctiles);
+      colsum_partial_kernel<float><<<grid, kThreads, 0, s>>>((const float*)X, (float*)scratch, T, n, rp, np, ctiles);
     MOSAIC_LAUNCH_CHECK();
   }
-  const int g2 = grid_for(quota, 8, ceil_div(n, kThreads));
-  if (dtype == MOSAIC_BF16) colsum_final_kernel<bf16><<<g2, kThreads, 0, s>>>((const float*)scratch, (bf16*)out, n, np);
-  else colsum_final_kernel<float><<<g2, kThreads, 0, s>>>((const float*)scratch, (float*)out, n, np);
+  const int g2 = grid_for(quota, 8, ceil_div(n, 32));
+  if (dtype == MOSAIC_BF16)
+    reduce_partials_kernel<bf16><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (bf16*)out, (bf16*)nullptr);
+  else
+    reduce_partials_kernel<float><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (float*)out, (float*)nullptr);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
