@@ -53,12 +53,13 @@ def roofline_gemm(mb, T, k, n, reps):
     Y = torch.empty(T, n, device="cuda", dtype=bf)
     dX = torch.empty(T, k, device="cuda", dtype=bf)
     dW = torch.empty(k, n, device="cuda", dtype=bf)
+    ws = torch.empty(mb.linear_wgrad_scratch_bytes(T, k, n), dtype=torch.uint8, device="cuda")
     q = mb.device_cu_count()
     flops = 2.0 * T * k * n
     out = {}
     out["fprop"] = time_kernel(lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y), reps)
     out["dgrad"] = time_kernel(lambda: mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY, W, None, dX), reps)
-    out["wgrad"] = time_kernel(lambda: mb.op_linear_wgrad(None, q, "bf16", T, k, n, X, dY, dW, None, None), reps)
+    out["wgrad"] = time_kernel(lambda: mb.op_linear_wgrad(None, q, "bf16", T, k, n, X, dY, dW, None, ws), reps)
     return flops, out
 
 

@@ -228,11 +228,15 @@ mosaic_status mosaic_op_linear_dgrad(void* stream, int32_t quota, int32_t dtype,
                                      int64_t T, int64_t k, int64_t n, const void* dY,
                                      const void* W, const void* R, void* dX);
 /* dW[k,n] = X[T,k]^T dY[T,n];  db[n] = column sums of dY (db may be NULL).
- * scratch: device buffer of at least mosaic_op_colsum_scratch_bytes(n) when db != NULL. */
+ * scratch: 16-byte aligned device buffer of at least
+ * mosaic_op_linear_wgrad_scratch_bytes(T,k,n); it holds the fp32 pieces of a long
+ * contraction that is split (by shape alone) when the output has few tiles, and the
+ * partial column sums. */
 mosaic_status mosaic_op_linear_wgrad(void* stream, int32_t quota, int32_t dtype,
                                      int64_t T, int64_t k, int64_t n, const void* X,
                                      const void* dY, void* dW, void* db, void* scratch);
 size_t        mosaic_op_colsum_scratch_bytes(int64_t n);
+size_t        mosaic_op_linear_wgrad_scratch_bytes(int64_t T, int64_t k, int64_t n);
 
 /* qkv [B*N, 3h], row = [q | k | v], head t in columns t*d..; O [B*N, h]; lse [B,H,N] f32. */
 mosaic_status mosaic_op_attention_fwd(void* stream, int32_t quota, int32_t dtype,

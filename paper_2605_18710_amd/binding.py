@@ -100,6 +100,7 @@ SIGNATURES = {
     "mosaic_op_linear_dgrad": (_i32, [_vp, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
     "mosaic_op_linear_wgrad": (_i32, [_vp, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_colsum_scratch_bytes": (_sz, [_i64]),
+    "mosaic_op_linear_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64]),
     "mosaic_op_attention_fwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "mosaic_op_attention_bwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_norm_fwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _f32, _vp, _vp, _vp, _vp, _vp]),
@@ -404,6 +405,10 @@ def norm_bwd_scratch_bytes(h: int) -> int:
 
 def colsum_scratch_bytes(n: int) -> int:
     return int(lib().mosaic_op_colsum_scratch_bytes(n))
+
+
+def linear_wgrad_scratch_bytes(T: int, k: int, n: int) -> int:
+    return int(lib().mosaic_op_linear_wgrad_scratch_bytes(T, k, n))
 
 
 def mse_scratch_bytes() -> int:

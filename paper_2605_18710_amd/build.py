@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libmosaic.so")
 SOURCES = ["elementwise.hip", "gemm.hip", "attention_simple.hip", "attention_mfma.hip", "module.hip", "launcher.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument"] + os.environ.get("MOSAIC_EXTRA_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

@@ -74,15 +74,21 @@ mosaic_status mosaic_op_linear_dgrad(void* stream, int32_t quota, int32_t dtype,
 
 size_t mosaic_op_colsum_scratch_bytes(int64_t n) { return colsum_scratch_bytes(n); }
 
+size_t mosaic_op_linear_wgrad_scratch_bytes(int64_t T, int64_t k, int64_t n) {
+  return align_up(gemm_splitk_scratch_bytes(k, n, T), 256) + colsum_scratch_bytes(n);
+}
+
 mosaic_status mosaic_op_linear_wgrad(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t k, int64_t n,
                                      const void* X, const void* dY, void* dW, void* db, void* scratch) {
   MOSAIC_TRY(check_common(quota, dtype));
   NONNULL(X); NONNULL(dY); NONNULL(dW);
   if (T < 0 || k <= 0 || n <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad linear sizes");
-  if (db && !scratch) MOSAIC_FAIL(MOSAIC_EINVAL, "bias gradient needs scratch");
+  NONNULL(scratch);
+  if ((uintptr_t)scratch % 16) MOSAIC_FAIL(MOSAIC_EINVAL, "scratch must be 16-byte aligned");
   if (T == 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "weight gradient over zero tokens");
-  MOSAIC_TRY(launch_gemm((hipStream_t)stream, quota, dtype, false, false, k, n, T, X, k, dY, n, dW, n, nullptr, nullptr));
-  if (db) MOSAIC_TRY(launch_colsum((hipStream_t)stream, quota, dtype, T, n, dY, db, scratch));
+  MOSAIC_TRY(launch_gemm((hipStream_t)stream, quota, dtype, false, false, k, n, T, X, k, dY, n, dW, n, nullptr, nullptr, scratch));
+  if (db) MOSAIC_TRY(launch_colsum((hipStream_t)stream, quota, dtype, T, n, dY, db,
+                                   (char*)scratch + align_up(gemm_splitk_scratch_bytes(k, n, T), 256)));
   return MOSAIC_OK;
 }
 

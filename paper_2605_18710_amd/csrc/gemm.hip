@@ -1,124 +1,203 @@
 // Linear-layer contractions (forward, input gradient, weight gradient) for gfx950.
 //
-// bf16 path: persistent MFMA kernel.  A workgroup of 4 waves walks output tiles
-// tile = blockIdx.x, blockIdx.x + gridDim.x, ...; the grid is sized to the module's CU
-// quota.  Each output element is produced by exactly one wave that accumulates k in
-// ascending order with v_mfma_f32_32x32x16_bf16, so the bits of the result do not
-// depend on the grid, the tile shape or which CU ran the tile.
+// bf16 path: persistent MFMA kernel.  A workgroup of 8 waves (256x256 tile, 128x64 per
+// wave) or 4 waves (128x128 tile, 64x64 per wave) walks output tiles;
+// the grid is sized to the module's CU quota.  Each output element is produced by exactly
+// one wave that accumulates k in ascending order with v_mfma_f32_32x32x16_bf16, so the
+// bits of the result do not depend on the grid, the tile shape, the tile order or the CU.
 //
-// Operands reach the matrix cores through LDS in "K-contiguous" form [row][BK] (pitch
-// BK+8 elements so that 16-lane groups of ds_read_b128 hit 64 distinct banks).  An
-// operand that is K-contiguous in HBM is copied with 128-bit loads/stores.  An operand
-// whose contraction index is the strided one (the weight in the forward pass, both
-// operands of the weight gradient) is transposed on the way in: a thread loads KB rows
-// of 8 consecutive elements, transposes the KBx8 block in registers with byte permutes
-// and writes 8 K-contiguous pieces.  Global loads for K-tile i+1 are issued before the
-// MFMAs of tile i and land in the second LDS buffer afterwards (one barrier per K-tile).
+// Data movement
+//   * HBM -> registers with 128-bit buffer loads; the buffer descriptor's bounds check
+//     returns zeros for rows past the end, so ragged tiles need no branches.
+//   * registers -> LDS in K-contiguous form, 32 k-values (64 bytes) per row, the four
+//     16-byte chunks of a row XOR-swizzled by (row/4)%4 so that fragment reads
+//     (ds_read_b128, 16 consecutive rows) and tile writes hit distinct banks without padding.
+//     An operand whose contraction index is the strided one in HBM (the weight in the
+//     forward pass, both operands of the weight gradient) is transposed in registers with
+//     byte permutes on the way in.
+//   * three LDS stages and two register sets: while tile t is multiplied, tile t+1 is
+//     already visible in LDS (its first fragments are fetched before the barrier), tile t+2
+//     is being written and tiles t+3 / t+4 are in flight from HBM.  One barrier per K-tile.
+//   * fragments are double-buffered in registers: the reads for the next 16 MFMAs are
+//     issued before the current 16.
+//   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
+//     so a lane owns four consecutive output columns per register group and the epilogue
+//     (bias, residual, bf16 rounding) uses 8-byte buffer loads and stores.
+//   * tiles are handed out so that the workgroups running on one XCD at the same time
+//     form a 4 x 8 patch of the tile grid and share operand panels in that XCD's L2.
 //
 // fp32 path (and shapes the MFMA path does not cover): a plain LDS-tiled FMA kernel with
 // arbitrary strides; ascending-k accumulation as well.
+#include <stdlib.h>
 #include "kernels.h"
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-constexpr int BK = 64;
-constexpr int PITCH = BK + 8;  // bf16 elements per LDS row
+constexpr int BK = 32;            // k-values per LDS tile row (64 bytes)
+constexpr int NSTAGE = 3;
+#ifndef GEMM_DEPTH
+#define GEMM_DEPTH 2
+#endif
+#ifndef GEMM_FDB
+#define GEMM_FDB 1
+#endif
+constexpr int DEPTH = GEMM_DEPTH;        // K-tiles in flight in registers
+constexpr bool FRAG_DB = GEMM_FDB;       // double-buffered fragments
+constexpr unsigned kOob = 0xFFFFFFF0u;   // byte offset beyond any descriptor's range
 
-__device__ __forceinline__ uint32_t perm_lo(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_perm(hi, lo, 0x05040100u); }
-__device__ __forceinline__ uint32_t perm_hi(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
 
-// Register image of one operand tile (ROWS x BK) in flight from HBM to LDS.
-template <int ROWS, bool KC>
+// LDS placement of tile row `row`: rows are permuted inside aligned groups of four by bits
+// 3-4 of the row index, so that the transposing writers (whose lanes hold rows 8 apart)
+// spread over all banks too
+__device__ __forceinline__ int lds_row(int row) { return row ^ ((row >> 3) & 3); }
+// byte offset inside a stage of 16-byte chunk `ch` (0..3) of tile row `row`
+__device__ __forceinline__ int lds_off(int row, int ch) {
+  const int p = lds_row(row);
+  return p * 64 + (((ch ^ (p >> 2)) & 3) << 4);
+}
+
+// One operand tile (ROWS x BK) in flight from HBM to LDS; two of these per operand are
+// alive at a time (tiles t+3 and t+4).
+template <int ROWS, bool KC, int NT>
 struct TileLoader {
-  // K-contiguous: thread owns chunk kc = t%8 (8 elements) of rows t/8 + 32*j.
-  // K-strided:    thread owns a KB x 8 block: k rows kb*KB.., x chunk c*8.., with
-  //               kb = t % (BK/KB), c = t / (BK/KB).
-  static constexpr int KB = ROWS * BK / 8 / 256;              // 8 for 256 rows, 4 for 128
-  static constexpr int NLOAD = KC ? ROWS / 32 : KB;
-  uint4 r[NLOAD];
+  static constexpr int NL = ROWS * 4 / NT;  // 16-byte loads per thread per tile
+  static constexpr int RSTEP = NT / 4;      // KC: rows between a thread's consecutive loads
+  struct Regs { u32x4 r[NL]; };             // one tile in flight
 
-  __device__ __forceinline__ void load(const bf16* __restrict__ src, int64_t ld, int x0, int k0,
-                                       int x_total, int k_total) {
+  // per-thread constants
+  unsigned voff[NL];    // byte offset of load j at K-tile 0
+  unsigned kstep;       // bytes between consecutive K-tiles
+  int kofs;             // KC: first k of this thread's chunk; strided: unused
+  bool xoob;            // strided: the 8-column chunk lies outside the matrix
+  int soff;             // LDS byte offset (KC: of load 0; strided: of column 8c at chunk 0)
+  int kb, c;
+
+  __device__ __forceinline__ void init(int64_t ld, int x0, int X) {
     const int t = threadIdx.x;
     if constexpr (KC) {
-      const int kc = t & 7;
-      const int k = k0 + kc * 8;
+      const int kc = t & 3, row = t >> 2;
+      kofs = kc * 8;
+      kstep = BK * 2;
+      xoob = false;
 #pragma unroll
-      for (int j = 0; j < NLOAD; ++j) {
-        const int x = x0 + (t >> 3) + 32 * j;
-        if (x < x_total && k < k_total)
-          r[j] = *reinterpret_cast<const uint4*>(src + (int64_t)x * ld + k);
-        else
-          r[j] = make_uint4(0, 0, 0, 0);
-      }
+      for (int j = 0; j < NL; ++j) voff[j] = (unsigned)(((int64_t)(x0 + row + RSTEP * j) * ld + kofs) * 2);
+      soff = lds_off(row, kc);
     } else {
-      constexpr int NKB = BK / KB;
-      const int kb = t % NKB, c = t / NKB;
-      const int x = x0 + c * 8;
+      constexpr int NKB = BK / NL;          // thread blocks along k
+      kb = t % NKB; c = t / NKB;
+      const int x = x0 + 8 * c;
+      xoob = x >= X;
+      kstep = (unsigned)(BK * ld * 2);
+      kofs = 0;
 #pragma unroll
-      for (int j = 0; j < NLOAD; ++j) {
-        const int k = k0 + kb * KB + j;
-        if (x < x_total && k < k_total)
-          r[j] = *reinterpret_cast<const uint4*>(src + (int64_t)k * ld + x);
-        else
-          r[j] = make_uint4(0, 0, 0, 0);
-      }
+      for (int j = 0; j < NL; ++j) voff[j] = (unsigned)(((int64_t)(kb * NL + j) * ld + x) * 2);
+      soff = 0;
     }
   }
 
-  __device__ __forceinline__ void store(bf16* __restrict__ lds) const {
-    const int t = threadIdx.x;
-    if constexpr (KC) {
-      const int kc = t & 7;
+  // K-tile kt (absolute index); tiles at or past kt_end read as zeros
+  __device__ __forceinline__ void load(Regs& g, __amdgpu_buffer_rsrc_t rsrc, int kt, int K, int kt_end) const {
+    const unsigned adv = (unsigned)kt * kstep;
+    bool oob = xoob || kt >= kt_end;
+    if constexpr (KC) oob = oob || (kt * BK + kofs) >= K;
 #pragma unroll
-      for (int j = 0; j < NLOAD; ++j) {
-        const int row = (t >> 3) + 32 * j;
-        *reinterpret_cast<uint4*>(lds + row * PITCH + kc * 8) = r[j];
-      }
+    for (int j = 0; j < NL; ++j) {
+      const unsigned off = oob ? kOob : voff[j] + adv;
+      g.r[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+    }
+  }
+
+  __device__ __forceinline__ void store(const Regs& g, unsigned char* __restrict__ stage) const {
+    if constexpr (KC) {
+#pragma unroll
+      for (int j = 0; j < NL; ++j) *reinterpret_cast<u32x4*>(stage + soff + j * RSTEP * 64) = g.r[j];
     } else {
-      constexpr int NKB = BK / KB;
-      const int kb = t % NKB, c = t / NKB;
+      const int kel = kb * NL;                       // first k of this thread's run
+      const int kch = kel >> 3, kin = (kel & 7) * 2; // 16-byte chunk and byte inside it
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        uint32_t o[KB / 2];
+        unsigned o[NL / 2];
 #pragma unroll
-        for (int p = 0; p < KB / 2; ++p) {
-          const uint32_t lo = (&r[2 * p].x)[i >> 1], hi = (&r[2 * p + 1].x)[i >> 1];
-          o[p] = (i & 1) ? perm_hi(hi, lo) : perm_lo(hi, lo);
+        for (int p = 0; p < NL / 2; ++p) {
+          const unsigned lo = g.r[2 * p][i >> 1], hi = g.r[2 * p + 1][i >> 1];
+          o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
-        bf16* dst = lds + (c * 8 + i) * PITCH + kb * KB;
-        if constexpr (KB == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
-        else if constexpr (KB == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
-        else *reinterpret_cast<uint32_t*>(dst) = o[0];
+        unsigned char* dst = stage + lds_off(8 * c + i, kch) + kin;
+        if constexpr (NL == 4) { u32x2 v = {o[0], o[1]}; *reinterpret_cast<u32x2*>(dst) = v; }
+        else *reinterpret_cast<unsigned*>(dst) = o[0];
       }
     }
   }
 };
 
-template <int BM, int BN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(
+// SPLITK: the K range is cut into `ksplit` contiguous pieces of `ktiles_per` K-tiles; piece s
+// of a tile is accumulated by its own workgroup and stored in fp32 to P[s][M][N]; a second
+// kernel adds the pieces in ascending s.  ksplit depends on the problem shape only.
+template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK>
+__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
     const bf16* __restrict__ bias, const bf16* __restrict__ R, int M, int N, int K,
-    int64_t lda, int64_t ldb, int64_t ldc, int tiles_m, int tiles_n) {
-  constexpr int WM = BM / 2, WN = BN / 2;   // 2 x 2 waves
+    int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
+    int tiles_m, int tiles_n, int ksplit, int ktiles_per, float* __restrict__ P) {
+  constexpr int NT = 64 * NWM * NWN;
+  constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int STAGE = (BM + BN) * PITCH;  // elements per LDS stage
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  constexpr int STAGE = (BM + BN) * 64;     // bytes per LDS stage
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, a_bytes), rb = make_rsrc(B, b_bytes);
+  const __amdgpu_buffer_rsrc_t rc = make_rsrc(C, c_bytes);
+  const __amdgpu_buffer_rsrc_t rr = make_rsrc(R, R ? c_bytes : 0u);
+  const __amdgpu_buffer_rsrc_t rbias = make_rsrc(bias, bias ? (uint32_t)N * 2u : 0u);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
-  const int lr = lane & 31, lk = (lane >> 5) * 8;
-  const int nk = (K + BK - 1) / BK;
-  const int ntiles = tiles_m * tiles_n;
+  const int wm = (wave / NWN) * WM, wn = (wave % NWN) * WN;
+  const int lr = lane & 31, hb = lane >> 5;
+  const int sw = (lr >> 2) & 3;
+  // fragment addresses inside a stage: row offset plus the swizzled chunk for k-step 0 / 1
+  const int fa_row = (wm + lds_row(lr)) * 64, fb_row = BM * 64 + (wn + lds_row(lr)) * 64;
+  const int ch0 = ((hb ^ sw) & 3) << 4, ch1 = (((2 + hb) ^ sw) & 3) << 4;
+  const int nk_all = (K + BK - 1) / BK;
 
-  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    // consecutive tiles share the same column block: a wave of workgroups reads few
-    // distinct B panels
-    const int tn_i = tile / tiles_m, tm_i = tile - tn_i * tiles_m;
+  // Work order.  Tiles are listed panel-major: panels of 8 tile columns, row-major inside a
+  // panel, so 32 consecutive entries form a 4 x 8 patch that shares operand panels.  Each
+  // round hands gridDim entries out; workgroup b runs on XCD b%8 (workgroups are dealt
+  // round-robin over XCDs), so XCD x takes the x-th contiguous eighth of the round and its
+  // workgroups reuse each other's panels in that XCD's L2.  Split pieces are split-major.
+  const int ntiles = tiles_m * tiles_n;
+  const int nitems = ntiles * ksplit;
+  const int G = gridDim.x;
+  const bool by_xcd = (G & 7) == 0;
+
+  for (int base = 0; base < nitems; base += G) {
+    const int cnt = min(G, nitems - base);
+    int local;
+    if (by_xcd) {
+      const int per = (cnt + 7) >> 3;
+      local = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+      if (((int)blockIdx.x >> 3) >= per || local >= cnt) continue;
+    } else {
+      local = blockIdx.x;
+      if (local >= cnt) continue;
+    }
+    const int item = base + local;
+    const int split = item / ntiles, tile = item - split * ntiles;
+    const int kt0 = split * ktiles_per;
+    const int kt_end = SPLITK ? min(nk_all, kt0 + ktiles_per) : nk_all;
+    const int nk = kt_end - kt0;
+    const int panel = tile / (tiles_m * 8);
+    const int pw = min(8, tiles_n - panel * 8);
+    const int in_panel = tile - panel * tiles_m * 8;
+    const int tm_i = in_panel / pw, tn_i = panel * 8 + in_panel % pw;
     const int m0 = tm_i * BM, n0 = tn_i * BN;
 
     f32x16 acc[TM][TN];
@@ -129,63 +208,121 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    TileLoader<BM, A_KC> la;
-    TileLoader<BN, B_KC> lb;
-    la.load(A, lda, m0, 0, M, K);
-    lb.load(B, ldb, n0, 0, N, K);
-    la.store(smem);
-    lb.store(smem + BM * PITCH);
+    typedef TileLoader<BM, A_KC, NT> LA;
+    typedef TileLoader<BN, B_KC, NT> LB;
+    LA la; LB lb;
+    la.init(lda, m0, M); lb.init(ldb, n0, N);
+    typename LA::Regs sa[DEPTH];
+    typename LB::Regs sb[DEPTH];
+
+    // prologue: tiles 0 and 1 into LDS, tiles 2 .. DEPTH+1 into registers
+    la.load(sa[0], ra, kt0, K, kt_end); lb.load(sb[0], rb, kt0, K, kt_end);
+    la.load(sa[1], ra, kt0 + 1, K, kt_end); lb.load(sb[1], rb, kt0 + 1, K, kt_end);
+    __syncthreads();                                   // the previous tile's readers are done
+    la.store(sa[0], smem); lb.store(sb[0], smem + BM * 64);
+    la.store(sa[1], smem + STAGE); lb.store(sb[1], smem + STAGE + BM * 64);
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) { la.load(sa[u], ra, kt0 + 2 + u, K, kt_end); lb.load(sb[u], rb, kt0 + 2 + u, K, kt_end); }
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-      const bf16* sa = smem + (kt & 1) * STAGE;
-      const bf16* sb = sa + BM * PITCH;
-      if (kt + 1 < nk) {
-        la.load(A, lda, m0, (kt + 1) * BK, M, K);
-        lb.load(B, ldb, n0, (kt + 1) * BK, N, K);
-      }
+    int rd = 0, nx = STAGE, wr = 2 * STAGE;            // stage byte offsets: read / next / write
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    auto frags = [&](bf16x8* fa, bf16x8* fb, int stage, int ch) {
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 fa[TM], fb[TN];
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(smem + stage + fa_row + i * 32 * 64 + ch);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          fa[i] = *reinterpret_cast<const bf16x8*>(sa + (wm + i * 32 + lr) * PITCH + ks * 16 + lk);
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(smem + stage + fb_row + j * 32 * 64 + ch);
+    };
+    auto mfmas = [&](const bf16x8* fa, const bf16x8* fb) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          fb[j] = *reinterpret_cast<const bf16x8*>(sb + (wn + j * 32 + lr) * PITCH + ks * 16 + lk);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-      }
-      if (kt + 1 < nk) {
-        bf16* da = smem + ((kt + 1) & 1) * STAGE;
-        la.store(da);
-        lb.store(da + BM * PITCH);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    };
+    if (FRAG_DB) frags(fa0, fb0, rd, ch0);
+
+    auto step = [&](int kt, typename LA::Regs& ga, typename LB::Regs& gb) {
+      // tile kt+2 (in registers since DEPTH iterations) -> LDS; tile kt+2+DEPTH -> registers
+      la.store(ga, smem + wr); lb.store(gb, smem + wr + BM * 64);
+      la.load(ga, ra, kt0 + kt + 2 + DEPTH, K, kt_end); lb.load(gb, rb, kt0 + kt + 2 + DEPTH, K, kt_end);
+      if (FRAG_DB) {
+        frags(fa1, fb1, rd, ch1);          // k-step 1 of this tile
+        mfmas(fa0, fb0);
+        frags(fa0, fb0, nx, ch0);          // k-step 0 of tile kt+1 (visible since the last barrier)
+        mfmas(fa1, fb1);
+      } else {
+        frags(fa0, fb0, rd, ch0);
+        mfmas(fa0, fb0);
+        frags(fa0, fb0, rd, ch1);
+        mfmas(fa0, fb0);
       }
       __syncthreads();
+      const int t = rd; rd = nx; nx = wr; wr = t;
+    };
+
+    for (int kt = 0; kt < nk; kt += DEPTH) {
+#pragma unroll
+      for (int u = 0; u < DEPTH; ++u)
+        if (kt + u < nk) step(kt + u, sa[u], sb[u]);
     }
 
-    // epilogue: element (row, col) of a 32x32 block sits in lane col + 32*((row/4)%2),
-    // register 4*(row/8) + row%4
+    // epilogue: acc[i][j][4g+e] is output (row m0+wm+32i+lr, column n0+wn+32j+8g+4hb+e)
+    if constexpr (SPLITK) {
+      float* Ps = P + (int64_t)split * M * N;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn + j * 32 + lr;
-        if (col >= N) continue;
-        const float bv = bias ? (float)bias[col] : 0.f;
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn + 32 * j + 8 * g + 4 * hb;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-          if (row < M) {
-            float v = acc[i][j][e] + bv;
-            if (R) v += (float)R[(int64_t)row * ldc + col];
-            C[(int64_t)row * ldc + col] = (bf16)v;
+          for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm + 32 * i + lr;
+            if (row < M && col < N) {
+              float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+              *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
+            }
           }
         }
+      continue;
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn + 32 * j + 8 * g + 4 * hb;
+        const bool cok = col < N;
+        const u32x2 braw = __builtin_amdgcn_raw_buffer_load_b64(rbias, cok ? col * 2 : (int)kOob, 0, 0);
+        const bf16x4 bv = __builtin_bit_cast(bf16x4, braw);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int row = m0 + wm + 32 * i + lr;
+          const unsigned off = cok ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
+          const u32x2 rraw = __builtin_amdgcn_raw_buffer_load_b64(rr, (int)off, 0, 0);
+          const bf16x4 rv = __builtin_bit_cast(bf16x4, rraw);
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[i][j][4 * g + e] + (float)bv[e] + (float)rv[e]);
+          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rc, (int)off, 0, 0);
+        }
       }
+  }
+}
+
+// out[row][col] = bf16( P[0] + P[1] + ... ) in ascending piece order
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, bf16* __restrict__ C,
+                                                            int64_t M, int64_t N, int64_t ldc, int ksplit) {
+  const int64_t nvec = M * N / 4;
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * 256) {
+    float4 a = reinterpret_cast<const float4*>(P)[v];
+    for (int s = 1; s < ksplit; ++s) {
+      const float4 b = reinterpret_cast<const float4*>(P + (int64_t)s * M * N)[v];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    const int64_t e = v * 4, row = e / N, col = e - row * N;
+    bf16x4 o;
+    o[0] = (bf16)a.x; o[1] = (bf16)a.y; o[2] = (bf16)a.z; o[3] = (bf16)a.w;
+    *reinterpret_cast<bf16x4*>(C + row * ldc + col) = o;
   }
 }
 
@@ -254,11 +391,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
   }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC>
+
+template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK = false>
 mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda,
-                          const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R) {
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * PITCH * sizeof(bf16);
-  auto kern = gemm_bf16_kernel<BM, BN, A_KC, B_KC>;
+                          const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
+                          uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, int ksplit = 1,
+                          int ktiles_per = 0, float* P = nullptr) {
+  constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64;
+  auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK>;
   static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
   if (!attr_set) {
     MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -266,42 +406,93 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
     attr_set = true;
   }
   const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
-  const int wg_per_cu = (smem > 80 * 1024) ? 1 : 2;
-  const int grid = grid_for(quota, wg_per_cu, (int64_t)tiles_m * tiles_n);
-  kern<<<grid, 256, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, tiles_m, tiles_n);
+  const int wg_per_cu = (BM == 256) ? 1 : 2;
+  const int grid = grid_for(quota, wg_per_cu, (int64_t)tiles_m * tiles_n * ksplit);
+  kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
+                                          tiles_m, tiles_n, ksplit, ktiles_per, P);
   MOSAIC_LAUNCH_CHECK();
+  if (SPLITK) {
+    const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
+    splitk_reduce_kernel<<<g2, 256, 0, s>>>(P, C, M, N, ldc, ksplit);
+    MOSAIC_LAUNCH_CHECK();
+  }
   return MOSAIC_OK;
+}
+
+int forced_tile() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("MOSAIC_GEMM_TILE"); v = e ? atoi(e) : 0; }
+  return v;
+}
+
+// Split count for the weight-gradient form: when the output has too few 256x256 tiles to
+// occupy the device and the contraction is long, cut K so that there are about as many
+// work items as CUs.  A function of the shape alone (256 = CUs of the device the kernels
+// are written for), never of the quota, so the bits stay quota-independent.
+int splitk_factor(int64_t M, int64_t N, int64_t K) {
+  const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
+  if (t256 > 128 || K < 2048 || (N % 4)) return 1;
+  int64_t s = 256 / t256;
+  if (s > 8) s = 8;
+  while (s > 1 && ceil_div(K, s) < 512) --s;
+  return (int)s;
 }
 
 template <bool A_KC, bool B_KC>
 mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda,
-                                const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R) {
-  // Tile shape is a function of the problem shape only.  Large tiles halve LDS traffic
-  // per MFMA; small problems keep 128x128 so that more CUs get a tile.
-  const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
-  if (big_tiles >= 512)
-    return launch_mfma<256, 256, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R);
-  return launch_mfma<128, 128, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R);
+                                const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
+                                uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, void* splitk_scratch) {
+  if constexpr (!A_KC && !B_KC) {
+    const int sk = splitk_factor(M, N, K);
+    if (sk > 1 && splitk_scratch && !bias && !R) {
+      const int per = (int)ceil_div(ceil_div(K, BK), sk);
+      return launch_mfma<256, 256, 2, 4, A_KC, B_KC, true>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
+                                                           b_bytes, c_bytes, sk, per, (float*)splitk_scratch);
+    }
+  }
+  // Tile shape only decides which workgroup computes an element, never its bits.  Large
+  // tiles halve LDS traffic per MFMA; small problems take 128x128 so that more CUs get work.
+  const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256), t128 = ceil_div(M, 128) * ceil_div(N, 128);
+  const double cost256 = (double)ceil_div(t256, quota) * 4.0;
+  const double cost128 = (double)ceil_div(t128, 2 * (int64_t)quota) * 2.0 * 1.35;
+  bool big = cost256 <= cost128;
+  if (forced_tile() == 128) big = false;
+  if (forced_tile() == 256) big = true;
+  if (big) return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
 }
 
 }  // namespace
 
+size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K) {
+  const int sk = splitk_factor(M, N, K);
+  return sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
 mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc, int64_t M, int64_t N,
                           int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
-                          int64_t ldc, const void* bias, const void* R) {
+                          int64_t ldc, const void* bias, const void* R, void* splitk_scratch) {
   if (M < 0 || N < 0 || K < 0) MOSAIC_FAIL(MOSAIC_EINVAL, "negative GEMM size");
   if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "GEMM dimension too large");
   if (M == 0 || N == 0) return MOSAIC_OK;
   const bool vec_ok = (lda % 8 == 0) && (ldb % 8 == 0) && (K % 8 == 0 || (!a_kc && !b_kc)) &&
                       (a_kc || M % 8 == 0) && (b_kc || N % 8 == 0) &&
-                      ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && K > 0;
-  if (dtype == MOSAIC_BF16 && vec_ok) {
+                      ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 8 == 0) &&
+                      (ldc % 4 == 0) && (N % 4 == 0) && K > 0 &&
+                      (R == nullptr || (uintptr_t)R % 8 == 0) && (bias == nullptr || (uintptr_t)bias % 8 == 0);
+  // extents in bytes as seen by the buffer descriptors (dense rows: ld >= logical width)
+  const int64_t a_ext = a_kc ? ((M - 1) * lda + K) * 2 : ((K - 1) * lda + M) * 2;
+  const int64_t b_ext = b_kc ? ((N - 1) * ldb + K) * 2 : ((K - 1) * ldb + N) * 2;
+  const int64_t c_ext = ((M - 1) * ldc + N) * 2;
+  const int64_t lim = (int64_t)1 << 31;
+  if (dtype == MOSAIC_BF16 && vec_ok && a_ext < lim && b_ext < lim && c_ext < lim) {
+    const uint32_t ab = (uint32_t)a_ext, bb = (uint32_t)b_ext, cb = (uint32_t)c_ext;
     const bf16 *a = (const bf16*)A, *b = (const bf16*)B, *bi = (const bf16*)bias, *r = (const bf16*)R;
     bf16* c = (bf16*)C;
-    if (a_kc && !b_kc) return launch_mfma_shape<true, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r);
-    if (a_kc && b_kc) return launch_mfma_shape<true, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r);
-    if (!a_kc && !b_kc) return launch_mfma_shape<false, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r);
-    return launch_mfma_shape<false, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r);
+    if (a_kc && !b_kc) return launch_mfma_shape<true, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
+    if (a_kc && b_kc) return launch_mfma_shape<true, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
+    if (!a_kc && !b_kc) return launch_mfma_shape<false, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
+    return launch_mfma_shape<false, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
   }
   const int64_t sam = a_kc ? lda : 1, sak = a_kc ? 1 : lda;
   const int64_t sbk = b_kc ? 1 : ldb, sbn = b_kc ? ldb : 1;

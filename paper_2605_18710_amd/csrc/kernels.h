@@ -13,7 +13,10 @@
 mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc,
                           int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                           const void* B, int64_t ldb, void* C, int64_t ldc,
-                          const void* bias, const void* R);
+                          const void* bias, const void* R, void* splitk_scratch = nullptr);
+// Bytes of fp32 scratch the weight-gradient form wants for a deterministic split of a long
+// contraction over few output tiles (0 when no split is used for this shape).
+size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K);
 
 // ------------------------------------------------------------------------- attention
 mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H,

@@ -6,6 +6,7 @@
 #include <string>
 #include <vector>
 #include <new>
+#include <algorithm>
 #include "kernels.h"
 
 struct mosaic_stream;
@@ -40,7 +41,7 @@ struct mosaic_module {
   int64_t param_elems = 0;
   size_t ws_bytes = 0;
   // scratch byte offsets
-  size_t s_dA, s_dZ, s_dU, s_dX1, s_dO, s_dQKV, s_delta, s_g0, s_g1, s_norm, s_colsum, s_mse, s_dyloss;
+  size_t s_dA, s_dZ, s_dU, s_dX1, s_dO, s_dQKV, s_delta, s_g0, s_g1, s_norm, s_colsum, s_mse, s_dyloss, s_splitk;
   size_t s_patches;
   // bound buffers
   char* params = nullptr;
@@ -169,6 +170,11 @@ void build_layout(mosaic_module* m) {
     m->s_norm = take(&cur, norm_bwd_scratch_bytes(h));
     const int64_t widest = (3 * h > zf) ? 3 * h : zf;
     m->s_colsum = take(&cur, colsum_scratch_bytes(widest));
+    size_t sk = gemm_splitk_scratch_bytes(h, 3 * h, T);
+    sk = std::max(sk, gemm_splitk_scratch_bytes(h, h, T));
+    sk = std::max(sk, gemm_splitk_scratch_bytes(h, zf, T));
+    sk = std::max(sk, gemm_splitk_scratch_bytes(f, h, T));
+    m->s_splitk = take(&cur, sk);
   } else if (d.kind == MOSAIC_PROJECTOR) {
     LayerParams q;
     q.w_1 = add_tensor(m, "w_1", d.in_dim, d.out_dim);
@@ -183,6 +189,8 @@ void build_layout(mosaic_module* m) {
     m->s_dA = take(&cur, T * d.out_dim * es);
     m->s_dZ = take(&cur, T * d.out_dim * es);
     m->s_colsum = take(&cur, colsum_scratch_bytes(d.out_dim));
+    m->s_splitk = take(&cur, std::max(gemm_splitk_scratch_bytes(d.out_dim, d.out_dim, T),
+                                      gemm_splitk_scratch_bytes(d.in_dim, d.out_dim, T)));
   } else if (d.kind == MOSAIC_PATCH_STEM) {
     LayerParams q;
     q.w_1 = add_tensor(m, "w_stem", d.in_dim, h);
@@ -191,6 +199,7 @@ void build_layout(mosaic_module* m) {
     m->lp.push_back(q);
     m->s_patches = take(&cur, T * d.in_dim * es);
     m->s_colsum = take(&cur, colsum_scratch_bytes(h));
+    m->s_splitk = take(&cur, gemm_splitk_scratch_bytes(d.in_dim, h, T));
   } else {  // TEXT_STEM
     LayerParams q;
     q.w_1 = add_tensor(m, "table", d.vocab, h);
@@ -254,26 +263,26 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     void* gout = (l == 0) ? (dx ? dx : W(m, m->s_g0)) : W(m, (l & 1) ? m->s_g1 : m->s_g0);
     // MLP down projection
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, f, h, gin, h, P(m, p.w_2), h, dA, f, nullptr, nullptr));
-    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, f, h, T, W(m, sv.a), f, gin, h, G(m, p.w_2), h, nullptr, nullptr));
+    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, f, h, T, W(m, sv.a), f, gin, h, G(m, p.w_2), h, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_2 >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, gin, G(m, p.b_2), csc));
     // activation
     if (glu) MOSAIC_TRY(launch_swiglu_bwd(s, q, dt, T, f, W(m, sv.z), dA, dZ));
     else MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * f, W(m, sv.z), dA, dZ));
     // MLP up projection
-    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, zf, T, W(m, sv.u2), h, dZ, zf, G(m, p.w_1), zf, nullptr, nullptr));
+    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, zf, T, W(m, sv.u2), h, dZ, zf, G(m, p.w_1), zf, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_1 >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, zf, dZ, G(m, p.b_1), csc));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, zf, dZ, zf, P(m, p.w_1), zf, dU, h, nullptr, nullptr));
     // second norm; residual branch adds the incoming gradient
     MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, W(m, sv.x1), P(m, p.n2_g), (const float*)W(m, sv.st2), dU, gin, dX1, G(m, p.n2_g), G(m, p.n2_b), nsc));
     // attention output projection
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, h, dX1, h, P(m, p.w_o), h, dO, h, nullptr, nullptr));
-    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, h, T, W(m, sv.o), h, dX1, h, G(m, p.w_o), h, nullptr, nullptr));
+    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, h, T, W(m, sv.o), h, dX1, h, G(m, p.w_o), h, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_o >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, dX1, G(m, p.b_o), csc));
     // attention
     MOSAIC_TRY(launch_attention_bwd(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o),
                                     (const float*)W(m, sv.lse), dO, dQKV, (float*)W(m, m->s_delta)));
     // QKV projection
-    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, 3 * h, T, W(m, sv.u1), h, dQKV, 3 * h, G(m, p.w_qkv), 3 * h, nullptr, nullptr));
+    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, 3 * h, T, W(m, sv.u1), h, dQKV, 3 * h, G(m, p.w_qkv), 3 * h, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_qkv >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, 3 * h, dQKV, G(m, p.b_qkv), csc));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, 3 * h, dQKV, 3 * h, P(m, p.w_qkv), 3 * h, dU, h, nullptr, nullptr));
     // first norm
@@ -303,10 +312,10 @@ mosaic_status projector_backward(mosaic_module* m, hipStream_t s, int q, const v
   const int dt = d.dtype;
   void* dA = W(m, m->s_dA); void* dZ = W(m, m->s_dZ); void* csc = W(m, m->s_colsum);
   MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, no, no, dy, no, P(m, p.w_2), no, dA, no, nullptr, nullptr));
-  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, no, no, T, W(m, sv.a), no, dy, no, G(m, p.w_2), no, nullptr, nullptr));
+  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, no, no, T, W(m, sv.a), no, dy, no, G(m, p.w_2), no, nullptr, nullptr, W(m, m->s_splitk)));
   MOSAIC_TRY(launch_colsum(s, q, dt, T, no, dy, G(m, p.b_2), csc));
   MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * no, W(m, sv.z), dA, dZ));
-  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, ni, no, T, m->last_x, ni, dZ, no, G(m, p.w_1), no, nullptr, nullptr));
+  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, ni, no, T, m->last_x, ni, dZ, no, G(m, p.w_1), no, nullptr, nullptr, W(m, m->s_splitk)));
   MOSAIC_TRY(launch_colsum(s, q, dt, T, no, dZ, G(m, p.b_1), csc));
   if (dx) MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, ni, no, dZ, no, P(m, p.w_1), no, dx, ni, nullptr, nullptr));
   return MOSAIC_OK;
@@ -332,7 +341,7 @@ mosaic_status patch_stem_backward(mosaic_module* m, hipStream_t s, int q, const 
   const LayerParams& p = m->lp[0];
   if (dx) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "the patch stem has no input gradient");
   const void* tokens = d.patch > 0 ? W(m, m->s_patches) : m->last_x;
-  MOSAIC_TRY(launch_gemm(s, q, d.dtype, false, false, d.in_dim, d.hidden, m->T, tokens, d.in_dim, dy, d.hidden, G(m, p.w_1), d.hidden, nullptr, nullptr));
+  MOSAIC_TRY(launch_gemm(s, q, d.dtype, false, false, d.in_dim, d.hidden, m->T, tokens, d.in_dim, dy, d.hidden, G(m, p.w_1), d.hidden, nullptr, nullptr, W(m, m->s_splitk)));
   MOSAIC_TRY(launch_colsum(s, q, d.dtype, m->T, d.hidden, dy, G(m, p.b_1), W(m, m->s_colsum)));
   MOSAIC_TRY(launch_pos_grad(s, q, d.dtype, d.batch, d.seq, d.hidden, dy, G(m, p.w_2)));
   return MOSAIC_OK;

@@ -37,6 +37,7 @@ LINEAR_SHAPES = [
     ("bf16", 1568, 768, 2304),        # ViT QKV projection of the CLIP-B-scale workload
     ("bf16", 4096, 512, 8192),        # enough tiles for the 256x256 configuration
     ("bf16", 40, 24, 16), ("bf16", 129, 600, 136),
+    ("bf16", 4104, 520, 264),         # long contraction over few output tiles: split weight gradient
 ]
 
 
@@ -52,7 +53,7 @@ def test_linear_fwd_dgrad_wgrad(mb, dtype, T, k, n):
     outs = []
     for q in QUOTAS:
         Y = empty((T, n), dtype); dX = empty((T, k), dtype); dW = empty((k, n), dtype); db = empty((n,), dtype)
-        scratch = torch.empty(mb.colsum_scratch_bytes(n), dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(mb.linear_wgrad_scratch_bytes(T, k, n), dtype=torch.uint8, device="cuda")
         mb.op_linear_fwd(None, q, dtype, T, k, n, dX_, W_, b_, R_, Y)
         mb.op_linear_dgrad(None, q, dtype, T, k, n, dY_, W_, Rk_, dX)
         mb.op_linear_wgrad(None, q, dtype, T, k, n, dX_, dY_, dW, db, scratch)
