@@ -18,6 +18,8 @@
 //   * three LDS stages and two register sets: while tile t is multiplied, tile t+1 is
 //     already visible in LDS (its first fragments are fetched before the barrier), tile t+2
 //     is being written and tiles t+3 / t+4 are in flight from HBM.  One barrier per K-tile.
+//     The stream of K-tiles runs across output tiles, so a new output tile starts without
+//     a pipeline refill.
 //   * fragments are double-buffered in registers: the reads for the next 16 MFMAs are
 //     issued before the current 16.
 //   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
@@ -65,53 +67,59 @@ __device__ __forceinline__ int lds_off(int row, int ch) {
   return p * 64 + (((ch ^ (p >> 2)) & 3) << 4);
 }
 
-// One operand tile (ROWS x BK) in flight from HBM to LDS; two of these per operand are
-// alive at a time (tiles t+3 and t+4).
+// Loads one operand tile (ROWS x BK) from HBM into registers and stores it to an LDS stage.
+// Thread constants are tile independent; a tile contributes its origin offset only.
 template <int ROWS, bool KC, int NT>
 struct TileLoader {
   static constexpr int NL = ROWS * 4 / NT;  // 16-byte loads per thread per tile
   static constexpr int RSTEP = NT / 4;      // KC: rows between a thread's consecutive loads
   struct Regs { u32x4 r[NL]; };             // one tile in flight
+  struct Tile { unsigned org; bool xoob; }; // byte offset of the tile origin; strided: chunk outside
 
-  // per-thread constants
-  unsigned voff[NL];    // byte offset of load j at K-tile 0
+  unsigned rel;         // byte offset of load 0 relative to the tile origin at K-tile 0
+  unsigned jstep;       // bytes between a thread's consecutive loads
   unsigned kstep;       // bytes between consecutive K-tiles
-  int kofs;             // KC: first k of this thread's chunk; strided: unused
-  bool xoob;            // strided: the 8-column chunk lies outside the matrix
-  int soff;             // LDS byte offset (KC: of load 0; strided: of column 8c at chunk 0)
-  int kb, c;
+  int kofs;             // KC: first k of this thread's chunk
+  int soff;             // KC: LDS byte offset of load 0
+  int kb, c;            // strided: k-run and 8-column chunk owned by this thread
 
-  __device__ __forceinline__ void init(int64_t ld, int x0, int X) {
+  __device__ __forceinline__ void init(int64_t ld) {
     const int t = threadIdx.x;
     if constexpr (KC) {
       const int kc = t & 3, row = t >> 2;
       kofs = kc * 8;
       kstep = BK * 2;
-      xoob = false;
-#pragma unroll
-      for (int j = 0; j < NL; ++j) voff[j] = (unsigned)(((int64_t)(x0 + row + RSTEP * j) * ld + kofs) * 2);
+      rel = (unsigned)(((int64_t)row * ld + kofs) * 2);
+      jstep = (unsigned)(RSTEP * ld * 2);
       soff = lds_off(row, kc);
+      kb = 0; c = 0;
     } else {
-      constexpr int NKB = BK / NL;          // thread blocks along k
+      constexpr int NKB = BK / NL;          // threads along k
       kb = t % NKB; c = t / NKB;
-      const int x = x0 + 8 * c;
-      xoob = x >= X;
+      kofs = 0; soff = 0;
       kstep = (unsigned)(BK * ld * 2);
-      kofs = 0;
-#pragma unroll
-      for (int j = 0; j < NL; ++j) voff[j] = (unsigned)(((int64_t)(kb * NL + j) * ld + x) * 2);
-      soff = 0;
+      rel = (unsigned)(((int64_t)(kb * NL) * ld + 8 * c) * 2);
+      jstep = (unsigned)(ld * 2);
     }
   }
 
-  // K-tile kt (absolute index); tiles at or past kt_end read as zeros
-  __device__ __forceinline__ void load(Regs& g, __amdgpu_buffer_rsrc_t rsrc, int kt, int K, int kt_end) const {
-    const unsigned adv = (unsigned)kt * kstep;
-    bool oob = xoob || kt >= kt_end;
+  __device__ __forceinline__ Tile tile(int64_t ld, int x0, int X) const {
+    Tile tl;
+    if constexpr (KC) { tl.org = (unsigned)((int64_t)x0 * ld * 2); tl.xoob = false; }
+    else { tl.org = (unsigned)(x0 * 2); tl.xoob = (x0 + 8 * c) >= X; }
+    return tl;
+  }
+
+  // K-tile kt (absolute index) of tile tl; reads as zeros when !valid, at or past kt_end,
+  // or outside the matrix (rows past the end fall outside the descriptor's range)
+  __device__ __forceinline__ void load(Regs& g, __amdgpu_buffer_rsrc_t rsrc, const Tile& tl, int kt, int K,
+                                       int kt_end, bool valid) const {
+    bool oob = tl.xoob || !valid || kt >= kt_end;
     if constexpr (KC) oob = oob || (kt * BK + kofs) >= K;
+    const unsigned base = tl.org + rel + (unsigned)kt * kstep;
 #pragma unroll
     for (int j = 0; j < NL; ++j) {
-      const unsigned off = oob ? kOob : voff[j] + adv;
+      const unsigned off = oob ? kOob : base + (unsigned)j * jstep;
       g.r[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
     }
   }
@@ -139,9 +147,20 @@ struct TileLoader {
   }
 };
 
+// One unit of work: an output tile, or (SPLITK) one K-piece of an output tile.
+struct WorkItem {
+  int m0, n0, kt0, kt_end, split;
+  bool valid;
+};
+
 // SPLITK: the K range is cut into `ksplit` contiguous pieces of `ktiles_per` K-tiles; piece s
 // of a tile is accumulated by its own workgroup and stored in fp32 to P[s][M][N]; a second
 // kernel adds the pieces in ascending s.  ksplit depends on the problem shape only.
+//
+// A workgroup streams the K-tiles of ALL its work items through one pipeline: a load
+// cursor runs DEPTH+2 K-tiles ahead of the compute cursor and crosses item boundaries, so
+// the first tiles of the next item are already in LDS while the epilogue of the current one
+// runs (the other wave on the SIMD keeps the matrix cores busy meanwhile).
 template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
@@ -177,135 +196,194 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   const int nitems = ntiles * ksplit;
   const int G = gridDim.x;
   const bool by_xcd = (G & 7) == 0;
-
-  for (int base = 0; base < nitems; base += G) {
+  auto get_item = [&](int round) -> WorkItem {
+    WorkItem it;
+    it.valid = false; it.m0 = 0; it.n0 = 0; it.kt0 = 0; it.kt_end = 0; it.split = 0;
+    const int base = round * G;
+    if (base >= nitems) return it;
     const int cnt = min(G, nitems - base);
     int local;
     if (by_xcd) {
       const int per = (cnt + 7) >> 3;
       local = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
-      if (((int)blockIdx.x >> 3) >= per || local >= cnt) continue;
+      if (((int)blockIdx.x >> 3) >= per || local >= cnt) return it;
     } else {
       local = blockIdx.x;
-      if (local >= cnt) continue;
+      if (local >= cnt) return it;
     }
     const int item = base + local;
-    const int split = item / ntiles, tile = item - split * ntiles;
-    const int kt0 = split * ktiles_per;
-    const int kt_end = SPLITK ? min(nk_all, kt0 + ktiles_per) : nk_all;
-    const int nk = kt_end - kt0;
+    it.split = item / ntiles;
+    const int tile = item - it.split * ntiles;
+    it.kt0 = it.split * ktiles_per;
+    it.kt_end = SPLITK ? min(nk_all, it.kt0 + ktiles_per) : nk_all;
     const int panel = tile / (tiles_m * 8);
     const int pw = min(8, tiles_n - panel * 8);
     const int in_panel = tile - panel * tiles_m * 8;
-    const int tm_i = in_panel / pw, tn_i = panel * 8 + in_panel % pw;
-    const int m0 = tm_i * BM, n0 = tn_i * BN;
+    it.m0 = (in_panel / pw) * BM;
+    it.n0 = (panel * 8 + in_panel % pw) * BN;
+    it.valid = true;
+    return it;
+  };
 
-    f32x16 acc[TM][TN];
+  WorkItem cur = get_item(0);
+  if (!cur.valid) return;          // only the last round is partial, so nothing follows either
+
+  typedef TileLoader<BM, A_KC, NT> LA;
+  typedef TileLoader<BN, B_KC, NT> LB;
+  LA la; LB lb;
+  la.init(lda); lb.init(ldb);
+  typename LA::Regs sa[DEPTH];
+  typename LB::Regs sb[DEPTH];
+
+  // load cursor: the next K-tile to fetch
+  WorkItem lit = cur;
+  int lround = 0, lkt = cur.kt0;
+  typename LA::Tile lta = la.tile(lda, lit.m0, M);
+  typename LB::Tile ltb = lb.tile(ldb, lit.n0, N);
+  auto fetch = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
+    la.load(ga, ra, lta, lkt, K, lit.kt_end, lit.valid);
+    lb.load(gb, rb, ltb, lkt, K, lit.kt_end, lit.valid);
+    ++lkt;
+    if (lit.valid && lkt >= lit.kt_end) {
+      lit = get_item(++lround);
+      lkt = lit.kt0;
+      lta = la.tile(lda, lit.m0, M);
+      ltb = lb.tile(ldb, lit.n0, N);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // prologue: the first two K-tiles of the stream into LDS, the next DEPTH into registers
+  fetch(sa[0], sb[0]);
+  fetch(sa[1], sb[1]);
+  la.store(sa[0], smem); lb.store(sb[0], smem + BM * 64);
+  la.store(sa[1], smem + STAGE); lb.store(sb[1], smem + STAGE + BM * 64);
+#pragma unroll
+  for (int u = 0; u < DEPTH; ++u) fetch(sa[u], sb[u]);
+  __syncthreads();
+
+  int rd = 0, nx = STAGE, wr = 2 * STAGE;            // stage byte offsets: read / next / write
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  auto frags = [&](bf16x8* fa, bf16x8* fb, int stage, int ch) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(smem + stage + fa_row + i * 32 * 64 + ch);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(smem + stage + fb_row + j * 32 * 64 + ch);
+  };
+  auto mfmas = [&](const bf16x8* fa, const bf16x8* fb) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+  frags(fa0, fb0, rd, ch0);
+
+  // Epilogue of one work item.  acc[i][j][4g+e] is output (row m0+wm+32i+lr, column
+  // n0+wn+32j+8g+4hb+e): a lane holds 4-column pieces of 32 different rows, which would
+  // reach memory as 16-byte fragments.  Each 32x32 block therefore passes through a 4 KB
+  // per-wave patch of the LDS stage that is free between two pipeline steps (fp32, XOR
+  // swizzled) and leaves row-contiguous: 64-byte runs of bf16 (bias and residual added in
+  // fp32, one rounding) or full 128-byte lines of fp32 pieces.
+  auto finish = [&](const WorkItem& it) {
+    float* stg = reinterpret_cast<float*>(smem + wr) + wave * 1024;
+    // bias for the 8 columns this lane writes back (same for every row block)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int cb = it.n0 + wn + 32 * j;                 // first column of the block
+      float bvals[8];
+      if constexpr (!SPLITK) {
+        const int col = cb + 8 * (lane & 3);
+        const u32x4 braw = __builtin_amdgcn_raw_buffer_load_b128(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bvals[e] = (float)bv[e];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rb0 = it.m0 + wm + 32 * i;              // first row of the block
+        // accumulator layout -> LDS: row lr, column group cg = 2g + hb (4 columns each)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int cg = (2 * g + hb) ^ ((lr >> 1) & 7);
+          float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+          *reinterpret_cast<float4*>(stg + lr * 32 + cg * 4) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if constexpr (SPLITK) {
+          float* Ps = P + (int64_t)it.split * M * N;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int r = (lane >> 3) + 8 * q, cgl = lane & 7;
+            const float4 v = *reinterpret_cast<const float4*>(stg + r * 32 + ((cgl ^ ((r >> 1) & 7)) * 4));
+            const int row = rb0 + r, col = cb + 4 * cgl;
+            if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int r = (lane >> 2) + 16 * q, c8 = lane & 3;
+            const int sx = (r >> 1) & 7;
+            const float4 v0 = *reinterpret_cast<const float4*>(stg + r * 32 + (((2 * c8) ^ sx) * 4));
+            const float4 v1 = *reinterpret_cast<const float4*>(stg + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
+            const int row = rb0 + r, col = cb + 8 * c8;
+            const unsigned off = (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
+            const u32x4 rraw = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off, 0, 0);
+            const bf16x8 rv = __builtin_bit_cast(bf16x8, rraw);
+            const float vals[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16)(vals[e] + bvals[e] + (float)rv[e]);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rc, (int)off, 0, 0);
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    __syncthreads();               // the patch lives in the stage the next step overwrites
+  };
 
-    typedef TileLoader<BM, A_KC, NT> LA;
-    typedef TileLoader<BN, B_KC, NT> LB;
-    LA la; LB lb;
-    la.init(lda, m0, M); lb.init(ldb, n0, N);
-    typename LA::Regs sa[DEPTH];
-    typename LB::Regs sb[DEPTH];
 
-    // prologue: tiles 0 and 1 into LDS, tiles 2 .. DEPTH+1 into registers
-    la.load(sa[0], ra, kt0, K, kt_end); lb.load(sb[0], rb, kt0, K, kt_end);
-    la.load(sa[1], ra, kt0 + 1, K, kt_end); lb.load(sb[1], rb, kt0 + 1, K, kt_end);
-    __syncthreads();                                   // the previous tile's readers are done
-    la.store(sa[0], smem); lb.store(sb[0], smem + BM * 64);
-    la.store(sa[1], smem + STAGE); lb.store(sb[1], smem + STAGE + BM * 64);
+  int round = 0, kt = cur.kt0;
+  bool more = true;
+  while (more) {
 #pragma unroll
-    for (int u = 0; u < DEPTH; ++u) { la.load(sa[u], ra, kt0 + 2 + u, K, kt_end); lb.load(sb[u], rb, kt0 + 2 + u, K, kt_end); }
-    __syncthreads();
-
-    int rd = 0, nx = STAGE, wr = 2 * STAGE;            // stage byte offsets: read / next / write
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    auto frags = [&](bf16x8* fa, bf16x8* fb, int stage, int ch) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(smem + stage + fa_row + i * 32 * 64 + ch);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(smem + stage + fb_row + j * 32 * 64 + ch);
-    };
-    auto mfmas = [&](const bf16x8* fa, const bf16x8* fb) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    };
-    if (FRAG_DB) frags(fa0, fb0, rd, ch0);
-
-    auto step = [&](int kt, typename LA::Regs& ga, typename LB::Regs& gb) {
-      // tile kt+2 (in registers since DEPTH iterations) -> LDS; tile kt+2+DEPTH -> registers
-      la.store(ga, smem + wr); lb.store(gb, smem + wr + BM * 64);
-      la.load(ga, ra, kt0 + kt + 2 + DEPTH, K, kt_end); lb.load(gb, rb, kt0 + kt + 2 + DEPTH, K, kt_end);
-      if (FRAG_DB) {
-        frags(fa1, fb1, rd, ch1);          // k-step 1 of this tile
-        mfmas(fa0, fb0);
-        frags(fa0, fb0, nx, ch0);          // k-step 0 of tile kt+1 (visible since the last barrier)
-        mfmas(fa1, fb1);
-      } else {
-        frags(fa0, fb0, rd, ch0);
-        mfmas(fa0, fb0);
-        frags(fa0, fb0, rd, ch1);
-        mfmas(fa0, fb0);
-      }
+    for (int u = 0; u < DEPTH; ++u) {
+      if (!more) break;
+      // the K-tile two ahead of the compute cursor (in registers since DEPTH steps) -> LDS;
+      // the K-tile DEPTH+2 ahead -> registers
+      la.store(sa[u], smem + wr); lb.store(sb[u], smem + wr + BM * 64);
+      fetch(sa[u], sb[u]);
+      frags(fa1, fb1, rd, ch1);            // k-step 1 of this K-tile
+      mfmas(fa0, fb0);
+      frags(fa0, fb0, nx, ch0);            // k-step 0 of the next K-tile (visible since the last barrier)
+      mfmas(fa1, fb1);
       __syncthreads();
       const int t = rd; rd = nx; nx = wr; wr = t;
-    };
-
-    for (int kt = 0; kt < nk; kt += DEPTH) {
-#pragma unroll
-      for (int u = 0; u < DEPTH; ++u)
-        if (kt + u < nk) step(kt + u, sa[u], sb[u]);
-    }
-
-    // epilogue: acc[i][j][4g+e] is output (row m0+wm+32i+lr, column n0+wn+32j+8g+4hb+e)
-    if constexpr (SPLITK) {
-      float* Ps = P + (int64_t)split * M * N;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn + 32 * j + 8 * g + 4 * hb;
-#pragma unroll
-          for (int i = 0; i < TM; ++i) {
-            const int row = m0 + wm + 32 * i + lr;
-            if (row < M && col < N) {
-              float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-              *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
-            }
-          }
-        }
-      continue;
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int col = n0 + wn + 32 * j + 8 * g + 4 * hb;
-        const bool cok = col < N;
-        const u32x2 braw = __builtin_amdgcn_raw_buffer_load_b64(rbias, cok ? col * 2 : (int)kOob, 0, 0);
-        const bf16x4 bv = __builtin_bit_cast(bf16x4, braw);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int row = m0 + wm + 32 * i + lr;
-          const unsigned off = cok ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
-          const u32x2 rraw = __builtin_amdgcn_raw_buffer_load_b64(rr, (int)off, 0, 0);
-          const bf16x4 rv = __builtin_bit_cast(bf16x4, rraw);
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[i][j][4 * g + e] + (float)bv[e] + (float)rv[e]);
-          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rc, (int)off, 0, 0);
-        }
+      if (++kt >= cur.kt_end) {
+        finish(cur);
+        cur = get_item(++round);
+        kt = cur.kt0;
+        more = cur.valid;
       }
+    }
   }
 }
 
@@ -477,9 +555,9 @@ mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b
   if (M == 0 || N == 0) return MOSAIC_OK;
   const bool vec_ok = (lda % 8 == 0) && (ldb % 8 == 0) && (K % 8 == 0 || (!a_kc && !b_kc)) &&
                       (a_kc || M % 8 == 0) && (b_kc || N % 8 == 0) &&
-                      ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 8 == 0) &&
-                      (ldc % 4 == 0) && (N % 4 == 0) && K > 0 &&
-                      (R == nullptr || (uintptr_t)R % 8 == 0) && (bias == nullptr || (uintptr_t)bias % 8 == 0);
+                      ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && ((uintptr_t)C % 16 == 0) &&
+                      (ldc % 8 == 0) && (N % 8 == 0) && K > 0 &&
+                      (R == nullptr || (uintptr_t)R % 16 == 0) && (bias == nullptr || (uintptr_t)bias % 16 == 0);
   // extents in bytes as seen by the buffer descriptors (dense rows: ld >= logical width)
   const int64_t a_ext = a_kc ? ((M - 1) * lda + K) * 2 : ((K - 1) * lda + M) * 2;
   const int64_t b_ext = b_kc ? ((N - 1) * ldb + K) * 2 : ((K - 1) * ldb + N) * 2;
