@@ -49,6 +49,16 @@ constexpr int NSTAGE = 3;
 #ifndef GEMM_FDB
 #define GEMM_FDB 1
 #endif
+#ifdef GEMM_NO_SCHED_FENCE
+#define SCHED_FENCE()
+#else
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+#ifdef GEMM_SETPRIO
+#define MFMA_PRIO(p) __builtin_amdgcn_s_setprio(p)
+#else
+#define MFMA_PRIO(p)
+#endif
 constexpr int DEPTH = GEMM_DEPTH;        // K-tiles in flight in registers
 constexpr bool FRAG_DB = GEMM_FDB;       // double-buffered fragments
 constexpr unsigned kOob = 0xFFFFFFF0u;   // byte offset beyond any descriptor's range
@@ -371,10 +381,21 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       // the K-tile DEPTH+2 ahead -> registers
       la.store(sa[u], smem + wr); lb.store(sb[u], smem + wr + BM * 64);
       fetch(sa[u], sb[u]);
+      // The scheduling fences keep each batch of fragment reads ahead of the MFMAs that run
+      // while they are in flight (the compiler would otherwise sink the reads next to their
+      // first use and expose the LDS latency).
       frags(fa1, fb1, rd, ch1);            // k-step 1 of this K-tile
+      SCHED_FENCE();
+      MFMA_PRIO(1);
       mfmas(fa0, fb0);
+      MFMA_PRIO(0);
+      SCHED_FENCE();
       frags(fa0, fb0, nx, ch0);            // k-step 0 of the next K-tile (visible since the last barrier)
+      SCHED_FENCE();
+      MFMA_PRIO(1);
       mfmas(fa1, fb1);
+      MFMA_PRIO(0);
+      SCHED_FENCE();
       __syncthreads();
       const int t = rd; rd = nx; nx = wr; wr = t;
       if (++kt >= cur.kt_end) {
