@@ -27,6 +27,14 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Position of streamed row r inside a transposed LDS row: each group of 16 keeps its four
+// 4-runs in the order 0,2,1,3, so that the 8 indices a half-wave lane owns in registers
+// 8*s2 .. 8*s2+7 of an accumulator block (two 4-runs, 8 apart) are 16 contiguous bytes.
+__device__ __forceinline__ int tr_pos(int r) {
+  const int sub = (r >> 2) & 3;
+  return (r & ~15) + ((((sub & 1) << 1) | (sub >> 1)) << 2) + (r & 3);
+}
+
 // Cooperative loader of a tile of RS rows x D columns (row stride `rs` elements) by 256
 // threads.  A thread owns KB consecutive rows of one 8-column chunk; it can store the
 // tile in natural form [row][D+8] and/or transposed form [col][RS+4].
@@ -34,7 +42,7 @@ template <int RS, int D>
 struct TileLoader {
   static constexpr int KB = RS * D / 2048;
   static_assert(KB >= 1, "tile too small for 256 threads");
-  static constexpr int PN = D + 8, PT = RS + 4;
+  static constexpr int PN = D + 8, PT = RS + 8;
   uint4 r[KB];
 
   __device__ __forceinline__ void load(const bf16* __restrict__ src, int64_t rs, int row0, int limit) {
@@ -54,7 +62,7 @@ struct TileLoader {
     const int t = threadIdx.x, cc = t % (D / 8), rb = t / (D / 8);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      bf16* dst = lds + (cc * 8 + i) * PT + rb * KB;
+      bf16* dst = lds + (cc * 8 + i) * PT + tr_pos(rb * KB);
       if constexpr (KB == 1) {
         const uint32_t w = (&r[0].x)[i >> 1];
         *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((i & 1) ? (w >> 16) : (w & 0xFFFFu));
@@ -77,17 +85,11 @@ struct TileLoader {
 __device__ __forceinline__ bf16x8 frag_nat(const bf16* lds, int pitch, int row, int s, int hb) {
   return *reinterpret_cast<const bf16x8*>(lds + row * pitch + 16 * s + 8 * hb);
 }
-// A-operand fragment from a transposed tile [c][r]: row c, the 8 streamed indices that a
-// lane of half hb owns in registers 8*s2 .. 8*s2+7 of a 32x32 accumulator block:
-// base + 16*s2 + 4*hb + {0..3} and base + 16*s2 + 8 + 4*hb + {0..3}
+// A-operand fragment from a transposed tile [c][tr_pos(r)]: row c, the 8 streamed indices
+// that a lane of half hb owns in registers 8*s2 .. 8*s2+7 of a 32x32 accumulator block
+// (base + 16*s2 + 4*hb + {0..3} and + 8), one 16-byte read thanks to tr_pos
 __device__ __forceinline__ bf16x8 frag_tr(const bf16* lds, int pitch, int c, int base, int s2, int hb) {
-  const bf16* p = lds + c * pitch + base + 16 * s2 + 4 * hb;
-  const bf16x4 a = *reinterpret_cast<const bf16x4*>(p);
-  const bf16x4 b = *reinterpret_cast<const bf16x4*>(p + 8);
-  bf16x8 v;
-  v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
-  v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
-  return v;
+  return *reinterpret_cast<const bf16x8*>(lds + c * pitch + base + 16 * s2 + 8 * hb);
 }
 // registers 8*s2 .. 8*s2+7 of an accumulator block as a bf16 B-operand
 __device__ __forceinline__ bf16x8 pack8(const float* v) {
@@ -99,9 +101,19 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
 // streamed index (within a 32-block) held by register r of a lane of half hb
 __device__ __forceinline__ int acc_row(int r, int hb) { return 8 * (r >> 2) + 4 * hb + (r & 3); }
 
+// Work order for tiles of unequal cost (causal masks): items are ranked heaviest first and
+// dealt to the persistent workgroups in a snake (even rounds ascending, odd rounds
+// descending), so a workgroup that drew a heavy tile next draws a light one.
+// Returns the rank of the `round`-th item of workgroup blockIdx.x, or -1.
+__device__ __forceinline__ int snake_item(int round, int items) {
+  const int G = gridDim.x, b = blockIdx.x;
+  const int idx = round * G + ((round & 1) ? (G - 1 - b) : b);
+  return idx < items ? idx : -1;
+}
+
 // --------------------------------------------------------------------------- forward
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                      float* __restrict__ lse, int B, int N, int H, int causal,
                                                      float scale_log2, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
@@ -114,9 +126,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
   const int h = H * D;
   const int64_t rs = 3 * (int64_t)h;
   const int items = B * H * qtiles;
-  for (int item = blockIdx.x; item < items; item += gridDim.x) {
-    // late query tiles carry the most keys under a causal mask: hand them out first
-    const int qt = qtiles - 1 - item % qtiles, hd = (item / qtiles) % H, b = item / (qtiles * H);
+  for (int round = 0; round * (int)gridDim.x < items; ++round) {
+    const int item = snake_item(round, items);
+    if (item < 0) continue;
+    // late query tiles carry the most keys under a causal mask: rank them first
+    const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
     const int q0 = qt * 128, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     bf16x8 qf[NS];
@@ -160,26 +174,38 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(ks, L::PN, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
         float sv[16];
         float mx = -INFINITY;
+        // only blocks that touch the diagonal or the end of the sequence need the mask
+        const bool need_mask = (jb + 32 > N) || (causal && jb + 31 > i0);
+        if (need_mask) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jb + acc_row(r, hb);
-          const bool masked = (j >= N) || (causal && j > i);
-          sv[r] = masked ? -INFINITY : sacc[r] * scale_log2;
-          mx = fmaxf(mx, sv[r]);
+          for (int r = 0; r < 16; ++r) {
+            const int j = jb + acc_row(r, hb);
+            const bool masked = (j >= N) || (causal && j > i);
+            sv[r] = masked ? -INFINITY : sacc[r] * scale_log2;
+            mx = fmaxf(mx, sv[r]);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sv[r] = sacc[r] * scale_log2; mx = fmaxf(mx, sv[r]); }
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float mn = fmaxf(m, mx);
-        const float mref = (mn == -INFINITY) ? 0.f : mn;        // row with nothing visible yet
-        const float corr = fast_exp2(m - mref);                  // m = -inf -> 0
+        // rescale the running sums only when some row's maximum moved (exact: the factor is 1 otherwise)
+        if (__any(mn > m)) {
+          const float mref0 = (mn == -INFINITY) ? 0.f : mn;
+          const float corr = fast_exp2(m - mref0);               // m = -inf -> 0
+          lsum *= corr;
+#pragma unroll
+          for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[c][e] *= corr;
+          m = mn;
+        }
+        const float mref = (m == -INFINITY) ? 0.f : m;           // row with nothing visible yet
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(sv[r] - mref); ps += sv[r]; }
-        lsum = lsum * corr + ps;
-        m = mn;
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) o[c][e] *= corr;
+        lsum += ps;
         const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -230,8 +256,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
   const int64_t rs = 3 * (int64_t)h;
   const float scale_log2 = scale * kLog2e;
   const int items = B * H * qtiles;
-  for (int item = blockIdx.x; item < items; item += gridDim.x) {
-    const int qt = qtiles - 1 - item % qtiles, hd = (item / qtiles) % H, b = item / (qtiles * H);
+  for (int round = 0; round * (int)gridDim.x < items; ++round) {
+    const int item = snake_item(round, items);
+    if (item < 0) continue;
+    const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
     const int q0 = qt * 128, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
@@ -319,7 +347,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
 
 // --------------------------------------------------------------------------- dK, dV
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                          float scale, int ktiles) {
@@ -336,9 +364,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict_
   const int64_t rs = 3 * (int64_t)h;
   const float scale_log2 = scale * kLog2e;
   const int items = B * H * ktiles;
-  for (int item = blockIdx.x; item < items; item += gridDim.x) {
-    // early key tiles see the most queries under a causal mask: hand them out first
-    const int kt_i = item % ktiles, hd = (item / ktiles) % H, b = item / (ktiles * H);
+  for (int round = 0; round * (int)gridDim.x < items; ++round) {
+    const int item = snake_item(round, items);
+    if (item < 0) continue;
+    // early key tiles see the most queries under a causal mask: rank them first
+    const int kt_i = item / (B * H), hd = item % H, b = (item / H) % B;
     const int k0 = kt_i * 128, j0w = k0 + 32 * wave, j = j0w + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
