@@ -1,0 +1,124 @@
+"""Parity at the benchmark's full sizes (configs[1]: CLIP-B / small-LM scale), in the launch
+configuration bench.py times.  The oracle cannot run the whole stage here in seconds, so:
+  * every output element of a linear layer is an independent dot product and every
+    (sample, head) of attention an independent problem: sampled rows / columns / heads are
+    checked against the oracle one by one;
+  * properties that hold at any size are checked on the full stage: colocated and
+    time-sliced execution give identical bits, the loss is finite and positive.
+"""
+import numpy as np
+import pytest
+
+from oracle import layers as O
+from paper_2605_18710_amd import synth
+from helpers import rel_l2, quantize, to_dev, from_dev
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_18710_amd import binding
+    binding.lib()
+    return binding
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy().copy()
+
+
+def test_decoder_gate_up_projection_sampled(mb):
+    """T=8192, k=2048, n=11264: the shape of the roofline entry."""
+    T, k, n = 8192, 2048, 11264
+    X = quantize(synth.normal(9001, (T, k)), "bf16")
+    W = quantize(synth.normal(9002, (k, n), 0, 0.02), "bf16")
+    dY = quantize(synth.uniform(9003, (T, n), -1.0, 1.0), "bf16")
+    X_, W_, dY_ = to_dev(X, "bf16"), to_dev(W, "bf16"), to_dev(dY, "bf16")
+    Y = torch.empty((T, n), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, k), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((k, n), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(mb.linear_wgrad_scratch_bytes(T, k, n), dtype=torch.uint8, device="cuda")
+    snaps = []
+    for q in (256, 192):
+        mb.op_linear_fwd(None, q, "bf16", T, k, n, X_, W_, None, None, Y)
+        mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY_, W_, None, dX)
+        mb.op_linear_wgrad(None, q, "bf16", T, k, n, X_, dY_, dW, None, ws)
+        torch.cuda.synchronize()
+        snaps.append([bits(Y), bits(dX), bits(dW)])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b), "full-size result depends on the quota"
+    rows = synth.integers(9004, (48,), 0, T)
+    rows[:4] = [0, 255, 256, T - 1]                      # tile edges
+    Yh, dXh = from_dev(Y[torch.from_numpy(rows).long().cuda()]), from_dev(dX[torch.from_numpy(rows).long().cuda()])
+    assert rel_l2(Yh, X[rows] @ W) <= 2e-2
+    assert rel_l2(dXh, dY[rows] @ W.T) <= 2e-2
+    cols = synth.integers(9005, (24,), 0, n)
+    cols[:3] = [0, 255, n - 1]
+    dWh = from_dev(dW[:, torch.from_numpy(cols).long().cuda()])
+    assert rel_l2(dWh, X.T @ dY[:, cols]) <= 2e-2
+
+
+def test_decoder_attention_sampled_heads(mb):
+    """B=8, N=1024, 16 heads of 128, causal: sampled (sample, head) problems."""
+    B, N, H, d = 8, 1024, 16, 128
+    h = H * d
+    qkv = quantize(synth.normal(9010, (B * N, 3 * h)), "bf16")
+    dO = quantize(synth.normal(9011, (B * N, h)), "bf16")
+    qkv_, dO_ = to_dev(qkv, "bf16"), to_dev(dO, "bf16")
+    Oo = torch.empty((B * N, h), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    dqkv = torch.empty_like(qkv_)
+    delta = torch.empty_like(lse)
+    snaps = []
+    for q in (256, 192):
+        mb.op_attention_fwd(None, q, "bf16", B, N, H, d, 1, qkv_, Oo, lse)
+        mb.op_attention_bwd(None, q, "bf16", B, N, H, d, 1, qkv_, Oo, lse, dO_, dqkv, delta)
+        torch.cuda.synchronize()
+        snaps.append([bits(Oo), bits(lse), bits(dqkv)])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b)
+    Oh, dh, lh = from_dev(Oo), from_dev(dqkv), from_dev(lse)
+    for (b, t) in ((0, 0), (3, 7), (7, 15), (5, 9)):
+        rows = slice(b * N, (b + 1) * N)
+        c = slice(t * d, (t + 1) * d)
+        qh, kh, vh = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
+        o_ref, P = O.attention_head_fwd(qh, kh, vh, 1)
+        dq, dk, dv = O.attention_head_bwd(qh, kh, vh, P, dO[rows, c])
+        assert rel_l2(Oh[rows, c], o_ref) <= 2e-2
+        assert rel_l2(dh[rows, t * d:(t + 1) * d], dq) <= 2e-2
+        assert rel_l2(dh[rows, h + t * d:h + (t + 1) * d], dk) <= 2e-2
+        assert rel_l2(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv) <= 2e-2
+        S = (qh @ kh.T) / np.sqrt(d)
+        S = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], -np.inf, S)
+        mx = S.max(-1)
+        assert rel_l2(lh[b, t], mx + np.log(np.exp(S - mx[:, None]).sum(-1))) <= 1e-2
+
+
+def test_full_stage_modes_are_bit_identical(mb):
+    """The benchmarked stage itself: colocated (64/192 CUs) and time-sliced runs of all
+    three modules give the same bits in every output, input gradient and parameter
+    gradient, and the decoder's loss is finite."""
+    from paper_2605_18710_amd.workload import StagedStage
+    stage = StagedStage(1)
+    cus = mb.device_cu_count()
+    mb.pool_reserve(cus, 0, mb.STRIPED)
+    stage.reserve([64, 192])
+    snaps = []
+    for quotas, mode in (([cus], mb.TIME_SLICED), ([64, 192], mb.COLOCATED)):
+        for m in stage.staged:
+            m.module.grads.zero_()
+        r = stage.run(quotas, mode)
+        assert r["stage_ms"] > 0
+        snaps.append([bits(m.y) for m in stage.staged] + [bits(m.dx) for m in stage.staged] +
+                     [bits(m.module.grads) for m in stage.staged] + [bits(stage.staged[-1].loss)])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b), "colocated and time-sliced runs differ at full size"
+    loss = float(stage.staged[-1].loss.item())
+    assert np.isfinite(loss) and loss > 0
+    for m in stage.staged:
+        g = m.module.grads.float()
+        assert torch.isfinite(g).all() and float(g.abs().max()) > 0
+    stage.destroy()
