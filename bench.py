@@ -42,6 +42,20 @@ def time_kernel(fn, reps, warm=3):
     return e0.elapsed_time(e1) / reps
 
 
+def profiled_traffic(form):
+    """HBM bytes per launch of the roofline kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size); None if the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_kernel_roofline_config2.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                vals = dict(kv.split("=") for kv in line.split(":", 1)[1].split())
+                return int(vals[form])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
 def roofline_gemm(mb, T, k, n, reps):
     """The dominant kernel: the bf16 MFMA GEMM at the decoder's gate/up projection shape,
     forward, input-gradient and weight-gradient forms, on all CUs."""
@@ -155,6 +169,13 @@ def main():
 
     gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=20)
     if args.roofline_only:
+        # a plain device copy of known size, so that HBM byte counters of the same run can
+        # be scaled: 1 GiB read + 1 GiB written per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
         print(json.dumps({"kernel": "gemm_bf16_kernel", "shape": [Tl, hl, 2 * fl], "ms": gms,
                           "tflops": {k: gflops / v / 1e9 for k, v in gms.items()}}))
         return
@@ -240,7 +261,9 @@ def main():
                                              "cu_grid": grid, "group_ms": [[round(v, 4) for v in row] for row in curves]}},
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel 256x256x64 {dominant} T={Tl} k={hl} n={2 * fl}",
                      "achieved": round(gflops / gms[dominant] / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gflops / gms[dominant] / 1e9 / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(gflops / gms[dominant] / 1e9 / PEAK_BF16_TFLOPS, 4),
+                     "traffic": profiled_traffic(dominant) if args.config == 1 else None,
+                     "algorithmic_bytes": 2 * (Tl * hl + hl * 2 * fl + Tl * 2 * fl),
                      "avg_ms": {k: round(v, 4) for k, v in gms.items()},
                      "all_forms_tflops": {k: round(gflops / v / 1e9, 2) for k, v in gms.items()},
                      "hbm_kernels_gbs": bw, "hbm_peak_gbs": PEAK_HBM_GBS},
