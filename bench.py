@@ -102,6 +102,28 @@ def bandwidth_kernels(mb, T, h, f, reps):
     return {k: round(v, 1) for k, v in res.items()}
 
 
+def stream_pool_latency(mb, cus, repeats=30):
+    """Analogue of the paper's stream-pool experiment (Sec. 5.3.1): latency of creating and
+    destroying a quota'd stream on demand, for quotas 0.1 .. 0.9 of the device, against
+    taking the same stream from the pre-created pool."""
+    create, pooled = [], []
+    for tenth in range(1, 10):
+        q = max(8, round(cus * tenth / 10))
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            s = mb.Stream(q, 0, mb.STRIPED)
+            s.destroy()
+            create.append((time.perf_counter() - t0) * 1e3)
+        mb.pool_reserve(q, 0, mb.STRIPED)
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            mb.pool_get(q, 0, mb.STRIPED)
+            pooled.append((time.perf_counter() - t0) * 1e3)
+    return dict(on_demand_create_destroy_ms=round(statistics.mean(create), 4),
+                on_demand_max_ms=round(max(create), 4), pooled_get_ms=round(statistics.mean(pooled), 5),
+                quotas="0.1..0.9 of the CUs, %d repeats each" % repeats)
+
+
 def cpu_baseline(wl):
     """The CPU checker as it stands, timed on this host on a bounded sample: one encoder
     layer at full batch and one decoder layer at half batch, forward+backward in float64,
@@ -180,6 +202,7 @@ def main():
                           "tflops": {k: gflops / v / 1e9 for k, v in gms.items()}}))
         return
     bw = bandwidth_kernels(mb, Tl, hl, fl, reps=20)
+    pool = stream_pool_latency(mb, cus)
 
     stage = StagedStage(args.config)
     B = stage.batch
@@ -259,7 +282,7 @@ def main():
                       "plans": [dict(plan=r["plan"], stage_ms=round(r["stage_ms"], 4)) for r in results],
                       "chosen_from_curves": {"plan": chosen, "predicted_ms": round(predicted, 4),
                                              "cu_grid": grid, "group_ms": [[round(v, 4) for v in row] for row in curves]}},
-        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel 256x256x64 {dominant} T={Tl} k={hl} n={2 * fl}",
+        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel 256x256x32 {dominant} T={Tl} k={hl} n={2 * fl}",
                      "achieved": round(gflops / gms[dominant] / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gflops / gms[dominant] / 1e9 / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic(dominant) if args.config == 1 else None,
@@ -267,8 +290,12 @@ def main():
                      "avg_ms": {k: round(v, 4) for k, v in gms.items()},
                      "all_forms_tflops": {k: round(gflops / v / 1e9, 2) for k, v in gms.items()},
                      "hbm_kernels_gbs": bw, "hbm_peak_gbs": PEAK_HBM_GBS},
+        "stream_pool": pool,
         "paper_context": "paper reports up to 1.31x per-iteration speedup on 32x H100-80GB (other hardware, other metric)",
     }
+    # what creating the stage's streams on demand would add to every step (one per group)
+    pool["share_of_step_if_on_demand"] = round(ngroups * pool["on_demand_create_destroy_ms"] /
+                                               (ms_per_step + ngroups * pool["on_demand_create_destroy_ms"]), 4)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
     stage.destroy()

@@ -59,7 +59,9 @@ constexpr int NSTAGE = 3;
 #else
 #define MFMA_PRIO(p)
 #endif
-constexpr int DEPTH = GEMM_DEPTH;        // K-tiles in flight in registers
+#ifndef GEMM_DEPTH_SMALL
+#define GEMM_DEPTH_SMALL 2
+#endif
 constexpr bool FRAG_DB = GEMM_FDB;       // double-buffered fragments
 constexpr unsigned kOob = 0xFFFFFFF0u;   // byte offset beyond any descriptor's range
 
@@ -178,6 +180,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
     int tiles_m, int tiles_n, int ksplit, int ktiles_per, float* __restrict__ P) {
   constexpr int NT = 64 * NWM * NWN;
+  constexpr int DEPTH = (BM * BN >= 256 * 256) ? GEMM_DEPTH : GEMM_DEPTH_SMALL;   // K-tiles in flight in registers
   constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * 64;     // bytes per LDS stage
