@@ -20,11 +20,13 @@
 //     is being written and tiles t+3 / t+4 are in flight from HBM.  One barrier per K-tile.
 //     The stream of K-tiles runs across output tiles, so a new output tile starts without
 //     a pipeline refill.
-//   * fragments are double-buffered in registers: the reads for the next 16 MFMAs are
-//     issued before the current 16.
+//   * fragments are double-buffered in registers: the reads for the next batch of MFMAs
+//     are issued under the current batch, one read per MFMA (scheduling group barriers fix
+//     that interleaving; LDS writes and HBM requests ride under the remaining MFMAs).
 //   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
 //     so a lane owns four consecutive output columns per register group and the epilogue
-//     (bias, residual, bf16 rounding) uses 8-byte buffer loads and stores.
+//     (bias, residual, bf16 rounding) can be staged through LDS into row-contiguous
+//     16-byte stores.
 //   * tiles are handed out so that the workgroups running on one XCD at the same time
 //     form a 4 x 8 patch of the tile grid and share operand panels in that XCD's L2.
 //
@@ -43,26 +45,7 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int BK = 32;            // k-values per LDS tile row (64 bytes)
 constexpr int NSTAGE = 3;
-#ifndef GEMM_DEPTH
-#define GEMM_DEPTH 2
-#endif
-#ifndef GEMM_FDB
-#define GEMM_FDB 1
-#endif
-#ifdef GEMM_NO_SCHED_FENCE
-#define SCHED_FENCE()
-#else
-#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
-#ifdef GEMM_SETPRIO
-#define MFMA_PRIO(p) __builtin_amdgcn_s_setprio(p)
-#else
-#define MFMA_PRIO(p)
-#endif
-#ifndef GEMM_DEPTH_SMALL
-#define GEMM_DEPTH_SMALL 2
-#endif
-constexpr bool FRAG_DB = GEMM_FDB;       // double-buffered fragments
+constexpr int DEPTH = 2;         // K-tiles in flight in registers (two register sets)
 constexpr unsigned kOob = 0xFFFFFFF0u;   // byte offset beyond any descriptor's range
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
@@ -180,7 +163,6 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
     int tiles_m, int tiles_n, int ksplit, int ktiles_per, float* __restrict__ P) {
   constexpr int NT = 64 * NWM * NWN;
-  constexpr int DEPTH = (BM * BN >= 256 * 256) ? GEMM_DEPTH : GEMM_DEPTH_SMALL;   // K-tiles in flight in registers
   constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * 64;     // bytes per LDS stage
@@ -253,16 +235,19 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   int lround = 0, lkt = cur.kt0;
   typename LA::Tile lta = la.tile(lda, lit.m0, M);
   typename LB::Tile ltb = lb.tile(ldb, lit.n0, N);
-  auto fetch = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
+  auto issue = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
     la.load(ga, ra, lta, lkt, K, lit.kt_end, lit.valid);
     lb.load(gb, rb, ltb, lkt, K, lit.kt_end, lit.valid);
-    ++lkt;
-    if (lit.valid && lkt >= lit.kt_end) {
-      lit = get_item(++lround);
-      lkt = lit.kt0;
-      lta = la.tile(lda, lit.m0, M);
-      ltb = lb.tile(ldb, lit.n0, N);
-    }
+  };
+  auto load_cursor_next_item = [&]() {
+    lit = get_item(++lround);
+    lkt = lit.kt0;
+    lta = la.tile(lda, lit.m0, M);
+    ltb = lb.tile(ldb, lit.n0, N);
+  };
+  auto fetch = [&](typename LA::Regs& ga, typename LB::Regs& gb) {    // prologue only
+    issue(ga, gb);
+    if (++lkt >= lit.kt_end && lit.valid) load_cursor_next_item();
   };
 
   f32x16 acc[TM][TN];
@@ -375,38 +360,63 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 
 
   int round = 0, kt = cur.kt0;
-  bool more = true;
-  while (more) {
+  static_assert(DEPTH == 2, "the step pairs below alternate between two register sets");
+  // One pipeline step: the K-tile two ahead of the compute cursor (in registers since two
+  // steps) goes to LDS, the K-tile four ahead is requested from HBM, the current K-tile is
+  // multiplied.  The step is straight-line code (work-list bookkeeping happens between
+  // runs of steps), so it is one scheduling region, and the group barriers below lay its
+  // memory operations out between the MFMAs: fragment reads one at a time under the first
+  // MFMAs of a batch, the LDS writes under the last MFMAs of the first batch, the HBM
+  // requests under the last MFMAs of the second.  Issued in a burst instead, they fill the
+  // LDS queue and the wave cannot issue its next MFMA until the queue drains.
+  auto step = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
+    frags(fa1, fb1, rd, ch1);            // k-step 1 of this K-tile
+    la.store(ga, smem + wr); lb.store(gb, smem + wr + BM * 64);
+    issue(ga, gb);
+    mfmas(fa0, fb0);
+    frags(fa0, fb0, nx, ch0);            // k-step 0 of the next K-tile (visible since the last barrier)
+    mfmas(fa1, fb1);
+#ifndef GEMM_NO_SCHED_GROUPS
+    {
+      constexpr int NM = TM * TN, NR = TM + TN;       // MFMAs and fragment reads per batch
+      constexpr int NW = (A_KC ? LA::NL : 8) + (B_KC ? LB::NL : 8);   // LDS writes per step
+      constexpr int NV = LA::NL + LB::NL;                             // HBM requests per step
+      constexpr int FREE = NM > NR ? NM - NR : NM;    // MFMAs that carry the writes / requests
 #pragma unroll
-    for (int u = 0; u < DEPTH; ++u) {
-      if (!more) break;
-      // the K-tile two ahead of the compute cursor (in registers since DEPTH steps) -> LDS;
-      // the K-tile DEPTH+2 ahead -> registers
-      la.store(sa[u], smem + wr); lb.store(sb[u], smem + wr + BM * 64);
-      fetch(sa[u], sb[u]);
-      // The scheduling fences keep each batch of fragment reads ahead of the MFMAs that run
-      // while they are in flight (the compiler would otherwise sink the reads next to their
-      // first use and expose the LDS latency).
-      frags(fa1, fb1, rd, ch1);            // k-step 1 of this K-tile
-      SCHED_FENCE();
-      MFMA_PRIO(1);
-      mfmas(fa0, fb0);
-      MFMA_PRIO(0);
-      SCHED_FENCE();
-      frags(fa0, fb0, nx, ch0);            // k-step 0 of the next K-tile (visible since the last barrier)
-      SCHED_FENCE();
-      MFMA_PRIO(1);
-      mfmas(fa1, fb1);
-      MFMA_PRIO(0);
-      SCHED_FENCE();
-      __syncthreads();
-      const int t = rd; rd = nx; nx = wr; wr = t;
-      if (++kt >= cur.kt_end) {
-        finish(cur);
-        cur = get_item(++round);
-        kt = cur.kt0;
-        more = cur.valid;
+      for (int q = 0; q < NM; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, (NR + NM - 1) / NM, 0);
+        if (q >= NM - FREE) __builtin_amdgcn_sched_group_barrier(0x200, (NW + FREE - 1) / FREE, 0);
       }
+#pragma unroll
+      for (int q = 0; q < NM; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, (NR + NM - 1) / NM, 0);
+        if (q >= NM - FREE) __builtin_amdgcn_sched_group_barrier(0x020, (NV + FREE - 1) / FREE, 0);
+      }
+    }
+#endif
+    __syncthreads();
+    const int t = rd; rd = nx; nx = wr; wr = t;
+    ++lkt; ++kt;
+  };
+  while (true) {
+    // run of steps until the compute cursor ends its item or the load cursor ends the one
+    // it reads from
+    int n = cur.kt_end - kt;
+    if (lit.valid) n = min(n, lit.kt_end - lkt);
+    for (; n >= 2; n -= 2) { step(sa[0], sb[0]); step(sa[1], sb[1]); }
+    if (n) {                             // odd run: one more step, then the two sets trade places
+      step(sa[0], sb[0]);
+      const typename LA::Regs ta = sa[0]; sa[0] = sa[1]; sa[1] = ta;
+      const typename LB::Regs tb = sb[0]; sb[0] = sb[1]; sb[1] = tb;
+    }
+    if (lit.valid && lkt >= lit.kt_end) load_cursor_next_item();
+    if (kt >= cur.kt_end) {
+      finish(cur);
+      cur = get_item(++round);
+      kt = cur.kt0;
+      if (!cur.valid) break;
     }
   }
 }
