@@ -161,7 +161,8 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
     const bf16* __restrict__ bias, const bf16* __restrict__ R, int M, int N, int K,
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
-    int tiles_m, int tiles_n, int ksplit, int ktiles_per, float* __restrict__ P) {
+    int tiles_m, int tiles_n, int tile_begin, int tile_count, int sub, int ksplit, int ktiles_per,
+    float* __restrict__ P) {
   constexpr int NT = 64 * NWM * NWN;
   constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -182,13 +183,17 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   const int ch0 = ((hb ^ sw) & 3) << 4, ch1 = (((2 + hb) ^ sw) & 3) << 4;
   const int nk_all = (K + BK - 1) / BK;
 
-  // Work order.  Tiles are listed panel-major: panels of 8 tile columns, row-major inside a
-  // panel, so 32 consecutive entries form a 4 x 8 patch that shares operand panels.  Each
-  // round hands gridDim entries out; workgroup b runs on XCD b%8 (workgroups are dealt
-  // round-robin over XCDs), so XCD x takes the x-th contiguous eighth of the round and its
-  // workgroups reuse each other's panels in that XCD's L2.  Split pieces are split-major.
-  const int ntiles = tiles_m * tiles_n;
-  const int nitems = ntiles * ksplit;
+  // Work order.  The output is cut into coarse tiles of (sub*BM) x (sub*BN), listed
+  // panel-major: panels of 8 coarse-tile columns, row-major inside a panel, so 32 consecutive
+  // entries form a 4 x 8 patch that shares operand panels.  This launch covers entries
+  // [tile_begin, tile_begin + tile_count) of that list, each as sub*sub tiles of BM x BN
+  // (sub = 2: the 128x128 kernel finishing the quarter tiles of the 256x256 tiles that did
+  // not fill a whole round of the large kernel).  Each round hands gridDim items out;
+  // workgroup b runs on XCD b%8 (workgroups are dealt round-robin over XCDs), so XCD x takes
+  // the x-th contiguous eighth of the round and its workgroups reuse each other's panels in
+  // that XCD's L2.  Split pieces are split-major.
+  const int per_split = tile_count * sub * sub;
+  const int nitems = per_split * ksplit;
   const int G = gridDim.x;
   const bool by_xcd = (G & 7) == 0;
   auto get_item = [&](int round) -> WorkItem {
@@ -207,15 +212,17 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       if (local >= cnt) return it;
     }
     const int item = base + local;
-    it.split = item / ntiles;
-    const int tile = item - it.split * ntiles;
+    it.split = item / per_split;
+    const int fine = item - it.split * per_split;
+    const int quad = fine % (sub * sub);
+    const int tile = tile_begin + fine / (sub * sub);
     it.kt0 = it.split * ktiles_per;
     it.kt_end = SPLITK ? min(nk_all, it.kt0 + ktiles_per) : nk_all;
     const int panel = tile / (tiles_m * 8);
     const int pw = min(8, tiles_n - panel * 8);
     const int in_panel = tile - panel * tiles_m * 8;
-    it.m0 = (in_panel / pw) * BM;
-    it.n0 = (panel * 8 + in_panel % pw) * BN;
+    it.m0 = ((in_panel / pw) * sub + quad / sub) * BM;
+    it.n0 = ((panel * 8 + in_panel % pw) * sub + quad % sub) * BN;
     it.valid = true;
     return it;
   };
@@ -504,11 +511,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 }
 
 
+// One launch of the MFMA kernel over coarse tiles [tile_begin, tile_begin + tile_count) of the
+// panel-major list of (sub*BM) x (sub*BN) tiles; tile_count < 0 means all of them.
 template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK = false>
 mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda,
                           const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
                           uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, int ksplit = 1,
-                          int ktiles_per = 0, float* P = nullptr) {
+                          int ktiles_per = 0, float* P = nullptr, int sub = 1, int tile_begin = 0,
+                          int tile_count = -1) {
   constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64;
   auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK>;
   static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
@@ -517,11 +527,13 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
+  const int tiles_m = (int)ceil_div(M, BM * sub), tiles_n = (int)ceil_div(N, BN * sub);
+  if (tile_count < 0) tile_count = tiles_m * tiles_n - tile_begin;
+  if (tile_count <= 0) return MOSAIC_OK;
   const int wg_per_cu = (BM == 256) ? 1 : 2;
-  const int grid = grid_for(quota, wg_per_cu, (int64_t)tiles_m * tiles_n * ksplit);
+  const int grid = grid_for(quota, wg_per_cu, (int64_t)tile_count * sub * sub * ksplit);
   kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                          tiles_m, tiles_n, ksplit, ktiles_per, P);
+                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P);
   MOSAIC_LAUNCH_CHECK();
   if (SPLITK) {
     const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
@@ -563,15 +575,35 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
     }
   }
   // Tile shape only decides which workgroup computes an element, never its bits.  Large
-  // tiles halve LDS traffic per MFMA; small problems take 128x128 so that more CUs get work.
+  // tiles halve LDS traffic per MFMA; small tiles fill the CUs when there are few large
+  // ones.  Three plans, priced in units of a quarter of a 256x256 tile's time on one CU:
+  //   all-256: whole rounds of 256x256 tiles, the last one possibly mostly idle;
+  //   all-128: 128x128 tiles, two workgroups per CU;
+  //   mixed:   the whole rounds with the large kernel, then the tiles of the partial round
+  //            as quarter tiles with the small kernel.
   const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256), t128 = ceil_div(M, 128) * ceil_div(N, 128);
+  auto cost_small = [&](int64_t tiles) {       // 128x128 tiles on `quota` CUs
+    const int64_t full = tiles / (2 * (int64_t)quota), rem = tiles % (2 * (int64_t)quota);
+    // a CU shared by two workgroups finishes both in about 2 x 1.35 units (more when the
+    // operands need the transposing LDS writes), a workgroup alone in 1.6
+    constexpr double pen = (A_KC && B_KC) ? 1.3 : (!A_KC && !B_KC) ? 1.8 : 1.45;
+    return (double)full * 2.0 * pen + (rem == 0 ? 0.0 : rem <= quota ? 1.2 * pen : 2.0 * pen);
+  };
+  const int64_t whole = t256 / quota, rest = t256 % quota;
   const double cost256 = (double)ceil_div(t256, quota) * 4.0;
-  const double cost128 = (double)ceil_div(t128, 2 * (int64_t)quota) * 2.0 * 1.35;
-  bool big = cost256 <= cost128;
-  if (forced_tile() == 128) big = false;
-  if (forced_tile() == 256) big = true;
-  if (big) return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
-  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  const double cost128 = cost_small(t128);
+  const double cost_mix = (whole > 0 && rest > 0) ? (double)whole * 4.0 + cost_small(4 * rest) + 0.15 : 1e30;
+  int plan = cost256 <= cost128 ? (cost256 <= cost_mix ? 256 : 0) : (cost128 <= cost_mix ? 128 : 0);
+  if (forced_tile() == 128 || forced_tile() == 256) plan = forced_tile();
+  if (forced_tile() == 1 && whole > 0 && rest > 0) plan = 0;
+  if (plan == 256) return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  if (plan == 128) return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  const int head = (int)(whole * quota);
+  mosaic_status st = launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
+                                                             b_bytes, c_bytes, 1, 0, nullptr, 1, 0, head);
+  if (st != MOSAIC_OK) return st;
+  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
+                                                 c_bytes, 1, 0, nullptr, 2, head, (int)rest);
 }
 
 }  // namespace
