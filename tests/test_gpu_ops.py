@@ -38,6 +38,7 @@ LINEAR_SHAPES = [
     ("bf16", 4096, 512, 8192),        # enough tiles for the 256x256 configuration
     ("bf16", 40, 24, 16), ("bf16", 129, 600, 136),
     ("bf16", 4104, 520, 264),         # long contraction over few output tiles: split weight gradient
+    ("bf16", 2100, 520, 1304),        # at 24 CUs: whole rounds of large tiles + a quarter-tile tail with ragged edges
 ]
 
 
