@@ -7,35 +7,40 @@
 // bits of the result do not depend on the grid, the tile shape, the tile order or the CU.
 //
 // Data movement
-//   * HBM -> registers with 128-bit buffer loads; the buffer descriptor's bounds check
-//     returns zeros for rows past the end, so ragged tiles need no branches.
-//   * registers -> LDS in K-contiguous form, 32 k-values (64 bytes) per row, the four
-//     16-byte chunks of a row XOR-swizzled by (row/4)%4 so that fragment reads
-//     (ds_read_b128, 16 consecutive rows) and tile writes hit distinct banks without padding.
-//     An operand whose contraction index is the strided one in HBM (the weight in the
-//     forward pass, both operands of the weight gradient) is transposed in registers with
-//     byte permutes on the way in.
-//   * three LDS stages and two register sets: while tile t is multiplied, tile t+1 is
-//     already visible in LDS (its first fragments are fetched before the barrier), tile t+2
-//     is being written and tiles t+3 / t+4 are in flight from HBM.  One barrier per K-tile.
-//     The stream of K-tiles runs across output tiles, so a new output tile starts without
-//     a pipeline refill.
+//   * HBM -> LDS directly (buffer_load ... lds): no register staging and no LDS write
+//     instructions.  A wave instruction fills 1 KB of consecutive LDS; each lane chooses
+//     which 16 bytes of the tile it requests, which realises the bank swizzle.  The
+//     descriptor's bounds check returns zeros for rows past the end, so ragged tiles need
+//     no branches.
+//   * an operand whose contraction index is contiguous in HBM sits in LDS as rows of 32
+//     k-values (64 bytes), 16-byte chunks XOR-swizzled by (row/4)%4, and is read with
+//     ds_read_b128.  An operand whose contraction index is the strided one (the weight in
+//     the forward pass, both operands of the weight gradient) sits in LDS as it is in HBM,
+//     k-row by k-row with 64-byte chunks XOR-swizzled by k%4, and its fragments come out
+//     with the transposing read ds_read_b64_tr_b16 (two per fragment).
+//   * five LDS stages: while K-tile t is multiplied, t+1 is visible (its first fragments
+//     are fetched before the barrier), t+2 is complete or landing and t+3 / t+4 are in
+//     flight.  One barrier per K-tile; before it every wave waits (vmcnt) for its own
+//     requests of tile t+2.  The stream of K-tiles runs across output tiles, so a new
+//     output tile starts without a pipeline refill.
 //   * fragments are double-buffered in registers: the reads for the next batch of MFMAs
-//     are issued under the current batch, one read per MFMA (scheduling group barriers fix
-//     that interleaving; LDS writes and HBM requests ride under the remaining MFMAs).
+//     are issued under the current batch (scheduling group barriers fix the interleaving).
 //   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
-//     so a lane owns four consecutive output columns per register group and the epilogue
-//     (bias, residual, bf16 rounding) can be staged through LDS into row-contiguous
-//     16-byte stores.
+//     so a lane owns four consecutive output columns per register group; the epilogue
+//     (bias, residual, bf16 rounding) is staged through the free LDS stage into
+//     row-contiguous 16-byte stores.
 //   * tiles are handed out so that the workgroups running on one XCD at the same time
 //     form a 4 x 8 patch of the tile grid and share operand panels in that XCD's L2.
 //
 // fp32 path (and shapes the MFMA path does not cover): a plain LDS-tiled FMA kernel with
 // arbitrary strides; ascending-k accumulation as well.
 #include <stdlib.h>
+#include <type_traits>
 #include "kernels.h"
 
 namespace {
+
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is named as a clobber on purpose
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -44,100 +49,129 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int BK = 32;            // k-values per LDS tile row (64 bytes)
-constexpr int NSTAGE = 3;
-constexpr int DEPTH = 2;         // K-tiles in flight in registers (two register sets)
 constexpr unsigned kOob = 0xFFFFFFF0u;   // byte offset beyond any descriptor's range
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-// LDS placement of tile row `row`: rows are permuted inside aligned groups of four by bits
-// 3-4 of the row index, so that the transposing writers (whose lanes hold rows 8 apart)
-// spread over all banks too
-__device__ __forceinline__ int lds_row(int row) { return row ^ ((row >> 3) & 3); }
-// byte offset inside a stage of 16-byte chunk `ch` (0..3) of tile row `row`
-__device__ __forceinline__ int lds_off(int row, int ch) {
-  const int p = lds_row(row);
-  return p * 64 + (((ch ^ (p >> 2)) & 3) << 4);
-}
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+constexpr int NS = 5;             // LDS stages
+constexpr int AHEAD = 4;          // K-tiles between the load cursor and the compute cursor
 
-// Loads one operand tile (ROWS x BK) from HBM into registers and stores it to an LDS stage.
-// Thread constants are tile independent; a tile contributes its origin offset only.
-template <int ROWS, bool KC, int NT>
-struct TileLoader {
-  static constexpr int NL = ROWS * 4 / NT;  // 16-byte loads per thread per tile
-  static constexpr int RSTEP = NT / 4;      // KC: rows between a thread's consecutive loads
-  struct Regs { u32x4 r[NL]; };             // one tile in flight
-  struct Tile { unsigned org; bool xoob; }; // byte offset of the tile origin; strided: chunk outside
+// Requests one operand tile (ROWS x BK) from HBM straight into an LDS stage: every wave
+// instruction moves 64 x 16 bytes to 1 KB of consecutive LDS; which 16 bytes of the tile a
+// lane asks for is free, and that choice realises the swizzle.
+//   K-contiguous operand: LDS rows of 64 bytes (32 k-values of one tile row), the four
+//     16-byte chunks of row r stored at position chunk ^ (r/4)%4.
+//   K-strided operand: LDS rows of ROWS*2 bytes (one k-row of the tile), the 64-byte chunks
+//     of k-row k stored at position chunk ^ k%4; fragments come out with transposing reads.
+template <int ROWS, bool KC, int NWAVES>
+struct DmaLoader {
+  static constexpr int NI = ROWS / 16 / NWAVES;     // wave instructions per wave and K-tile
+  static constexpr int ROWB = ROWS * 2;             // strided: bytes per k-row
+  static constexpr int RPI = 1024 / ROWB;           // strided: k-rows per wave instruction
+  struct Tile { unsigned org; unsigned oobmask; };
 
-  unsigned rel;         // byte offset of load 0 relative to the tile origin at K-tile 0
-  unsigned jstep;       // bytes between a thread's consecutive loads
+  unsigned rel[NI];     // byte offset of instruction j's chunk relative to the tile origin at K-tile 0
   unsigned kstep;       // bytes between consecutive K-tiles
-  int kofs;             // KC: first k of this thread's chunk
-  int soff;             // KC: LDS byte offset of load 0
-  int kb, c;            // strided: k-run and 8-column chunk owned by this thread
+  int kofs;             // KC: first k of this lane's chunk
+  int xofs[NI];         // strided: first tile column of this lane's chunk
+  int wave_base;        // LDS byte offset of this wave's first instruction inside the operand area
 
   __device__ __forceinline__ void init(int64_t ld) {
-    const int t = threadIdx.x;
-    if constexpr (KC) {
-      const int kc = t & 3, row = t >> 2;
-      kofs = kc * 8;
-      kstep = BK * 2;
-      rel = (unsigned)(((int64_t)row * ld + kofs) * 2);
-      jstep = (unsigned)(RSTEP * ld * 2);
-      soff = lds_off(row, kc);
-      kb = 0; c = 0;
-    } else {
-      constexpr int NKB = BK / NL;          // threads along k
-      kb = t % NKB; c = t / NKB;
-      kofs = 0; soff = 0;
-      kstep = (unsigned)(BK * ld * 2);
-      rel = (unsigned)(((int64_t)(kb * NL) * ld + 8 * c) * 2);
-      jstep = (unsigned)(ld * 2);
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    wave_base = w * NI * 1024;
+    kofs = 0;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      if constexpr (KC) {
+        const int r = 16 * (w * NI + j) + (lane >> 2), pos = lane & 3;
+        const int ch = pos ^ ((r >> 2) & 3);
+        kofs = ch * 8;
+        rel[j] = (unsigned)(((int64_t)r * ld + ch * 8) * 2);
+        xofs[j] = 0;
+        kstep = BK * 2;
+      } else {
+        const int byte = 16 * lane;
+        const int kr = (w * NI + j) * RPI + byte / ROWB, bp = byte % ROWB;
+        const int c64 = (bp >> 6) ^ (kr & 3), p = (bp & 63) >> 4;
+        xofs[j] = c64 * 32 + p * 8;
+        rel[j] = (unsigned)(((int64_t)kr * ld + xofs[j]) * 2);
+        kstep = (unsigned)(BK * ld * 2);
+      }
     }
   }
 
   __device__ __forceinline__ Tile tile(int64_t ld, int x0, int X) const {
     Tile tl;
-    if constexpr (KC) { tl.org = (unsigned)((int64_t)x0 * ld * 2); tl.xoob = false; }
-    else { tl.org = (unsigned)(x0 * 2); tl.xoob = (x0 + 8 * c) >= X; }
+    tl.oobmask = 0;
+    if constexpr (KC) tl.org = (unsigned)((int64_t)x0 * ld * 2);
+    else {
+      tl.org = (unsigned)(x0 * 2);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) if (x0 + xofs[j] >= X) tl.oobmask |= 1u << j;
+    }
     return tl;
   }
 
-  // K-tile kt (absolute index) of tile tl; reads as zeros when !valid, at or past kt_end,
-  // or outside the matrix (rows past the end fall outside the descriptor's range)
-  __device__ __forceinline__ void load(Regs& g, __amdgpu_buffer_rsrc_t rsrc, const Tile& tl, int kt, int K,
-                                       int kt_end, bool valid) const {
-    bool oob = tl.xoob || !valid || kt >= kt_end;
+  // K-tile kt (absolute index) of tile tl -> operand area `dst` of a stage; zeros when
+  // !valid, at or past kt_lim, or outside the matrix (rows past the end fall outside the
+  // descriptor's range)
+  __device__ __forceinline__ void issue(i32x4 rsrc, const Tile& tl, int kt, int K, int kt_lim,
+                                        bool valid, unsigned dst) const {
+    bool oob = !valid || kt >= kt_lim;
     if constexpr (KC) oob = oob || (kt * BK + kofs) >= K;
-    const unsigned base = tl.org + rel + (unsigned)kt * kstep;
+    const unsigned base = tl.org + (unsigned)kt * kstep;
 #pragma unroll
-    for (int j = 0; j < NL; ++j) {
-      const unsigned off = oob ? kOob : base + (unsigned)j * jstep;
-      g.r[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+    for (int j = 0; j < NI; ++j) {
+      const unsigned off = (oob || ((tl.oobmask >> j) & 1)) ? kOob : base + rel[j];
+      // m0 = LDS byte address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Written as
+      // assembly so that the compiler's wait-count pass does not see an LDS write and put a
+      // full vmcnt(0) in front of every following LDS read; completion is waited for by
+      // hand (wait_loads in the kernel).  The compiler itself never uses m0 in this file.
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(rsrc) : "m0");
     }
   }
+};
 
-  __device__ __forceinline__ void store(const Regs& g, unsigned char* __restrict__ stage) const {
+// Fragment addresses of one operand inside its stage area: NF blocks of 32 tile rows
+// starting at row w0, for lane (lr = lane%32, hb = lane/32).
+template <int ROWS, bool KC, int NF>
+struct FragReader {
+  int addr[KC ? 1 : NF];
+  int ch[2];
+  __device__ __forceinline__ void init(int w0) {
+    const int lane = threadIdx.x & 63;
     if constexpr (KC) {
-#pragma unroll
-      for (int j = 0; j < NL; ++j) *reinterpret_cast<u32x4*>(stage + soff + j * RSTEP * 64) = g.r[j];
+      const int lr = lane & 31, hb = lane >> 5, sw = (lr >> 2) & 3;
+      addr[0] = (w0 + lr) * 64;
+      ch[0] = ((hb ^ sw) & 3) << 4; ch[1] = (((2 + hb) ^ sw) & 3) << 4;
     } else {
-      const int kel = kb * NL;                       // first k of this thread's run
-      const int kch = kel >> 3, kin = (kel & 7) * 2; // 16-byte chunk and byte inside it
+      const int G = lane >> 4, i = lane & 15, hh = G >> 1, q = i >> 2, g = i & 3;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        unsigned o[NL / 2];
-#pragma unroll
-        for (int p = 0; p < NL / 2; ++p) {
-          const unsigned lo = g.r[2 * p][i >> 1], hi = g.r[2 * p + 1][i >> 1];
-          o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-        }
-        unsigned char* dst = stage + lds_off(8 * c + i, kch) + kin;
-        if constexpr (NL == 4) { u32x2 v = {o[0], o[1]}; *reinterpret_cast<u32x2*>(dst) = v; }
-        else *reinterpret_cast<unsigned*>(dst) = o[0];
+      for (int f = 0; f < NF; ++f) {
+        const int c64 = (w0 + 32 * f) >> 5;
+        addr[f] = (8 * hh + q) * (ROWS * 2) + ((c64 ^ q) << 6) + 32 * (G & 1) + 8 * g;
       }
+      ch[0] = 0; ch[1] = 0;
+    }
+  }
+  // fragment f for k-step ks (0/1) of the K-tile in operand area `base`
+  __device__ __forceinline__ bf16x8 read(const lds_byte* base, int f, int ks) const {
+    if constexpr (KC) {
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(base + addr[0] + f * 32 * 64 + ch[ks]);
+    } else {
+      const lds_byte* p = base + addr[f] + ks * 16 * (ROWS * 2);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * (ROWS * 2)));
+      typedef __attribute__((ext_vector_type(8))) short s16x8;
+      const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
     }
   }
 };
@@ -153,7 +187,7 @@ struct WorkItem {
 // kernel adds the pieces in ascending s.  ksplit depends on the problem shape only.
 //
 // A workgroup streams the K-tiles of ALL its work items through one pipeline: a load
-// cursor runs DEPTH+2 K-tiles ahead of the compute cursor and crosses item boundaries, so
+// cursor runs AHEAD K-tiles ahead of the compute cursor and crosses item boundaries, so
 // the first tiles of the next item are already in LDS while the epilogue of the current one
 // runs (the other wave on the SIMD keeps the matrix cores busy meanwhile).
 template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK>
@@ -177,10 +211,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave / NWN) * WM, wn = (wave % NWN) * WN;
   const int lr = lane & 31, hb = lane >> 5;
-  const int sw = (lr >> 2) & 3;
-  // fragment addresses inside a stage: row offset plus the swizzled chunk for k-step 0 / 1
-  const int fa_row = (wm + lds_row(lr)) * 64, fb_row = BM * 64 + (wn + lds_row(lr)) * 64;
-  const int ch0 = ((hb ^ sw) & 3) << 4, ch1 = (((2 + hb) ^ sw) & 3) << 4;
+  lds_byte* const lds = (lds_byte*)smem;
   const int nk_all = (K + BK - 1) / BK;
 
   // Work order.  The output is cut into coarse tiles of (sub*BM) x (sub*BN), listed
@@ -230,31 +261,35 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   WorkItem cur = get_item(0);
   if (!cur.valid) return;          // only the last round is partial, so nothing follows either
 
-  typedef TileLoader<BM, A_KC, NT> LA;
-  typedef TileLoader<BN, B_KC, NT> LB;
+  typedef DmaLoader<BM, A_KC, NWM * NWN> LA;
+  typedef DmaLoader<BN, B_KC, NWM * NWN> LB;
   LA la; LB lb;
   la.init(lda); lb.init(ldb);
-  typename LA::Regs sa[DEPTH];
-  typename LB::Regs sb[DEPTH];
+  constexpr int NLOADS = LA::NI + LB::NI;      // requests per lane and K-tile
 
-  // load cursor: the next K-tile to fetch
+  // load cursor: the next K-tile to request
   WorkItem lit = cur;
   int lround = 0, lkt = cur.kt0;
   typename LA::Tile lta = la.tile(lda, lit.m0, M);
   typename LB::Tile ltb = lb.tile(ldb, lit.n0, N);
-  auto issue = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
-    la.load(ga, ra, lta, lkt, K, lit.kt_end, lit.valid);
-    lb.load(gb, rb, ltb, lkt, K, lit.kt_end, lit.valid);
+  // buffer descriptors for the direct-to-LDS requests: base, no stride, size in bytes, raw 32-bit format
+  auto desc = [](const void* p, uint32_t bytes) {
+    i32x4 d;
+    d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
+    d.z = (int)bytes; d.w = 0x00020000;
+    return d;
+  };
+  const i32x4 da = desc(A, a_bytes), db = desc(B, b_bytes);
+  const unsigned lds0 = (unsigned)(uintptr_t)lds;      // LDS byte address of the dynamic segment
+  auto issue = [&](int stage) {
+    la.issue(da, lta, lkt, K, lit.kt_end, lit.valid, lds0 + (unsigned)stage);
+    lb.issue(db, ltb, lkt, K, lit.kt_end, lit.valid, lds0 + (unsigned)(stage + BM * 64));
   };
   auto load_cursor_next_item = [&]() {
     lit = get_item(++lround);
     lkt = lit.kt0;
     lta = la.tile(lda, lit.m0, M);
     ltb = lb.tile(ldb, lit.n0, N);
-  };
-  auto fetch = [&](typename LA::Regs& ga, typename LB::Regs& gb) {    // prologue only
-    issue(ga, gb);
-    if (++lkt >= lit.kt_end && lit.valid) load_cursor_next_item();
   };
 
   f32x16 acc[TM][TN];
@@ -265,22 +300,30 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // prologue: the first two K-tiles of the stream into LDS, the next DEPTH into registers
-  fetch(sa[0], sb[0]);
-  fetch(sa[1], sb[1]);
-  la.store(sa[0], smem); lb.store(sb[0], smem + BM * 64);
-  la.store(sa[1], smem + STAGE); lb.store(sb[1], smem + STAGE + BM * 64);
+  // stage ring: K-tile number t of the stream lives in stage t % NS
+  int si = 0;                                   // stage of the compute cursor's K-tile
+  auto stg = [&](int ahead) { const int i = si + ahead; return (i >= NS ? i - NS : i) * STAGE; };
+  // vmcnt(n) alone: lgkmcnt and expcnt fields at "no wait"
+  auto wait_loads = [](auto n) { constexpr int N = decltype(n)::value; __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14)); };
+
+  // prologue: the first AHEAD K-tiles of the stream are requested; the first two must have
+  // landed before anyone reads
 #pragma unroll
-  for (int u = 0; u < DEPTH; ++u) fetch(sa[u], sb[u]);
+  for (int u = 0; u < AHEAD; ++u) {
+    issue(u * STAGE);
+    if (++lkt >= lit.kt_end && lit.valid) load_cursor_next_item();
+  }
+  wait_loads(std::integral_constant<int, 2 * NLOADS>{});
   __syncthreads();
 
-  int rd = 0, nx = STAGE, wr = 2 * STAGE;            // stage byte offsets: read / next / write
+  FragReader<BM, A_KC, TM> fra; FragReader<BN, B_KC, TN> frb;
+  fra.init(wm); frb.init(wn);
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  auto frags = [&](bf16x8* fa, bf16x8* fb, int stage, int ch) {
+  auto frags = [&](bf16x8* fa, bf16x8* fb, int stage, int ks) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(smem + stage + fa_row + i * 32 * 64 + ch);
+    for (int i = 0; i < TM; ++i) fa[i] = fra.read(lds + stage, i, ks);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(smem + stage + fb_row + j * 32 * 64 + ch);
+    for (int j = 0; j < TN; ++j) fb[j] = frb.read(lds + stage + BM * 64, j, ks);
   };
   auto mfmas = [&](const bf16x8* fa, const bf16x8* fb) {
 #pragma unroll
@@ -289,7 +332,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
   };
-  frags(fa0, fb0, rd, ch0);
+  frags(fa0, fb0, 0, 0);
 
   // Epilogue of one work item.  acc[i][j][4g+e] is output (row m0+wm+32i+lr, column
   // n0+wn+32j+8g+4hb+e): a lane holds 4-column pieces of 32 different rows, which would
@@ -297,8 +340,8 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   // per-wave patch of the LDS stage that is free between two pipeline steps (fp32, XOR
   // swizzled) and leaves row-contiguous: 64-byte runs of bf16 (bias and residual added in
   // fp32, one rounding) or full 128-byte lines of fp32 pieces.
-  auto finish = [&](const WorkItem& it) {
-    float* stg = reinterpret_cast<float*>(smem + wr) + wave * 1024;
+  auto finish = [&](const WorkItem& it, int free_stage) {
+    float* patch = reinterpret_cast<float*>(smem + free_stage) + wave * 1024;
     // bias for the 8 columns this lane writes back (same for every row block)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -319,7 +362,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
         for (int g = 0; g < 4; ++g) {
           const int cg = (2 * g + hb) ^ ((lr >> 1) & 7);
           float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-          *reinterpret_cast<float4*>(stg + lr * 32 + cg * 4) = v;
+          *reinterpret_cast<float4*>(patch + lr * 32 + cg * 4) = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -329,7 +372,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int r = (lane >> 3) + 8 * q, cgl = lane & 7;
-            const float4 v = *reinterpret_cast<const float4*>(stg + r * 32 + ((cgl ^ ((r >> 1) & 7)) * 4));
+            const float4 v = *reinterpret_cast<const float4*>(patch + r * 32 + ((cgl ^ ((r >> 1) & 7)) * 4));
             const int row = rb0 + r, col = cb + 4 * cgl;
             if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
           }
@@ -338,8 +381,8 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
           for (int q = 0; q < 2; ++q) {
             const int r = (lane >> 2) + 16 * q, c8 = lane & 3;
             const int sx = (r >> 1) & 7;
-            const float4 v0 = *reinterpret_cast<const float4*>(stg + r * 32 + (((2 * c8) ^ sx) * 4));
-            const float4 v1 = *reinterpret_cast<const float4*>(stg + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
+            const float4 v0 = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8) ^ sx) * 4));
+            const float4 v1 = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
             const int row = rb0 + r, col = cb + 8 * c8;
             const unsigned off = (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
             const u32x4 rraw = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off, 0, 0);
@@ -367,65 +410,53 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 
 
   int round = 0, kt = cur.kt0;
-  static_assert(DEPTH == 2, "the step pairs below alternate between two register sets");
-  // One pipeline step: the K-tile two ahead of the compute cursor (in registers since two
-  // steps) goes to LDS, the K-tile four ahead is requested from HBM, the current K-tile is
-  // multiplied.  The step is straight-line code (work-list bookkeeping happens between
-  // runs of steps), so it is one scheduling region, and the group barriers below lay its
-  // memory operations out between the MFMAs: fragment reads one at a time under the first
-  // MFMAs of a batch, the LDS writes under the last MFMAs of the first batch, the HBM
-  // requests under the last MFMAs of the second.  Issued in a burst instead, they fill the
-  // LDS queue and the wave cannot issue its next MFMA until the queue drains.
-  auto step = [&](typename LA::Regs& ga, typename LB::Regs& gb) {
-    frags(fa1, fb1, rd, ch1);            // k-step 1 of this K-tile
-    la.store(ga, smem + wr); lb.store(gb, smem + wr + BM * 64);
-    issue(ga, gb);
+  // One pipeline step, straight-line: the K-tile AHEAD of the compute cursor is requested
+  // into the stage that was read last step, the current K-tile is multiplied, and before
+  // the barrier every wave waits for its own requests of the K-tile two ahead, so that
+  // after the barrier that tile is complete for all waves.
+  auto step = [&]() {
+    const int rd = stg(0), nx = stg(1), ldst = stg(AHEAD);
+    frags(fa1, fb1, rd, 1);              // k-step 1 of this K-tile
+    issue(ldst);
     mfmas(fa0, fb0);
-    frags(fa0, fb0, nx, ch0);            // k-step 0 of the next K-tile (visible since the last barrier)
+    frags(fa0, fb0, nx, 0);              // k-step 0 of the next K-tile
     mfmas(fa1, fb1);
 #ifndef GEMM_NO_SCHED_GROUPS
     {
-      constexpr int NM = TM * TN, NR = TM + TN;       // MFMAs and fragment reads per batch
-      constexpr int NW = (A_KC ? LA::NL : 8) + (B_KC ? LB::NL : 8);   // LDS writes per step
-      constexpr int NV = LA::NL + LB::NL;                             // HBM requests per step
-      constexpr int FREE = NM > NR ? NM - NR : NM;    // MFMAs that carry the writes / requests
+      constexpr int NM = TM * TN;
+      constexpr int NR = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);   // LDS reads per batch
+      constexpr int RPM = (NR + NM - 1) / NM;
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, (NR + NM - 1) / NM, 0);
-        if (q >= NM - FREE) __builtin_amdgcn_sched_group_barrier(0x200, (NW + FREE - 1) / FREE, 0);
+        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+        if (q >= NM - 2) __builtin_amdgcn_sched_group_barrier(0x020, (NLOADS + 1) / 2, 0);
       }
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, (NR + NM - 1) / NM, 0);
-        if (q >= NM - FREE) __builtin_amdgcn_sched_group_barrier(0x020, (NV + FREE - 1) / FREE, 0);
+        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
       }
     }
 #endif
+    wait_loads(std::integral_constant<int, 2 * NLOADS>{});
     __syncthreads();
-    const int t = rd; rd = nx; nx = wr; wr = t;
+    si = si + 1 >= NS ? 0 : si + 1;
     ++lkt; ++kt;
   };
   while (true) {
-    // run of steps until the compute cursor ends its item or the load cursor ends the one
-    // it reads from
     int n = cur.kt_end - kt;
     if (lit.valid) n = min(n, lit.kt_end - lkt);
-    for (; n >= 2; n -= 2) { step(sa[0], sb[0]); step(sa[1], sb[1]); }
-    if (n) {                             // odd run: one more step, then the two sets trade places
-      step(sa[0], sb[0]);
-      const typename LA::Regs ta = sa[0]; sa[0] = sa[1]; sa[1] = ta;
-      const typename LB::Regs tb = sb[0]; sb[0] = sb[1]; sb[1] = tb;
-    }
+    for (; n > 0; --n) step();
     if (lit.valid && lkt >= lit.kt_end) load_cursor_next_item();
     if (kt >= cur.kt_end) {
-      finish(cur);
+      finish(cur, stg(NS - 1));
       cur = get_item(++round);
       kt = cur.kt0;
       if (!cur.valid) break;
     }
   }
+  wait_loads(std::integral_constant<int, 0>{});
 }
 
 // out[row][col] = bf16( P[0] + P[1] + ... ) in ascending piece order
@@ -519,7 +550,7 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
                           uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, int ksplit = 1,
                           int ktiles_per = 0, float* P = nullptr, int sub = 1, int tile_begin = 0,
                           int tile_count = -1) {
-  constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64;
+  constexpr size_t smem = (size_t)NS * (BM + BN) * 64;
   auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK>;
   static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
   if (!attr_set) {
