@@ -58,6 +58,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+#ifndef GEMM_RPM2
+#define GEMM_RPM2 1
+#endif
 constexpr int NS = 5;             // LDS stages
 constexpr int AHEAD = 4;          // K-tiles between the load cursor and the compute cursor
 
@@ -342,12 +345,29 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   // fp32, one rounding) or full 128-byte lines of fp32 pieces.
   auto finish = [&](const WorkItem& it, int free_stage) {
     float* patch = reinterpret_cast<float*>(smem + free_stage) + wave * 1024;
-    // bias for the 8 columns this lane writes back (same for every row block)
+    const bool has_r = R != nullptr;
+    // byte offset in C (and in the residual) of the 8 columns this lane writes back for row
+    // half q of block b; rows past M fall outside the descriptor's range
+    auto out_off = [&](int b, int q) -> unsigned {
+      const int row = it.m0 + wm + 32 * (b % TM) + (lane >> 2) + 16 * q;
+      const int col = it.n0 + wn + 32 * (b / TM) + 8 * (lane & 3);
+      return (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
+    };
+    // The residual of block b+1 is requested before block b is stored, so the wait for it
+    // never has to cover a store's acknowledgement.
+    u32x4 rnext[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+    if constexpr (!SPLITK) {
+      if (has_r) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(0, q), 0, 0);
+      }
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int cb = it.n0 + wn + 32 * j;                 // first column of the block
       float bvals[8];
       if constexpr (!SPLITK) {
+        // bias for the 8 columns this lane writes back (same for every row block)
         const int col = cb + 8 * (lane & 3);
         const u32x4 braw = __builtin_amdgcn_raw_buffer_load_b128(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
         const bf16x8 bv = __builtin_bit_cast(bf16x8, braw);
@@ -356,6 +376,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
+        const int b = j * TM + i;
         const int rb0 = it.m0 + wm + 32 * i;              // first row of the block
         // accumulator layout -> LDS: row lr, column group cg = 2g + hb (4 columns each)
 #pragma unroll
@@ -377,21 +398,27 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
             if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
           }
         } else {
+          float4 v0[2], v1[2];
 #pragma unroll
           for (int q = 0; q < 2; ++q) {
             const int r = (lane >> 2) + 16 * q, c8 = lane & 3;
             const int sx = (r >> 1) & 7;
-            const float4 v0 = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8) ^ sx) * 4));
-            const float4 v1 = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
-            const int row = rb0 + r, col = cb + 8 * c8;
-            const unsigned off = (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
-            const u32x4 rraw = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off, 0, 0);
-            const bf16x8 rv = __builtin_bit_cast(bf16x8, rraw);
-            const float vals[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+            v0[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8) ^ sx) * 4));
+            v1[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
+          }
+          const u32x4 rcur[2] = {rnext[0], rnext[1]};
+          if (has_r && b + 1 < TM * TN) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(b + 1, q), 0, 0);
+          }
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const bf16x8 rv = __builtin_bit_cast(bf16x8, rcur[q]);
+            const float vals[8] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w, v1[q].x, v1[q].y, v1[q].z, v1[q].w};
             bf16x8 o;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = (bf16)(vals[e] + bvals[e] + (float)rv[e]);
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rc, (int)off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rc, (int)out_off(b, q), 0, 0);
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -425,7 +452,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     {
       constexpr int NM = TM * TN;
       constexpr int NR = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);   // LDS reads per batch
-      constexpr int RPM = (NR + NM - 1) / NM;
+      constexpr int RPM = (NR + NM - 1) / NM, RPM2 = GEMM_RPM2 * RPM;
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -435,7 +462,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+        if (q * RPM2 < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM2, 0);   // early: they must land before the barrier
       }
     }
 #endif
