@@ -8,7 +8,15 @@
 // per-lane scalar.  The probabilities feed the second product O^T = V^T P^T straight from
 // registers: MFMA's contraction index may be enumerated in any order as long as both
 // operands agree, so V^T is read from LDS in the key order the accumulator layout
-// dictates (two 4-key runs per 16-key step).  V is transposed on its way into LDS.
+// dictates (two 4-key runs per 16-key step).
+//
+// Streamed tiles go from HBM straight into LDS (buffer_load ... lds), in natural row order
+// with the 16-byte chunks of a row XOR-swizzled; a lane chooses which chunk it requests, so
+// the swizzle costs nothing.  One copy of a tile serves both uses: as an operand whose
+// contraction runs along the row it is read with ds_read_b128, as an operand whose
+// contraction runs across rows (V in O^T = V^T P^T, K in dQ, Q and dO in dK / dV) with the
+// transposing read ds_read_b64_tr_b16, two per fragment.  The swizzle makes both kinds of
+// read conflict-free.
 //
 // Backward is split in two kernels so that every sum has one owner and a fixed order
 // (bit-identical for any grid): the dK/dV kernel owns 128 keys and streams query tiles;
@@ -27,70 +35,90 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Position of streamed row r inside a transposed LDS row: each group of 16 keeps its four
-// 4-runs in the order 0,2,1,3, so that the 8 indices a half-wave lane owns in registers
-// 8*s2 .. 8*s2+7 of an accumulator block (two 4-runs, 8 apart) are 16 contiguous bytes.
-__device__ __forceinline__ int tr_pos(int r) {
-  const int sub = (r >> 2) & 3;
-  return (r & ~15) + ((((sub & 1) << 1) | (sub >> 1)) << 2) + (r & 3);
-}
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
-// Cooperative loader of a tile of RS rows x D columns (row stride `rs` elements) by 256
-// threads.  A thread owns KB consecutive rows of one 8-column chunk; it can store the
-// tile in natural form [row][D+8] and/or transposed form [col][RS+4].
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is named as a clobber on purpose
+
+// A tile of RS rows x D bf16 columns in LDS, natural order, rows of 2*D bytes, filled by 256
+// threads with direct-to-LDS requests.  Chunk c (16 bytes) of row r sits at position
+// c ^ swz(r).  swz is chosen so that (a) sixteen lanes reading the same chunk of sixteen
+// consecutive rows and (b) sixteen lanes of a transposing read (four consecutive rows x 32
+// bytes, two neighbouring groups 32 bytes apart) both touch every bank once.
 template <int RS, int D>
-struct TileLoader {
-  static constexpr int KB = RS * D / 2048;
-  static_assert(KB >= 1, "tile too small for 256 threads");
-  static constexpr int PN = D + 8, PT = RS + 8;
-  uint4 r[KB];
+struct LdsTile {
+  static constexpr int ROWB = 2 * D;                 // bytes per row
+  static constexpr int BYTES = RS * ROWB;
+  static constexpr int RPI = 1024 / ROWB;            // rows per wave instruction (1 KB)
+  static constexpr int NI = BYTES / 1024 / 4;        // wave instructions per wave (4 waves)
+  static_assert(NI >= 1, "tile too small for four waves");
 
-  __device__ __forceinline__ void load(const bf16* __restrict__ src, int64_t rs, int row0, int limit) {
-    const int t = threadIdx.x, cc = t % (D / 8), rb = t / (D / 8);
+  __device__ static __forceinline__ int swz(int r) {
+    if constexpr (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+    else return (((r >> 1) & 1) << 2) | (((r >> 3) & 1) << 1) | ((r >> 2) & 1);
+  }
+
+  int rrow[NI], rcol[NI];   // row inside the tile and first column of this lane's chunk, per instruction
+  int wave_base;
+  __device__ __forceinline__ void init() {
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    wave_base = w * NI * 1024;
 #pragma unroll
-    for (int j = 0; j < KB; ++j) {
-      const int row = row0 + rb * KB + j;
-      r[j] = (row < limit) ? *reinterpret_cast<const uint4*>(src + (int64_t)row * rs + cc * 8) : make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < NI; ++j) {
+      const int byte = 16 * lane;
+      const int row = (w * NI + j) * RPI + byte / ROWB, pos = (byte % ROWB) >> 4;
+      rrow[j] = row;
+      rcol[j] = (pos ^ swz(row)) * 8;
     }
   }
-  __device__ __forceinline__ void store_nat(bf16* __restrict__ lds) const {
-    const int t = threadIdx.x, cc = t % (D / 8), rb = t / (D / 8);
+  // rows row0 .. row0+RS-1 of the matrix described by `desc` (row stride rs_bytes) -> LDS
+  // byte address dst; rows beyond the descriptor's range arrive as zeros.
+  __device__ __forceinline__ void issue(i32x4 desc, unsigned rs_bytes, int row0, unsigned dst) const {
 #pragma unroll
-    for (int j = 0; j < KB; ++j) *reinterpret_cast<uint4*>(lds + (rb * KB + j) * PN + cc * 8) = r[j];
-  }
-  __device__ __forceinline__ void store_tr(bf16* __restrict__ lds) const {
-    const int t = threadIdx.x, cc = t % (D / 8), rb = t / (D / 8);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      bf16* dst = lds + (cc * 8 + i) * PT + tr_pos(rb * KB);
-      if constexpr (KB == 1) {
-        const uint32_t w = (&r[0].x)[i >> 1];
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((i & 1) ? (w >> 16) : (w & 0xFFFFu));
-      } else {
-        uint32_t o[KB / 2];
-#pragma unroll
-        for (int p = 0; p < KB / 2; ++p) {
-          const uint32_t lo = (&r[2 * p].x)[i >> 1], hi = (&r[2 * p + 1].x)[i >> 1];
-          o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-        }
-        if constexpr (KB == 2) *reinterpret_cast<uint32_t*>(dst) = o[0];
-        else if constexpr (KB == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
-        else *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
-      }
+    for (int j = 0; j < NI; ++j) {
+      const unsigned off = (unsigned)(row0 + rrow[j]) * rs_bytes + (unsigned)rcol[j] * 2u;
+      // m0 = LDS address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Assembly, so that
+      // the compiler's wait-count pass does not put a vmcnt(0) in front of every LDS read;
+      // completion is waited for by hand before the barrier that publishes the tile.
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(desc) : "m0");
     }
+  }
+  // fragment whose contraction runs along the row: row `row`, columns 16*s + 8*hb .. +7
+  __device__ static __forceinline__ bf16x8 nat(const lds_byte* t, int row, int s, int hb) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(t + row * ROWB + (((2 * s + hb) ^ swz(row)) << 4));
+  }
+  // fragment whose contraction runs across rows: for the lane that owns column 32*cblk + lr
+  // of MFMA's first operand, rows kb + 4*hb + {0..3} and kb + 8 + 4*hb + {0..3} -- the eight
+  // streamed indices a lane of half hb holds in registers 8*s2 .. 8*s2+7 of a 32x32
+  // accumulator block when kb = block base + 16*s2
+  __device__ static __forceinline__ bf16x8 tr(const lds_byte* t, int cblk, int kb) {
+    const int lane = threadIdx.x & 63;
+    const int G = lane >> 4, i = lane & 15, hh = G >> 1, q = i >> 2, g = i & 3;
+    const int r0 = kb + 4 * hh + q, r1 = r0 + 8;
+    const int ch = 4 * cblk + 2 * (G & 1) + (g >> 1);
+    const lds_byte* p0 = t + r0 * ROWB + ((ch ^ swz(r0)) << 4) + (g & 1) * 8;
+    const lds_byte* p1 = t + r1 * ROWB + ((ch ^ swz(r1)) << 4) + (g & 1) * 8;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+    return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   }
 };
 
-// A-operand fragment from a natural tile: row `row`, columns 16*s + 8*hb .. +7
-__device__ __forceinline__ bf16x8 frag_nat(const bf16* lds, int pitch, int row, int s, int hb) {
-  return *reinterpret_cast<const bf16x8*>(lds + row * pitch + 16 * s + 8 * hb);
+// descriptor of the rows of one (sample, head) slice: base pointer, no stride, bytes up to
+// the end of the slice's last row, raw 32-bit format
+__device__ __forceinline__ i32x4 slice_desc(const bf16* p, int64_t rows, int64_t rs, int D) {
+  i32x4 d;
+  d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
+  d.z = (int)(uint32_t)(((rows - 1) * rs + D) * 2); d.w = 0x00020000;
+  return d;
 }
-// A-operand fragment from a transposed tile [c][tr_pos(r)]: row c, the 8 streamed indices
-// that a lane of half hb owns in registers 8*s2 .. 8*s2+7 of a 32x32 accumulator block
-// (base + 16*s2 + 4*hb + {0..3} and + 8), one 16-byte read thanks to tr_pos
-__device__ __forceinline__ bf16x8 frag_tr(const bf16* lds, int pitch, int c, int base, int s2, int hb) {
-  return *reinterpret_cast<const bf16x8*>(lds + c * pitch + base + 16 * s2 + 8 * hb);
-}
+// vmcnt(0) alone: every direct-to-LDS request of this wave has landed
+__device__ __forceinline__ void wait_requests() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }
+
 // registers 8*s2 .. 8*s2+7 of an accumulator block as a bf16 B-operand
 __device__ __forceinline__ bf16x8 pack8(const float* v) {
   bf16x8 o;
@@ -117,10 +145,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
                                                      float* __restrict__ lse, int B, int N, int H, int causal,
                                                      float scale_log2, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
-  typedef TileLoader<RS, D> L;
-  constexpr int KSZ = RS * L::PN, VSZ = D * L::PT;
+  typedef LdsTile<RS, D> L;
+  constexpr int STAGE = 2 * L::BYTES;                      // K | V
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);          // [2][KSZ + VSZ]
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  L ld;
+  ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
@@ -147,19 +178,20 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
     float m = -INFINITY, lsum = 0.f;
     const int kv_end = causal ? min(N, q0 + 128) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
-    L lk, lv;
-    lk.load(base + h, rs, 0, N);
-    lv.load(base + 2 * h, rs, 0, N);
+    const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
+    const unsigned rsb = (unsigned)(rs * 2);
     __syncthreads();                      // previous item's readers are done with buffer 0
-    lk.store_nat(smem);
-    lv.store_tr(smem + KSZ);
+    ld.issue(dk_, rsb, 0, lds0);
+    ld.issue(dv_, rsb, 0, lds0 + L::BYTES);
+    wait_requests();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-      const bf16* ks = smem + (t & 1) * (KSZ + VSZ);
-      const bf16* vt = ks + KSZ;
-      if (t + 1 < ntiles) {
-        lk.load(base + h, rs, (t + 1) * RS, N);
-        lv.load(base + 2 * h, rs, (t + 1) * RS, N);
+      const lds_byte* ks = smem + (t & 1) * STAGE;
+      const lds_byte* vs = ks + L::BYTES;
+      if (t + 1 < ntiles) {                // the other buffer was last read before the previous barrier
+        const unsigned nb = lds0 + (unsigned)(((t + 1) & 1) * STAGE);
+        ld.issue(dk_, rsb, (t + 1) * RS, nb);
+        ld.issue(dv_, rsb, (t + 1) * RS, nb + L::BYTES);
       }
       const int j0 = t * RS;
 #pragma unroll
@@ -171,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
         for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(ks, L::PN, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
         float sv[16];
         float mx = -INFINITY;
         // only blocks that touch the diagonal or the end of the sequence need the mask
@@ -209,15 +241,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
         const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(vt, L::PT, 32 * c + lr, 32 * sub, 0, hb), p0, o[c], 0, 0, 0);
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(vt, L::PT, 32 * c + lr, 32 * sub, 1, hb), p1, o[c], 0, 0, 0);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, 32 * sub), p0, o[c], 0, 0, 0);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, 32 * sub + 16), p1, o[c], 0, 0, 0);
         }
       }
-      if (t + 1 < ntiles) {
-        bf16* nk = smem + ((t + 1) & 1) * (KSZ + VSZ);
-        lk.store_nat(nk);
-        lv.store_tr(nk + KSZ);
-      }
+      wait_requests();                     // this wave's share of the next tile has landed
       __syncthreads();
     }
     const float ltot = lsum + __shfl_xor(lsum, 32, 64);
@@ -245,11 +273,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
                                                         bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                         float scale, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
-  typedef TileLoader<RS, D> L;
-  constexpr int NSZ = RS * L::PN, TSZ = D * L::PT;
+  typedef LdsTile<RS, D> L;
+  constexpr int STAGE = 2 * L::BYTES;                      // K | V
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);          // [2][K nat | V nat | K tr]
-  constexpr int STAGE = 2 * NSZ + TSZ;
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  L ld;
+  ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
@@ -282,19 +312,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
       for (int e = 0; e < 16; ++e) dq[c][e] = 0.f;
     const int kv_end = causal ? min(N, q0 + 128) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
-    L lk, lv;
-    lk.load(base + h, rs, 0, N);
-    lv.load(base + 2 * h, rs, 0, N);
+    const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
+    const unsigned rsb = (unsigned)(rs * 2);
     __syncthreads();
-    lk.store_nat(smem); lv.store_nat(smem + NSZ); lk.store_tr(smem + 2 * NSZ);
+    ld.issue(dk_, rsb, 0, lds0);
+    ld.issue(dv_, rsb, 0, lds0 + L::BYTES);
+    wait_requests();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-      const bf16* ks = smem + (t & 1) * STAGE;
-      const bf16* vs = ks + NSZ;
-      const bf16* kt = ks + 2 * NSZ;
+      const lds_byte* ks = smem + (t & 1) * STAGE;
+      const lds_byte* vs = ks + L::BYTES;
       if (t + 1 < ntiles) {
-        lk.load(base + h, rs, (t + 1) * RS, N);
-        lv.load(base + 2 * h, rs, (t + 1) * RS, N);
+        const unsigned nb = lds0 + (unsigned)(((t + 1) & 1) * STAGE);
+        ld.issue(dk_, rsb, (t + 1) * RS, nb);
+        ld.issue(dv_, rsb, (t + 1) * RS, nb + L::BYTES);
       }
       const int j0 = t * RS;
 #pragma unroll
@@ -306,8 +337,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
         for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(ks, L::PN, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(vs, L::PN, 32 * sub + lr, s, hb), dof[s], pacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(vs, 32 * sub + lr, s, hb), dof[s], pacc, 0, 0, 0);
         }
         float ds[16];
 #pragma unroll
@@ -320,14 +351,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
         const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(kt, L::PT, 32 * c + lr, 32 * sub, 0, hb), d0, dq[c], 0, 0, 0);
-          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(kt, L::PT, 32 * c + lr, 32 * sub, 1, hb), d1, dq[c], 0, 0, 0);
+          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(ks, c, 32 * sub), d0, dq[c], 0, 0, 0);
+          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(ks, c, 32 * sub + 16), d1, dq[c], 0, 0, 0);
         }
       }
-      if (t + 1 < ntiles) {
-        bf16* nk = smem + ((t + 1) & 1) * STAGE;
-        lk.store_nat(nk); lv.store_nat(nk + NSZ); lk.store_tr(nk + 2 * NSZ);
-      }
+      wait_requests();
       __syncthreads();
     }
     if (i < N) {
@@ -352,12 +380,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
                                                          bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                          float scale, int ktiles) {
   constexpr int RS = 32, NS = D / 16, NC = D / 32;
-  typedef TileLoader<RS, D> L;
-  constexpr int NSZ = RS * L::PN, TSZ = D * L::PT;
-  constexpr int STAGE = 2 * NSZ + 2 * TSZ;                 // Q nat | dO nat | Q tr | dO tr
+  typedef LdsTile<RS, D> L;
+  constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  float* stat = reinterpret_cast<float*>(smem + 2 * STAGE);  // [2][2][RS]: lse*log2e, delta
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  float* stat = reinterpret_cast<float*>(smem_raw + 2 * STAGE);  // [2][2][RS]: lse*log2e, delta
+  L ld;
+  ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
@@ -391,7 +421,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
       for (int e = 0; e < 16; ++e) { dk[c][e] = 0.f; dv[c][e] = 0.f; }
     const int q_begin = causal ? (k0 / RS) * RS : 0;
     const int ntiles = (N - q_begin + RS - 1) / RS;
-    L lq, ld;
     float st_l = 0.f, st_d = 0.f;
     auto load_stats = [&](int row0) {
       if (threadIdx.x < RS) {
@@ -400,28 +429,28 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
         st_d = (gi < N) ? del_b[gi] : 0.f;
       }
     };
-    auto store_all = [&](int buf) {
-      bf16* s0 = smem + buf * STAGE;
-      lq.store_nat(s0); ld.store_nat(s0 + NSZ); lq.store_tr(s0 + 2 * NSZ); ld.store_tr(s0 + 2 * NSZ + TSZ);
+    auto store_stats = [&](int buf) {
       if (threadIdx.x < RS) { stat[(buf * 2 + 0) * RS + threadIdx.x] = st_l; stat[(buf * 2 + 1) * RS + threadIdx.x] = st_d; }
     };
-    lq.load(base, rs, q_begin, N);
-    ld.load(dob, (int64_t)h, q_begin, N);
-    load_stats(q_begin);
+    const i32x4 dq_ = slice_desc(base, N, rs, D), do_ = slice_desc(dob, N, h, D);
+    const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
     __syncthreads();
-    store_all(0);
+    ld.issue(dq_, rsb, q_begin, lds0);
+    ld.issue(do_, hsb, q_begin, lds0 + L::BYTES);
+    load_stats(q_begin);
+    store_stats(0);
+    wait_requests();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
       const int buf = t & 1;
-      const bf16* qs = smem + buf * STAGE;
-      const bf16* dos = qs + NSZ;
-      const bf16* qt = qs + 2 * NSZ;
-      const bf16* dot = qt + TSZ;
+      const lds_byte* qs = smem + buf * STAGE;
+      const lds_byte* dos = qs + L::BYTES;
       const float* sl = stat + (buf * 2 + 0) * RS;
       const float* sd = stat + (buf * 2 + 1) * RS;
       if (t + 1 < ntiles) {
-        lq.load(base, rs, q_begin + (t + 1) * RS, N);
-        ld.load(dob, (int64_t)h, q_begin + (t + 1) * RS, N);
+        const unsigned nb = lds0 + (unsigned)((buf ^ 1) * STAGE);
+        ld.issue(dq_, rsb, q_begin + (t + 1) * RS, nb);
+        ld.issue(do_, hsb, q_begin + (t + 1) * RS, nb + L::BYTES);
         load_stats(q_begin + (t + 1) * RS);
       }
       const int ib = q_begin + t * RS;
@@ -431,8 +460,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
         for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(qs, L::PN, lr, s, hb), kf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_nat(dos, L::PN, lr, s, hb), vf[s], pacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), vf[s], pacc, 0, 0, 0);
         }
         float pv[16], ds[16];
 #pragma unroll
@@ -446,13 +475,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
         const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dot, L::PT, 32 * c + lr, 0, 0, hb), p0, dv[c], 0, 0, 0);
-          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dot, L::PT, 32 * c + lr, 0, 1, hb), p1, dv[c], 0, 0, 0);
-          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(qt, L::PT, 32 * c + lr, 0, 0, hb), d0, dk[c], 0, 0, 0);
-          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(qt, L::PT, 32 * c + lr, 0, 1, hb), d1, dk[c], 0, 0, 0);
+          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 0), p0, dv[c], 0, 0, 0);
+          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 16), p1, dv[c], 0, 0, 0);
+          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 0), d0, dk[c], 0, 0, 0);
+          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 16), d1, dk[c], 0, 0, 0);
         }
       }
-      if (t + 1 < ntiles) store_all(buf ^ 1);
+      if (t + 1 < ntiles) store_stats(buf ^ 1);
+      wait_requests();
       __syncthreads();
     }
     if (j < N) {
@@ -479,8 +509,7 @@ mosaic_status set_smem(K kern, size_t bytes) {
 
 template <int D>
 mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, bf16* O, float* lse) {
-  typedef TileLoader<64, D> L;
-  constexpr size_t smem = 2 * (size_t)(64 * L::PN + D * L::PT) * sizeof(bf16);
+  constexpr size_t smem = 2 * 2 * (size_t)LdsTile<64, D>::BYTES;
   static bool once = false;
   if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D>, smem)); once = true; }
   const int qtiles = (int)ceil_div(N, 128);
@@ -498,8 +527,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
   const int64_t items = (int64_t)B * H * tiles;
   const float scale = 1.0f / sqrtf((float)D);
   {
-    typedef TileLoader<32, D> L;
-    constexpr size_t smem = 2 * (size_t)(2 * 32 * L::PN + 2 * D * L::PT) * sizeof(bf16) + 2 * 2 * 32 * sizeof(float);
+    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<32, D>::BYTES + 2 * 2 * 32 * sizeof(float);
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D>, smem)); once = true; }
     const int grid = grid_for(quota, 2, items);
@@ -507,8 +535,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
     MOSAIC_LAUNCH_CHECK();
   }
   {
-    typedef TileLoader<64, D> L;
-    constexpr size_t smem = 2 * (size_t)(2 * 64 * L::PN + D * L::PT) * sizeof(bf16);
+    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<64, D>::BYTES;
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D>, smem)); once = true; }
     const int grid = grid_for(quota, (smem > 80 * 1024) ? 1 : 2, items);
