@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
 
 // ------------------------------------------------------------------------------- dQ
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
                                                         bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                         float scale, int qtiles) {
@@ -385,9 +385,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  float* stat = reinterpret_cast<float*>(smem_raw + 2 * STAGE);  // [2][2][RS]: lse*log2e, delta
+  // the V rows of the 128 owned keys stay in LDS for the whole item (as registers they would
+  // push the kernel past its register budget and into scratch)
+  typedef LdsTile<128, D> LV;
+  const lds_byte* vblk = smem + 2 * STAGE;
+  float* stat = reinterpret_cast<float*>(smem_raw + 2 * STAGE + LV::BYTES);  // [2][2][RS]: lse*log2e, delta
   L ld;
   ld.init();
+  LV ldv;
+  ldv.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
@@ -404,15 +410,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
     const float* lse_b = lse + ((int64_t)b * H + hd) * N;
     const float* del_b = delta + ((int64_t)b * H + hd) * N;
-    bf16x8 kf[NS], vf[NS];
+    bf16x8 kf[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      if (j < N) {
-        kf[s] = *reinterpret_cast<const bf16x8*>(base + h + (int64_t)j * rs + 16 * s + 8 * hb);
-        vf[s] = *reinterpret_cast<const bf16x8*>(base + 2 * h + (int64_t)j * rs + 16 * s + 8 * hb);
-      } else {
-        for (int e = 0; e < 8; ++e) { kf[s][e] = (bf16)0.f; vf[s][e] = (bf16)0.f; }
-      }
+      if (j < N) kf[s] = *reinterpret_cast<const bf16x8*>(base + h + (int64_t)j * rs + 16 * s + 8 * hb);
+      else { for (int e = 0; e < 8; ++e) kf[s][e] = (bf16)0.f; }
     }
     f32x16 dk[NC], dv[NC];
 #pragma unroll
@@ -437,6 +439,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
     __syncthreads();
     ld.issue(dq_, rsb, q_begin, lds0);
     ld.issue(do_, hsb, q_begin, lds0 + L::BYTES);
+    ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + 2 * STAGE);
     load_stats(q_begin);
     store_stats(0);
     wait_requests();
@@ -461,7 +464,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), vf[s], pacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
         }
         float pv[16], ds[16];
 #pragma unroll
@@ -527,7 +530,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
   const int64_t items = (int64_t)B * H * tiles;
   const float scale = 1.0f / sqrtf((float)D);
   {
-    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<32, D>::BYTES + 2 * 2 * 32 * sizeof(float);
+    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<32, D>::BYTES + LdsTile<128, D>::BYTES + 2 * 2 * 32 * sizeof(float);
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D>, smem)); once = true; }
     const int grid = grid_for(quota, 2, items);
@@ -538,7 +541,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
     constexpr size_t smem = 2 * 2 * (size_t)LdsTile<64, D>::BYTES;
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D>, smem)); once = true; }
-    const int grid = grid_for(quota, (smem > 80 * 1024) ? 1 : 2, items);
+    const int grid = grid_for(quota, 2, items);
     attn_bwd_dq_mfma<D><<<grid, 256, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
