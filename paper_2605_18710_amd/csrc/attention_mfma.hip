@@ -1,7 +1,8 @@
 // Flash-style attention for bf16 on the gfx950 matrix cores, head size 64 or 128.
 //
-// Forward: a workgroup owns 128 queries of one (sample, head), one wave per 32 queries, and
-// streams key/value tiles of 64 through LDS with online softmax.  Scores are computed
+// Forward: a workgroup of 4 or 8 waves owns 128 or 256 queries of one (sample, head), one
+// wave per 32 queries, and streams key/value tiles of 64 through a ring of LDS stages with
+// online softmax.  Scores are computed
 // transposed, S^T = K Q^T, so that in the 32x32 accumulator layout a lane owns ONE query
 // (column lane%32) and 16 keys (its registers): the row maximum and sum are in-lane
 // reductions plus one exchange between the two half-waves, and the running rescale is a
@@ -19,8 +20,8 @@
 // read conflict-free.
 //
 // Backward is split in two kernels so that every sum has one owner and a fixed order
-// (bit-identical for any grid): the dK/dV kernel owns 128 keys and streams query tiles;
-// the dQ kernel owns 128 queries and streams key tiles.  Both recompute P from the saved
+// (bit-identical for any grid): the dK/dV kernel owns 128 or 256 keys and streams query
+// tiles; the dQ kernel owns 128 or 256 queries and streams key tiles.  Both recompute P from the saved
 // row log-sum-exp; D_i = sum_c dO_ic O_ic comes from a small per-row kernel.
 #include "kernels.h"
 
@@ -42,18 +43,18 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 #pragma clang diagnostic ignored "-Winline-asm"   // m0 is named as a clobber on purpose
 
-// A tile of RS rows x D bf16 columns in LDS, natural order, rows of 2*D bytes, filled by 256
-// threads with direct-to-LDS requests.  Chunk c (16 bytes) of row r sits at position
+// A tile of RS rows x D bf16 columns in LDS, natural order, rows of 2*D bytes, filled by a
+// workgroup of NW waves with direct-to-LDS requests.  Chunk c (16 bytes) of row r sits at position
 // c ^ swz(r).  swz is chosen so that (a) sixteen lanes reading the same chunk of sixteen
 // consecutive rows and (b) sixteen lanes of a transposing read (four consecutive rows x 32
 // bytes, two neighbouring groups 32 bytes apart) both touch every bank once.
-template <int RS, int D>
+template <int RS, int D, int NW>
 struct LdsTile {
   static constexpr int ROWB = 2 * D;                 // bytes per row
   static constexpr int BYTES = RS * ROWB;
   static constexpr int RPI = 1024 / ROWB;            // rows per wave instruction (1 KB)
-  static constexpr int NI = BYTES / 1024 / 4;        // wave instructions per wave (4 waves)
-  static_assert(NI >= 1, "tile too small for four waves");
+  static constexpr int NI = BYTES / 1024 / NW;       // wave instructions per wave (NW waves)
+  static_assert(NI >= 1, "tile too small for the workgroup");
 
   __device__ static __forceinline__ int swz(int r) {
     if constexpr (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
@@ -116,8 +117,17 @@ __device__ __forceinline__ i32x4 slice_desc(const bf16* p, int64_t rows, int64_t
   d.z = (int)(uint32_t)(((rows - 1) * rs + D) * 2); d.w = 0x00020000;
   return d;
 }
-// vmcnt(0) alone: every direct-to-LDS request of this wave has landed
-__device__ __forceinline__ void wait_requests() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }
+// vmcnt(N) alone: all but the newest N requests of this wave have landed
+template <int N>
+__device__ __forceinline__ void wait_requests() {
+  static_assert(N < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+// Streamed tiles live in a ring of NST stages; tile t+PD is requested at the start of step t
+// (its stage was last read in step t-1) and tile t+1 is waited for before the barrier that
+// ends step t.  Requests are issued for every step, past the last tile too (they point
+// outside the descriptor and fetch nothing), so that the wait count is a constant.
+template <int NW> struct Ring { static constexpr int NST = (NW == 8) ? 4 : 2, PD = NST - 1; };
 
 // registers 8*s2 .. 8*s2+7 of an accumulator block as a bf16 B-operand
 __device__ __forceinline__ bf16x8 pack8(const float* v) {
@@ -140,15 +150,16 @@ __device__ __forceinline__ int snake_item(int round, int items) {
 }
 
 // --------------------------------------------------------------------------- forward
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                      float* __restrict__ lse, int B, int N, int H, int causal,
                                                      float scale_log2, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
-  typedef LdsTile<RS, D> L;
+  typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // K | V
+  constexpr int NST = Ring<NW>::NST, PD = Ring<NW>::PD, QT = 32 * NW, NREQ = 2 * L::NI;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   L ld;
   ld.init();
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
     if (item < 0) continue;
     // late query tiles carry the most keys under a causal mask: rank them first
     const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
-    const int q0 = qt * 128, i0 = q0 + 32 * wave, i = i0 + lr;
+    const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     bf16x8 qf[NS];
 #pragma unroll
@@ -176,34 +187,48 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[c][e] = 0.f;
     float m = -INFINITY, lsum = 0.f;
-    const int kv_end = causal ? min(N, q0 + 128) : N;
+    const int kv_end = causal ? min(N, q0 + QT) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
     const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
     const unsigned rsb = (unsigned)(rs * 2);
-    __syncthreads();                      // previous item's readers are done with buffer 0
-    ld.issue(dk_, rsb, 0, lds0);
-    ld.issue(dv_, rsb, 0, lds0 + L::BYTES);
-    wait_requests();
+    auto request = [&](int tile) {         // tiles past the last one point outside the slice
+      const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
+      const int row0 = tile < ntiles ? tile * RS : N;
+      ld.issue(dk_, rsb, row0, nb);
+      ld.issue(dv_, rsb, row0, nb + L::BYTES);
+    };
+    __syncthreads();                      // previous item's readers are done with every stage
+#pragma unroll
+    for (int u = 0; u < PD; ++u) request(u);
+    wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-      const lds_byte* ks = smem + (t & 1) * STAGE;
+      const lds_byte* ks = smem + (t % NST) * STAGE;
       const lds_byte* vs = ks + L::BYTES;
-      if (t + 1 < ntiles) {                // the other buffer was last read before the previous barrier
-        const unsigned nb = lds0 + (unsigned)(((t + 1) & 1) * STAGE);
-        ld.issue(dk_, rsb, (t + 1) * RS, nb);
-        ld.issue(dv_, rsb, (t + 1) * RS, nb + L::BYTES);
-      }
+      request(t + PD);
       const int j0 = t * RS;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int jb = j0 + 32 * sub;
         if (jb >= kv_end || (causal && jb > i0 + 31)) continue;     // nothing for this wave
+        // all K fragments are requested before the first MFMA and all V fragments before
+        // the softmax arithmetic, so LDS latency is paid once per phase and hidden behind
+        // the MFMAs / the softmax (left alone, the scheduler reads two fragments at a time
+        // and stalls on each pair)
+        bf16x8 kfr[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfr[s] = L::nat(ks, 32 * sub + lr, s, hb);
+        __builtin_amdgcn_sched_barrier(0);
         f32x16 sacc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
+        bf16x8 vfr[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfr[c][0] = L::tr(vs, c, 32 * sub); vfr[c][1] = L::tr(vs, c, 32 * sub + 16); }
+        __builtin_amdgcn_sched_barrier(0);
         float sv[16];
         float mx = -INFINITY;
         // only blocks that touch the diagonal or the end of the sequence need the mask
@@ -241,11 +266,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
         const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, 32 * sub), p0, o[c], 0, 0, 0);
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, 32 * sub + 16), p1, o[c], 0, 0, 0);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][0], p0, o[c], 0, 0, 0);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][1], p1, o[c], 0, 0, 0);
         }
       }
-      wait_requests();                     // this wave's share of the next tile has landed
+      wait_requests<(PD - 1) * NREQ>();    // this wave's share of the next tile has landed
       __syncthreads();
     }
     const float ltot = lsum + __shfl_xor(lsum, 32, 64);
@@ -267,16 +292,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16* __restrict__
 }
 
 // ------------------------------------------------------------------------------- dQ
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
                                                         bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                         float scale, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
-  typedef LdsTile<RS, D> L;
+  typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // K | V
+  constexpr int NST = Ring<NW>::NST, PD = Ring<NW>::PD, QT = 32 * NW, NREQ = 2 * L::NI;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   L ld;
   ld.init();
@@ -290,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restric
     const int item = snake_item(round, items);
     if (item < 0) continue;
     const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
-    const int q0 = qt * 128, i0 = q0 + 32 * wave, i = i0 + lr;
+    const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
     bf16x8 qf[NS], dof[NS];
@@ -310,23 +336,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restric
     for (int c = 0; c < NC; ++c)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dq[c][e] = 0.f;
-    const int kv_end = causal ? min(N, q0 + 128) : N;
+    const int kv_end = causal ? min(N, q0 + QT) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
     const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
     const unsigned rsb = (unsigned)(rs * 2);
+    auto request = [&](int tile) {
+      const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
+      const int row0 = tile < ntiles ? tile * RS : N;
+      ld.issue(dk_, rsb, row0, nb);
+      ld.issue(dv_, rsb, row0, nb + L::BYTES);
+    };
     __syncthreads();
-    ld.issue(dk_, rsb, 0, lds0);
-    ld.issue(dv_, rsb, 0, lds0 + L::BYTES);
-    wait_requests();
+#pragma unroll
+    for (int u = 0; u < PD; ++u) request(u);
+    wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-      const lds_byte* ks = smem + (t & 1) * STAGE;
+      const lds_byte* ks = smem + (t % NST) * STAGE;
       const lds_byte* vs = ks + L::BYTES;
-      if (t + 1 < ntiles) {
-        const unsigned nb = lds0 + (unsigned)(((t + 1) & 1) * STAGE);
-        ld.issue(dk_, rsb, (t + 1) * RS, nb);
-        ld.issue(dv_, rsb, (t + 1) * RS, nb + L::BYTES);
-      }
+      request(t + PD);
       const int j0 = t * RS;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
@@ -355,7 +383,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restric
           dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(ks, c, 32 * sub + 16), d1, dq[c], 0, 0, 0);
         }
       }
-      wait_requests();
+      wait_requests<(PD - 1) * NREQ>();
       __syncthreads();
     }
     if (i < N) {
@@ -374,22 +402,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16* __restric
 }
 
 // --------------------------------------------------------------------------- dK, dV
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16* __restrict__ dqkv, int B, int N, int H, int causal,
                                                          float scale, int ktiles) {
   constexpr int RS = 32, NS = D / 16, NC = D / 32;
-  typedef LdsTile<RS, D> L;
+  typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
+  constexpr int NST = Ring<NW>::NST, PD = Ring<NW>::PD, KT = 32 * NW, NREQ = 2 * L::NI + 2;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  // the V rows of the 128 owned keys stay in LDS for the whole item (as registers they would
+  // the V rows of the owned keys stay in LDS for the whole item (as registers they would
   // push the kernel past its register budget and into scratch)
-  typedef LdsTile<128, D> LV;
-  const lds_byte* vblk = smem + 2 * STAGE;
-  float* stat = reinterpret_cast<float*>(smem_raw + 2 * STAGE + LV::BYTES);  // [2][2][RS]: lse*log2e, delta
+  typedef LdsTile<KT, D, NW> LV;
+  const lds_byte* vblk = smem + NST * STAGE;
+  const float* stat = reinterpret_cast<const float*>(smem_raw + NST * STAGE + LV::BYTES);  // [NST][2][64]: lse, delta
   L ld;
   ld.init();
   LV ldv;
@@ -405,7 +434,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
     if (item < 0) continue;
     // early key tiles see the most queries under a causal mask: rank them first
     const int kt_i = item / (B * H), hd = item % H, b = (item / H) % B;
-    const int k0 = kt_i * 128, j0w = k0 + 32 * wave, j = j0w + lr;
+    const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
     const float* lse_b = lse + ((int64_t)b * H + hd) * N;
@@ -423,39 +452,44 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
       for (int e = 0; e < 16; ++e) { dk[c][e] = 0.f; dv[c][e] = 0.f; }
     const int q_begin = causal ? (k0 / RS) * RS : 0;
     const int ntiles = (N - q_begin + RS - 1) / RS;
-    float st_l = 0.f, st_d = 0.f;
-    auto load_stats = [&](int row0) {
-      if (threadIdx.x < RS) {
-        const int gi = row0 + threadIdx.x;
-        st_l = (gi < N) ? lse_b[gi] * kLog2e : 0.f;
-        st_d = (gi < N) ? del_b[gi] : 0.f;
-      }
+    // per-row statistics of streamed tile `tile` (lse, delta) take the same road as the tiles:
+    // one 4-byte request per lane straight into the tile's stage slot.  Every wave issues
+    // them (same values, same place) so that all waves count the same number of requests.
+    auto desc_f32 = [&](const float* p) {
+      i32x4 d;
+      d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
+      d.z = N * 4; d.w = 0x00020000;
+      return d;
     };
-    auto store_stats = [&](int buf) {
-      if (threadIdx.x < RS) { stat[(buf * 2 + 0) * RS + threadIdx.x] = st_l; stat[(buf * 2 + 1) * RS + threadIdx.x] = st_d; }
+    const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
+    auto stage_stats = [&](int tile) {
+      const unsigned off = (lane < RS && tile < ntiles) ? (unsigned)(q_begin + tile * RS + lane) * 4u : 0xFFFFFFF0u;
+      const unsigned dst = lds0 + (unsigned)(NST * STAGE + LV::BYTES + (tile % NST) * 2 * 64 * 4);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
     };
     const i32x4 dq_ = slice_desc(base, N, rs, D), do_ = slice_desc(dob, N, h, D);
     const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
+    auto request = [&](int tile) {
+      const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
+      const int row0 = tile < ntiles ? q_begin + tile * RS : N;
+      ld.issue(dq_, rsb, row0, nb);
+      ld.issue(do_, hsb, row0, nb + L::BYTES);
+    };
     __syncthreads();
-    ld.issue(dq_, rsb, q_begin, lds0);
-    ld.issue(do_, hsb, q_begin, lds0 + L::BYTES);
-    ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + 2 * STAGE);
-    load_stats(q_begin);
-    store_stats(0);
-    wait_requests();
+    ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + NST * STAGE);
+#pragma unroll
+    for (int u = 0; u < PD; ++u) { request(u); stage_stats(u); }
+    wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-      const int buf = t & 1;
-      const lds_byte* qs = smem + buf * STAGE;
+      const int slot = t % NST;
+      const lds_byte* qs = smem + slot * STAGE;
       const lds_byte* dos = qs + L::BYTES;
-      const float* sl = stat + (buf * 2 + 0) * RS;
-      const float* sd = stat + (buf * 2 + 1) * RS;
-      if (t + 1 < ntiles) {
-        const unsigned nb = lds0 + (unsigned)((buf ^ 1) * STAGE);
-        ld.issue(dq_, rsb, q_begin + (t + 1) * RS, nb);
-        ld.issue(do_, hsb, q_begin + (t + 1) * RS, nb + L::BYTES);
-        load_stats(q_begin + (t + 1) * RS);
-      }
+      const float* sl = stat + (slot * 2 + 0) * 64;
+      const float* sd = stat + (slot * 2 + 1) * 64;
+      request(t + PD);
+      stage_stats(t + PD);
       const int ib = q_begin + t * RS;
       if (!(causal && ib + 31 < j0w) && j0w < N) {            // otherwise every (i, j) here is masked
         f32x16 sacc, pacc;
@@ -471,7 +505,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
         for (int r = 0; r < 16; ++r) {
           const int il = acc_row(r, hb), gi = ib + il;
           const bool masked = (gi >= N) || (j >= N) || (causal && j > gi);
-          const float p = masked ? 0.f : fast_exp2(sacc[r] * scale_log2 - sl[il]);
+          const float p = masked ? 0.f : fast_exp2(sacc[r] * scale_log2 - sl[il] * kLog2e);
           pv[r] = p;
           ds[r] = p * (pacc[r] - sd[il]);
         }
@@ -484,8 +518,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma(const bf16* __restri
           dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 16), d1, dk[c], 0, 0, 0);
         }
       }
-      if (t + 1 < ntiles) store_stats(buf ^ 1);
-      wait_requests();
+      wait_requests<(PD - 1) * NREQ>();
       __syncthreads();
     }
     if (j < N) {
@@ -510,39 +543,44 @@ mosaic_status set_smem(K kern, size_t bytes) {
   return MOSAIC_OK;
 }
 
-template <int D>
+// Workgroup shape.  The kernels are written for NW waves and a ring of stages; measured on
+// the 8 x 1024 x 16 x 128 causal problem, 8 waves with four stages (one workgroup per CU,
+// three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU):
+// the loop is bound by the softmax arithmetic sharing the VALU port with MFMA issue, not by
+// load latency.  Only the 4-wave shape is instantiated.
+template <int D, int NW>
 mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, bf16* O, float* lse) {
-  constexpr size_t smem = 2 * 2 * (size_t)LdsTile<64, D>::BYTES;
+  constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
   static bool once = false;
-  if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D>, smem)); once = true; }
-  const int qtiles = (int)ceil_div(N, 128);
+  if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
+  const int qtiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * qtiles;
-  const int grid = grid_for(quota, 2, items);
-  attn_fwd_mfma<D><<<grid, 256, smem, s>>>(qkv, O, lse, B, N, H, causal, kLog2e / sqrtf((float)D), qtiles);
+  const int grid = grid_for(quota, 8 / NW, items);
+  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, causal, kLog2e / sqrtf((float)D), qtiles);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
 
-template <int D>
+template <int D, int NW>
 mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, const float* lse,
                     const bf16* dO, bf16* dqkv, const float* delta) {
-  const int tiles = (int)ceil_div(N, 128);
+  const int tiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * tiles;
   const float scale = 1.0f / sqrtf((float)D);
+  const int grid = grid_for(quota, 8 / NW, items);
   {
-    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<32, D>::BYTES + LdsTile<128, D>::BYTES + 2 * 2 * 32 * sizeof(float);
+    constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<32, D, NW>::BYTES + LdsTile<32 * NW, D, NW>::BYTES +
+                            (size_t)Ring<NW>::NST * 2 * 64 * sizeof(float);
     static bool once = false;
-    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D>, smem)); once = true; }
-    const int grid = grid_for(quota, 2, items);
-    attn_bwd_dkv_mfma<D><<<grid, 256, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
+    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D, NW>, smem)); once = true; }
+    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   {
-    constexpr size_t smem = 2 * 2 * (size_t)LdsTile<64, D>::BYTES;
+    constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
     static bool once = false;
-    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D>, smem)); once = true; }
-    const int grid = grid_for(quota, 2, items);
-    attn_bwd_dq_mfma<D><<<grid, 256, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
+    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
+    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
@@ -554,13 +592,13 @@ bool attention_mfma_supported(int dtype, int d) { return dtype == MOSAIC_BF16 &&
 
 mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
                                         const void* qkv, void* O, float* lse) {
-  if (d == 64) return fwd_t<64>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
-  return fwd_t<128>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
+  if (d == 64) return fwd_t<64, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
+  return fwd_t<128, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
 }
 
 mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
                                         const void* qkv, const float* lse, const void* dO, void* dqkv,
                                         const float* delta) {
-  if (d == 64) return bwd_t<64>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
-  return bwd_t<128>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+  if (d == 64) return bwd_t<64, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+  return bwd_t<128, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
 }
