@@ -122,3 +122,90 @@ def test_full_stage_modes_are_bit_identical(mb):
         g = m.module.grads.float()
         assert torch.isfinite(g).all() and float(g.abs().max()) > 0
     stage.destroy()
+
+
+def _linear_three_forms(mb, T, k, n, seed, quotas=(256, 192)):
+    """Runs forward / input-gradient / weight-gradient of one linear layer at full shape for
+    two quotas, checks the bits agree, and returns host inputs and device outputs.  Activations
+    are drawn uniform in [-2, 2) here: the counter-based normal generator needs several
+    seconds per 10^7 values on the host and these operands hold 10^8."""
+    X = quantize(synth.uniform(seed, (T, k), -2.0, 2.0), "bf16")
+    W = quantize(synth.normal(seed + 1, (k, n), 0, 0.02), "bf16")
+    dY = quantize(synth.uniform(seed + 2, (T, n), -1.0, 1.0), "bf16")
+    X_, W_, dY_ = to_dev(X, "bf16"), to_dev(W, "bf16"), to_dev(dY, "bf16")
+    Y = torch.empty((T, n), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, k), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((k, n), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(1, mb.linear_wgrad_scratch_bytes(T, k, n)), dtype=torch.uint8, device="cuda")
+    snaps = []
+    for q in quotas:
+        mb.op_linear_fwd(None, q, "bf16", T, k, n, X_, W_, None, None, Y)
+        mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY_, W_, None, dX)
+        mb.op_linear_wgrad(None, q, "bf16", T, k, n, X_, dY_, dW, None, ws)
+        torch.cuda.synchronize()
+        snaps.append([bits(Y), bits(dX), bits(dW)])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b), "full-size result depends on the quota"
+    return X, W, dY, Y, dX, dW
+
+
+def _check_sampled(T, k, n, seed, X, W, dY, Y, dX, dW, edge_rows, edge_cols):
+    rows = synth.integers(seed + 3, (32,), 0, T)
+    rows[:len(edge_rows)] = edge_rows
+    ridx = torch.from_numpy(rows).long().cuda()
+    assert rel_l2(from_dev(Y[ridx]), X[rows] @ W) <= 2e-2
+    assert rel_l2(from_dev(dX[ridx]), dY[rows] @ W.T) <= 2e-2
+    cols = synth.integers(seed + 4, (16,), 0, n)
+    cols[:len(edge_cols)] = edge_cols
+    cidx = torch.from_numpy(cols).long().cuda()
+    assert rel_l2(from_dev(dW[:, cidx]), X.T @ dY[:, cols]) <= 2e-2
+
+
+def test_config3_decoder_output_projection_sampled(mb):
+    """7B-shaped decoder of configs[2]: T = 16 x 2048 tokens, attention output projection
+    4096 -> 4096 (2048 tiles of 256 x 256: eight whole rounds; the weight gradient contracts
+    over 32768 tokens)."""
+    T, k, n = 32768, 4096, 4096
+    out = _linear_three_forms(mb, T, k, n, 9100)
+    _check_sampled(T, k, n, 9100, *out, edge_rows=[0, 255, 256, T - 1], edge_cols=[0, 255, 256, n - 1])
+
+
+def test_config4_vit_qkv_projection_sampled(mb):
+    """6B-ViT slice of configs[3]: T = 4 x 1024 tokens, h = 3200 (12.5 tiles of 256: ragged in
+    both the contraction and the output), fused QKV projection 3200 -> 9600."""
+    T, k, n = 4096, 3200, 9600
+    out = _linear_three_forms(mb, T, k, n, 9200)
+    _check_sampled(T, k, n, 9200, *out, edge_rows=[0, 4095, 3840, 3839], edge_cols=[0, 9599, 9472, 9471])
+
+
+def test_config5_audio_attention_sampled_heads(mb):
+    """Audio encoder of configs[4]: B = 8, N = 1500 frames (not a multiple of the 64-row
+    streamed tile nor of the 128-row workgroup tile), 20 heads of 64, full attention."""
+    B, N, H, d = 8, 1500, 20, 64
+    h = H * d
+    qkv = quantize(synth.normal(9300, (B * N, 3 * h)), "bf16")
+    dO = quantize(synth.normal(9301, (B * N, h)), "bf16")
+    qkv_, dO_ = to_dev(qkv, "bf16"), to_dev(dO, "bf16")
+    Oo = torch.empty((B * N, h), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    dqkv = torch.empty_like(qkv_)
+    delta = torch.empty_like(lse)
+    snaps = []
+    for q in (256, 96):
+        mb.op_attention_fwd(None, q, "bf16", B, N, H, d, 0, qkv_, Oo, lse)
+        mb.op_attention_bwd(None, q, "bf16", B, N, H, d, 0, qkv_, Oo, lse, dO_, dqkv, delta)
+        torch.cuda.synchronize()
+        snaps.append([bits(Oo), bits(lse), bits(dqkv)])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b)
+    Oh, dh = from_dev(Oo), from_dev(dqkv)
+    for (b, t) in ((0, 0), (7, 19), (4, 11)):
+        rows = slice(b * N, (b + 1) * N)
+        c = slice(t * d, (t + 1) * d)
+        qh, kh, vh = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
+        o_ref, P = O.attention_head_fwd(qh, kh, vh, 0)
+        dq, dk, dv = O.attention_head_bwd(qh, kh, vh, P, dO[rows, c])
+        assert rel_l2(Oh[rows, c], o_ref) <= 2e-2
+        assert rel_l2(dh[rows, t * d:(t + 1) * d], dq) <= 2e-2
+        assert rel_l2(dh[rows, h + t * d:h + (t + 1) * d], dk) <= 2e-2
+        assert rel_l2(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv) <= 2e-2
