@@ -343,34 +343,57 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
   // per-wave patch of the LDS stage that is free between two pipeline steps (fp32, XOR
   // swizzled) and leaves row-contiguous: 64-byte runs of bf16 (bias and residual added in
   // fp32, one rounding) or full 128-byte lines of fp32 pieces.
-  auto finish = [&](const WorkItem& it, int free_stage) {
+  // Three variants, chosen by a uniform branch, so that each holds no request it does not
+  // need.  The compiler's wait before a use of a loaded value counts every request of the
+  // wave in issue order, stores included: a bias or residual request issued between two
+  // stores makes the block that uses it wait until all earlier blocks' stores have been
+  // acknowledged.
+  //   EPI_PLAIN: no bias, no residual - stores only, nothing waits.
+  //   EPI_BIAS:  every bias value is requested before the first store.
+  //   EPI_RES:   residual (and bias, if any: a null bias reads zeros through its empty
+  //              descriptor); the requests for block b+1 are issued before block b is stored,
+  //              so a wait never covers the newest stores.
+  constexpr int EPI_PLAIN = 0, EPI_BIAS = 1, EPI_RES = 2;
+  auto finish_impl = [&](const WorkItem& it, int free_stage, auto mode_) {
+    constexpr int MODE = decltype(mode_)::value;
     float* patch = reinterpret_cast<float*>(smem + free_stage) + wave * 1024;
-    const bool has_r = R != nullptr;
+    // The lane index passes through an empty asm so that the write-back offsets are computed
+    // here, per tile, instead of being kept in registers across the K loop.
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int elr = ln & 31, ehb = ln >> 5;
     // byte offset in C (and in the residual) of the 8 columns this lane writes back for row
     // half q of block b; rows past M fall outside the descriptor's range
     auto out_off = [&](int b, int q) -> unsigned {
-      const int row = it.m0 + wm + 32 * (b % TM) + (lane >> 2) + 16 * q;
-      const int col = it.n0 + wn + 32 * (b / TM) + 8 * (lane & 3);
+      const int row = it.m0 + wm + 32 * (b % TM) + (ln >> 2) + 16 * q;
+      const int col = it.n0 + wn + 32 * (b / TM) + 8 * (ln & 3);
       return (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
     };
-    // The residual of block b+1 is requested before block b is stored, so the wait for it
-    // never has to cover a store's acknowledgement.
+    // bias for the 8 columns this lane writes back in column block j (same for every row block)
+    auto bias_req = [&](int j) -> u32x4 {
+      const int col = it.n0 + wn + 32 * j + 8 * (ln & 3);
+      return __builtin_amdgcn_raw_buffer_load_b128(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
+    };
     u32x4 rnext[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
-    if constexpr (!SPLITK) {
-      if (has_r) {
+    u32x4 braw[MODE == EPI_BIAS ? TN : 1] = {};
+    u32x4 bnext = {0u, 0u, 0u, 0u};
+    if constexpr (MODE == EPI_BIAS) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(0, q), 0, 0);
-      }
+      for (int j = 0; j < TN; ++j) braw[j] = bias_req(j);
+    }
+    if constexpr (MODE == EPI_RES) {
+      bnext = bias_req(0);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(0, q), 0, 0);
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int cb = it.n0 + wn + 32 * j;                 // first column of the block
       float bvals[8];
-      if constexpr (!SPLITK) {
-        // bias for the 8 columns this lane writes back (same for every row block)
-        const int col = cb + 8 * (lane & 3);
-        const u32x4 braw = __builtin_amdgcn_raw_buffer_load_b128(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
-        const bf16x8 bv = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bvals[e] = 0.f;
+      if constexpr (MODE != EPI_PLAIN) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, MODE == EPI_BIAS ? braw[MODE == EPI_BIAS ? j : 0] : bnext);
 #pragma unroll
         for (int e = 0; e < 8; ++e) bvals[e] = (float)bv[e];
       }
@@ -381,9 +404,9 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
         // accumulator layout -> LDS: row lr, column group cg = 2g + hb (4 columns each)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int cg = (2 * g + hb) ^ ((lr >> 1) & 7);
+          const int cg = (2 * g + ehb) ^ ((elr >> 1) & 7);
           float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-          *reinterpret_cast<float4*>(patch + lr * 32 + cg * 4) = v;
+          *reinterpret_cast<float4*>(patch + elr * 32 + cg * 4) = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -392,7 +415,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
           float* Ps = P + (int64_t)it.split * M * N;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int r = (lane >> 3) + 8 * q, cgl = lane & 7;
+            const int r = (ln >> 3) + 8 * q, cgl = ln & 7;
             const float4 v = *reinterpret_cast<const float4*>(patch + r * 32 + ((cgl ^ ((r >> 1) & 7)) * 4));
             const int row = rb0 + r, col = cb + 4 * cgl;
             if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
@@ -401,15 +424,18 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
           float4 v0[2], v1[2];
 #pragma unroll
           for (int q = 0; q < 2; ++q) {
-            const int r = (lane >> 2) + 16 * q, c8 = lane & 3;
+            const int r = (ln >> 2) + 16 * q, c8 = ln & 3;
             const int sx = (r >> 1) & 7;
             v0[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8) ^ sx) * 4));
             v1[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
           }
           const u32x4 rcur[2] = {rnext[0], rnext[1]};
-          if (has_r && b + 1 < TM * TN) {
+          if constexpr (MODE == EPI_RES) {
+            if (b + 1 < TM * TN) {
 #pragma unroll
-            for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(b + 1, q), 0, 0);
+              for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(b + 1, q), 0, 0);
+              if ((b + 1) % TM == 0) bnext = bias_req((b + 1) / TM);
+            }
           }
 #pragma unroll
           for (int q = 0; q < 2; ++q) {
@@ -417,7 +443,14 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
             const float vals[8] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w, v1[q].x, v1[q].y, v1[q].z, v1[q].w};
             bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16)(vals[e] + bvals[e] + (float)rv[e]);
+            for (int e = 0; e < 8; ++e) {
+              // one order of additions in every variant (value + bias + residual; the absent
+              // terms are exact zeros), so the variant never changes a bit
+              float v = vals[e];
+              if constexpr (MODE != EPI_PLAIN) v += bvals[e];
+              if constexpr (MODE == EPI_RES) v += (float)rv[e];
+              o[e] = (bf16)v;
+            }
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rc, (int)out_off(b, q), 0, 0);
           }
         }
@@ -434,7 +467,22 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     __syncthreads();               // the patch lives in the stage the next step overwrites
   };
-
+  // Only the forward form meets a bias without a residual often enough to hold a variant for
+  // it; elsewhere such a call takes EPI_RES, whose empty residual descriptor reads zeros.
+  constexpr bool BIAS_VARIANT = A_KC && !B_KC;
+  const int epi_mode = SPLITK ? EPI_PLAIN : (R != nullptr) ? EPI_RES
+                     : (bias != nullptr) ? (BIAS_VARIANT ? EPI_BIAS : EPI_RES) : EPI_PLAIN;
+  auto finish = [&](const WorkItem& it, int free_stage) {
+    if constexpr (SPLITK) {
+      finish_impl(it, free_stage, std::integral_constant<int, EPI_PLAIN>{});
+    } else {
+      if (epi_mode == EPI_RES) { finish_impl(it, free_stage, std::integral_constant<int, EPI_RES>{}); return; }
+      if constexpr (BIAS_VARIANT) {
+        if (epi_mode == EPI_BIAS) { finish_impl(it, free_stage, std::integral_constant<int, EPI_BIAS>{}); return; }
+      }
+      finish_impl(it, free_stage, std::integral_constant<int, EPI_PLAIN>{});
+    }
+  };
 
   int round = 0, kt = cur.kt0;
   // One pipeline step, straight-line: the K-tile AHEAD of the compute cursor is requested
