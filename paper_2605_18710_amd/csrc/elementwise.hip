@@ -153,17 +153,33 @@ __global__ __launch_bounds__(kThreads) void norm_colgrad_partial_kernel(
     for (int i = 0; i < VN; ++i) { ag[i] = 0.f; ab[i] = 0.f; }
     const int64_t r0 = (int64_t)p * rp;
     const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
-    for (int64_t row = r0; row < r1; ++row) {
-      const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
-      Vec16<T> xv, dv;
-      xv.load(x + row * h + c);
-      dv.load(dy + row * h + c);
+    auto add_row = [&](const Vec16<T>& xv, const Vec16<T>& dv, float mean, float rstd) {
 #pragma unroll
       for (int i = 0; i < VN; ++i) {
         const float d = dv.get(i);
         if (NORM == MOSAIC_LAYERNORM) { ag[i] += d * ((xv.get(i) - mean) * rstd); ab[i] += d; }
         else ag[i] += d * xv.get(i) * rstd;
       }
+    };
+    int64_t row = r0;
+    // four rows requested together, added in ascending row order
+    for (; row + 4 <= r1; row += 4) {
+      Vec16<T> xv[4], dv[4];
+      float mean[4], rstd[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        xv[u].load(x + (row + u) * h + c);
+        dv[u].load(dy + (row + u) * h + c);
+        mean[u] = stats[(row + u) * 2]; rstd[u] = stats[(row + u) * 2 + 1];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) add_row(xv[u], dv[u], mean[u], rstd[u]);
+    }
+    for (; row < r1; ++row) {
+      Vec16<T> xv, dv;
+      xv.load(x + row * h + c);
+      dv.load(dy + row * h + c);
+      add_row(xv, dv, stats[row * 2], stats[row * 2 + 1]);
     }
 #pragma unroll
     for (int i = 0; i < VN; ++i) {
@@ -189,7 +205,16 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
     float acc = 0.f;
     if (col < ncols && !(col >= split && out1 == nullptr)) {
       const int p1 = (sl + 1) * per < np ? (sl + 1) * per : np;
-      for (int p = sl * per; p < p1; ++p) acc += partial[(int64_t)p * ld + col];
+      int p = sl * per;
+      // eight independent requests in flight, added in ascending p as before
+      for (; p + 8 <= p1; p += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(p + u) * ld + col];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+      }
+      for (; p < p1; ++p) acc += partial[(int64_t)p * ld + col];
     }
     red[sl][cl] = acc;
     __syncthreads();
@@ -347,7 +372,18 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __res
     for (int k = 0; k < VN; ++k) acc[k] = 0.f;
     const int64_t r0 = (int64_t)p * rp;
     const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
-    for (int64_t r = r0; r < r1; ++r) {
+    int64_t r = r0;
+    // four rows requested together, added in ascending row order
+    for (; r + 4 <= r1; r += 4) {
+      Vec16<T> v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u].load(X + (r + u) * n + c);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int k = 0; k < VN; ++k) acc[k] += v[u].get(k);
+    }
+    for (; r < r1; ++r) {
       Vec16<T> v;
       v.load(X + r * n + c);
 #pragma unroll
