@@ -207,28 +207,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
       const lds_byte* vs = ks + L::BYTES;
       request(t + PD);
       const int j0 = t * RS;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        const int jb = j0 + 32 * sub;
-        if (jb >= kv_end || (causal && jb > i0 + 31)) continue;     // nothing for this wave
-        // all K fragments are requested before the first MFMA and all V fragments before
-        // the softmax arithmetic, so LDS latency is paid once per phase and hidden behind
-        // the MFMAs / the softmax (left alone, the scheduler reads two fragments at a time
-        // and stalls on each pair)
-        bf16x8 kfr[NS];
-#pragma unroll
-        for (int s = 0; s < NS; ++s) kfr[s] = L::nat(ks, 32 * sub + lr, s, hb);
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16 sacc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
-        bf16x8 vfr[NC][2];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) { vfr[c][0] = L::tr(vs, c, 32 * sub); vfr[c][1] = L::tr(vs, c, 32 * sub + 16); }
-        __builtin_amdgcn_sched_barrier(0);
+      // A 32-key block is visible to this wave when it starts before the end of the keys and
+      // (causal) not after the wave's last query; the second block of a tile is visible only
+      // if the first is.
+      auto visible = [&](int jb) { return jb < kv_end && !(causal && jb > i0 + 31); };
+      // online-softmax update with one block of scores (raw dot products, this lane's query
+      // against 16 keys): returns the probabilities as two B-operands
+      auto softmax_block = [&](const f32x16& sacc, int jb, bf16x8& p0, bf16x8& p1) {
         float sv[16];
         float mx = -INFINITY;
         // only blocks that touch the diagonal or the end of the sequence need the mask
@@ -238,14 +223,14 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
           for (int r = 0; r < 16; ++r) {
             const int j = jb + acc_row(r, hb);
             const bool masked = (j >= N) || (causal && j > i);
-            sv[r] = masked ? -INFINITY : sacc[r] * scale_log2;
+            sv[r] = masked ? -INFINITY : sacc[r];
             mx = fmaxf(mx, sv[r]);
           }
         } else {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { sv[r] = sacc[r] * scale_log2; mx = fmaxf(mx, sv[r]); }
+          for (int r = 0; r < 16; ++r) { sv[r] = sacc[r]; mx = fmaxf(mx, sv[r]); }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;       // scale > 0: max commutes with it
         const float mn = fmaxf(m, mx);
         // rescale the running sums only when some row's maximum moved (exact: the factor is 1 otherwise)
         if (__any(mn > m)) {
@@ -261,14 +246,63 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
         const float mref = (m == -INFINITY) ? 0.f : m;           // row with nothing visible yet
         float ps = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(sv[r] - mref); ps += sv[r]; }
+        for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(fmaf(sv[r], scale_log2, -mref)); ps += sv[r]; }
         lsum += ps;
-        const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
+        p0 = pack8(sv); p1 = pack8(sv + 8);
+      };
+      auto scores = [&](const bf16x8* kfr) {
+        f32x16 sacc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
+        return sacc;
+      };
+      auto add_pv = [&](const bf16x8 (*vfr)[2], const bf16x8& p0, const bf16x8& p1) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
           o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][0], p0, o[c], 0, 0, 0);
           o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][1], p1, o[c], 0, 0, 0);
         }
+      };
+      if (visible(j0) && visible(j0 + 32)) {
+        // Both blocks: the scores of the second block are on the matrix cores while the
+        // first block's softmax runs on the vector ALU, and the first block's P V product
+        // runs under the second block's softmax.  Fragment reads are issued a phase ahead.
+        bf16x8 kfa[NS], kfb[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfa[s] = L::nat(ks, lr, s, hb);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfb[s] = L::nat(ks, 32 + lr, s, hb);
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 sa = scores(kfa);
+        const f32x16 sb = scores(kfb);
+        bf16x8 vfa[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfa[c][0] = L::tr(vs, c, 0); vfa[c][1] = L::tr(vs, c, 16); }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 p0, p1;
+        softmax_block(sa, j0, p0, p1);
+        bf16x8 vfb[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfb[c][0] = L::tr(vs, c, 32); vfb[c][1] = L::tr(vs, c, 48); }
+        add_pv(vfa, p0, p1);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_block(sb, j0 + 32, p0, p1);
+        add_pv(vfb, p0, p1);
+      } else if (visible(j0)) {
+        bf16x8 kfr[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfr[s] = L::nat(ks, lr, s, hb);
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 sa = scores(kfr);
+        bf16x8 vfr[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfr[c][0] = L::tr(vs, c, 0); vfr[c][1] = L::tr(vs, c, 16); }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 p0, p1;
+        softmax_block(sa, j0, p0, p1);
+        add_pv(vfr, p0, p1);
       }
       wait_requests<(PD - 1) * NREQ>();    // this wave's share of the next tile has landed
       __syncthreads();
