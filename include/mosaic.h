@@ -214,6 +214,66 @@ mosaic_status mosaic_plan_choose(int32_t n_modules, int32_t n_points, const int3
                                  const float* times, int32_t cu_total,
                                  int32_t* quota_out, float* time_out);
 
+/* ------------------------------------- performance-model correction (Sec. 3.3, Eq. 7-8) */
+/* Host-only.  A module that shares its GPU is delayed by
+ *   delta = e1 + e2 * sum_m B_m + e3 * prod_m B_m                                  (Eq. 8)
+ * over the memory-bandwidth utilisations B_m in [0,1] of ALL modules on that GPU (itself
+ * included); its rectified time is the grid-sampled time plus delta (Eq. 7; one GPU, so
+ * the maximum over GPUs has one term).  mosaic_interference_delta evaluates Eq. 8 for k
+ * modules (NaN on null arguments). */
+enum { MOSAIC_INTERFERENCE_ADDITIVE = 0,    /* e3 = 0: the additive-only comparison model */
+       MOSAIC_INTERFERENCE_COMPOSITE = 1 }; /* Eq. 8 */
+double        mosaic_interference_delta(const double* e /*[3]*/, int32_t k, const double* bw);
+/* Ordinary least-squares fit of (e1,e2,e3) to n_obs measured delays.  Observation i lists
+ * the utilisations of the group_size[i] modules that shared the GPU, concatenated in bw;
+ * delta_ms[i] is the delay measured for one of them.  e_out receives 3 doubles (e3 = 0 for
+ * ADDITIVE); *r2_out (may be NULL) the coefficient of determination of the fit.
+ * MOSAIC_EINVAL when the observations do not determine the coefficients. */
+mosaic_status mosaic_interference_fit(int32_t n_obs, const int32_t* group_size,
+                                      const double* bw, const double* delta_ms,
+                                      int32_t model, double* e_out, double* r2_out);
+
+/* ------------------------------------------ mapping solver on one GPU (Sec. 3.4, Alg. 1) */
+/* Host-only.  The job is a DAG of n_modules modules (edges = pairs (src, dst): dst
+ * consumes src's output).  times[m*n_points + p] is module m's measured time in ms on
+ * cu_points[p] CUs (the scaling surface of Sec. 3.3 on one GPU); bw, if given, holds the
+ * bandwidth utilisation measured at the same points and e the fitted coefficients of
+ * Eq. 8 (both or neither); a stage of two or more modules is then charged Eq. 8's delay,
+ * a module alone is not.  At most 16 modules and 16 quota levels. */
+typedef struct {
+  int32_t        n_modules, n_edges;
+  const int32_t* edges;        /* 2*n_edges entries */
+  int32_t        n_points;
+  const int32_t* cu_points;
+  const double*  times;
+  const double*  bw;           /* may be NULL */
+  const double*  e;            /* 3 doubles, NULL iff bw is NULL */
+  int32_t        cu_total;
+} mosaic_planner_problem;
+typedef struct { int64_t stage_evals, cache_hits, pruned, rounds; } mosaic_planner_stats;
+enum { MOSAIC_PLANNER_EARLY_PRUNE = 1, MOSAIC_PLANNER_CACHE = 2 };
+
+/* StageEval: the allocation of one quota level per module of the stage `module_mask`
+ * (bit m = module m) that minimises the slowest module's time (Eq. 4) with the quotas
+ * summing to at most cu_total (Eq. 5).  Without interference terms: binary search on a
+ * target latency with a feasibility test per trial; with them: every level tuple within
+ * the budget is visited.  quota_out[m] = CUs of member m (0 for non-members);
+ * *t_out = stage time in ms, +infinity when the stage does not fit.  Ties go to the
+ * lexicographically smallest tuple of level indices. */
+mosaic_status mosaic_stage_eval(const mosaic_planner_problem*, uint32_t module_mask,
+                                int32_t* quota_out, double* t_out);
+/* Alg. 1: every module starts as its own stage in a topological order; each round merges
+ * the pair of stages with the largest strictly positive saving T_x + T_y - T_xy among the
+ * pairs whose merge keeps the stage order acyclic; stops when no merge saves time.
+ * flags: MOSAIC_PLANNER_EARLY_PRUNE skips pairs that cannot beat the round's best saving,
+ * MOSAIC_PLANNER_CACHE remembers StageEval results per stage composition; neither changes
+ * the result.  stage_of[m] = index of m's stage in execution order, quota_of[m] = its
+ * CUs, *n_stages (may be NULL), *t_iter = sum of stage times (Eq. 1), stats may be NULL.
+ * MOSAIC_EINVAL for a cyclic edge list. */
+mosaic_status mosaic_planner_solve(const mosaic_planner_problem*, int32_t flags,
+                                   int32_t* stage_of, int32_t* quota_of, int32_t* n_stages,
+                                   double* t_iter, mosaic_planner_stats* stats);
+
 /* ------------------------------------------------ single operations (kernel level) */
 /* Each enqueues one operation on `stream` (hipStream_t, NULL = default) with persistent
  * grids sized for `quota` CUs.  They are what the module steps are made of and exist at

@@ -75,6 +75,12 @@ SIGNATURES = {
     "mosaic_stream_quota": (_i32, [_vp]),
     "mosaic_stream_offset": (_i32, [_vp]),
     "mosaic_stream_destroy": (_i32, [_vp]),
+    "mosaic_interference_delta": (C.c_double, [C.POINTER(C.c_double), _i32, C.POINTER(C.c_double)]),
+    "mosaic_interference_fit": (_i32, [_i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double), _i32,
+                                       C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "mosaic_stage_eval": (_i32, [_vp, C.c_uint32, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "mosaic_planner_solve": (_i32, [_vp, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_double), _vp]),
     "mosaic_pool_reserve": (_i32, [_i32, _i32, _i32]),
     "mosaic_pool_get": (_i32, [_i32, _i32, _i32, C.POINTER(_vp)]),
     "mosaic_pool_creations": (_i64, []),
@@ -342,6 +348,79 @@ def plan_choose(cu_points: Sequence[int], times: Sequence[Sequence[float]], cu_t
     tout = C.c_float()
     check(lib().mosaic_plan_choose(n_mod, n_pts, pts, flat, cu_total, out, C.byref(tout)))
     return [int(v) for v in out], float(tout.value)
+
+
+# ------------------------------------------------- performance-model correction, planner
+ADDITIVE, COMPOSITE = 0, 1
+EARLY_PRUNE, CACHE = 1, 2
+
+
+def interference_delta(e: Sequence[float], bw: Sequence[float]) -> float:
+    ev = (C.c_double * 3)(*[float(v) for v in e])
+    b = (C.c_double * max(1, len(bw)))(*[float(v) for v in bw])
+    return float(lib().mosaic_interference_delta(ev, len(bw), b))
+
+
+def interference_fit(groups: Sequence[Sequence[float]], delta: Sequence[float], model: int = COMPOSITE):
+    n = len(groups)
+    sizes = (C.c_int32 * max(1, n))(*[len(g) for g in groups])
+    flat = [float(v) for g in groups for v in g]
+    bw = (C.c_double * max(1, len(flat)))(*flat)
+    d = (C.c_double * max(1, n))(*[float(v) for v in delta])
+    e = (C.c_double * 3)()
+    r2 = C.c_double()
+    check(lib().mosaic_interference_fit(n, sizes, bw, d, model, e, C.byref(r2)))
+    return [float(v) for v in e], float(r2.value)
+
+
+class _PlannerProblem(C.Structure):
+    _fields_ = [("n_modules", C.c_int32), ("n_edges", C.c_int32), ("edges", C.POINTER(C.c_int32)),
+                ("n_points", C.c_int32), ("cu_points", C.POINTER(C.c_int32)), ("times", C.POINTER(C.c_double)),
+                ("bw", C.POINTER(C.c_double)), ("e", C.POINTER(C.c_double)), ("cu_total", C.c_int32)]
+
+
+class _PlannerStats(C.Structure):
+    _fields_ = [("stage_evals", C.c_int64), ("cache_hits", C.c_int64), ("pruned", C.c_int64), ("rounds", C.c_int64)]
+
+
+def _planner_problem(n_modules, edges, cu_points, times, cu_total, bw=None, e=None):
+    keep = []          # ctypes arrays the struct points into
+    def arr(ty, vals):
+        a = (ty * max(1, len(vals)))(*vals)
+        keep.append(a)
+        return a
+    p = _PlannerProblem()
+    p.n_modules, p.n_edges, p.n_points, p.cu_total = n_modules, len(edges), len(cu_points), cu_total
+    p.edges = arr(C.c_int32, [int(v) for ed in edges for v in ed])
+    p.cu_points = arr(C.c_int32, [int(v) for v in cu_points])
+    p.times = arr(C.c_double, [float(v) for row in times for v in row])
+    if bw is not None:
+        p.bw = arr(C.c_double, [float(v) for row in bw for v in row])
+        p.e = arr(C.c_double, [float(v) for v in e])
+    return p, keep
+
+
+def stage_eval(modules: Sequence[int], n_modules: int, cu_points, times, cu_total: int, bw=None, e=None):
+    """StageEval for the stage holding `modules`: (time in ms, {module: CUs})."""
+    p, keep = _planner_problem(n_modules, [], cu_points, times, cu_total, bw, e)
+    mask = 0
+    for m in modules:
+        mask |= 1 << m
+    q = (C.c_int32 * n_modules)()
+    t = C.c_double()
+    check(lib().mosaic_stage_eval(C.byref(p), mask, q, C.byref(t)))
+    return float(t.value), {m: int(q[m]) for m in modules if q[m] > 0}
+
+
+def planner_solve(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None, flags: int = EARLY_PRUNE | CACHE):
+    """Alg. 1: (stages in execution order as lists of modules, {module: CUs}, iteration time, stats)."""
+    p, keep = _planner_problem(n_modules, edges, cu_points, times, cu_total, bw, e)
+    so, qo = (C.c_int32 * n_modules)(), (C.c_int32 * n_modules)()
+    ns, t, st = C.c_int32(), C.c_double(), _PlannerStats()
+    check(lib().mosaic_planner_solve(C.byref(p), flags, so, qo, C.byref(ns), C.byref(t), C.byref(st)))
+    stages = [[m for m in range(n_modules) if so[m] == i] for i in range(ns.value)]
+    stats = dict(stage_evals=int(st.stage_evals), cache_hits=int(st.cache_hits), pruned=int(st.pruned), rounds=int(st.rounds))
+    return stages, {m: int(qo[m]) for m in range(n_modules)}, float(t.value), stats
 
 
 # ------------------------------------------------------------------- single operations
