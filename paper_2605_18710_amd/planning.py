@@ -1,0 +1,96 @@
+"""Plans and runs a multi-module job on one GPU with the library's planner: measures each
+module's time-vs-CU curve (the scaling surface of Sec. 3.3 restricted to one GPU), derives
+the bandwidth-utilisation proxy, fits the interference coefficients of Eq. 8 from a few
+colocated probe runs, forms stages with Alg. 1 and executes the stages one after another,
+each colocated under its allocation.  Only argument marshalling and bookkeeping happen
+here; every step of the arithmetic runs in the library.
+"""
+from __future__ import annotations
+
+import statistics
+from typing import Dict, List, Sequence, Tuple
+
+from . import binding as mb
+from . import synth
+from .workload import StagedModule
+
+PEAK_HBM_BYTES_PER_S = 8.0e12
+
+
+class PlannedJob:
+    """modules: list of module dicts (synth._enc / _dec / _proj form, unique names);
+    edges: (producer name, consumer name) pairs.  Modules read staged buffers, so an edge
+    only orders stages; it does not move data."""
+
+    def __init__(self, modules: Sequence[dict], edges: Sequence[Tuple[str, str]], dtype: str = "bf16", seed: int = 18710000):
+        self.cfgs = [dict(m) for m in modules]
+        self.names = [m["name"] for m in self.cfgs]
+        self.edges = [(self.names.index(a), self.names.index(b)) for a, b in edges]
+        self.staged: List[StagedModule] = [
+            StagedModule(cfg, dtype, seed + 10000 * (i + 1), with_target=(cfg["kind"] == "decoder"))
+            for i, cfg in enumerate(self.cfgs)]
+        self.cus = mb.device_cu_count()
+        self.elem = 2 if dtype == "bf16" else 4
+
+    # ------------------------------------------------------------------ measurement
+    def _run(self, members: Sequence[int], quotas: Sequence[int], iters: int) -> dict:
+        """Colocated run of `members` (module indices) at `quotas`, packed from CU 0; medians."""
+        s = self.staged
+        offsets, o = [], 0
+        for q in quotas:
+            offsets.append(o)
+            o += q
+        mb.pool_clear()            # a masked stream holds a hardware queue: keep only those in use
+        for q, off in zip(quotas, offsets):
+            mb.pool_reserve(q, off, mb.STRIPED)
+        def once():
+            return mb.stage_run([s[i].module for i in members], [s[i].x for i in members], [s[i].y for i in members],
+                                list(quotas), offsets, mb.STRIPED, mb.COLOCATED,
+                                dy=[s[i].dy for i in members], target=[s[i].target for i in members],
+                                dx=[s[i].dx for i in members], loss=[s[i].loss for i in members])
+        once()
+        rs = [once() for _ in range(iters)]
+        return dict(stage_ms=statistics.median(r["stage_ms"] for r in rs),
+                    module_ms=[statistics.median(r["module_ms"][k] for r in rs) for k in range(len(members))])
+
+    def measure_curves(self, grid: Sequence[int], iters: int = 3) -> List[List[float]]:
+        """times[m][p]: module m alone on grid[p] CUs, ms."""
+        return [[self._run([m], [q], iters)["stage_ms"] for q in grid] for m in range(len(self.staged))]
+
+    def bandwidth_table(self, times: List[List[float]]) -> List[List[float]]:
+        """B(m, a) in [0,1]: algorithmic bytes of a step over the time it took, against the HBM peak."""
+        out = []
+        for cfg, row in zip(self.cfgs, times):
+            b = synth.module_bytes(cfg, self.elem)
+            out.append([min(1.0, b / (t * 1e-3) / PEAK_HBM_BYTES_PER_S) for t in row])
+        return out
+
+    def fit_interference(self, grid, times, bw, probes: Sequence[Dict[int, int]], iters: int = 3):
+        """probes: list of {module index: CUs on the grid} with two or more modules each.  Every
+        module of every probe gives one observation: delay = colocated time - time alone at
+        the same quota.  Returns the Eq. 8 fit, the additive-only fit and the observations."""
+        groups, delays = [], []
+        for pr in probes:
+            members = sorted(pr)
+            r = self._run(members, [pr[m] for m in members], iters)
+            bs = [bw[m][grid.index(pr[m])] for m in members]
+            for k, m in enumerate(members):
+                groups.append(bs)
+                delays.append(r["module_ms"][k] - times[m][grid.index(pr[m])])
+        e3, r2_3 = mb.interference_fit(groups, delays, mb.COMPOSITE)
+        e2, r2_2 = mb.interference_fit(groups, delays, mb.ADDITIVE)
+        return dict(e=e3, r2=r2_3, e_additive=e2, r2_additive=r2_2, n_obs=len(delays), groups=groups, delays=delays)
+
+    # ---------------------------------------------------------------- plan and run
+    def solve(self, grid, times, bw=None, e=None, flags=mb.EARLY_PRUNE | mb.CACHE):
+        return mb.planner_solve(len(self.staged), self.edges, list(grid), times, self.cus, bw=bw, e=e, flags=flags)
+
+    def run_plan(self, stages: Sequence[Sequence[int]], alloc: Dict[int, int], iters: int = 3) -> dict:
+        """Executes the stages one after another (Eq. 1); each stage colocated under its quotas."""
+        per_stage = [self._run(list(st), [alloc[m] for m in st], iters)["stage_ms"] for st in stages]
+        return dict(iteration_ms=sum(per_stage), stage_ms=per_stage)
+
+    def destroy(self):
+        mb.pool_clear()
+        for s in self.staged:
+            s.destroy()

@@ -154,3 +154,26 @@ def module_flops(m: dict) -> float:
     gemm = 8.0 * T * h * h + (6.0 if m["act"] == "swiglu" else 4.0) * T * h * f
     attn = 4.0 * B * N * N * h * (0.5 if m["causal"] else 1.0)
     return 3.0 * m["layers"] * (gemm + attn)
+
+
+def module_bytes(m: dict, elem: int = 2) -> float:
+    """Algorithmic HBM bytes of one forward+backward step: every kernel reads its operands and
+    writes its result once (GEMM: the three matrices; attention: packed q|k|v, output and
+    their gradients; norms, activations and residuals: one pass per tensor).  Used as the
+    numerator of the bandwidth-utilisation proxy B(m, a) = bytes / (time x peak)."""
+    T = m["batch"] * m["seq"]
+
+    def gemm3(k, n):          # forward, input-gradient and weight-gradient forms of one linear layer
+        one = T * k + k * n + T * n
+        return 3.0 * one
+
+    if m["kind"] == "projector":
+        d_in, d_out = m["in_dim"], m["out_dim"]
+        return elem * (gemm3(d_in, d_out) + gemm3(d_out, d_out) + 5.0 * T * d_out)
+    h, f = m["hidden"], m["mlp"]
+    zf = 2 * f if m["act"] == "swiglu" else f
+    gemms = gemm3(h, 3 * h) + gemm3(h, h) + gemm3(h, zf) + gemm3(f, h) + 2.0 * T * h      # + two residual reads
+    attn = 4.0 * T * h + 8.0 * T * h                      # fwd: q|k|v in, O out; bwd: q|k|v, O, dO in, dq|dk|dv out
+    norms = 2 * (2.0 * T * h) + 2 * (4.0 * T * h + 2.0 * T * h)
+    act = (3.0 + 5.0) * T * f if m["act"] == "swiglu" else (2.0 + 3.0) * T * f
+    return elem * m["layers"] * (gemms + attn + norms + act)
