@@ -15,6 +15,7 @@ from . import synth
 from .workload import StagedModule
 
 PEAK_HBM_BYTES_PER_S = 8.0e12
+PEAK_BF16_FLOPS = 2.5e15
 
 
 class PlannedJob:
@@ -31,6 +32,7 @@ class PlannedJob:
             for i, cfg in enumerate(self.cfgs)]
         self.cus = mb.device_cu_count()
         self.elem = 2 if dtype == "bf16" else 4
+        self._probe_cache: Dict[tuple, dict] = {}     # colocated probe runs already measured
 
     # ------------------------------------------------------------------ measurement
     def _run(self, members: Sequence[int], quotas: Sequence[int], iters: int) -> dict:
@@ -57,12 +59,19 @@ class PlannedJob:
         """times[m][p]: module m alone on grid[p] CUs, ms."""
         return [[self._run([m], [q], iters)["stage_ms"] for q in grid] for m in range(len(self.staged))]
 
-    def bandwidth_table(self, times: List[List[float]]) -> List[List[float]]:
-        """B(m, a) in [0,1]: algorithmic bytes of a step over the time it took, against the HBM peak."""
+    def bandwidth_table(self, times: List[List[float]], proxy: str = "bandwidth") -> List[List[float]]:
+        """B(m, a) in [0,1], the utilisation proxy of Eq. 8.  "bandwidth" (the paper's): algorithmic
+        bytes of a step over the time it took, against the HBM peak.  "compute": model FLOPs
+        over the time, against the bf16 matrix peak -- on this GPU co-runners contend for the
+        board's power budget before they contend for bandwidth, and matrix-core utilisation is
+        the better stand-in for a module's share of that budget."""
         out = []
         for cfg, row in zip(self.cfgs, times):
-            b = synth.module_bytes(cfg, self.elem)
-            out.append([min(1.0, b / (t * 1e-3) / PEAK_HBM_BYTES_PER_S) for t in row])
+            if proxy == "bandwidth":
+                w, peak = synth.module_bytes(cfg, self.elem), PEAK_HBM_BYTES_PER_S
+            else:
+                w, peak = synth.module_flops(cfg), PEAK_BF16_FLOPS
+            out.append([min(1.0, w / (t * 1e-3) / peak) for t in row])
         return out
 
     def fit_interference(self, grid, times, bw, probes: Sequence[Dict[int, int]], iters: int = 3):
@@ -72,7 +81,10 @@ class PlannedJob:
         groups, delays = [], []
         for pr in probes:
             members = sorted(pr)
-            r = self._run(members, [pr[m] for m in members], iters)
+            key = tuple(sorted(pr.items()))
+            if key not in self._probe_cache:
+                self._probe_cache[key] = self._run(members, [pr[m] for m in members], iters)
+            r = self._probe_cache[key]
             bs = [bw[m][grid.index(pr[m])] for m in members]
             for k, m in enumerate(members):
                 groups.append(bs)
