@@ -24,6 +24,11 @@ Readings where the sources are silent (all recorded in the design notes as well)
     causal mask forbids j > i, masked probability is exactly 0, no dropout.
   * loss = mean over all elements of (y - target)^2.
   * patch vector index = (c*p + i)*p + j, patches row-major over the image.
+  * layer variants (not named by the workloads; offered as options): the tanh form of GELU
+    (act "gelu_tanh"); rotary position embedding on q and k (cfg "rope" = base, 0 = off) in
+    the original interleaved-pair form: pair i of a head, at position n of its sample, is
+    rotated by the angle n * base^(-2i/d); AdamW with decoupled weight decay and bias
+    correction.
 
 Pins (tests/test_oracle_*.py): brute-force triple-loop matmul, naive per-row softmax
 attention in python loops, closed-form invariants, math.erf scalar reference, central
@@ -100,6 +105,16 @@ def gelu(z):
 
 def gelu_grad(z):
     return 0.5 * (1.0 + _erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
+
+
+def gelu_tanh(z):
+    """tanh form: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3)))."""
+    return 0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)))
+
+
+def gelu_tanh_grad(z):
+    t = np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3))
+    return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * np.sqrt(2.0 / np.pi) * (1.0 + 3.0 * 0.044715 * z * z)
 
 
 def sigmoid(z):
@@ -201,6 +216,44 @@ def attention_lse(qkv, B, N, H, causal):
     return out
 
 
+# ------------------------------------------------------------- rotary position embedding
+
+
+def rope_rotate(qkv, B, N, H, base, sign=1.0):
+    """Rotates the q and k parts of packed [B*N, 3h] rows; v is left alone.  Pair
+    (x[2i], x[2i+1]) of every head, in the row at position n of its sample, turns by the
+    angle sign * n * base^(-2i/d).  sign = -1 is the transposed rotation, i.e. the map that
+    takes gradients with respect to rotated q, k back to the unrotated ones."""
+    h = qkv.shape[1] // 3
+    d = h // H
+    out = qkv.copy()
+    n = np.arange(B * N) % N
+    i = np.arange(d // 2)
+    ang = sign * n[:, None].astype(np.float64) * (float(base) ** (-2.0 * i / d))[None, :]
+    c, s_ = np.cos(ang).astype(qkv.dtype), np.sin(ang).astype(qkv.dtype)
+    for part in (0, 1):                       # q, k
+        for t in range(H):
+            c0 = part * h + t * d
+            xe, xo = qkv[:, c0:c0 + d:2], qkv[:, c0 + 1:c0 + d:2]
+            out[:, c0:c0 + d:2] = xe * c - xo * s_
+            out[:, c0 + 1:c0 + d:2] = xe * s_ + xo * c
+    return out
+
+
+# -------------------------------------------------------------------------- optimizer
+
+
+def adamw_step(p, g, m, v, step, lr, beta1, beta2, eps, weight_decay):
+    """One AdamW update (decoupled weight decay, bias-corrected moments); step counts from 1.
+    Returns the new (p, m, v)."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    p = p - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * p)
+    return p, m, v
+
+
 # ------------------------------------------------------------------------------- loss
 
 
@@ -227,15 +280,17 @@ def layer_fwd(x, p, cfg):
     else:
         u1 = rmsnorm_fwd(x, p["rms1_g"], eps)
     qkv = linear_fwd(u1, p["w_qkv"], p.get("b_qkv"))
+    if cfg.get("rope"):
+        qkv = rope_rotate(qkv, B, N, H, cfg["rope"])       # saved and attended in rotated form
     o = attention_fwd(qkv, B, N, H, cfg["causal"])
     x1 = x + linear_fwd(o, p["w_o"], p.get("b_o"))
     if cfg["norm"] == "layernorm":
         u2 = layernorm_fwd(x1, p["ln2_g"], p["ln2_b"], eps)
     else:
         u2 = rmsnorm_fwd(x1, p["rms2_g"], eps)
-    if cfg["act"] == "gelu":
+    if cfg["act"] in ("gelu", "gelu_tanh"):
         z = linear_fwd(u2, p["w_1"], p.get("b_1"))
-        a = gelu(z)
+        a = gelu(z) if cfg["act"] == "gelu" else gelu_tanh(z)
         y = x1 + linear_fwd(a, p["w_2"], p.get("b_2"))
         saved = dict(x=x, u1=u1, qkv=qkv, o=o, x1=x1, u2=u2, z=z, a=a)
     else:
@@ -252,9 +307,9 @@ def layer_bwd(dy, p, s, cfg):
     B, N, H, eps = cfg["batch"], cfg["seq"], cfg["heads"], cfg["eps"]
     bias = bool(cfg["bias"])
     g = {}
-    if cfg["act"] == "gelu":
+    if cfg["act"] in ("gelu", "gelu_tanh"):
         da, g["w_2"], db2 = linear_bwd(s["a"], p["w_2"], dy, bias)
-        dz = da * gelu_grad(s["z"])
+        dz = da * (gelu_grad(s["z"]) if cfg["act"] == "gelu" else gelu_tanh_grad(s["z"]))
         du2, g["w_1"], db1 = linear_bwd(s["u2"], p["w_1"], dz, bias)
         if bias:
             g["b_2"], g["b_1"] = db2, db1
@@ -274,6 +329,8 @@ def layer_bwd(dy, p, s, cfg):
     if bias:
         g["b_o"] = dbo
     dqkv = attention_bwd(s["qkv"], do, B, N, H, cfg["causal"])
+    if cfg.get("rope"):
+        dqkv = rope_rotate(dqkv, B, N, H, cfg["rope"], -1.0)
     du1, g["w_qkv"], dbqkv = linear_bwd(s["u1"], p["w_qkv"], dqkv, bias)
     if bias:
         g["b_qkv"] = dbqkv

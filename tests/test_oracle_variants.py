@@ -1,0 +1,135 @@
+"""Pins for the layer variants of the CPU checker (tanh GELU, rotary position embedding,
+AdamW): closed forms, invariants, finite differences, and the same quantities computed
+by an independent library routine (PyTorch on the CPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as O
+from paper_2605_18710_amd import synth
+from helpers import layer_params, small_cfg
+
+
+# ---------------------------------------------------------------------- tanh GELU
+def test_gelu_tanh_special_values_and_library():
+    assert O.gelu_tanh(np.array([0.0]))[0] == 0.0
+    assert O.gelu_tanh_grad(np.array([0.0]))[0] == 0.5
+    z = synth.normal(9001, (257,), 0.0, 2.0)
+    assert np.allclose(O.gelu_tanh(-z), O.gelu_tanh(z) - z, atol=1e-15)          # odd part is z/2
+    assert np.allclose(O.gelu_tanh(np.array([12.0])), 12.0, atol=1e-12)
+    ref = torch.nn.functional.gelu(torch.from_numpy(z), approximate="tanh").numpy()
+    assert np.allclose(O.gelu_tanh(z), ref, rtol=0, atol=1e-14)
+    # it is an approximation of the erf form: close, not equal
+    assert 1e-5 < np.abs(O.gelu_tanh(z) - O.gelu(z)).max() < 1e-3
+
+
+def test_gelu_tanh_grad_by_finite_differences():
+    z = synth.normal(9002, (101,), 0.0, 1.5)
+    fd = (O.gelu_tanh(z + 1e-6) - O.gelu_tanh(z - 1e-6)) / 2e-6
+    assert np.allclose(O.gelu_tanh_grad(z), fd, atol=1e-8)
+
+
+# ---------------------------------------------------------------------------- RoPE
+def test_rope_is_a_rotation_identity_at_position_zero_and_leaves_v():
+    B, N, H, d = 2, 9, 3, 8
+    h = H * d
+    qkv = synth.normal(9010, (B * N, 3 * h))
+    r = O.rope_rotate(qkv, B, N, H, 10000.0)
+    assert np.array_equal(r[:, 2 * h:], qkv[:, 2 * h:])
+    assert np.array_equal(r[0::N], qkv[0::N])                                   # position 0 of every sample
+    pairs = lambda a: a[:, :2 * h].reshape(B * N, 2 * H * d // 2, 2)
+    assert np.allclose((pairs(r) ** 2).sum(-1), (pairs(qkv) ** 2).sum(-1), atol=1e-13)   # each pair keeps its length
+    back = O.rope_rotate(r, B, N, H, 10000.0, -1.0)
+    assert np.allclose(back, qkv, atol=1e-13)                                   # transpose = inverse
+    assert not np.allclose(r[1::N, :2 * h], qkv[1::N, :2 * h])
+
+
+def test_rope_pair_angles_written_out():
+    # one head of size 4 at position 3: pair 0 turns by 3 rad, pair 1 by 3 * base^(-1/2)
+    base = 100.0
+    qkv = np.zeros((4, 12)); qkv[3, 0:4] = [1.0, 0.0, 0.0, 2.0]; qkv[3, 4:8] = [0.0, 1.0, 1.0, 0.0]
+    r = O.rope_rotate(qkv, 1, 4, 1, base)
+    a0, a1 = 3.0, 3.0 / 10.0
+    assert np.allclose(r[3, 0:4], [np.cos(a0), np.sin(a0), -2.0 * np.sin(a1), 2.0 * np.cos(a1)], atol=1e-15)
+    assert np.allclose(r[3, 4:8], [-np.sin(a0), np.cos(a0), np.cos(a1), np.sin(a1)], atol=1e-15)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    # the same q and k vectors placed at (m, n) and at (m + s, n + s) give the same dot product
+    H, d, N = 1, 16, 12
+    qv, kv = synth.normal(9011, (d,)), synth.normal(9012, (d,))
+    def score(m, n):
+        qkv = np.zeros((N, 3 * d)); qkv[m, :d] = qv; qkv[n, d:2 * d] = kv
+        r = O.rope_rotate(qkv, 1, N, H, 10000.0)
+        return float(r[m, :d] @ r[n, d:2 * d])
+    assert score(5, 2) == pytest.approx(score(9, 6), abs=1e-12)
+    assert score(5, 2) != pytest.approx(score(5, 3), abs=1e-6)
+
+
+def test_decoder_layer_with_rope_by_finite_differences():
+    cfg = dict(small_cfg("decoder"), rope=100.0)
+    p = {k: v * (10.0 if v.ndim == 2 else 1.0) for k, v in layer_params(cfg, 9020).items()}
+    x = synth.normal(9021, (cfg["batch"] * cfg["seq"], cfg["hidden"]))
+    R = synth.normal(9022, x.shape)
+    y, s = O.layer_fwd(x, p, cfg)
+    dx, g = O.layer_bwd(R, p, s, cfg)
+    y0, _ = O.layer_fwd(x, p, dict(cfg, rope=0))
+    assert np.abs(y - y0).max() > 1e-4                                          # the option does something
+    loss = lambda pp, xx=x: float((O.layer_fwd(xx, pp, cfg)[0] * R).sum())
+    for key in p:
+        D = synth.normal(9030 + len(key), p[key].shape)
+        pp, pm = dict(p), dict(p)
+        pp[key] = p[key] + 1e-5 * D; pm[key] = p[key] - 1e-5 * D
+        fd = (loss(pp) - loss(pm)) / 2e-5
+        assert fd == pytest.approx(float((g[key] * D).sum()), rel=1e-6, abs=1e-9), key
+    D = synth.normal(9040, x.shape)
+    fd = (loss(p, x + 1e-5 * D) - loss(p, x - 1e-5 * D)) / 2e-5
+    assert fd == pytest.approx(float((dx * D).sum()), rel=1e-6, abs=1e-9)
+
+
+def test_encoder_layer_with_tanh_gelu_by_finite_differences():
+    cfg = dict(small_cfg("encoder"), act="gelu_tanh")
+    p = {k: v * (10.0 if v.ndim == 2 else 1.0) for k, v in layer_params(cfg, 9050).items()}
+    x = synth.normal(9051, (cfg["batch"] * cfg["seq"], cfg["hidden"]))
+    R = synth.normal(9052, x.shape)
+    y, s = O.layer_fwd(x, p, cfg)
+    _, g = O.layer_bwd(R, p, s, cfg)
+    loss = lambda pp: float((O.layer_fwd(x, pp, cfg)[0] * R).sum())
+    for key in ("w_1", "b_1", "w_2"):
+        D = synth.normal(9060 + len(key), p[key].shape)
+        pp, pm = dict(p), dict(p)
+        pp[key] = p[key] + 1e-5 * D; pm[key] = p[key] - 1e-5 * D
+        assert (loss(pp) - loss(pm)) / 2e-5 == pytest.approx(float((g[key] * D).sum()), rel=1e-6, abs=1e-9), key
+
+
+# --------------------------------------------------------------------------- AdamW
+def test_adamw_first_step_closed_form():
+    # zero moments, step 1: mhat = g, vhat = g^2, so p' = p - lr (g/(|g|+eps) + wd p)
+    p = synth.normal(9100, (50,)); g = synth.normal(9101, (50,))
+    lr, b1, b2, eps, wd = 1e-2, 0.9, 0.999, 1e-8, 0.1
+    p1, m1, v1 = O.adamw_step(p, g, np.zeros(50), np.zeros(50), 1, lr, b1, b2, eps, wd)
+    assert np.allclose(p1, p - lr * (g / (np.abs(g) + eps) + wd * p), rtol=0, atol=1e-15)
+    assert np.allclose(m1, 0.1 * g, atol=1e-16) and np.allclose(v1, 0.001 * g * g, atol=1e-18)
+
+
+def test_adamw_zero_gradient_is_pure_decay():
+    p = synth.normal(9102, (20,))
+    q, m, v = p.copy(), np.zeros(20), np.zeros(20)
+    for t in range(1, 6):
+        q, m, v = O.adamw_step(q, np.zeros(20), m, v, t, 0.05, 0.9, 0.999, 1e-8, 0.2)
+    assert np.allclose(q, p * (1.0 - 0.05 * 0.2) ** 5, rtol=1e-14)
+
+
+def test_adamw_matches_library_over_several_steps():
+    p0 = synth.normal(9103, (33,))
+    tp = torch.nn.Parameter(torch.from_numpy(p0.copy()))
+    opt = torch.optim.AdamW([tp], lr=3e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.05)
+    p, m, v = p0.copy(), np.zeros(33), np.zeros(33)
+    for t in range(1, 8):
+        g = synth.normal(9110 + t, (33,))
+        tp.grad = torch.from_numpy(g.copy())
+        opt.step()
+        p, m, v = O.adamw_step(p, g, m, v, t, 3e-3, 0.9, 0.95, 1e-8, 0.05)
+    # the library writes the same update as p (1 - lr wd) - lr mhat / (sqrt vhat + eps)
+    assert np.allclose(p, tp.detach().numpy(), rtol=0, atol=1e-13)
+    assert np.abs(p - p0).max() > 1e-3
