@@ -99,6 +99,19 @@ def bandwidth_kernels(mb, T, h, f, reps):
     res["swiglu_fwd"] = 6.0 * T * f / ms / 1e6
     ms = time_kernel(lambda: mb.op_swiglu_bwd(None, q, "bf16", T, f, gu, da, dgu), reps)
     res["swiglu_bwd"] = 10.0 * T * f / ms / 1e6
+    # layer variants: rotary embedding in place on q|k of [T, 3h] (4 B per q|k element), AdamW
+    # on bf16 parameters with fp32 moments (read p, g, m, v; write p, m, v: 22 B per element)
+    H = max(1, h // 128)
+    qkv = torch.randn(T, 3 * h, device="cuda", dtype=bf)
+    table = torch.empty(mb.rope_table_bytes(T, 128), dtype=torch.uint8, device="cuda")
+    mb.op_rope_table(None, q, T, 128, 10000.0, table)
+    ms = time_kernel(lambda: mb.op_rope(None, q, "bf16", 1, T, H, 128, 1, qkv, table), reps)
+    res["rope"] = 4.0 * T * 2 * H * 128 / ms / 1e6
+    n = h * 2 * f
+    p_ = torch.randn(n, device="cuda", dtype=bf); g_ = torch.randn(n, device="cuda", dtype=bf)
+    m_ = torch.zeros(n, device="cuda", dtype=torch.float32); v_ = torch.zeros_like(m_)
+    ms = time_kernel(lambda: mb.op_adamw(None, q, "bf16", n, p_, g_, m_, v_, None, 1e-4, 0.9, 0.999, 1e-8, 0.01, 7), reps)
+    res["adamw"] = 22.0 * n / ms / 1e6
     return {k: round(v, 1) for k, v in res.items()}
 
 

@@ -49,7 +49,8 @@ enum { MOSAIC_F32 = 0, MOSAIC_BF16 = 1 };
 enum { MOSAIC_ENCODER = 0, MOSAIC_DECODER = 1, MOSAIC_PROJECTOR = 2,
        MOSAIC_PATCH_STEM = 3, MOSAIC_TEXT_STEM = 4 };
 enum { MOSAIC_NORM_NONE = 0, MOSAIC_LAYERNORM = 1, MOSAIC_RMSNORM = 2 };
-enum { MOSAIC_GELU = 0, MOSAIC_SWIGLU = 1 };
+enum { MOSAIC_GELU = 0, MOSAIC_SWIGLU = 1,
+       MOSAIC_GELU_TANH = 2 };  /* tanh form of GELU: a layer variant, not used by the workloads */
 /* How a quota's CUs are chosen.  STRIPED takes the same share of every XCD (keeps
  * workgroup dispatch balanced over XCDs).  XCD_ALIGNED fills whole XCDs first (would keep
  * a module's L2 private); quota and offset must then be multiples of the CUs per XCD.
@@ -121,6 +122,9 @@ typedef struct {
   float   eps;
   int32_t in_dim, out_dim;
   int32_t vocab, n_img, patch;
+  float   rope_base;   /* ENCODER / DECODER: > 0 turns on rotary position embedding of q and k
+                          (pair (2i, 2i+1) of a head at position n turns by n * rope_base^(-2i/d));
+                          0 = none, as in the workloads */
 } mosaic_module_desc;
 
 typedef struct mosaic_module mosaic_module;
@@ -163,6 +167,18 @@ mosaic_status mosaic_module_backward(mosaic_module*, int32_t quota, const mosaic
 mosaic_status mosaic_module_step(mosaic_module*, int32_t quota, const mosaic_stream*,
                                  const void* x, const void* dy, const void* target,
                                  void* y, void* dx, float* loss);
+
+/* Optimizer step over the module's flat parameter buffer (a layer-variant extra that makes
+ * a training iteration complete): AdamW with decoupled weight decay and bias-corrected
+ * moments, step counting from 1.  `state` is a caller-owned device buffer of
+ * mosaic_module_optimizer_state_bytes: fp32 first moments, fp32 second moments and, when
+ * use_master != 0, an fp32 master copy of the parameters (the caller initialises it from
+ * the parameters; moments start at zero).  Reads `grads`, updates `params` in place. */
+size_t        mosaic_module_optimizer_state_bytes(const mosaic_module*, int32_t use_master);
+mosaic_status mosaic_module_adamw_step(mosaic_module*, int32_t quota, const mosaic_stream*,
+                                       void* state, size_t state_bytes, int32_t use_master,
+                                       float lr, float beta1, float beta2, float eps,
+                                       float weight_decay, int64_t step);
 
 /* ----------------------------------------------------------------- stages and plans */
 /* A stage: n modules with their staged buffers.  In COLOCATED and TIME_SLICED mode the
@@ -327,6 +343,11 @@ mosaic_status mosaic_op_gelu_fwd(void* stream, int32_t quota, int32_t dtype, int
                                  const void* z, void* a);
 mosaic_status mosaic_op_gelu_bwd(void* stream, int32_t quota, int32_t dtype, int64_t n,
                                  const void* z, const void* da, void* dz);
+/* The tanh form: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))). */
+mosaic_status mosaic_op_gelu_tanh_fwd(void* stream, int32_t quota, int32_t dtype, int64_t n,
+                                      const void* z, void* a);
+mosaic_status mosaic_op_gelu_tanh_bwd(void* stream, int32_t quota, int32_t dtype, int64_t n,
+                                      const void* z, const void* da, void* dz);
 /* gu [T,2f] = [gate | up];  a[T,f] = silu(gate)*up;  dgu [T,2f] = [dgate | dup]. */
 mosaic_status mosaic_op_swiglu_fwd(void* stream, int32_t quota, int32_t dtype, int64_t T,
                                    int64_t f, const void* gu, void* a);
@@ -338,6 +359,28 @@ mosaic_status mosaic_op_mse(void* stream, int32_t quota, int32_t dtype, int64_t 
                             const void* y, const void* target, void* dy, float* loss,
                             void* scratch);
 size_t        mosaic_op_mse_scratch_bytes(void);
+
+
+/* Rotary position embedding.  table: device buffer of mosaic_op_rope_table_bytes(N, d) that
+ * mosaic_op_rope_table fills with (cos, sin)(n * base^(-2i/d)) for n < N, i < d/2 (angles
+ * formed in double).  mosaic_op_rope rotates, in place, pair (2i, 2i+1) of every head of
+ * the q and k parts of qkv [B*N, 3*H*d] by the angle of (row's position in its sample, i);
+ * direction = +1 forward, -1 the transposed rotation (gradients back to unrotated q, k). */
+size_t        mosaic_op_rope_table_bytes(int32_t N, int32_t d);
+mosaic_status mosaic_op_rope_table(void* stream, int32_t quota, int32_t N, int32_t d, float base,
+                                   void* table);
+mosaic_status mosaic_op_rope(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N,
+                             int32_t H, int32_t d, int32_t direction, void* qkv,
+                             const void* table);
+
+/* AdamW over n elements: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2;
+ * p -= lr * ( (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps) + weight_decay * p ).
+ * params, grads in `dtype`; m, v and master (may be NULL) fp32; master, when given, is the
+ * value that is updated and params receives its rounding. */
+mosaic_status mosaic_op_adamw(void* stream, int32_t quota, int32_t dtype, int64_t n, void* params,
+                              const void* grads, float* m, float* v, float* master, float lr,
+                              float beta1, float beta2, float eps, float weight_decay,
+                              int64_t step);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,8 @@ MAX_STAGE_MODULES = 8
 _KIND = {"encoder": ENCODER, "decoder": DECODER, "projector": PROJECTOR,
          "patch_stem": PATCH_STEM, "text_stem": TEXT_STEM}
 _NORM = {"none": NORM_NONE, "layernorm": LAYERNORM, "rmsnorm": RMSNORM}
-_ACT = {"gelu": GELU, "swiglu": SWIGLU}
+GELU_TANH = 2
+_ACT = {"gelu": GELU, "swiglu": SWIGLU, "gelu_tanh": GELU_TANH}
 _DTYPE = {"f32": F32, "bf16": BF16}
 
 
@@ -44,7 +45,8 @@ class ModuleDesc(C.Structure):
                 ("norm", C.c_int32), ("act", C.c_int32), ("causal", C.c_int32), ("bias", C.c_int32),
                 ("eps", C.c_float),
                 ("in_dim", C.c_int32), ("out_dim", C.c_int32),
-                ("vocab", C.c_int32), ("n_img", C.c_int32), ("patch", C.c_int32)]
+                ("vocab", C.c_int32), ("n_img", C.c_int32), ("patch", C.c_int32),
+                ("rope_base", C.c_float)]
 
 
 class Stage(C.Structure):
@@ -99,6 +101,8 @@ SIGNATURES = {
     "mosaic_module_forward": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "mosaic_module_backward": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "mosaic_module_step": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mosaic_module_optimizer_state_bytes": (C.c_size_t, [_vp, _i32]),
+    "mosaic_module_adamw_step": (_i32, [_vp, _i32, _vp, _vp, C.c_size_t, _i32, _f32, _f32, _f32, _f32, _f32, _i64]),
     "mosaic_plan_validate": (_i32, [C.POINTER(Plan), _i32, _i32]),
     "mosaic_stage_run": (_i32, [C.POINTER(Stage), C.POINTER(Plan), C.POINTER(Timing)]),
     "mosaic_plan_choose": (_i32, [_i32, _i32, C.POINTER(_i32), C.POINTER(_f32), _i32, C.POINTER(_i32), C.POINTER(_f32)]),
@@ -114,6 +118,12 @@ SIGNATURES = {
     "mosaic_op_norm_bwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_gelu_fwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp]),
     "mosaic_op_gelu_bwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp]),
+    "mosaic_op_gelu_tanh_fwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp]),
+    "mosaic_op_gelu_tanh_bwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp]),
+    "mosaic_op_rope_table_bytes": (C.c_size_t, [_i32, _i32]),
+    "mosaic_op_rope_table": (_i32, [_vp, _i32, _i32, _i32, _f32, _vp]),
+    "mosaic_op_rope": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "mosaic_op_adamw": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _f32, _i64]),
     "mosaic_op_swiglu_fwd": (_i32, [_vp, _i32, _i32, _i64, _i64, _vp, _vp]),
     "mosaic_op_swiglu_bwd": (_i32, [_vp, _i32, _i32, _i64, _i64, _vp, _vp, _vp]),
     "mosaic_op_mse": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp]),
@@ -236,6 +246,7 @@ def make_desc(cfg: dict, dtype: str) -> ModuleDesc:
     d.norm = _NORM[cfg.get("norm", "none")]
     d.act = _ACT[cfg.get("act", "gelu")]
     d.eps = float(cfg.get("eps", 0.0))
+    d.rope_base = float(cfg.get("rope", 0.0) or 0.0)
     return d
 
 
@@ -295,6 +306,22 @@ class Module:
     def step(self, quota: int, stream: Optional[Stream], x, y, dy=None, target=None, dx=None, loss=None) -> None:
         check(lib().mosaic_module_step(self.handle, quota, stream.handle if stream else None, _ptr(x), _ptr(dy),
                                        _ptr(target), _ptr(y), _ptr(dx), _ptr(loss)))
+
+    def init_optimizer(self, use_master: bool = False) -> None:
+        """Allocates the AdamW state (zero moments; the master copy, if asked for, starts as
+        the current parameters)."""
+        import torch
+        n = lib().mosaic_module_optimizer_state_bytes(self.handle, int(use_master)) // 4
+        self.opt_state = torch.zeros(n, dtype=torch.float32, device=self.params.device)
+        self.use_master = bool(use_master)
+        if use_master:
+            self.opt_state[2 * self.param_elems:3 * self.param_elems].copy_(self.params[:self.param_elems].float())
+
+    def adamw_step(self, quota: int, stream: Optional[Stream], step: int, lr: float, beta1: float = 0.9,
+                   beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.0) -> None:
+        check(lib().mosaic_module_adamw_step(self.handle, quota, stream.handle if stream else None, _ptr(self.opt_state),
+                                             self.opt_state.numel() * 4, int(self.use_master), lr, beta1, beta2, eps,
+                                             weight_decay, step))
 
     def destroy(self) -> None:
         if self.handle:
@@ -464,6 +491,31 @@ def op_gelu_fwd(stream, quota, dtype, n, z, a):
 
 def op_gelu_bwd(stream, quota, dtype, n, z, da, dz):
     check(lib().mosaic_op_gelu_bwd(stream, quota, _dt(dtype), n, _ptr(z), _ptr(da), _ptr(dz)))
+
+
+def op_gelu_tanh_fwd(stream, quota, dtype, n, z, a):
+    check(lib().mosaic_op_gelu_tanh_fwd(stream, quota, _dt(dtype), n, _ptr(z), _ptr(a)))
+
+
+def op_gelu_tanh_bwd(stream, quota, dtype, n, z, da, dz):
+    check(lib().mosaic_op_gelu_tanh_bwd(stream, quota, _dt(dtype), n, _ptr(z), _ptr(da), _ptr(dz)))
+
+
+def rope_table_bytes(N, d) -> int:
+    return int(lib().mosaic_op_rope_table_bytes(N, d))
+
+
+def op_rope_table(stream, quota, N, d, base, table):
+    check(lib().mosaic_op_rope_table(stream, quota, N, d, base, _ptr(table)))
+
+
+def op_rope(stream, quota, dtype, B, N, H, d, direction, qkv, table):
+    check(lib().mosaic_op_rope(stream, quota, _dt(dtype), B, N, H, d, direction, _ptr(qkv), _ptr(table)))
+
+
+def op_adamw(stream, quota, dtype, n, params, grads, m, v, master, lr, beta1, beta2, eps, weight_decay, step):
+    check(lib().mosaic_op_adamw(stream, quota, _dt(dtype), n, _ptr(params), _ptr(grads), _ptr(m), _ptr(v), _ptr(master),
+                                lr, beta1, beta2, eps, weight_decay, step))
 
 
 def op_swiglu_fwd(stream, quota, dtype, T, f, gu, a):

@@ -153,6 +153,42 @@ mosaic_status mosaic_op_swiglu_bwd(void* stream, int32_t quota, int32_t dtype, i
   return launch_swiglu_bwd((hipStream_t)stream, quota, dtype, T, f, gu, da, dgu);
 }
 
+mosaic_status mosaic_op_gelu_tanh_fwd(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* z, void* a) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(z); NONNULL(a);
+  return launch_gelu_tanh_fwd((hipStream_t)stream, quota, dtype, n, z, a);
+}
+
+mosaic_status mosaic_op_gelu_tanh_bwd(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* z, const void* da, void* dz) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(z); NONNULL(da); NONNULL(dz);
+  return launch_gelu_tanh_bwd((hipStream_t)stream, quota, dtype, n, z, da, dz);
+}
+
+size_t mosaic_op_rope_table_bytes(int32_t N, int32_t d) { return (N > 0 && d > 0) ? rope_table_bytes(N, d) : 0; }
+
+mosaic_status mosaic_op_rope_table(void* stream, int32_t quota, int32_t N, int32_t d, float base, void* table) {
+  MOSAIC_TRY(check_common(quota, MOSAIC_F32));
+  NONNULL(table);
+  return launch_rope_table((hipStream_t)stream, quota, N, d, base, table);
+}
+
+mosaic_status mosaic_op_rope(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H, int32_t d,
+                             int32_t direction, void* qkv, const void* table) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(qkv); NONNULL(table);
+  return launch_rope((hipStream_t)stream, quota, dtype, B, N, H, d, direction, qkv, table);
+}
+
+mosaic_status mosaic_op_adamw(void* stream, int32_t quota, int32_t dtype, int64_t n, void* params, const void* grads,
+                              float* m, float* v, float* master, float lr, float beta1, float beta2, float eps,
+                              float weight_decay, int64_t step) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(params); NONNULL(grads); NONNULL(m); NONNULL(v);
+  if (n < 0) MOSAIC_FAIL(MOSAIC_EINVAL, "negative element count");
+  return launch_adamw((hipStream_t)stream, quota, dtype, n, params, grads, m, v, master, lr, beta1, beta2, eps, weight_decay, step);
+}
+
 size_t mosaic_op_mse_scratch_bytes(void) { return mse_scratch_bytes(); }
 
 mosaic_status mosaic_op_mse(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* y, const void* target,

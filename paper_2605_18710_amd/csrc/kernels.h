@@ -41,6 +41,20 @@ mosaic_status launch_swiglu_fwd(hipStream_t s, int quota, int dtype, int64_t T, 
                                 const void* gu, void* a);
 mosaic_status launch_swiglu_bwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f,
                                 const void* gu, const void* da, void* dgu);
+// ------------------------------------------------------------------- layer variants
+mosaic_status launch_gelu_tanh_fwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, void* a);
+mosaic_status launch_gelu_tanh_bwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z,
+                                   const void* da, void* dz);
+// (cos, sin) of n * base^(-2i/d) for n < N, i < d/2, as float2[N][d/2]
+size_t rope_table_bytes(int N, int d);
+mosaic_status launch_rope_table(hipStream_t s, int quota, int N, int d, float base, void* table);
+// rotates the q and k parts of packed [B*N, 3*H*d] rows in place; direction -1 turns back
+mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+                          int direction, void* qkv, const void* table);
+// p, m, v (and master, if not null) updated in place; m, v, master are fp32
+mosaic_status launch_adamw(hipStream_t s, int quota, int dtype, int64_t n, void* p, const void* g,
+                           float* m, float* v, float* master, float lr, float beta1, float beta2,
+                           float eps, float weight_decay, int64_t step);
 size_t mse_scratch_bytes();
 mosaic_status launch_mse(hipStream_t s, int quota, int dtype, int64_t n, const void* y,
                          const void* target, void* dy, float* loss, void* scratch);

@@ -43,6 +43,7 @@ struct mosaic_module {
   // scratch byte offsets
   size_t s_dA, s_dZ, s_dU, s_dX1, s_dO, s_dQKV, s_delta, s_g0, s_g1, s_norm, s_colsum, s_mse, s_dyloss, s_splitk;
   size_t s_patches;
+  size_t s_rope = 0;     // (cos, sin) table of the rotary embedding, when on
   // bound buffers
   char* params = nullptr;
   char* grads = nullptr;
@@ -82,7 +83,9 @@ mosaic_status validate(const mosaic_module_desc& d) {
       if (d.hidden / d.heads > 128) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "head size %d > 128", d.hidden / d.heads);
       if (d.hidden % vn || d.mlp % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "hidden and mlp must be multiples of %d", vn);
       if (d.norm != MOSAIC_LAYERNORM && d.norm != MOSAIC_RMSNORM) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm %d", d.norm);
-      if (d.act != MOSAIC_GELU && d.act != MOSAIC_SWIGLU) MOSAIC_FAIL(MOSAIC_EINVAL, "bad activation %d", d.act);
+      if (d.act != MOSAIC_GELU && d.act != MOSAIC_SWIGLU && d.act != MOSAIC_GELU_TANH) MOSAIC_FAIL(MOSAIC_EINVAL, "bad activation %d", d.act);
+      if (!(d.rope_base >= 0.f)) MOSAIC_FAIL(MOSAIC_EINVAL, "rope_base must be 0 (off) or positive");
+      if (d.rope_base > 0.f && (d.hidden / d.heads) % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "rotary embedding needs a head size that is a multiple of %d", vn);
       if (!(d.eps > 0.f)) MOSAIC_FAIL(MOSAIC_EINVAL, "eps must be positive");
       break;
     case MOSAIC_PROJECTOR:
@@ -175,6 +178,7 @@ void build_layout(mosaic_module* m) {
     sk = std::max(sk, gemm_splitk_scratch_bytes(h, zf, T));
     sk = std::max(sk, gemm_splitk_scratch_bytes(f, h, T));
     m->s_splitk = take(&cur, sk);
+    if (d.rope_base > 0.f) m->s_rope = take(&cur, rope_table_bytes(d.seq, (int)(h / d.heads)));
   } else if (d.kind == MOSAIC_PROJECTOR) {
     LayerParams q;
     q.w_1 = add_tensor(m, "w_1", d.in_dim, d.out_dim);
@@ -227,18 +231,23 @@ mosaic_status layers_forward(mosaic_module* m, hipStream_t s, int q, const void*
   const int dt = d.dtype;
   const bool glu = d.act == MOSAIC_SWIGLU;
   const void* xin = x;
+  const bool rope = d.rope_base > 0.f;
+  const int dh = (int)(h / d.heads);
+  if (rope) MOSAIC_TRY(launch_rope_table(s, q, d.seq, dh, d.rope_base, W(m, m->s_rope)));
   for (int l = 0; l < d.layers; ++l) {
     const LayerParams& p = m->lp[l];
     const LayerSaved& sv = m->ls[l];
     void* yout = (l + 1 < d.layers) ? W(m, sv.y) : y;
     MOSAIC_TRY(launch_norm_fwd(s, q, dt, d.norm, T, h, d.eps, xin, P(m, p.n1_g), P(m, p.n1_b), W(m, sv.u1), (float*)W(m, sv.st1)));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, 3 * h, h, W(m, sv.u1), h, P(m, p.w_qkv), 3 * h, W(m, sv.qkv), 3 * h, P(m, p.b_qkv), nullptr));
-    MOSAIC_TRY(launch_attention_fwd(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o), (float*)W(m, sv.lse)));
+    if (rope) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, dh, +1, W(m, sv.qkv), W(m, m->s_rope)));   // saved rotated
+    MOSAIC_TRY(launch_attention_fwd(s, q, dt, d.batch, d.seq, d.heads, dh, d.causal, W(m, sv.qkv), W(m, sv.o), (float*)W(m, sv.lse)));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, h, W(m, sv.o), h, P(m, p.w_o), h, W(m, sv.x1), h, P(m, p.b_o), xin));
     MOSAIC_TRY(launch_norm_fwd(s, q, dt, d.norm, T, h, d.eps, W(m, sv.x1), P(m, p.n2_g), P(m, p.n2_b), W(m, sv.u2), (float*)W(m, sv.st2)));
     const int64_t zf = glu ? 2 * f : f;
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, zf, h, W(m, sv.u2), h, P(m, p.w_1), zf, W(m, sv.z), zf, P(m, p.b_1), nullptr));
     if (glu) MOSAIC_TRY(launch_swiglu_fwd(s, q, dt, T, f, W(m, sv.z), W(m, sv.a)));
+    else if (d.act == MOSAIC_GELU_TANH) MOSAIC_TRY(launch_gelu_tanh_fwd(s, q, dt, T * f, W(m, sv.z), W(m, sv.a)));
     else MOSAIC_TRY(launch_gelu_fwd(s, q, dt, T * f, W(m, sv.z), W(m, sv.a)));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, f, W(m, sv.a), f, P(m, p.w_2), h, yout, h, P(m, p.b_2), W(m, sv.x1)));
     xin = yout;
@@ -267,6 +276,7 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     if (p.b_2 >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, gin, G(m, p.b_2), csc));
     // activation
     if (glu) MOSAIC_TRY(launch_swiglu_bwd(s, q, dt, T, f, W(m, sv.z), dA, dZ));
+    else if (d.act == MOSAIC_GELU_TANH) MOSAIC_TRY(launch_gelu_tanh_bwd(s, q, dt, T * f, W(m, sv.z), dA, dZ));
     else MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * f, W(m, sv.z), dA, dZ));
     // MLP up projection
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, zf, T, W(m, sv.u2), h, dZ, zf, G(m, p.w_1), zf, nullptr, nullptr, W(m, m->s_splitk)));
@@ -281,6 +291,9 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     // attention
     MOSAIC_TRY(launch_attention_bwd(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o),
                                     (const float*)W(m, sv.lse), dO, dQKV, (float*)W(m, m->s_delta)));
+    // gradients of the rotated q, k go back through the transposed rotation (the table of
+    // the forward pass is still in the workspace)
+    if (d.rope_base > 0.f) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), -1, dQKV, W(m, m->s_rope)));
     // QKV projection
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, 3 * h, T, W(m, sv.u1), h, dQKV, 3 * h, G(m, p.w_qkv), 3 * h, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_qkv >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, 3 * h, dQKV, G(m, p.b_qkv), csc));
@@ -484,6 +497,28 @@ mosaic_status mosaic_module_step(mosaic_module* m, int32_t quota, const mosaic_s
     g = W(m, m->s_dyloss);
   }
   return mosaic_module_backward(m, quota, stream, g, dx);
+}
+
+size_t mosaic_module_optimizer_state_bytes(const mosaic_module* m, int32_t use_master) {
+  return m ? (size_t)m->param_elems * sizeof(float) * (use_master ? 3 : 2) : 0;
+}
+
+mosaic_status mosaic_module_adamw_step(mosaic_module* m, int32_t quota, const mosaic_stream* stream, void* state,
+                                       size_t state_bytes, int32_t use_master, float lr, float beta1, float beta2,
+                                       float eps, float weight_decay, int64_t step) {
+  MOSAIC_TRY(check_bound(m));
+  if (!state) MOSAIC_FAIL(MOSAIC_EINVAL, "null optimizer state");
+  if (state_bytes < mosaic_module_optimizer_state_bytes(m, use_master)) MOSAIC_FAIL(MOSAIC_ENOMEM, "optimizer state too small");
+  if ((uintptr_t)state % 16) MOSAIC_FAIL(MOSAIC_EINVAL, "optimizer state must be 16-byte aligned");
+  int q;
+  MOSAIC_TRY(resolve_quota(quota, stream, &q));
+  float* mom = (float*)state;
+  float* var = mom + m->param_elems;
+  float* master = use_master ? var + m->param_elems : nullptr;
+  // one launch over the flat buffer: every tensor starts on a 16-byte boundary and the padding
+  // between tensors holds zeros with zero gradients, which the update leaves at zero
+  return launch_adamw(mosaic_stream_hip(stream), q, m->d.dtype, m->param_elems, m->params, m->grads, mom, var, master,
+                      lr, beta1, beta2, eps, weight_decay, step);
 }
 
 }  // extern "C"

@@ -1,0 +1,168 @@
+"""GPU parity of the layer variants (tanh GELU, rotary position embedding, AdamW) against
+the CPU checker, through the C ABI: 1e-5 relative L2 on the fp32 path, 2e-2 for bf16 storage
+with fp32 accumulation, and raw-bit equality across quotas."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as O
+from paper_2605_18710_amd import synth
+from helpers import (layer_params, quantize, quantize_tree, to_dev, from_dev, rel_l2, tol,
+                     load_layer_params, read_layer_grads)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_18710_amd import binding
+    binding.lib()
+    return binding
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy().copy()
+
+
+@pytest.mark.parametrize("dtype,n", [("f32", 4 * 1031), ("bf16", 1568 * 3072), ("bf16", 8)])
+def test_gelu_tanh(mb, dtype, n):
+    z = quantize(synth.normal(3300, (n,), 0.0, 1.5), dtype)
+    da = quantize(synth.normal(3301, (n,)), dtype)
+    z_, da_ = to_dev(z, dtype), to_dev(da, dtype)
+    outs = []
+    for q in (256, 40):
+        a, dz = torch.empty_like(z_), torch.empty_like(z_)
+        mb.op_gelu_tanh_fwd(None, q, dtype, n, z_, a)
+        mb.op_gelu_tanh_bwd(None, q, dtype, n, z_, da_, dz)
+        torch.cuda.synchronize()
+        outs.append((bits(a), bits(dz)))
+    assert rel_l2(from_dev(a), O.gelu_tanh(z)) <= tol(dtype)
+    assert rel_l2(from_dev(dz), da * O.gelu_tanh_grad(z)) <= tol(dtype)
+    assert all(np.array_equal(x, y) for x, y in zip(outs[0], outs[1]))
+
+
+@pytest.mark.parametrize("dtype,B,N,H,d", [("f32", 2, 128, 4, 32), ("bf16", 2, 1000, 3, 128), ("bf16", 1, 4096, 2, 64)])
+def test_rope_forward_and_transposed(mb, dtype, B, N, H, d):
+    h = H * d
+    qkv = quantize(synth.normal(3400, (B * N, 3 * h)), dtype)
+    table = torch.empty(mb.rope_table_bytes(N, d), dtype=torch.uint8, device="cuda")
+    mb.op_rope_table(None, 256, N, d, 10000.0, table)
+    # the table itself: angles formed in double, so the last position is as good as the first
+    tab = table.view(torch.float32).cpu().numpy().reshape(N, d // 2, 2).astype(np.float64)
+    ang = np.arange(N)[:, None] * (10000.0 ** (-2.0 * np.arange(d // 2) / d))[None, :]
+    assert np.abs(tab[..., 0] - np.cos(ang)).max() < 2e-7 and np.abs(tab[..., 1] - np.sin(ang)).max() < 2e-7
+    outs = []
+    for q in (256, 24):
+        x = to_dev(qkv, dtype)
+        mb.op_rope(None, q, dtype, B, N, H, d, +1, x, table)
+        torch.cuda.synchronize()
+        fwd = from_dev(x)
+        y = to_dev(qkv, dtype)
+        mb.op_rope(None, q, dtype, B, N, H, d, -1, y, table)
+        torch.cuda.synchronize()
+        outs.append((bits(x), bits(y)))
+    assert rel_l2(fwd, O.rope_rotate(qkv, B, N, H, 10000.0)) <= tol(dtype)
+    assert rel_l2(from_dev(y), O.rope_rotate(qkv, B, N, H, 10000.0, -1.0)) <= tol(dtype)
+    assert np.array_equal(fwd[:, 2 * h:], qkv[:, 2 * h:])                      # v untouched, bit for bit
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0], outs[1]))
+
+
+def dec(B, N, h, H, f, L, **kw):
+    return dict(dict(kind="decoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=L,
+                     norm="rmsnorm", act="swiglu", causal=1, bias=0, eps=1e-5), **kw)
+
+
+def enc(B, N, h, H, f, L, **kw):
+    return dict(dict(kind="encoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=L,
+                     norm="layernorm", act="gelu", causal=0, bias=1, eps=1e-5), **kw)
+
+
+@pytest.mark.parametrize("dtype,cfg", [
+    ("f32", dec(2, 128, 128, 4, 384, 1, rope=10000.0)),
+    ("bf16", dec(2, 160, 512, 4, 768, 2, rope=10000.0)),
+    ("bf16", enc(2, 196, 256, 4, 1024, 2, act="gelu_tanh")),
+    ("f32", enc(2, 16, 128, 4, 512, 1, act="gelu_tanh", rope=500.0)),
+])
+def test_stack_with_variants_matches_oracle_and_is_quota_invariant(mb, dtype, cfg):
+    T, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    layers = quantize_tree([layer_params(cfg, 5000 + 100 * l) for l in range(cfg["layers"])], dtype)
+    x = quantize(synth.normal(5050, (T, h)), dtype)
+    target = quantize(synth.normal(5051, (T, h)), dtype)
+    y_ref, saved = O.stack_fwd(x, layers, cfg)
+    dx_ref, g_ref = O.stack_bwd(O.mse_bwd(y_ref, target), layers, saved, cfg)
+    plain = dict(cfg, rope=0.0, act=("gelu" if cfg["act"] == "gelu_tanh" else cfg["act"]))
+    assert rel_l2(O.stack_fwd(x, layers, plain)[0], y_ref) > 1e-6         # the variant changes the result
+    m = mb.Module(cfg, dtype)
+    load_layer_params(m, layers)
+    x_, t_ = to_dev(x, dtype), to_dev(target, dtype)
+    first = None
+    for q in (256, 56):
+        y = torch.empty_like(x_); dx = torch.empty_like(x_)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        m.grads.zero_()
+        m.step(q, None, x_, y, target=t_, dx=dx, loss=loss)
+        torch.cuda.synchronize()
+        snap = [bits(y), bits(dx), bits(m.grads)]
+        if first is None:
+            first = snap
+            assert rel_l2(from_dev(y), y_ref) <= tol(dtype)
+            assert rel_l2(from_dev(dx), dx_ref) <= tol(dtype)
+            g = read_layer_grads(m, layers)
+            for l in range(cfg["layers"]):
+                for k in g_ref[l]:
+                    assert rel_l2(g[l][k], g_ref[l][k]) <= tol(dtype), (l, k)
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(snap, first)), "step depends on the quota"
+    m.destroy()
+
+
+@pytest.mark.parametrize("dtype,n,master", [("f32", 4 * 1031, False), ("bf16", 8 * 4099, False), ("bf16", 8 * 4099, True)])
+def test_adamw_steps(mb, dtype, n, master):
+    hp = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.05)
+    p0 = quantize(synth.normal(3500, (n,), 0.0, 0.02), dtype)
+    p_ = to_dev(p0, dtype)
+    m_ = torch.zeros(n, dtype=torch.float32, device="cuda"); v_ = torch.zeros_like(m_)
+    mast = p_.float().clone() if master else None
+    p, m, v = p0.copy(), np.zeros(n), np.zeros(n)
+    for t in range(1, 5):
+        g = quantize(synth.normal(3510 + t, (n,), 0.0, 1e-3), dtype)
+        mb.op_adamw(None, 256 if t % 2 else 48, dtype, n, p_, to_dev(g, dtype), m_, v_, mast, step=t, **hp)
+        if dtype == "bf16" and not master:
+            # without a master copy the parameter is re-rounded to storage every step: the checker follows it
+            p, m, v = O.adamw_step(p, g, m, v, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"])
+            p = quantize(p, dtype)
+        else:
+            p, m, v = O.adamw_step(p, g, m, v, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"])
+    torch.cuda.synchronize()
+    assert rel_l2(from_dev(m_), m) <= 1e-5 and rel_l2(from_dev(v_), v) <= 1e-5      # moments are fp32 on every path
+    got = from_dev(mast) if master else from_dev(p_)
+    # the update itself (what the step changed) is the quantity that must agree
+    bound = 1e-5 if (dtype == "f32" or master) else tol(dtype)
+    assert rel_l2(got - p0, p - p0) <= (1e-4 if bound == 1e-5 else bound)
+    if master:
+        assert np.array_equal(from_dev(p_), quantize(from_dev(mast), "bf16"))        # params = rounding of the master copy
+
+
+def test_module_adamw_step_moves_every_tensor(mb):
+    cfg = dec(2, 64, 128, 4, 256, 2)
+    m = mb.Module(cfg, "bf16")
+    layers = quantize_tree([layer_params(cfg, 6000 + 100 * l) for l in range(2)], "bf16")
+    load_layer_params(m, layers)
+    T, h = 128, 128
+    x_, t_ = to_dev(quantize(synth.normal(6050, (T, h)), "bf16"), "bf16"), to_dev(quantize(synth.normal(6051, (T, h)), "bf16"), "bf16")
+    y = torch.empty_like(x_); loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    m.init_optimizer(use_master=True)
+    losses = []
+    for step in range(1, 4):
+        m.step(256, None, x_, y, target=t_, loss=loss)
+        m.adamw_step(256, None, step, lr=1e-3, weight_decay=0.01)
+        torch.cuda.synchronize()
+        losses.append(loss.item())
+    assert losses[2] < losses[0]                    # three steps on one batch reduce its loss
+    before = quantize_tree(layers, "bf16")
+    for l in range(2):
+        for k in ("w_qkv", "w_o", "rms1_g", "w_down"):
+            assert np.abs(m.get_tensor(f"L{l}.{k}") - before[l][k]).max() > 0
+    m.destroy()
