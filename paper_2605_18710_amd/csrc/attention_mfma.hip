@@ -33,6 +33,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+// Online softmax keeps, per row, a reference value m and sums of exp2(s - m).  Any m works
+// (softmax is shift-invariant) as long as the exponentials stay in range, so the reference
+// only follows the running maximum when some row's maximum has grown by more than this many
+// powers of two: probabilities then reach at most 2^8, well inside bf16 and fp32, and the
+// rescale of the running sums (one multiply per accumulator register) becomes rare instead
+// of happening on almost every block of a long row.
+constexpr float kLazyRescale = 8.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -139,14 +146,30 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
 // streamed index (within a 32-block) held by register r of a lane of half hb
 __device__ __forceinline__ int acc_row(int r, int hb) { return 8 * (r >> 2) + 4 * hb + (r & 3); }
 
-// Work order for tiles of unequal cost (causal masks): items are ranked heaviest first and
-// dealt to the persistent workgroups in a snake (even rounds ascending, odd rounds
-// descending), so a workgroup that drew a heavy tile next draws a light one.
-// Returns the rank of the `round`-th item of workgroup blockIdx.x, or -1.
-__device__ __forceinline__ int snake_item(int round, int items) {
-  const int G = gridDim.x, b = blockIdx.x;
-  const int idx = round * G + ((round & 1) ? (G - 1 - b) : b);
-  return idx < items ? idx : -1;
+// Work order.  All query tiles of one (sample, head) stream the same K and V rows (all key
+// tiles the same Q and dO rows), so they should run at the same time on the same XCD and
+// meet in its L2: handed out head by head otherwise, 512 resident workgroups stream 512
+// different heads and every tile comes from HBM (the forward kernel then moves ~4.4 GB per
+// millisecond and is bandwidth-bound).  Workgroup w runs on XCD w % 8 (workgroups are dealt
+// round-robin over XCDs); the workgroups of one XCD walk that XCD's heads (head % 8 == XCD)
+// one after another, `tiles` consecutive slots per head.  Tiles cost unequally under a causal
+// mask: when a round covers whole heads the position inside the head is mirrored every
+// other round, so a workgroup that drew a heavy tile next draws a light one.  Grids that are not a multiple of 8 take the
+// same walk over all heads.  Returns false when the workgroup has no item in this round
+// (nor in any later one).
+__device__ __forceinline__ bool attn_item(int round, int heads, int tiles, int* head, int* tile) {
+  const int G = gridDim.x, w = blockIdx.x;
+  const bool by_xcd = (G & 7) == 0;
+  const int nx = by_xcd ? 8 : 1, xcd = by_xcd ? (w & 7) : 0, slot = by_xcd ? (w >> 3) : w, spx = by_xcd ? (G >> 3) : G;
+  const int64_t l = (int64_t)round * spx + slot;
+  const int hs = (int)(l / tiles), pos = (int)(l - (int64_t)hs * tiles);
+  const int hh = hs * nx + xcd;
+  if (hh >= heads) return false;
+  *head = hh;
+  // mirroring is a bijection only when a round covers whole heads; otherwise the position
+  // of a workgroup rotates from round to round by itself
+  *tile = ((round & 1) && spx % tiles == 0) ? tiles - 1 - pos : pos;
+  return true;
 }
 
 // --------------------------------------------------------------------------- forward
@@ -167,12 +190,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
   const int64_t rs = 3 * (int64_t)h;
-  const int items = B * H * qtiles;
-  for (int round = 0; round * (int)gridDim.x < items; ++round) {
-    const int item = snake_item(round, items);
-    if (item < 0) continue;
-    // late query tiles carry the most keys under a causal mask: rank them first
-    const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
+  for (int round = 0;; ++round) {
+    int head_, qt;
+    if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
+    const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     bf16x8 qf[NS];
@@ -232,8 +253,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;       // scale > 0: max commutes with it
         const float mn = fmaxf(m, mx);
-        // rescale the running sums only when some row's maximum moved (exact: the factor is 1 otherwise)
-        if (__any(mn > m)) {
+        if (__any(mx > m + kLazyRescale)) {
           const float mref0 = (mn == -INFINITY) ? 0.f : mn;
           const float corr = fast_exp2(m - mref0);               // m = -inf -> 0
           lsum *= corr;
@@ -345,11 +365,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
   const int h = H * D;
   const int64_t rs = 3 * (int64_t)h;
   const float scale_log2 = scale * kLog2e;
-  const int items = B * H * qtiles;
-  for (int round = 0; round * (int)gridDim.x < items; ++round) {
-    const int item = snake_item(round, items);
-    if (item < 0) continue;
-    const int qt = qtiles - 1 - item / (B * H), hd = item % H, b = (item / H) % B;
+  for (int round = 0;; ++round) {
+    int head_, qt;
+    if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
+    const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
@@ -403,12 +422,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
           pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(vs, 32 * sub + lr, s, hb), dof[s], pacc, 0, 0, 0);
         }
         float ds[16];
+        // only blocks that touch the diagonal or the end of the sequence need the mask
+        const bool need_mask = (jb + 32 > N) || (i0 + 32 > N) || (causal && jb + 31 > i0);
+        if (need_mask) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jb + acc_row(r, hb);
-          const bool masked = (j >= N) || (i >= N) || (causal && j > i);
-          const float p = masked ? 0.f : fast_exp2(sacc[r] * scale_log2 - lse2);
-          ds[r] = p * (pacc[r] - dlt);
+          for (int r = 0; r < 16; ++r) {
+            const int j = jb + acc_row(r, hb);
+            const bool masked = (j >= N) || (i >= N) || (causal && j > i);
+            const float p = masked ? 0.f : fast_exp2(fmaf(sacc[r], scale_log2, -lse2));
+            ds[r] = p * (pacc[r] - dlt);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
         }
         const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
@@ -462,12 +488,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   const int h = H * D;
   const int64_t rs = 3 * (int64_t)h;
   const float scale_log2 = scale * kLog2e;
-  const int items = B * H * ktiles;
-  for (int round = 0; round * (int)gridDim.x < items; ++round) {
-    const int item = snake_item(round, items);
-    if (item < 0) continue;
-    // early key tiles see the most queries under a causal mask: rank them first
-    const int kt_i = item / (B * H), hd = item % H, b = (item / H) % B;
+  for (int round = 0;; ++round) {
+    int head_, kt_i;
+    if (!attn_item(round, B * H, ktiles, &head_, &kt_i)) break;
+    const int hd = head_ % H, b = head_ / H;
     const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
     const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
@@ -535,13 +559,25 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
           pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
         }
         float pv[16], ds[16];
+        // only blocks that touch the diagonal or the end of the sequence need the mask
+        const bool need_mask = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
+        if (need_mask) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int il = acc_row(r, hb), gi = ib + il;
-          const bool masked = (gi >= N) || (j >= N) || (causal && j > gi);
-          const float p = masked ? 0.f : fast_exp2(sacc[r] * scale_log2 - sl[il] * kLog2e);
-          pv[r] = p;
-          ds[r] = p * (pacc[r] - sd[il]);
+          for (int r = 0; r < 16; ++r) {
+            const int il = acc_row(r, hb), gi = ib + il;
+            const bool masked = (gi >= N) || (j >= N) || (causal && j > gi);
+            const float p = masked ? 0.f : fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
+            pv[r] = p;
+            ds[r] = p * (pacc[r] - sd[il]);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int il = acc_row(r, hb);
+            const float p = fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
+            pv[r] = p;
+            ds[r] = p * (pacc[r] - sd[il]);
+          }
         }
         const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
@@ -584,12 +620,12 @@ mosaic_status set_smem(K kern, size_t bytes) {
 // load latency.  Only the 4-wave shape is instantiated.
 template <int D, int NW>
 mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, bf16* O, float* lse) {
-  constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
-  static bool once = false;
-  if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
   const int qtiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * qtiles;
   const int grid = grid_for(quota, 8 / NW, items);
+  constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
+  static bool once = false;
+  if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
   attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, causal, kLog2e / sqrtf((float)D), qtiles);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
