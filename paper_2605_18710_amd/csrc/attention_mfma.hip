@@ -421,21 +421,18 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
           pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(vs, 32 * sub + lr, s, hb), dof[s], pacc, 0, 0, 0);
         }
-        float ds[16];
-        // only blocks that touch the diagonal or the end of the sequence need the mask
-        const bool need_mask = (jb + 32 > N) || (i0 + 32 > N) || (causal && jb + 31 > i0);
-        if (need_mask) {
+        // only blocks that touch the diagonal or the end of the sequence need the mask: a
+        // masked score becomes -inf, so its recomputed probability is exactly 0
+        if ((jb + 32 > N) || (i0 + 32 > N) || (causal && jb + 31 > i0)) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int j = jb + acc_row(r, hb);
-            const bool masked = (j >= N) || (i >= N) || (causal && j > i);
-            const float p = masked ? 0.f : fast_exp2(fmaf(sacc[r], scale_log2, -lse2));
-            ds[r] = p * (pacc[r] - dlt);
+            if ((j >= N) || (i >= N) || (causal && j > i)) sacc[r] = -INFINITY;
           }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
         }
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
         const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -481,8 +478,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   const float* stat = reinterpret_cast<const float*>(smem_raw + NST * STAGE + LV::BYTES);  // [NST][2][64]: lse, delta
   L ld;
   ld.init();
-  LV ldv;
-  ldv.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   const int h = H * D;
@@ -535,7 +530,11 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       ld.issue(do_, hsb, row0, nb + L::BYTES);
     };
     __syncthreads();
-    ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + NST * STAGE);
+    {
+      LV ldv;            // built here so that its per-lane offsets do not live across the tile loop
+      ldv.init();
+      ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + NST * STAGE);
+    }
 #pragma unroll
     for (int u = 0; u < PD; ++u) { request(u); stage_stats(u); }
     wait_requests<(PD - 1) * NREQ>();
@@ -558,26 +557,22 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
           pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
         }
+        // only blocks that touch the diagonal or the end of the sequence need the mask: a
+        // masked score becomes -inf, so its recomputed probability is exactly 0
+        if ((ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib)) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int gi = ib + acc_row(r, hb);
+            if ((gi >= N) || (j >= N) || (causal && j > gi)) sacc[r] = -INFINITY;
+          }
+        }
         float pv[16], ds[16];
-        // only blocks that touch the diagonal or the end of the sequence need the mask
-        const bool need_mask = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
-        if (need_mask) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int il = acc_row(r, hb), gi = ib + il;
-            const bool masked = (gi >= N) || (j >= N) || (causal && j > gi);
-            const float p = masked ? 0.f : fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
-            pv[r] = p;
-            ds[r] = p * (pacc[r] - sd[il]);
-          }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int il = acc_row(r, hb);
-            const float p = fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
-            pv[r] = p;
-            ds[r] = p * (pacc[r] - sd[il]);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int il = acc_row(r, hb);
+          const float p = fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
+          pv[r] = p;
+          ds[r] = p * (pacc[r] - sd[il]);
         }
         const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
