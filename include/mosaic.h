@@ -256,6 +256,13 @@ mosaic_status mosaic_interference_fit(int32_t n_obs, const int32_t* group_size,
  * bandwidth utilisation measured at the same points and e the fitted coefficients of
  * Eq. 8 (both or neither); a stage of two or more modules is then charged Eq. 8's delay,
  * a module alone is not.  At most 16 modules and 16 quota levels. */
+/* How the fitted expression enters a module's time.  ABSOLUTE is the paper's: one delay in
+ * ms per GPU, computed over all its modules, added to each (Eq. 7-8).  PEER_RELATIVE is
+ * this build's addition for a GPU whose co-runners slow each other through a shared power
+ * budget: module m's time is multiplied by 1 + e1 + e2 * sum B + e3 * prod B taken over the
+ * OTHER modules of the stage (fit the coefficients to relative delays and peers' values
+ * with the same mosaic_interference_fit). */
+enum { MOSAIC_DELAY_ABSOLUTE = 0, MOSAIC_DELAY_PEER_RELATIVE = 1 };
 typedef struct {
   int32_t        n_modules, n_edges;
   const int32_t* edges;        /* 2*n_edges entries */
@@ -265,6 +272,7 @@ typedef struct {
   const double*  bw;           /* may be NULL */
   const double*  e;            /* 3 doubles, NULL iff bw is NULL */
   int32_t        cu_total;
+  int32_t        delay_form;   /* MOSAIC_DELAY_ABSOLUTE (Eq. 7-8) | MOSAIC_DELAY_PEER_RELATIVE */
 } mosaic_planner_problem;
 typedef struct { int64_t stage_evals, cache_hits, pruned, rounds; } mosaic_planner_stats;
 enum { MOSAIC_PLANNER_EARLY_PRUNE = 1, MOSAIC_PLANNER_CACHE = 2 };

@@ -26,6 +26,14 @@ What is written out here, and from where:
     the amount of work, never the result, and are NOT part of this checker: the C++ planner
     has them and must agree with this plain loop with either switched on or off.
 
+A second way of charging the delay is offered beside the paper's (it is this build's, not
+the paper's): PEER_RELATIVE evaluates Eq. 8's expression over the utilisations of the OTHER
+modules on the GPU and charges it as a fraction of the module's own time,
+T_m * (1 + e1 + e2 * sum_{m' != m} B_m' + e3 * prod_{m' != m} B_m').  On the GPU this build
+targets, co-runners slow a module down through the shared power budget, in proportion to
+its own run time and to the co-runners' matrix-core utilisation, which the paper's one
+additive term per GPU cannot express.
+
 Readings where the paper is silent (the C++ planner takes the same ones):
   * a module alone on the GPU suffers no delay: Eq. 8 is applied only to stages of two or
     more modules (the grid-sampled time of a module already contains its own traffic);
@@ -55,6 +63,8 @@ from typing import Dict, FrozenSet, List, Optional, Sequence, Tuple
 import numpy as np
 
 ADDITIVE, COMPOSITE = 0, 1
+# how a fitted delay enters a module's time
+ABSOLUTE, PEER_RELATIVE = 0, 1
 
 
 # ------------------------------------------------------------------------ Eq. 7-8
@@ -93,16 +103,26 @@ def interference_fit(groups: Sequence[Sequence[float]], delta: Sequence[float], 
 
 
 # ------------------------------------------------------------------------ Eq. 4-5, 7
-def stage_time(levels: Sequence[int], modules: Sequence[int], times, bw=None, e=None) -> float:
+def stage_time(levels: Sequence[int], modules: Sequence[int], times, bw=None, e=None, form: int = ABSOLUTE) -> float:
     """Time of a stage whose module modules[k] runs at grid level levels[k]: the slowest
-    module's grid-sampled time plus, for a shared GPU and a fitted model, Eq. 8's delay."""
-    d = 0.0
-    if e is not None and bw is not None and len(modules) >= 2:
-        d = interference_delta(e, [bw[m][p] for m, p in zip(modules, levels)])
-    return max(times[m][p] + d for m, p in zip(modules, levels))
+    module's rectified time.  ABSOLUTE (Eq. 7-8): grid-sampled time plus one delay computed
+    over all modules of the stage.  PEER_RELATIVE: grid-sampled time times one plus the
+    expression of Eq. 8 over the other modules of the stage.  A module alone is not delayed."""
+    if e is None or bw is None or len(modules) < 2:
+        return max(times[m][p] for m, p in zip(modules, levels))
+    b = [bw[m][p] for m, p in zip(modules, levels)]
+    if form == ABSOLUTE:
+        d = interference_delta(e, b)
+        return max(times[m][p] + d for m, p in zip(modules, levels))
+    worst = -math.inf
+    for k, (m, p) in enumerate(zip(modules, levels)):
+        peers = b[:k] + b[k + 1:]
+        worst = max(worst, times[m][p] * (1.0 + interference_delta(e, peers)))
+    return worst
 
 
-def stage_eval(modules: Sequence[int], cu_points: Sequence[int], times, cu_total: int, bw=None, e=None):
+def stage_eval(modules: Sequence[int], cu_points: Sequence[int], times, cu_total: int, bw=None, e=None,
+               form: int = ABSOLUTE):
     """Eq. 4-5 by definition: the assignment of one grid level per module, quotas summing
     to at most cu_total, that minimises the stage time.  Returns (time, {module: CUs});
     (inf, {}) when nothing fits."""
@@ -111,7 +131,7 @@ def stage_eval(modules: Sequence[int], cu_points: Sequence[int], times, cu_total
     for levels in itertools.product(range(len(cu_points)), repeat=len(modules)):
         if sum(cu_points[p] for p in levels) > cu_total:
             continue
-        t = stage_time(levels, modules, times, bw, e)
+        t = stage_time(levels, modules, times, bw, e, form)
         if t < best_t:            # product() runs in lexicographic order: first minimum wins
             best_t, best_levels = t, levels
     if best_levels is None:
@@ -170,10 +190,10 @@ def merge_is_legal(stages: List[FrozenSet[int]], edges, x: int, y: int) -> bool:
     return not _reachable(adj, x, y) and not _reachable(adj, y, x)
 
 
-def gahc(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None):
+def gahc(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None, form: int = ABSOLUTE):
     """Alg. 1.  Returns (stages in execution order, {module: CUs}, iteration time)."""
     stages = topo_order([frozenset([m]) for m in range(n_modules)], edges)
-    ev = {s: stage_eval(s, cu_points, times, cu_total, bw, e) for s in stages}
+    ev = {s: stage_eval(s, cu_points, times, cu_total, bw, e, form) for s in stages}
     while len(stages) > 1:
         best_gain, best = 0.0, None
         for x in range(len(stages)):
@@ -182,7 +202,7 @@ def gahc(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None
                     continue
                 u = stages[x] | stages[y]
                 if u not in ev:
-                    ev[u] = stage_eval(u, cu_points, times, cu_total, bw, e)
+                    ev[u] = stage_eval(u, cu_points, times, cu_total, bw, e, form)
                 gain = ev[stages[x]][0] + ev[stages[y]][0] - ev[u][0]
                 if gain > best_gain:
                     best_gain, best = gain, (x, y)

@@ -380,6 +380,7 @@ def plan_choose(cu_points: Sequence[int], times: Sequence[Sequence[float]], cu_t
 # ------------------------------------------------- performance-model correction, planner
 ADDITIVE, COMPOSITE = 0, 1
 EARLY_PRUNE, CACHE = 1, 2
+DELAY_ABSOLUTE, DELAY_PEER_RELATIVE = 0, 1
 
 
 def interference_delta(e: Sequence[float], bw: Sequence[float]) -> float:
@@ -403,14 +404,15 @@ def interference_fit(groups: Sequence[Sequence[float]], delta: Sequence[float], 
 class _PlannerProblem(C.Structure):
     _fields_ = [("n_modules", C.c_int32), ("n_edges", C.c_int32), ("edges", C.POINTER(C.c_int32)),
                 ("n_points", C.c_int32), ("cu_points", C.POINTER(C.c_int32)), ("times", C.POINTER(C.c_double)),
-                ("bw", C.POINTER(C.c_double)), ("e", C.POINTER(C.c_double)), ("cu_total", C.c_int32)]
+                ("bw", C.POINTER(C.c_double)), ("e", C.POINTER(C.c_double)), ("cu_total", C.c_int32),
+                ("delay_form", C.c_int32)]
 
 
 class _PlannerStats(C.Structure):
     _fields_ = [("stage_evals", C.c_int64), ("cache_hits", C.c_int64), ("pruned", C.c_int64), ("rounds", C.c_int64)]
 
 
-def _planner_problem(n_modules, edges, cu_points, times, cu_total, bw=None, e=None):
+def _planner_problem(n_modules, edges, cu_points, times, cu_total, bw=None, e=None, form=0):
     keep = []          # ctypes arrays the struct points into
     def arr(ty, vals):
         a = (ty * max(1, len(vals)))(*vals)
@@ -418,6 +420,7 @@ def _planner_problem(n_modules, edges, cu_points, times, cu_total, bw=None, e=No
         return a
     p = _PlannerProblem()
     p.n_modules, p.n_edges, p.n_points, p.cu_total = n_modules, len(edges), len(cu_points), cu_total
+    p.delay_form = form
     p.edges = arr(C.c_int32, [int(v) for ed in edges for v in ed])
     p.cu_points = arr(C.c_int32, [int(v) for v in cu_points])
     p.times = arr(C.c_double, [float(v) for row in times for v in row])
@@ -427,9 +430,9 @@ def _planner_problem(n_modules, edges, cu_points, times, cu_total, bw=None, e=No
     return p, keep
 
 
-def stage_eval(modules: Sequence[int], n_modules: int, cu_points, times, cu_total: int, bw=None, e=None):
+def stage_eval(modules: Sequence[int], n_modules: int, cu_points, times, cu_total: int, bw=None, e=None, form: int = 0):
     """StageEval for the stage holding `modules`: (time in ms, {module: CUs})."""
-    p, keep = _planner_problem(n_modules, [], cu_points, times, cu_total, bw, e)
+    p, keep = _planner_problem(n_modules, [], cu_points, times, cu_total, bw, e, form)
     mask = 0
     for m in modules:
         mask |= 1 << m
@@ -439,9 +442,10 @@ def stage_eval(modules: Sequence[int], n_modules: int, cu_points, times, cu_tota
     return float(t.value), {m: int(q[m]) for m in modules if q[m] > 0}
 
 
-def planner_solve(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None, flags: int = EARLY_PRUNE | CACHE):
+def planner_solve(n_modules: int, edges, cu_points, times, cu_total: int, bw=None, e=None, flags: int = EARLY_PRUNE | CACHE,
+                  form: int = 0):
     """Alg. 1: (stages in execution order as lists of modules, {module: CUs}, iteration time, stats)."""
-    p, keep = _planner_problem(n_modules, edges, cu_points, times, cu_total, bw, e)
+    p, keep = _planner_problem(n_modules, edges, cu_points, times, cu_total, bw, e, form)
     so, qo = (C.c_int32 * n_modules)(), (C.c_int32 * n_modules)()
     ns, t, st = C.c_int32(), C.c_double(), _PlannerStats()
     check(lib().mosaic_planner_solve(C.byref(p), flags, so, qo, C.byref(ns), C.byref(t), C.byref(st)))

@@ -56,6 +56,7 @@ struct Problem {
   std::vector<int> cus;                 // [np]
   std::vector<double> t, bw;            // [n*np]
   bool rect;
+  int form;
   double e[3];
   std::vector<std::pair<int, int>> edges;
 };
@@ -105,9 +106,19 @@ struct StageSolver {
     if (k == mods.size()) {
       double b[kMaxModules];
       for (size_t i = 0; i < mods.size(); ++i) b[i] = P.bw[(size_t)mods[i] * P.np + lv[i]];
-      const double d = mods.size() >= 2 ? delta_of(P.e, (int)mods.size(), b) : 0.0;
       double t = -kInf;
-      for (size_t i = 0; i < mods.size(); ++i) t = std::max(t, T(mods[i], lv[i]) + d);
+      if (P.form == MOSAIC_DELAY_ABSOLUTE) {
+        const double d = delta_of(P.e, (int)mods.size(), b);
+        for (size_t i = 0; i < mods.size(); ++i) t = std::max(t, T(mods[i], lv[i]) + d);
+      } else {
+        // the expression over the other modules of the stage, charged as a fraction of own time
+        double peers[kMaxModules];
+        for (size_t i = 0; i < mods.size(); ++i) {
+          int k = 0;
+          for (size_t j = 0; j < mods.size(); ++j) if (j != i) peers[k++] = b[j];
+          t = std::max(t, T(mods[i], lv[i]) * (1.0 + delta_of(P.e, k, peers)));
+        }
+      }
       if (t < best->t) {
         best->t = t;
         for (size_t i = 0; i < mods.size(); ++i) best->level[mods[i]] = lv[i];
@@ -267,9 +278,10 @@ mosaic_status load_problem(const mosaic_planner_problem* pp, Problem* P) {
   if (pp->n_modules < 1 || pp->n_modules > kMaxModules) MOSAIC_FAIL(MOSAIC_EINVAL, "planner handles 1..%d modules, got %d", kMaxModules, pp->n_modules);
   if (pp->n_points < 1 || pp->n_points > kMaxPoints) MOSAIC_FAIL(MOSAIC_EINVAL, "planner handles 1..%d quota levels, got %d", kMaxPoints, pp->n_points);
   if (pp->cu_total < 1) MOSAIC_FAIL(MOSAIC_EQUOTA, "cu_total %d", pp->cu_total);
+  if (pp->delay_form != MOSAIC_DELAY_ABSOLUTE && pp->delay_form != MOSAIC_DELAY_PEER_RELATIVE) MOSAIC_FAIL(MOSAIC_EINVAL, "bad delay form %d", pp->delay_form);
   if (pp->n_edges < 0 || (pp->n_edges > 0 && !pp->edges)) MOSAIC_FAIL(MOSAIC_EINVAL, "bad edge list");
   if ((pp->bw == nullptr) != (pp->e == nullptr)) MOSAIC_FAIL(MOSAIC_EINVAL, "bandwidth table and coefficients are given together or not at all");
-  P->n = pp->n_modules; P->np = pp->n_points; P->total = pp->cu_total;
+  P->n = pp->n_modules; P->np = pp->n_points; P->total = pp->cu_total; P->form = pp->delay_form;
   P->cus.assign(pp->cu_points, pp->cu_points + pp->n_points);
   for (int c : P->cus) if (c < 1) MOSAIC_FAIL(MOSAIC_EQUOTA, "quota level %d", c);
   const size_t cells = (size_t)P->n * P->np;

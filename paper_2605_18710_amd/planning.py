@@ -74,10 +74,14 @@ class PlannedJob:
             out.append([min(1.0, w / (t * 1e-3) / peak) for t in row])
         return out
 
-    def fit_interference(self, grid, times, bw, probes: Sequence[Dict[int, int]], iters: int = 3):
+    def fit_interference(self, grid, times, bw, probes: Sequence[Dict[int, int]], iters: int = 3,
+                         form: int = mb.DELAY_ABSOLUTE):
         """probes: list of {module index: CUs on the grid} with two or more modules each.  Every
-        module of every probe gives one observation: delay = colocated time - time alone at
-        the same quota.  Returns the Eq. 8 fit, the additive-only fit and the observations."""
+        module of every probe gives one observation.  DELAY_ABSOLUTE (Eq. 7-8): the delay in ms
+        (colocated time - time alone at the same quota) against the utilisations of all modules
+        of the probe.  DELAY_PEER_RELATIVE: the delay as a fraction of the time alone, against
+        the utilisations of the other modules of the probe.  Returns the fit of Eq. 8's
+        expression, the additive-only fit and the observations."""
         groups, delays = [], []
         for pr in probes:
             members = sorted(pr)
@@ -87,15 +91,23 @@ class PlannedJob:
             r = self._probe_cache[key]
             bs = [bw[m][grid.index(pr[m])] for m in members]
             for k, m in enumerate(members):
-                groups.append(bs)
-                delays.append(r["module_ms"][k] - times[m][grid.index(pr[m])])
-        e3, r2_3 = mb.interference_fit(groups, delays, mb.COMPOSITE)
+                alone = times[m][grid.index(pr[m])]
+                if form == mb.DELAY_ABSOLUTE:
+                    groups.append(bs)
+                    delays.append(r["module_ms"][k] - alone)
+                else:
+                    groups.append(bs[:k] + bs[k + 1:])
+                    delays.append((r["module_ms"][k] - alone) / alone)
         e2, r2_2 = mb.interference_fit(groups, delays, mb.ADDITIVE)
+        try:
+            e3, r2_3 = mb.interference_fit(groups, delays, mb.COMPOSITE)
+        except mb.MosaicError:       # e.g. only pairs probed in peer form: sum and product coincide
+            e3, r2_3 = e2, r2_2
         return dict(e=e3, r2=r2_3, e_additive=e2, r2_additive=r2_2, n_obs=len(delays), groups=groups, delays=delays)
 
     # ---------------------------------------------------------------- plan and run
-    def solve(self, grid, times, bw=None, e=None, flags=mb.EARLY_PRUNE | mb.CACHE):
-        return mb.planner_solve(len(self.staged), self.edges, list(grid), times, self.cus, bw=bw, e=e, flags=flags)
+    def solve(self, grid, times, bw=None, e=None, flags=mb.EARLY_PRUNE | mb.CACHE, form=mb.DELAY_ABSOLUTE):
+        return mb.planner_solve(len(self.staged), self.edges, list(grid), times, self.cus, bw=bw, e=e, flags=flags, form=form)
 
     def run_plan(self, stages: Sequence[Sequence[int]], alloc: Dict[int, int], iters: int = 3) -> dict:
         """Executes the stages one after another (Eq. 1); each stage colocated under its quotas."""

@@ -55,7 +55,7 @@ def test_stage_eval_matches_checker(seed):
     pts = [32, 64, 96, 128, 160, 192, 224][: 4 + seed % 4]
     times, bw, _ = random_job(7000 + seed, n, pts)
     for members in ([0], list(range(n)), list(range(0, n, 2))):
-        for kw in ({}, dict(bw=bw, e=[0.05, 0.3, 0.8])):
+        for kw in ({}, dict(bw=bw, e=[0.05, 0.3, 0.8]), dict(bw=bw, e=[0.02, 0.9, 0.4], form=PL.PEER_RELATIVE)):
             t_ref, a_ref = PL.stage_eval(members, pts, times, 256, **kw)
             t, a = mb.stage_eval(members, n, pts, times, 256, **kw)
             assert t == t_ref and a == a_ref, (members, kw.keys())
@@ -71,7 +71,7 @@ def test_planner_matches_checker_with_and_without_pruning_and_caching(seed):
     n = 2 + seed % 6
     pts = [32, 64, 128, 192, 224]
     times, bw, edges = random_job(8000 + seed, n, pts)
-    for kw in ({}, dict(bw=bw, e=[0.05, 0.3, 0.8])):
+    for kw in ({}, dict(bw=bw, e=[0.05, 0.3, 0.8]), dict(bw=bw, e=[0.02, 0.9, 0.4], form=PL.PEER_RELATIVE)):
         st_ref, al_ref, t_ref = PL.gahc(n, edges, pts, times, 256, **kw)
         results = []
         for flags in (0, mb.EARLY_PRUNE, mb.CACHE, mb.EARLY_PRUNE | mb.CACHE):

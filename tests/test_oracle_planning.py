@@ -101,6 +101,21 @@ def test_rectified_stage_time_adds_the_delay_to_shared_stages_only():
                                    for i in range(3) for j in range(3) if pts[i] + pts[j] <= 8), abs=1e-15)
 
 
+def test_peer_relative_delay_written_out():
+    # two modules at fixed levels: module 0 is slowed by module 1's utilisation and vice versa
+    times = [[10.0], [4.0]]
+    bw = [[0.5], [0.2]]
+    e = [0.1, 2.0, 0.0]
+    t = PL.stage_time([0, 0], [0, 1], times, bw, e, PL.PEER_RELATIVE)
+    assert t == pytest.approx(max(10.0 * (1 + 0.1 + 2.0 * 0.2), 4.0 * (1 + 0.1 + 2.0 * 0.5)), abs=1e-14)
+    # three modules: module 2's peers are 0 and 1 (sum 0.7, product 0.1)
+    times3, bw3 = [[1.0], [1.0], [5.0]], [[0.5], [0.2], [0.9]]
+    t3 = PL.stage_time([0, 0, 0], [0, 1, 2], times3, bw3, [0.0, 1.0, 10.0], PL.PEER_RELATIVE)
+    assert t3 == pytest.approx(5.0 * (1 + 0.7 + 10.0 * 0.1), abs=1e-14)
+    # alone: no delay in either form
+    assert PL.stage_time([0], [2], times3, bw3, [9.0, 9.0, 9.0], PL.PEER_RELATIVE) == 5.0
+
+
 # ------------------------------------------------------------------------ Alg. 1
 def set_partitions(items):
     if not items:
