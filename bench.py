@@ -115,6 +115,24 @@ def bandwidth_kernels(mb, T, h, f, reps):
     return {k: round(v, 1) for k, v in res.items()}
 
 
+def attention_kernels(mb, B, N, H, d, causal, reps):
+    """Flash-style attention forward and backward at the decoder's shape; TFLOP/s with model
+    FLOPs (4*B*N^2*h forward, halved under the causal mask; backward = 2x forward)."""
+    import torch
+    bf = torch.bfloat16
+    q = mb.device_cu_count()
+    h = H * d
+    qkv = torch.randn(B * N, 3 * h, device="cuda", dtype=bf)
+    O = torch.empty(B * N, h, device="cuda", dtype=bf); dO = torch.randn(B * N, h, device="cuda", dtype=bf)
+    lse = torch.empty(B * H * N, device="cuda", dtype=torch.float32); delta = torch.empty_like(lse)
+    dqkv = torch.empty_like(qkv)
+    tf = time_kernel(lambda: mb.op_attention_fwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse), reps)
+    tb = time_kernel(lambda: mb.op_attention_bwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta), reps)
+    fl = 4.0 * B * N * N * h * (0.5 if causal else 1.0)
+    return dict(shape=dict(B=B, N=N, H=H, d=d, causal=causal), fwd_ms=round(tf, 4), bwd_ms=round(tb, 4),
+                fwd_tflops=round(fl / tf / 1e9, 1), bwd_tflops=round(2.0 * fl / tb / 1e9, 1))
+
+
 def stream_pool_latency(mb, cus, repeats=30):
     """Analogue of the paper's stream-pool experiment (Sec. 5.3.1): latency of creating and
     destroying a quota'd stream on demand, for quotas 0.1 .. 0.9 of the device, against
@@ -183,6 +201,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="index into the workload list (1 = CLIP-B / small-LM scale)")
     ap.add_argument("--roofline-only", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-pool-bench", action="store_true",
                     help="skip the create/destroy microbenchmark of masked streams (the profiler's queue interception does not survive it)")
@@ -204,6 +223,9 @@ def main():
     Tl, hl, fl = llm["batch"] * llm["seq"], llm["hidden"], llm["mlp"]
     cus = mb.device_cu_count()
 
+    if args.attention_only:
+        print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20)))
+        return
     gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=20)
     if args.roofline_only:
         # a plain device copy of known size, so that HBM byte counters of the same run can
@@ -217,6 +239,7 @@ def main():
                           "tflops": {k: gflops / v / 1e9 for k, v in gms.items()}}))
         return
     bw = bandwidth_kernels(mb, Tl, hl, fl, reps=20)
+    attn = attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20)
     pool = None if args.no_pool_bench else stream_pool_latency(mb, cus)
 
     stage = StagedStage(args.config)
@@ -312,6 +335,7 @@ def main():
                      "avg_ms": {k: round(v, 4) for k, v in gms.items()},
                      "all_forms_tflops": {k: round(gflops / v / 1e9, 2) for k, v in gms.items()},
                      "hbm_kernels_gbs": bw, "hbm_peak_gbs": PEAK_HBM_GBS},
+        "attention": attn,
         "stream_pool": pool,
         "paper_context": "paper reports up to 1.31x per-iteration speedup on 32x H100-80GB (other hardware, other metric)",
     }

@@ -89,7 +89,11 @@ def test_linear_without_bias_and_residual_and_empty(mb):
 ATTN_SHAPES = [("f32", 2, 16, 4, 32, 0), ("f32", 2, 128, 4, 32, 1), ("f32", 1, 37, 2, 24, 1),
                ("bf16", 2, 196, 3, 64, 0), ("bf16", 1, 300, 2, 128, 1), ("bf16", 2, 1, 2, 64, 1),
                ("bf16", 1, 1024, 2, 128, 1), ("bf16", 2, 577, 2, 64, 0), ("bf16", 1, 129, 1, 64, 1),
-               ("bf16", 1, 200, 2, 32, 1)]
+               ("bf16", 1, 200, 2, 32, 1),
+               # many heads over few workgroups: several rounds of the head-by-head work order,
+               # mirrored on odd rounds (3 tiles per head), and a head count that is not a
+               # multiple of the XCD count
+               ("bf16", 2, 384, 19, 64, 1), ("bf16", 3, 100, 20, 64, 0)]
 
 
 @pytest.mark.parametrize("dtype,B,N,H,d,causal", ATTN_SHAPES)
