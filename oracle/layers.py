@@ -27,8 +27,9 @@ Readings where the sources are silent (all recorded in the design notes as well)
   * layer variants (not named by the workloads; offered as options): the tanh form of GELU
     (act "gelu_tanh"); rotary position embedding on q and k (cfg "rope" = base, 0 = off) in
     the original interleaved-pair form: pair i of a head, at position n of its sample, is
-    rotated by the angle n * base^(-2i/d); AdamW with decoupled weight decay and bias
-    correction.
+    rotated by the angle n * base^(-2i/d); grouped-query attention (cfg "kv_heads" < heads:
+    query head t attends to key/value head t // (heads/kv_heads), w_qkv is
+    [h, (heads + 2 kv_heads) d]); AdamW with decoupled weight decay and bias correction.
 
 Pins (tests/test_oracle_*.py): brute-force triple-loop matmul, naive per-row softmax
 attention in python loops, closed-form invariants, math.erf scalar reference, central
@@ -168,47 +169,64 @@ def attention_head_bwd(q, k, v, P, do):
     return dq, dk, dv
 
 
-def attention_fwd(qkv, B, N, H, causal):
-    """qkv [B*N, 3h] with row = [q | k | v], head t owns columns t*d:(t+1)*d of each."""
-    h = qkv.shape[1] // 3
-    d = h // H
-    o = np.zeros((B * N, h), dtype=qkv.dtype)
+def _split_heads(qkv, H, Hkv):
+    """Column ranges of packed rows [q (H heads) | k (Hkv heads) | v (Hkv heads)]."""
+    d = qkv.shape[1] // (H + 2 * Hkv)
+    return d, H * d, (H + Hkv) * d
+
+
+def attention_fwd(qkv, B, N, H, causal, Hkv=None):
+    """qkv [B*N, (H + 2*Hkv)*d] with row = [q | k | v]; query head t owns columns t*d:(t+1)*d
+    of q and attends to key/value head t // (H/Hkv) (grouped-query attention; Hkv = H is
+    ordinary multi-head attention)."""
+    Hkv = H if Hkv is None else Hkv
+    d, ko, vo = _split_heads(qkv, H, Hkv)
+    G = H // Hkv
+    o = np.zeros((B * N, H * d), dtype=qkv.dtype)
     for b in range(B):
         rows = slice(b * N, (b + 1) * N)
         for t in range(H):
-            c = slice(t * d, (t + 1) * d)
-            q, k, v = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
-            o[rows, c], _ = attention_head_fwd(q, k, v, causal)
+            u = t // G
+            q = qkv[rows, t * d:(t + 1) * d]
+            k = qkv[rows, ko + u * d:ko + (u + 1) * d]
+            v = qkv[rows, vo + u * d:vo + (u + 1) * d]
+            o[rows, t * d:(t + 1) * d], _ = attention_head_fwd(q, k, v, causal)
     return o
 
 
-def attention_bwd(qkv, do, B, N, H, causal):
-    h = qkv.shape[1] // 3
-    d = h // H
+def attention_bwd(qkv, do, B, N, H, causal, Hkv=None):
+    """Gradient of packed q|k|v; a key/value head collects the gradients of every query head
+    of its group."""
+    Hkv = H if Hkv is None else Hkv
+    d, ko, vo = _split_heads(qkv, H, Hkv)
+    G = H // Hkv
     dqkv = np.zeros_like(qkv)
     for b in range(B):
         rows = slice(b * N, (b + 1) * N)
         for t in range(H):
-            c = slice(t * d, (t + 1) * d)
-            q, k, v = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
+            u = t // G
+            q = qkv[rows, t * d:(t + 1) * d]
+            k = qkv[rows, ko + u * d:ko + (u + 1) * d]
+            v = qkv[rows, vo + u * d:vo + (u + 1) * d]
             _, P = attention_head_fwd(q, k, v, causal)
-            dq, dk, dv = attention_head_bwd(q, k, v, P, do[rows, c])
+            dq, dk, dv = attention_head_bwd(q, k, v, P, do[rows, t * d:(t + 1) * d])
             dqkv[rows, t * d:(t + 1) * d] = dq
-            dqkv[rows, h + t * d:h + (t + 1) * d] = dk
-            dqkv[rows, 2 * h + t * d:2 * h + (t + 1) * d] = dv
+            dqkv[rows, ko + u * d:ko + (u + 1) * d] += dk
+            dqkv[rows, vo + u * d:vo + (u + 1) * d] += dv
     return dqkv
 
 
-def attention_lse(qkv, B, N, H, causal):
+def attention_lse(qkv, B, N, H, causal, Hkv=None):
     """Row log-sum-exp of the scaled, masked scores: [B, H, N]."""
-    h = qkv.shape[1] // 3
-    d = h // H
+    Hkv = H if Hkv is None else Hkv
+    d, ko, vo = _split_heads(qkv, H, Hkv)
+    G = H // Hkv
     out = np.zeros((B, H, N), dtype=qkv.dtype)
     for b in range(B):
         rows = slice(b * N, (b + 1) * N)
         for t in range(H):
-            c = slice(t * d, (t + 1) * d)
-            S = (qkv[rows, 0:h][:, c] @ qkv[rows, h:2 * h][:, c].T) / np.sqrt(float(d))
+            u = t // G
+            S = (qkv[rows, t * d:(t + 1) * d] @ qkv[rows, ko + u * d:ko + (u + 1) * d].T) / np.sqrt(float(d))
             if causal:
                 S = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], -np.inf, S)
             m = S.max(axis=-1)
@@ -219,24 +237,23 @@ def attention_lse(qkv, B, N, H, causal):
 # ------------------------------------------------------------- rotary position embedding
 
 
-def rope_rotate(qkv, B, N, H, base, sign=1.0):
-    """Rotates the q and k parts of packed [B*N, 3h] rows; v is left alone.  Pair
+def rope_rotate(qkv, B, N, H, base, sign=1.0, Hkv=None):
+    """Rotates the q and k parts of packed [B*N, (H + 2*Hkv)*d] rows; v is left alone.  Pair
     (x[2i], x[2i+1]) of every head, in the row at position n of its sample, turns by the
     angle sign * n * base^(-2i/d).  sign = -1 is the transposed rotation, i.e. the map that
     takes gradients with respect to rotated q, k back to the unrotated ones."""
-    h = qkv.shape[1] // 3
-    d = h // H
+    Hkv = H if Hkv is None else Hkv
+    d = qkv.shape[1] // (H + 2 * Hkv)
     out = qkv.copy()
     n = np.arange(B * N) % N
     i = np.arange(d // 2)
     ang = sign * n[:, None].astype(np.float64) * (float(base) ** (-2.0 * i / d))[None, :]
     c, s_ = np.cos(ang).astype(qkv.dtype), np.sin(ang).astype(qkv.dtype)
-    for part in (0, 1):                       # q, k
-        for t in range(H):
-            c0 = part * h + t * d
-            xe, xo = qkv[:, c0:c0 + d:2], qkv[:, c0 + 1:c0 + d:2]
-            out[:, c0:c0 + d:2] = xe * c - xo * s_
-            out[:, c0 + 1:c0 + d:2] = xe * s_ + xo * c
+    for t in range(H + Hkv):                  # the q heads, then the k heads
+        c0 = t * d
+        xe, xo = qkv[:, c0:c0 + d:2], qkv[:, c0 + 1:c0 + d:2]
+        out[:, c0:c0 + d:2] = xe * c - xo * s_
+        out[:, c0 + 1:c0 + d:2] = xe * s_ + xo * c
     return out
 
 
@@ -280,9 +297,10 @@ def layer_fwd(x, p, cfg):
     else:
         u1 = rmsnorm_fwd(x, p["rms1_g"], eps)
     qkv = linear_fwd(u1, p["w_qkv"], p.get("b_qkv"))
+    Hkv = cfg.get("kv_heads") or H
     if cfg.get("rope"):
-        qkv = rope_rotate(qkv, B, N, H, cfg["rope"])       # saved and attended in rotated form
-    o = attention_fwd(qkv, B, N, H, cfg["causal"])
+        qkv = rope_rotate(qkv, B, N, H, cfg["rope"], 1.0, Hkv)       # saved and attended in rotated form
+    o = attention_fwd(qkv, B, N, H, cfg["causal"], Hkv)
     x1 = x + linear_fwd(o, p["w_o"], p.get("b_o"))
     if cfg["norm"] == "layernorm":
         u2 = layernorm_fwd(x1, p["ln2_g"], p["ln2_b"], eps)
@@ -328,9 +346,10 @@ def layer_bwd(dy, p, s, cfg):
     do, g["w_o"], dbo = linear_bwd(s["o"], p["w_o"], dx1, bias)
     if bias:
         g["b_o"] = dbo
-    dqkv = attention_bwd(s["qkv"], do, B, N, H, cfg["causal"])
+    Hkv = cfg.get("kv_heads") or H
+    dqkv = attention_bwd(s["qkv"], do, B, N, H, cfg["causal"], Hkv)
     if cfg.get("rope"):
-        dqkv = rope_rotate(dqkv, B, N, H, cfg["rope"], -1.0)
+        dqkv = rope_rotate(dqkv, B, N, H, cfg["rope"], -1.0, Hkv)
     du1, g["w_qkv"], dbqkv = linear_bwd(s["u1"], p["w_qkv"], dqkv, bias)
     if bias:
         g["b_qkv"] = dbqkv

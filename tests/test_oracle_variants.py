@@ -102,6 +102,49 @@ def test_encoder_layer_with_tanh_gelu_by_finite_differences():
         assert (loss(pp) - loss(pm)) / 2e-5 == pytest.approx(float((g[key] * D).sum()), rel=1e-6, abs=1e-9), key
 
 
+# ------------------------------------------------------------ grouped-query attention
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    # sharing a K/V head inside a group is the same as giving every query head its own copy;
+    # the shared head's gradient is the sum of the copies' gradients
+    B, N, H, Hkv, d = 2, 7, 6, 2, 4
+    G = H // Hkv
+    qkv = synth.normal(9200, (B * N, (H + 2 * Hkv) * d))
+    do = synth.normal(9201, (B * N, H * d))
+    q, k, v = qkv[:, :H * d], qkv[:, H * d:(H + Hkv) * d], qkv[:, (H + Hkv) * d:]
+    rep = lambda a: np.concatenate([a[:, (t // G) * d:(t // G + 1) * d] for t in range(H)], axis=1)
+    full = np.concatenate([q, rep(k), rep(v)], axis=1)
+    for causal in (0, 1):
+        assert np.allclose(O.attention_fwd(qkv, B, N, H, causal, Hkv), O.attention_fwd(full, B, N, H, causal), atol=1e-14)
+        assert np.allclose(O.attention_lse(qkv, B, N, H, causal, Hkv), O.attention_lse(full, B, N, H, causal), atol=1e-14)
+        g, gf = O.attention_bwd(qkv, do, B, N, H, causal, Hkv), O.attention_bwd(full, do, B, N, H, causal)
+        assert np.allclose(g[:, :H * d], gf[:, :H * d], atol=1e-14)
+        for part, off_f in ((0, H * d), (1, 2 * H * d)):
+            for u in range(Hkv):
+                want = sum(gf[:, off_f + t * d:off_f + (t + 1) * d] for t in range(u * G, (u + 1) * G))
+                c0 = (H + part * Hkv + u) * d
+                assert np.allclose(g[:, c0:c0 + d], want, atol=1e-13)
+
+
+def test_decoder_layer_with_gqa_and_rope_by_finite_differences():
+    cfg = dict(small_cfg("decoder", h=16, H=4), kv_heads=2, rope=100.0)
+    h, d = 16, 4
+    p = {k: v * (10.0 if v.ndim == 2 else 1.0) for k, v in layer_params(cfg, 9220).items()}
+    p["w_qkv"] = p["w_qkv"][:, :(4 + 2 * 2) * d].copy()
+    x = synth.normal(9221, (cfg["batch"] * cfg["seq"], h))
+    R = synth.normal(9222, x.shape)
+    y, s = O.layer_fwd(x, p, cfg)
+    dx, g = O.layer_bwd(R, p, s, cfg)
+    assert g["w_qkv"].shape == p["w_qkv"].shape
+    loss = lambda pp, xx=x: float((O.layer_fwd(xx, pp, cfg)[0] * R).sum())
+    for key in ("w_qkv", "w_o", "rms1_g"):
+        D = synth.normal(9230 + len(key), p[key].shape)
+        pp, pm = dict(p), dict(p)
+        pp[key] = p[key] + 1e-5 * D; pm[key] = p[key] - 1e-5 * D
+        assert (loss(pp) - loss(pm)) / 2e-5 == pytest.approx(float((g[key] * D).sum()), rel=1e-6, abs=1e-9), key
+    D = synth.normal(9240, x.shape)
+    assert (loss(p, x + 1e-5 * D) - loss(p, x - 1e-5 * D)) / 2e-5 == pytest.approx(float((dx * D).sum()), rel=1e-6, abs=1e-9)
+
+
 # --------------------------------------------------------------------------- AdamW
 def test_adamw_first_step_closed_form():
     # zero moments, step 1: mhat = g, vhat = g^2, so p' = p - lr (g/(|g|+eps) + wd p)
