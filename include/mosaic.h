@@ -125,6 +125,10 @@ typedef struct {
   float   rope_base;   /* ENCODER / DECODER: > 0 turns on rotary position embedding of q and k
                           (pair (2i, 2i+1) of a head at position n turns by n * rope_base^(-2i/d));
                           0 = none, as in the workloads */
+  int32_t kv_heads;    /* ENCODER / DECODER: key/value heads of grouped-query attention; must divide
+                          heads; query head t attends to key/value head t / (heads/kv_heads); the
+                          QKV weight is [hidden, (heads + 2*kv_heads) * d].  0 = heads (multi-head
+                          attention, as in the workloads) */
 } mosaic_module_desc;
 
 typedef struct mosaic_module mosaic_module;
@@ -332,6 +336,18 @@ mosaic_status mosaic_op_attention_bwd(void* stream, int32_t quota, int32_t dtype
                                       int32_t causal, const void* qkv, const void* O,
                                       const float* lse, const void* dO, void* dqkv,
                                       float* delta);
+
+/* Grouped-query attention: qkv [B*N, (H + 2*Hkv)*d], row = [q (H heads) | k (Hkv heads) | v (Hkv
+ * heads)], Hkv divides H, query head t attends to key/value head t / (H/Hkv); dqkv has the
+ * same layout and a key/value head's gradient sums over its group in a fixed order. */
+mosaic_status mosaic_op_attention_gqa_fwd(void* stream, int32_t quota, int32_t dtype,
+                                          int32_t B, int32_t N, int32_t H, int32_t Hkv, int32_t d,
+                                          int32_t causal, const void* qkv, void* O, float* lse);
+mosaic_status mosaic_op_attention_gqa_bwd(void* stream, int32_t quota, int32_t dtype,
+                                          int32_t B, int32_t N, int32_t H, int32_t Hkv, int32_t d,
+                                          int32_t causal, const void* qkv, const void* O,
+                                          const float* lse, const void* dO, void* dqkv,
+                                          float* delta);
 
 /* y = norm(x) * gamma (+ beta).  norm = MOSAIC_LAYERNORM | MOSAIC_RMSNORM.
  * stats [T,2] f32 receives (mean, rstd) (mean = 0 for RMSNorm). */

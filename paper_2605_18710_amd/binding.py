@@ -46,7 +46,7 @@ class ModuleDesc(C.Structure):
                 ("eps", C.c_float),
                 ("in_dim", C.c_int32), ("out_dim", C.c_int32),
                 ("vocab", C.c_int32), ("n_img", C.c_int32), ("patch", C.c_int32),
-                ("rope_base", C.c_float)]
+                ("rope_base", C.c_float), ("kv_heads", C.c_int32)]
 
 
 class Stage(C.Structure):
@@ -113,6 +113,8 @@ SIGNATURES = {
     "mosaic_op_linear_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64]),
     "mosaic_op_attention_fwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "mosaic_op_attention_bwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mosaic_op_attention_gqa_fwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "mosaic_op_attention_gqa_bwd": (_i32, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_norm_fwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _f32, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_norm_bwd_scratch_bytes": (_sz, [_i64]),
     "mosaic_op_norm_bwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -247,6 +249,7 @@ def make_desc(cfg: dict, dtype: str) -> ModuleDesc:
     d.act = _ACT[cfg.get("act", "gelu")]
     d.eps = float(cfg.get("eps", 0.0))
     d.rope_base = float(cfg.get("rope", 0.0) or 0.0)
+    d.kv_heads = int(cfg.get("kv_heads", 0) or 0)
     return d
 
 
@@ -478,6 +481,15 @@ def op_attention_fwd(stream, quota, dtype, B, N, H, d, causal, qkv, O, lse):
 def op_attention_bwd(stream, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta):
     check(lib().mosaic_op_attention_bwd(stream, quota, _dt(dtype), B, N, H, d, causal, _ptr(qkv), _ptr(O), _ptr(lse),
                                         _ptr(dO), _ptr(dqkv), _ptr(delta)))
+
+
+def op_attention_gqa_fwd(stream, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse):
+    check(lib().mosaic_op_attention_gqa_fwd(stream, quota, _dt(dtype), B, N, H, Hkv, d, causal, _ptr(qkv), _ptr(O), _ptr(lse)))
+
+
+def op_attention_gqa_bwd(stream, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse, dO, dqkv, delta):
+    check(lib().mosaic_op_attention_gqa_bwd(stream, quota, _dt(dtype), B, N, H, Hkv, d, causal, _ptr(qkv), _ptr(O), _ptr(lse),
+                                            _ptr(dO), _ptr(dqkv), _ptr(delta)))
 
 
 def op_norm_fwd(stream, quota, dtype, norm, T, h, eps, x, gamma, beta, y, stats):

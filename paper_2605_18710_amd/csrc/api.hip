@@ -2,46 +2,47 @@
 // kernels and the plain FMA ones.
 #include "kernels.h"
 
-mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
                                           int causal, const void* qkv, void* O, float* lse);
-mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
                                           int causal, const void* qkv, const void* O, const float* lse,
                                           const void* dO, void* dqkv, float* delta);
 
 mosaic_status launch_attention_delta(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
                                      const void* O, const void* dO, float* delta);
 bool attention_mfma_supported(int dtype, int d);
-mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
                                         const void* qkv, void* O, float* lse);
-mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
                                         const void* qkv, const float* lse, const void* dO, void* dqkv,
                                         const float* delta);
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-static mosaic_status check_attn(int B, int N, int H, int d) {
+static mosaic_status check_attn(int B, int N, int H, int Hkv, int d) {
   if (B <= 0 || N <= 0 || H <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "attention sizes must be positive");
+  if (Hkv <= 0 || H % Hkv) MOSAIC_FAIL(MOSAIC_EINVAL, "key/value heads (%d) must divide the query heads (%d)", Hkv, H);
   if (d > 128) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "head size %d > 128", d);
   return MOSAIC_OK;
 }
 
-mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d, int causal,
                                    const void* qkv, void* O, float* lse) {
-  MOSAIC_TRY(check_attn(B, N, H, d));
+  MOSAIC_TRY(check_attn(B, N, H, Hkv, d));
   if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(O))
-    return launch_attention_fwd_mfma(s, quota, B, N, H, d, causal, qkv, O, lse);
-  return launch_attention_fwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse);
+    return launch_attention_fwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, O, lse);
+  return launch_attention_fwd_simple(s, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse);
 }
 
-mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d, int causal,
                                    const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
                                    float* delta) {
-  MOSAIC_TRY(check_attn(B, N, H, d));
+  MOSAIC_TRY(check_attn(B, N, H, Hkv, d));
   if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(dO) && aligned16(dqkv)) {
     MOSAIC_TRY(launch_attention_delta(s, quota, dtype, B, N, H, d, O, dO, delta));
-    return launch_attention_bwd_mfma(s, quota, B, N, H, d, causal, qkv, lse, dO, dqkv, delta);
+    return launch_attention_bwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, lse, dO, dqkv, delta);
   }
-  return launch_attention_bwd_simple(s, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta);
+  return launch_attention_bwd_simple(s, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse, dO, dqkv, delta);
 }
 
 static mosaic_status check_common(int32_t quota, int32_t dtype) {
@@ -96,7 +97,7 @@ mosaic_status mosaic_op_attention_fwd(void* stream, int32_t quota, int32_t dtype
                                       int32_t d, int32_t causal, const void* qkv, void* O, float* lse) {
   MOSAIC_TRY(check_common(quota, dtype));
   NONNULL(qkv); NONNULL(O); NONNULL(lse);
-  return launch_attention_fwd((hipStream_t)stream, quota, dtype, B, N, H, d, causal, qkv, O, lse);
+  return launch_attention_fwd((hipStream_t)stream, quota, dtype, B, N, H, H, d, causal, qkv, O, lse);
 }
 
 mosaic_status mosaic_op_attention_bwd(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H,
@@ -104,7 +105,22 @@ mosaic_status mosaic_op_attention_bwd(void* stream, int32_t quota, int32_t dtype
                                       const void* dO, void* dqkv, float* delta) {
   MOSAIC_TRY(check_common(quota, dtype));
   NONNULL(qkv); NONNULL(O); NONNULL(lse); NONNULL(dO); NONNULL(dqkv); NONNULL(delta);
-  return launch_attention_bwd((hipStream_t)stream, quota, dtype, B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta);
+  return launch_attention_bwd((hipStream_t)stream, quota, dtype, B, N, H, H, d, causal, qkv, O, lse, dO, dqkv, delta);
+}
+
+mosaic_status mosaic_op_attention_gqa_fwd(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H,
+                                          int32_t Hkv, int32_t d, int32_t causal, const void* qkv, void* O, float* lse) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(qkv); NONNULL(O); NONNULL(lse);
+  return launch_attention_fwd((hipStream_t)stream, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse);
+}
+
+mosaic_status mosaic_op_attention_gqa_bwd(void* stream, int32_t quota, int32_t dtype, int32_t B, int32_t N, int32_t H,
+                                          int32_t Hkv, int32_t d, int32_t causal, const void* qkv, const void* O,
+                                          const float* lse, const void* dO, void* dqkv, float* delta) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(qkv); NONNULL(O); NONNULL(lse); NONNULL(dO); NONNULL(dqkv); NONNULL(delta);
+  return launch_attention_bwd((hipStream_t)stream, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse, dO, dqkv, delta);
 }
 
 mosaic_status mosaic_op_norm_fwd(void* stream, int32_t quota, int32_t dtype, int32_t norm, int64_t T, int64_t h,
@@ -177,7 +193,7 @@ mosaic_status mosaic_op_rope(void* stream, int32_t quota, int32_t dtype, int32_t
                              int32_t direction, void* qkv, const void* table) {
   MOSAIC_TRY(check_common(quota, dtype));
   NONNULL(qkv); NONNULL(table);
-  return launch_rope((hipStream_t)stream, quota, dtype, B, N, H, d, direction, qkv, table);
+  return launch_rope((hipStream_t)stream, quota, dtype, B, N, H, H, d, direction, qkv, table);
 }
 
 mosaic_status mosaic_op_adamw(void* stream, int32_t quota, int32_t dtype, int64_t n, void* params, const void* grads,

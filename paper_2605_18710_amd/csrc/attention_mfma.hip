@@ -84,10 +84,10 @@ struct LdsTile {
   }
   // rows row0 .. row0+RS-1 of the matrix described by `desc` (row stride rs_bytes) -> LDS
   // byte address dst; rows beyond the descriptor's range arrive as zeros.
-  __device__ __forceinline__ void issue(i32x4 desc, unsigned rs_bytes, int row0, unsigned dst) const {
+  __device__ __forceinline__ void issue(i32x4 desc, unsigned rs_bytes, int row0, unsigned dst, unsigned col_bytes = 0u) const {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const unsigned off = (unsigned)(row0 + rrow[j]) * rs_bytes + (unsigned)rcol[j] * 2u;
+      const unsigned off = (unsigned)(row0 + rrow[j]) * rs_bytes + (unsigned)rcol[j] * 2u + col_bytes;
       // m0 = LDS address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Assembly, so that
       // the compiler's wait-count pass does not put a vmcnt(0) in front of every LDS read;
       // completion is waited for by hand before the barrier that publishes the tile.
@@ -175,7 +175,7 @@ __device__ __forceinline__ bool attn_item(int round, int heads, int tiles, int* 
 // --------------------------------------------------------------------------- forward
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
-                                                     float* __restrict__ lse, int B, int N, int H, int causal,
+                                                     float* __restrict__ lse, int B, int N, int H, int Hkv, int causal,
                                                      float scale_log2, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
@@ -188,14 +188,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
   ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
-  const int h = H * D;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   for (int round = 0;; ++round) {
     int head_, qt;
     if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
     const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
-    const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
+    const bf16* rowb = qkv + (int64_t)b * N * rs;
+    const bf16* base = rowb + hd * D;
+    const int kvh = hd / GQ;
     bf16x8 qf[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
     float m = -INFINITY, lsum = 0.f;
     const int kv_end = causal ? min(N, q0 + QT) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
-    const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
+    const i32x4 dk_ = slice_desc(rowb + ko + kvh * D, N, rs, D), dv_ = slice_desc(rowb + vo + kvh * D, N, rs, D);
     const unsigned rsb = (unsigned)(rs * 2);
     auto request = [&](int tile) {         // tiles past the last one point outside the slice
       const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
-                                                        bf16* __restrict__ dqkv, int B, int N, int H, int causal,
+                                                        bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
                                                         float scale, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
@@ -362,15 +365,18 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
   ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
-  const int h = H * D;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   const float scale_log2 = scale * kLog2e;
   for (int round = 0;; ++round) {
     int head_, qt;
     if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
     const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
-    const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
+    const bf16* rowb = qkv + (int64_t)b * N * rs;
+    const bf16* base = rowb + hd * D;
+    const int kvh = hd / GQ;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
     bf16x8 qf[NS], dof[NS];
 #pragma unroll
@@ -391,7 +397,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
       for (int e = 0; e < 16; ++e) dq[c][e] = 0.f;
     const int kv_end = causal ? min(N, q0 + QT) : N;
     const int ntiles = (kv_end + RS - 1) / RS;
-    const i32x4 dk_ = slice_desc(base + h, N, rs, D), dv_ = slice_desc(base + 2 * h, N, rs, D);
+    const i32x4 dk_ = slice_desc(rowb + ko + kvh * D, N, rs, D), dv_ = slice_desc(rowb + vo + kvh * D, N, rs, D);
     const unsigned rsb = (unsigned)(rs * 2);
     auto request = [&](int tile) {
       const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
@@ -462,7 +468,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16* __restrict__ dqkv, int B, int N, int H, int causal,
+                                                         bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
                                                          float scale, int ktiles) {
   constexpr int RS = 32, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
@@ -480,22 +486,25 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   ld.init();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
-  const int h = H * D;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   const float scale_log2 = scale * kLog2e;
   for (int round = 0;; ++round) {
     int head_, kt_i;
-    if (!attn_item(round, B * H, ktiles, &head_, &kt_i)) break;
-    const int hd = head_ % H, b = head_ / H;
+    if (!attn_item(round, B * Hkv, ktiles, &head_, &kt_i)) break;
+    const int kvh = head_ % Hkv, b = head_ / Hkv;
+    const int hd0 = kvh * GQ;                    // first query head of the group
     const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
-    const bf16* base = qkv + (int64_t)b * N * rs + hd * D;
-    const bf16* dob = dO + (int64_t)b * N * h + hd * D;
-    const float* lse_b = lse + ((int64_t)b * H + hd) * N;
-    const float* del_b = delta + ((int64_t)b * H + hd) * N;
+    const bf16* rowb = qkv + (int64_t)b * N * rs;
+    const bf16* base = rowb + hd0 * D;           // q columns of the group's heads are adjacent
+    const bf16* dob = dO + (int64_t)b * N * h + hd0 * D;
+    const float* lse_b = lse + ((int64_t)b * H + hd0) * N;
+    const float* del_b = delta + ((int64_t)b * H + hd0) * N;
     bf16x8 kf[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      if (j < N) kf[s] = *reinterpret_cast<const bf16x8*>(base + h + (int64_t)j * rs + 16 * s + 8 * hb);
+      if (j < N) kf[s] = *reinterpret_cast<const bf16x8*>(rowb + ko + kvh * D + (int64_t)j * rs + 16 * s + 8 * hb);
       else { for (int e = 0; e < 8; ++e) kf[s][e] = (bf16)0.f; }
     }
     f32x16 dk[NC], dv[NC];
@@ -504,36 +513,42 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
 #pragma unroll
       for (int e = 0; e < 16; ++e) { dk[c][e] = 0.f; dv[c][e] = 0.f; }
     const int q_begin = causal ? (k0 / RS) * RS : 0;
-    const int ntiles = (N - q_begin + RS - 1) / RS;
+    const int ntq = (N - q_begin + RS - 1) / RS;       // query tiles of one head
+    const int ntiles = ntq * GQ;                         // streamed for every query head of the group in turn
     // per-row statistics of streamed tile `tile` (lse, delta) take the same road as the tiles:
     // one 4-byte request per lane straight into the tile's stage slot.  Every wave issues
     // them (same values, same place) so that all waves count the same number of requests.
     auto desc_f32 = [&](const float* p) {
       i32x4 d;
       d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
-      d.z = N * 4; d.w = 0x00020000;
+      d.z = GQ * N * 4; d.w = 0x00020000;
       return d;
     };
     const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
     auto stage_stats = [&](int tile) {
-      const unsigned off = (lane < RS && tile < ntiles) ? (unsigned)(q_begin + tile * RS + lane) * 4u : 0xFFFFFFF0u;
+      const int g = tile / ntq, tq = tile - g * ntq;
+      const unsigned off = (lane < RS && tile < ntiles && q_begin + tq * RS + lane < N)
+                               ? (unsigned)(g * N + q_begin + tq * RS + lane) * 4u : 0xFFFFFFF0u;
       const unsigned dst = lds0 + (unsigned)(NST * STAGE + LV::BYTES + (tile % NST) * 2 * 64 * 4);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
     };
-    const i32x4 dq_ = slice_desc(base, N, rs, D), do_ = slice_desc(dob, N, h, D);
+    // one descriptor spans the group's GQ adjacent heads; the head is a column offset
+    const i32x4 dq_ = slice_desc(base, N, rs, GQ * D), do_ = slice_desc(dob, N, h, GQ * D);
     const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
     auto request = [&](int tile) {
       const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
-      const int row0 = tile < ntiles ? q_begin + tile * RS : N;
-      ld.issue(dq_, rsb, row0, nb);
-      ld.issue(do_, hsb, row0, nb + L::BYTES);
+      const int g = tile / ntq, tq = tile - g * ntq;
+      const int row0 = tile < ntiles ? q_begin + tq * RS : N;
+      const unsigned col = tile < ntiles ? (unsigned)(g * D * 2) : 0u;
+      ld.issue(dq_, rsb, row0, nb, col);
+      ld.issue(do_, hsb, row0, nb + L::BYTES, col);
     };
     __syncthreads();
     {
       LV ldv;            // built here so that its per-lane offsets do not live across the tile loop
       ldv.init();
-      ldv.issue(slice_desc(base + 2 * h, N, rs, D), rsb, k0, lds0 + NST * STAGE);
+      ldv.issue(slice_desc(rowb + vo + kvh * D, N, rs, D), rsb, k0, lds0 + NST * STAGE);
     }
 #pragma unroll
     for (int u = 0; u < PD; ++u) { request(u); stage_stats(u); }
@@ -547,7 +562,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       const float* sd = stat + (slot * 2 + 1) * 64;
       request(t + PD);
       stage_stats(t + PD);
-      const int ib = q_begin + t * RS;
+      const int ib = q_begin + (t % ntq) * RS;
       if (!(causal && ib + 31 < j0w) && j0w < N) {            // otherwise every (i, j) here is masked
         f32x16 sacc, pacc;
 #pragma unroll
@@ -587,7 +602,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       __syncthreads();
     }
     if (j < N) {
-      bf16* out = dqkv + ((int64_t)b * N + j) * rs + hd * D;
+      bf16* out = dqkv + ((int64_t)b * N + j) * rs + kvh * D;
 #pragma unroll
       for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -595,8 +610,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
           bf16x4 vk, vv;
 #pragma unroll
           for (int e = 0; e < 4; ++e) { vk[e] = (bf16)(dk[c][4 * g + e] * scale); vv[e] = (bf16)dv[c][4 * g + e]; }
-          *reinterpret_cast<bf16x4*>(out + h + 32 * c + 8 * g + 4 * hb) = vk;
-          *reinterpret_cast<bf16x4*>(out + 2 * h + 32 * c + 8 * g + 4 * hb) = vv;
+          *reinterpret_cast<bf16x4*>(out + ko + 32 * c + 8 * g + 4 * hb) = vk;
+          *reinterpret_cast<bf16x4*>(out + vo + 32 * c + 8 * g + 4 * hb) = vv;
         }
     }
   }
@@ -614,20 +629,20 @@ mosaic_status set_smem(K kern, size_t bytes) {
 // the loop is bound by the softmax arithmetic sharing the VALU port with MFMA issue, not by
 // load latency.  Only the 4-wave shape is instantiated.
 template <int D, int NW>
-mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, bf16* O, float* lse) {
+mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, bf16* O, float* lse) {
   const int qtiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * qtiles;
   const int grid = grid_for(quota, 8 / NW, items);
   constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
   static bool once = false;
   if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
-  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, causal, kLog2e / sqrtf((float)D), qtiles);
+  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
 
 template <int D, int NW>
-mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, const bf16* qkv, const float* lse,
+mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, const float* lse,
                     const bf16* dO, bf16* dqkv, const float* delta) {
   const int tiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * tiles;
@@ -638,14 +653,14 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
                             (size_t)Ring<NW>::NST * 2 * 64 * sizeof(float);
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D, NW>, smem)); once = true; }
-    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
+    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   {
     constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
-    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, causal, scale, tiles);
+    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
@@ -655,15 +670,15 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int causal, c
 
 bool attention_mfma_supported(int dtype, int d) { return dtype == MOSAIC_BF16 && (d == 64 || d == 128); }
 
-mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
                                         const void* qkv, void* O, float* lse) {
-  if (d == 64) return fwd_t<64, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
-  return fwd_t<128, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, (bf16*)O, lse);
+  if (d == 64) return fwd_t<64, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, (bf16*)O, lse);
+  return fwd_t<128, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, (bf16*)O, lse);
 }
 
-mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int d, int causal,
+mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
                                         const void* qkv, const float* lse, const void* dO, void* dqkv,
                                         const float* delta) {
-  if (d == 64) return bwd_t<64, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
-  return bwd_t<128, 4>(s, quota, B, N, H, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+  if (d == 64) return bwd_t<64, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+  return bwd_t<128, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
 }

@@ -38,21 +38,23 @@ __device__ __forceinline__ float group16_sum(float v) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_simple(const T* __restrict__ qkv, T* __restrict__ O,
-                                                       float* __restrict__ lse, int B, int N, int H, int d,
+                                                       float* __restrict__ lse, int B, int N, int H, int Hkv, int d,
                                                        int causal, float scale, int qtiles) {
   __shared__ float Qs[OWN * DMAX];
   __shared__ float Ks[STR * (DMAX + 1)];
   __shared__ float Vs[STR * (DMAX + 1)];
   __shared__ float Ss[OWN * STR];
-  const int h = H * d;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * d, ko = H * d, vo = (H + Hkv) * d, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * d;
   const int t = threadIdx.x;
   const int i = t >> 4, sub = t & 15;          // query row in tile, position in 16-lane group
   const int items = B * H * qtiles;
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
     const int qt = item % qtiles, hd = (item / qtiles) % H, b = item / (qtiles * H);
     const int q0 = qt * OWN;
-    const T* base = qkv + (int64_t)b * N * rs + hd * d;
+    const T* rowb = qkv + (int64_t)b * N * rs;
+    const T* base = rowb + hd * d;
     __syncthreads();
     load_rows(Qs, d, base, rs, q0, OWN, N, d);
     float o[DMAX / 16];
@@ -62,8 +64,8 @@ __global__ __launch_bounds__(256) void attn_fwd_simple(const T* __restrict__ qkv
     const int kv_end = causal ? min(N, q0 + OWN) : N;
     for (int k0 = 0; k0 < kv_end; k0 += STR) {
       __syncthreads();
-      load_rows(Ks, d + 1, base + h, rs, k0, STR, N, d);
-      load_rows(Vs, d + 1, base + 2 * h, rs, k0, STR, N, d);
+      load_rows(Ks, d + 1, rowb + ko + (hd / GQ) * d, rs, k0, STR, N, d);
+      load_rows(Vs, d + 1, rowb + vo + (hd / GQ) * d, rs, k0, STR, N, d);
       __syncthreads();
       float s[2];
 #pragma unroll
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ O
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_kv_simple(const T* __restrict__ qkv, const T* __restrict__ dO,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          T* __restrict__ dqkv, int B, int N, int H, int d, int causal,
+                                                          T* __restrict__ dqkv, int B, int N, int H, int Hkv, int d, int causal,
                                                           float scale, int ktiles) {
   __shared__ float Ks[OWN * DMAX];
   __shared__ float Vs[OWN * DMAX];
@@ -143,24 +145,29 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_simple(const T* __restrict__ 
   __shared__ float Ps[STR * OWN];
   __shared__ float dSs[STR * OWN];
   __shared__ float Ls[STR], Dl[STR];
-  const int h = H * d;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * d, ko = H * d, vo = (H + Hkv) * d, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * d;
   const int t = threadIdx.x;
-  const int items = B * H * ktiles;
+  const int items = B * Hkv * ktiles;
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
-    const int kt = item % ktiles, hd = (item / ktiles) % H, b = item / (ktiles * H);
+    const int kt = item % ktiles, kvh = (item / ktiles) % Hkv, b = item / (ktiles * Hkv);
     const int j0 = kt * OWN;
-    const T* base = qkv + (int64_t)b * N * rs + hd * d;
-    const T* dob = dO + (int64_t)b * N * h + hd * d;
+    const T* rowb = qkv + (int64_t)b * N * rs;
     __syncthreads();
-    load_rows(Ks, d, base + h, rs, j0, OWN, N, d);
-    load_rows(Vs, d, base + 2 * h, rs, j0, OWN, N, d);
+    load_rows(Ks, d, rowb + ko + kvh * d, rs, j0, OWN, N, d);
+    load_rows(Vs, d, rowb + vo + kvh * d, rs, j0, OWN, N, d);
     const int jo = t >> 4, sub = t & 15;       // accumulation mapping: key jo, columns sub+16*cc
     float dk[DMAX / 16], dv[DMAX / 16];
 #pragma unroll
     for (int c = 0; c < DMAX / 16; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
     const int q_begin = causal ? (j0 / STR) * STR : 0;
+    // every query head of the group in turn, query blocks ascending inside a head
+    for (int g = 0; g < GQ; ++g)
     for (int i0 = q_begin; i0 < N; i0 += STR) {
+      const int hd = kvh * GQ + g;
+      const T* base = rowb + hd * d;
+      const T* dob = dO + (int64_t)b * N * h + hd * d;
       __syncthreads();
       load_rows(Qs, d + 1, base, rs, i0, STR, N, d);
       load_rows(Ds, d + 1, dob, (int64_t)h, i0, STR, N, d);
@@ -202,11 +209,11 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_simple(const T* __restrict__ 
     }
     const int gj = j0 + jo;
     if (gj < N) {
-      T* out = dqkv + ((int64_t)b * N + gj) * rs + hd * d;
+      T* out = dqkv + ((int64_t)b * N + gj) * rs + kvh * d;
 #pragma unroll
       for (int cc = 0; cc < DMAX / 16; ++cc) {
         const int c = sub + 16 * cc;
-        if (c < d) { out[h + c] = from_f32<T>(dk[cc] * scale); out[2 * h + c] = from_f32<T>(dv[cc]); }
+        if (c < d) { out[ko + c] = from_f32<T>(dk[cc] * scale); out[vo + c] = from_f32<T>(dv[cc]); }
       }
     }
   }
@@ -216,22 +223,24 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_simple(const T* __restrict__ 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_q_simple(const T* __restrict__ qkv, const T* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         T* __restrict__ dqkv, int B, int N, int H, int d, int causal,
+                                                         T* __restrict__ dqkv, int B, int N, int H, int Hkv, int d, int causal,
                                                          float scale, int qtiles) {
   __shared__ float Qs[OWN * DMAX];
   __shared__ float Ds[OWN * DMAX];
   __shared__ float Ks[STR * (DMAX + 1)];
   __shared__ float Vs[STR * (DMAX + 1)];
   __shared__ float dSs[OWN * STR];
-  const int h = H * d;
-  const int64_t rs = 3 * (int64_t)h;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * d, ko = H * d, vo = (H + Hkv) * d, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * d;
   const int t = threadIdx.x;
   const int i = t >> 4, sub = t & 15;
   const int items = B * H * qtiles;
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
     const int qt = item % qtiles, hd = (item / qtiles) % H, b = item / (qtiles * H);
     const int q0 = qt * OWN;
-    const T* base = qkv + (int64_t)b * N * rs + hd * d;
+    const T* rowb = qkv + (int64_t)b * N * rs;
+    const T* base = rowb + hd * d;
     const T* dob = dO + (int64_t)b * N * h + hd * d;
     __syncthreads();
     load_rows(Qs, d, base, rs, q0, OWN, N, d);
@@ -245,8 +254,8 @@ __global__ __launch_bounds__(256) void attn_bwd_q_simple(const T* __restrict__ q
     const int kv_end = causal ? min(N, q0 + OWN) : N;
     for (int k0 = 0; k0 < kv_end; k0 += STR) {
       __syncthreads();
-      load_rows(Ks, d + 1, base + h, rs, k0, STR, N, d);
-      load_rows(Vs, d + 1, base + 2 * h, rs, k0, STR, N, d);
+      load_rows(Ks, d + 1, rowb + ko + (hd / GQ) * d, rs, k0, STR, N, d);
+      load_rows(Vs, d + 1, rowb + vo + (hd / GQ) * d, rs, k0, STR, N, d);
       __syncthreads();
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -285,7 +294,7 @@ __global__ __launch_bounds__(256) void attn_bwd_q_simple(const T* __restrict__ q
 
 }  // namespace
 
-mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
                                           int causal, const void* qkv, void* O, float* lse) {
   const int qtiles = (int)ceil_div(N, OWN);
   const int64_t items = (int64_t)B * H * qtiles;
@@ -293,9 +302,9 @@ mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, i
   const int grid = grid_for(quota, 2, items);
   const float scale = 1.0f / sqrtf((float)d);
   if (dtype == MOSAIC_BF16)
-    attn_fwd_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (bf16*)O, lse, B, N, H, d, causal, scale, qtiles);
+    attn_fwd_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (bf16*)O, lse, B, N, H, Hkv, d, causal, scale, qtiles);
   else
-    attn_fwd_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (float*)O, lse, B, N, H, d, causal, scale, qtiles);
+    attn_fwd_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (float*)O, lse, B, N, H, Hkv, d, causal, scale, qtiles);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
@@ -313,7 +322,7 @@ mosaic_status launch_attention_delta(hipStream_t s, int quota, int dtype, int B,
   return MOSAIC_OK;
 }
 
-mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
                                           int causal, const void* qkv, const void* O, const float* lse,
                                           const void* dO, void* dqkv, float* delta) {
   MOSAIC_TRY(launch_attention_delta(s, quota, dtype, B, N, H, d, O, dO, delta));
@@ -323,11 +332,11 @@ mosaic_status launch_attention_bwd_simple(hipStream_t s, int quota, int dtype, i
   const int grid = grid_for(quota, 1, items);
   const float scale = 1.0f / sqrtf((float)d);
   if (dtype == MOSAIC_BF16) {
-    attn_bwd_kv_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (const bf16*)dO, lse, delta, (bf16*)dqkv, B, N, H, d, causal, scale, tiles);
-    attn_bwd_q_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (const bf16*)dO, lse, delta, (bf16*)dqkv, B, N, H, d, causal, scale, tiles);
+    attn_bwd_kv_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (const bf16*)dO, lse, delta, (bf16*)dqkv, B, N, H, Hkv, d, causal, scale, tiles);
+    attn_bwd_q_simple<bf16><<<grid, 256, 0, s>>>((const bf16*)qkv, (const bf16*)dO, lse, delta, (bf16*)dqkv, B, N, H, Hkv, d, causal, scale, tiles);
   } else {
-    attn_bwd_kv_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (const float*)dO, lse, delta, (float*)dqkv, B, N, H, d, causal, scale, tiles);
-    attn_bwd_q_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (const float*)dO, lse, delta, (float*)dqkv, B, N, H, d, causal, scale, tiles);
+    attn_bwd_kv_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (const float*)dO, lse, delta, (float*)dqkv, B, N, H, Hkv, d, causal, scale, tiles);
+    attn_bwd_q_simple<float><<<grid, 256, 0, s>>>((const float*)qkv, (const float*)dO, lse, delta, (float*)dqkv, B, N, H, Hkv, d, causal, scale, tiles);
   }
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;

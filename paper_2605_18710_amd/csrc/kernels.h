@@ -19,9 +19,11 @@ mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b
 size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K);
 
 // ------------------------------------------------------------------------- attention
-mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H,
+// packed rows [q (H heads) | k (Hkv heads) | v (Hkv heads)]; Hkv divides H; query head t
+// attends to key/value head t / (H/Hkv)
+mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv,
                                    int d, int causal, const void* qkv, void* O, float* lse);
-mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H,
+mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv,
                                    int d, int causal, const void* qkv, const void* O,
                                    const float* lse, const void* dO, void* dqkv, float* delta);
 
@@ -48,8 +50,8 @@ mosaic_status launch_gelu_tanh_bwd(hipStream_t s, int quota, int dtype, int64_t 
 // (cos, sin) of n * base^(-2i/d) for n < N, i < d/2, as float2[N][d/2]
 size_t rope_table_bytes(int N, int d);
 mosaic_status launch_rope_table(hipStream_t s, int quota, int N, int d, float base, void* table);
-// rotates the q and k parts of packed [B*N, 3*H*d] rows in place; direction -1 turns back
-mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int H, int d,
+// rotates the q and k parts of packed [B*N, (H+2*Hkv)*d] rows in place; direction -1 turns back
+mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
                           int direction, void* qkv, const void* table);
 // p, m, v (and master, if not null) updated in place; m, v, master are fp32
 mosaic_status launch_adamw(hipStream_t s, int quota, int dtype, int64_t n, void* p, const void* g,

@@ -84,6 +84,8 @@ mosaic_status validate(const mosaic_module_desc& d) {
       if (d.hidden % vn || d.mlp % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "hidden and mlp must be multiples of %d", vn);
       if (d.norm != MOSAIC_LAYERNORM && d.norm != MOSAIC_RMSNORM) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm %d", d.norm);
       if (d.act != MOSAIC_GELU && d.act != MOSAIC_SWIGLU && d.act != MOSAIC_GELU_TANH) MOSAIC_FAIL(MOSAIC_EINVAL, "bad activation %d", d.act);
+      if (d.kv_heads < 0 || (d.kv_heads > 0 && d.heads % d.kv_heads)) MOSAIC_FAIL(MOSAIC_EINVAL, "kv_heads %d must divide heads %d", d.kv_heads, d.heads);
+      if (d.kv_heads > 0 && ((d.hidden / d.heads) * d.kv_heads) % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "key/value width must be a multiple of %d", vn);
       if (!(d.rope_base >= 0.f)) MOSAIC_FAIL(MOSAIC_EINVAL, "rope_base must be 0 (off) or positive");
       if (d.rope_base > 0.f && (d.hidden / d.heads) % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "rotary embedding needs a head size that is a multiple of %d", vn);
       if (!(d.eps > 0.f)) MOSAIC_FAIL(MOSAIC_EINVAL, "eps must be positive");
@@ -114,6 +116,13 @@ mosaic_status validate(const mosaic_module_desc& d) {
   return MOSAIC_OK;
 }
 
+// width of a packed [q | k | v] row: heads query heads, kv key and value heads each
+inline int64_t qkv_width(const mosaic_module_desc& d) {
+  const int kv = d.kv_heads > 0 ? d.kv_heads : d.heads;
+  return (int64_t)(d.heads + 2 * kv) * (d.hidden / d.heads);
+}
+inline int kv_heads_of(const mosaic_module_desc& d) { return d.kv_heads > 0 ? d.kv_heads : d.heads; }
+
 void build_layout(mosaic_module* m) {
   const mosaic_module_desc& d = m->d;
   const int64_t T = m->T, h = d.hidden, f = d.mlp;
@@ -121,14 +130,15 @@ void build_layout(mosaic_module* m) {
   size_t cur = 0;
   if (d.kind == MOSAIC_ENCODER || d.kind == MOSAIC_DECODER) {
     const bool ln = d.norm == MOSAIC_LAYERNORM, glu = d.act == MOSAIC_SWIGLU;
+    const int64_t qw = qkv_width(d);
     const char* nn = ln ? "ln" : "rms";
     for (int l = 0; l < d.layers; ++l) {
       const std::string p = "L" + std::to_string(l) + ".";
       LayerParams q;
       q.n1_g = add_tensor(m, p + nn + "1_g", 1, h);
       if (ln) q.n1_b = add_tensor(m, p + nn + "1_b", 1, h);
-      q.w_qkv = add_tensor(m, p + "w_qkv", h, 3 * h);
-      if (d.bias) q.b_qkv = add_tensor(m, p + "b_qkv", 1, 3 * h);
+      q.w_qkv = add_tensor(m, p + "w_qkv", h, qw);
+      if (d.bias) q.b_qkv = add_tensor(m, p + "b_qkv", 1, qw);
       q.w_o = add_tensor(m, p + "w_o", h, h);
       if (d.bias) q.b_o = add_tensor(m, p + "b_o", 1, h);
       q.n2_g = add_tensor(m, p + nn + "2_g", 1, h);
@@ -148,7 +158,7 @@ void build_layout(mosaic_module* m) {
       LayerSaved s;
       const int64_t zf = glu ? 2 * f : f;
       s.u1 = take(&cur, T * h * es);
-      s.qkv = take(&cur, T * 3 * h * es);
+      s.qkv = take(&cur, T * qw * es);
       s.o = take(&cur, T * h * es);
       s.lse = take(&cur, (size_t)d.batch * d.heads * d.seq * sizeof(float));
       s.st1 = take(&cur, T * 2 * sizeof(float));
@@ -166,14 +176,14 @@ void build_layout(mosaic_module* m) {
     m->s_dU = take(&cur, T * h * es);
     m->s_dX1 = take(&cur, T * h * es);
     m->s_dO = take(&cur, T * h * es);
-    m->s_dQKV = take(&cur, T * 3 * h * es);
+    m->s_dQKV = take(&cur, T * qw * es);
     m->s_delta = take(&cur, (size_t)d.batch * d.heads * d.seq * sizeof(float));
     m->s_g0 = take(&cur, T * h * es);
     m->s_g1 = take(&cur, T * h * es);
     m->s_norm = take(&cur, norm_bwd_scratch_bytes(h));
-    const int64_t widest = (3 * h > zf) ? 3 * h : zf;
+    const int64_t widest = (qw > zf) ? qw : zf;
     m->s_colsum = take(&cur, colsum_scratch_bytes(widest));
-    size_t sk = gemm_splitk_scratch_bytes(h, 3 * h, T);
+    size_t sk = gemm_splitk_scratch_bytes(h, qw, T);
     sk = std::max(sk, gemm_splitk_scratch_bytes(h, h, T));
     sk = std::max(sk, gemm_splitk_scratch_bytes(h, zf, T));
     sk = std::max(sk, gemm_splitk_scratch_bytes(f, h, T));
@@ -232,16 +242,17 @@ mosaic_status layers_forward(mosaic_module* m, hipStream_t s, int q, const void*
   const bool glu = d.act == MOSAIC_SWIGLU;
   const void* xin = x;
   const bool rope = d.rope_base > 0.f;
-  const int dh = (int)(h / d.heads);
+  const int dh = (int)(h / d.heads), kvh = kv_heads_of(d);
+  const int64_t qw = qkv_width(d);
   if (rope) MOSAIC_TRY(launch_rope_table(s, q, d.seq, dh, d.rope_base, W(m, m->s_rope)));
   for (int l = 0; l < d.layers; ++l) {
     const LayerParams& p = m->lp[l];
     const LayerSaved& sv = m->ls[l];
     void* yout = (l + 1 < d.layers) ? W(m, sv.y) : y;
     MOSAIC_TRY(launch_norm_fwd(s, q, dt, d.norm, T, h, d.eps, xin, P(m, p.n1_g), P(m, p.n1_b), W(m, sv.u1), (float*)W(m, sv.st1)));
-    MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, 3 * h, h, W(m, sv.u1), h, P(m, p.w_qkv), 3 * h, W(m, sv.qkv), 3 * h, P(m, p.b_qkv), nullptr));
-    if (rope) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, dh, +1, W(m, sv.qkv), W(m, m->s_rope)));   // saved rotated
-    MOSAIC_TRY(launch_attention_fwd(s, q, dt, d.batch, d.seq, d.heads, dh, d.causal, W(m, sv.qkv), W(m, sv.o), (float*)W(m, sv.lse)));
+    MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, qw, h, W(m, sv.u1), h, P(m, p.w_qkv), qw, W(m, sv.qkv), qw, P(m, p.b_qkv), nullptr));
+    if (rope) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, kvh, dh, +1, W(m, sv.qkv), W(m, m->s_rope)));   // saved rotated
+    MOSAIC_TRY(launch_attention_fwd(s, q, dt, d.batch, d.seq, d.heads, kvh, dh, d.causal, W(m, sv.qkv), W(m, sv.o), (float*)W(m, sv.lse)));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, h, W(m, sv.o), h, P(m, p.w_o), h, W(m, sv.x1), h, P(m, p.b_o), xin));
     MOSAIC_TRY(launch_norm_fwd(s, q, dt, d.norm, T, h, d.eps, W(m, sv.x1), P(m, p.n2_g), P(m, p.n2_b), W(m, sv.u2), (float*)W(m, sv.st2)));
     const int64_t zf = glu ? 2 * f : f;
@@ -261,6 +272,8 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
   const int dt = d.dtype;
   const bool glu = d.act == MOSAIC_SWIGLU;
   const int64_t zf = glu ? 2 * f : f;
+  const int kvh = kv_heads_of(d);
+  const int64_t qw = qkv_width(d);
   void* dA = W(m, m->s_dA); void* dZ = W(m, m->s_dZ); void* dU = W(m, m->s_dU);
   void* dX1 = W(m, m->s_dX1); void* dO = W(m, m->s_dO); void* dQKV = W(m, m->s_dQKV);
   void* nsc = W(m, m->s_norm); void* csc = W(m, m->s_colsum);
@@ -289,15 +302,15 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, h, T, W(m, sv.o), h, dX1, h, G(m, p.w_o), h, nullptr, nullptr, W(m, m->s_splitk)));
     if (p.b_o >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, dX1, G(m, p.b_o), csc));
     // attention
-    MOSAIC_TRY(launch_attention_bwd(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o),
+    MOSAIC_TRY(launch_attention_bwd(s, q, dt, d.batch, d.seq, d.heads, kvh, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o),
                                     (const float*)W(m, sv.lse), dO, dQKV, (float*)W(m, m->s_delta)));
     // gradients of the rotated q, k go back through the transposed rotation (the table of
     // the forward pass is still in the workspace)
-    if (d.rope_base > 0.f) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, (int)(h / d.heads), -1, dQKV, W(m, m->s_rope)));
+    if (d.rope_base > 0.f) MOSAIC_TRY(launch_rope(s, q, dt, d.batch, d.seq, d.heads, kvh, (int)(h / d.heads), -1, dQKV, W(m, m->s_rope)));
     // QKV projection
-    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, 3 * h, T, W(m, sv.u1), h, dQKV, 3 * h, G(m, p.w_qkv), 3 * h, nullptr, nullptr, W(m, m->s_splitk)));
-    if (p.b_qkv >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, 3 * h, dQKV, G(m, p.b_qkv), csc));
-    MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, 3 * h, dQKV, 3 * h, P(m, p.w_qkv), 3 * h, dU, h, nullptr, nullptr));
+    MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, qw, T, W(m, sv.u1), h, dQKV, qw, G(m, p.w_qkv), qw, nullptr, nullptr, W(m, m->s_splitk)));
+    if (p.b_qkv >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, qw, dQKV, G(m, p.b_qkv), csc));
+    MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, qw, dQKV, qw, P(m, p.w_qkv), qw, dU, h, nullptr, nullptr));
     // first norm
     MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, xin, P(m, p.n1_g), (const float*)W(m, sv.st1), dU, dX1, gout, G(m, p.n1_g), G(m, p.n1_b), nsc));
     gin = gout;

@@ -55,13 +55,14 @@ __global__ __launch_bounds__(kThreads) void rope_table_kernel(float2* __restrict
   }
 }
 
-// In place on the q and k parts of rows [q | k | v] of width 3h: pair (x[2i], x[2i+1]) of a
-// head turns by the tabulated angle of (row's position, i); sign = -1 turns back.
+// In place on the q and k parts (the first `rot` columns) of rows [q | k | v] of width `width`:
+// pair (x[2i], x[2i+1]) of a head turns by the tabulated angle of (row's position, i);
+// sign = -1 turns back.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void rope_kernel(T* __restrict__ qkv, const float2* __restrict__ table, int64_t rows,
-                                                        int N, int h, int d, float sign) {
+                                                        int N, int rot, int width, int d, float sign) {
   constexpr int VN = Vec16<T>::N;
-  const int vpr = 2 * h / VN;                       // vectors of the q|k part of a row
+  const int vpr = rot / VN;                         // vectors of the q|k part of a row
   const int64_t nvec = rows * vpr;
   const int half = d / 2;
   for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * kThreads) {
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void rope_kernel(T* __restrict__ qkv, con
     const int col = (int)(v - row * vpr) * VN;      // first column inside [q | k]
     const int n = (int)(row % N);
     const int i0 = (col % d) / 2;                   // first pair index inside the head (VN divides d)
-    T* p = qkv + row * 3 * (int64_t)h + col;
+    T* p = qkv + row * (int64_t)width + col;
     Vec16<T> x, o;
     x.load(p);
 #pragma unroll
@@ -148,18 +149,18 @@ mosaic_status launch_rope_table(hipStream_t s, int quota, int N, int d, float ba
   return MOSAIC_OK;
 }
 
-mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int H, int d, int direction,
+mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d, int direction,
                           void* qkv, const void* table) {
   const int vn = dtype == MOSAIC_BF16 ? 8 : 4;
-  if (B < 0 || N <= 0 || H <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad rotary sizes");
+  if (B < 0 || N <= 0 || H <= 0 || Hkv <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad rotary sizes");
   if (d % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "head size %d is not a multiple of %d", d, vn);
   if (direction != 1 && direction != -1) MOSAIC_FAIL(MOSAIC_EINVAL, "direction must be +1 or -1");
   const int64_t rows = (int64_t)B * N;
   if (rows == 0) return MOSAIC_OK;
-  const int h = H * d;
-  const int grid = grid_for(quota, 8, ceil_div(rows * (2 * h / vn), kThreads));
-  if (dtype == MOSAIC_BF16) rope_kernel<bf16><<<grid, kThreads, 0, s>>>((bf16*)qkv, (const float2*)table, rows, N, h, d, (float)direction);
-  else rope_kernel<float><<<grid, kThreads, 0, s>>>((float*)qkv, (const float2*)table, rows, N, h, d, (float)direction);
+  const int rot = (H + Hkv) * d, width = (H + 2 * Hkv) * d;
+  const int grid = grid_for(quota, 8, ceil_div(rows * (rot / vn), kThreads));
+  if (dtype == MOSAIC_BF16) rope_kernel<bf16><<<grid, kThreads, 0, s>>>((bf16*)qkv, (const float2*)table, rows, N, rot, width, d, (float)direction);
+  else rope_kernel<float><<<grid, kThreads, 0, s>>>((float*)qkv, (const float2*)table, rows, N, rot, width, d, (float)direction);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }

@@ -69,6 +69,35 @@ def test_rope_forward_and_transposed(mb, dtype, B, N, H, d):
     assert all(np.array_equal(a, b) for a, b in zip(outs[0], outs[1]))
 
 
+@pytest.mark.parametrize("dtype,B,N,H,Hkv,d,causal", [
+    ("f32", 2, 70, 4, 2, 32, 1), ("f32", 1, 37, 6, 1, 24, 0),
+    ("bf16", 2, 300, 8, 2, 128, 1), ("bf16", 2, 196, 6, 3, 64, 0), ("bf16", 1, 1024, 8, 1, 128, 1),
+    ("bf16", 3, 129, 20, 4, 64, 1)])
+def test_grouped_query_attention(mb, dtype, B, N, H, Hkv, d, causal):
+    w = (H + 2 * Hkv) * d
+    qkv = quantize(synth.normal(3600, (B * N, w)), dtype)
+    dO = quantize(synth.normal(3601, (B * N, H * d)), dtype)
+    ref_o = O.attention_fwd(qkv, B, N, H, causal, Hkv)
+    ref_lse = O.attention_lse(qkv, B, N, H, causal, Hkv)
+    ref_d = O.attention_bwd(qkv, dO, B, N, H, causal, Hkv)
+    qkv_, dO_ = to_dev(qkv, dtype), to_dev(dO, dtype)
+    outs = []
+    for q in (256, 64, 24):
+        Oo = torch.empty_like(dO_); lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        dqkv = torch.full_like(qkv_, float("nan")); delta = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        mb.op_attention_gqa_fwd(None, q, dtype, B, N, H, Hkv, d, causal, qkv_, Oo, lse)
+        mb.op_attention_gqa_bwd(None, q, dtype, B, N, H, Hkv, d, causal, qkv_, Oo, lse, dO_, dqkv, delta)
+        torch.cuda.synchronize()
+        outs.append([bits(Oo), bits(lse), bits(dqkv)])
+    assert rel_l2(from_dev(Oo), ref_o) <= tol(dtype)
+    assert rel_l2(from_dev(lse), ref_lse) <= (1e-5 if dtype == "f32" else 1e-2)
+    got = from_dev(dqkv)
+    for lo, hi in ((0, H * d), (H * d, (H + Hkv) * d), ((H + Hkv) * d, w)):      # dq, dk, dv
+        assert rel_l2(got[:, lo:hi], ref_d[:, lo:hi]) <= tol(dtype), (lo, hi)
+    for o in outs[1:]:
+        assert all(np.array_equal(a, b) for a, b in zip(o, outs[0]))
+
+
 def dec(B, N, h, H, f, L, **kw):
     return dict(dict(kind="decoder", batch=B, seq=N, hidden=h, heads=H, mlp=f, layers=L,
                      norm="rmsnorm", act="swiglu", causal=1, bias=0, eps=1e-5), **kw)
@@ -84,16 +113,24 @@ def enc(B, N, h, H, f, L, **kw):
     ("bf16", dec(2, 160, 512, 4, 768, 2, rope=10000.0)),
     ("bf16", enc(2, 196, 256, 4, 1024, 2, act="gelu_tanh")),
     ("f32", enc(2, 16, 128, 4, 512, 1, act="gelu_tanh", rope=500.0)),
+    ("f32", dec(2, 64, 128, 4, 384, 1, kv_heads=2)),
+    ("bf16", dec(2, 160, 512, 8, 768, 2, kv_heads=2, rope=10000.0)),
 ])
 def test_stack_with_variants_matches_oracle_and_is_quota_invariant(mb, dtype, cfg):
     T, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
-    layers = quantize_tree([layer_params(cfg, 5000 + 100 * l) for l in range(cfg["layers"])], dtype)
+    layers = [layer_params(cfg, 5000 + 100 * l) for l in range(cfg["layers"])]
+    if cfg.get("kv_heads"):
+        qw = (cfg["heads"] + 2 * cfg["kv_heads"]) * (h // cfg["heads"])
+        for p in layers:
+            p["w_qkv"] = p["w_qkv"][:, :qw].copy()
+    layers = quantize_tree(layers, dtype)
     x = quantize(synth.normal(5050, (T, h)), dtype)
     target = quantize(synth.normal(5051, (T, h)), dtype)
     y_ref, saved = O.stack_fwd(x, layers, cfg)
     dx_ref, g_ref = O.stack_bwd(O.mse_bwd(y_ref, target), layers, saved, cfg)
-    plain = dict(cfg, rope=0.0, act=("gelu" if cfg["act"] == "gelu_tanh" else cfg["act"]))
-    assert rel_l2(O.stack_fwd(x, layers, plain)[0], y_ref) > 1e-6         # the variant changes the result
+    if not cfg.get("kv_heads"):
+        plain = dict(cfg, rope=0.0, act=("gelu" if cfg["act"] == "gelu_tanh" else cfg["act"]))
+        assert rel_l2(O.stack_fwd(x, layers, plain)[0], y_ref) > 1e-6         # the variant changes the result
     m = mb.Module(cfg, dtype)
     load_layer_params(m, layers)
     x_, t_ = to_dev(x, dtype), to_dev(target, dtype)
