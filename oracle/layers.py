@@ -29,7 +29,10 @@ Readings where the sources are silent (all recorded in the design notes as well)
     the original interleaved-pair form: pair i of a head, at position n of its sample, is
     rotated by the angle n * base^(-2i/d); grouped-query attention (cfg "kv_heads" < heads:
     query head t attends to key/value head t // (heads/kv_heads), w_qkv is
-    [h, (heads + 2 kv_heads) d]); AdamW with decoupled weight decay and bias correction.
+    [h, (heads + 2 kv_heads) d]); AdamW with decoupled weight decay and bias correction;
+    a two-convolution audio stem in the style of speech encoders: Conv1d(k=3, stride 1,
+    pad 1) - GELU - Conv1d(k=3, stride 2, pad 1) - GELU - learned positions, frames-major
+    input [B, 2*seq, bins], weights stored [3*C_in, C_out] with row index tap*C_in + channel.
 
 Pins (tests/test_oracle_*.py): brute-force triple-loop matmul, naive per-row softmax
 attention in python loops, closed-form invariants, math.erf scalar reference, central
@@ -255,6 +258,61 @@ def rope_rotate(qkv, B, N, H, base, sign=1.0, Hkv=None):
         out[:, c0:c0 + d:2] = xe * c - xo * s_
         out[:, c0 + 1:c0 + d:2] = xe * s_ + xo * c
     return out
+
+
+# ------------------------------------------------------------- strided-convolution stem
+
+
+def conv1d_fwd(x, w, b, stride):
+    """x [B, L, C] frames-major, w [3*C, Co] (row = tap*C + channel), zero padding 1:
+    y[b, t, :] = b + sum_k x[b, t*stride - 1 + k, :] @ w[k], t < L_out = (L - 1)//stride + 1."""
+    B, L, C = x.shape
+    Lo = (L - 1) // stride + 1
+    y = np.zeros((B, Lo, w.shape[1]), dtype=x.dtype) + b
+    for k in range(3):
+        wk = w[k * C:(k + 1) * C]
+        for t in range(Lo):
+            s_ = t * stride - 1 + k
+            if 0 <= s_ < L:
+                y[:, t, :] += x[:, s_, :] @ wk
+    return y
+
+
+def conv1d_bwd(x, w, dy, stride):
+    """Gradients of conv1d_fwd: (dx, dw, db)."""
+    B, L, C = x.shape
+    Lo = dy.shape[1]
+    dx = np.zeros_like(x)
+    dw = np.zeros_like(w)
+    for k in range(3):
+        wk = w[k * C:(k + 1) * C]
+        for t in range(Lo):
+            s_ = t * stride - 1 + k
+            if 0 <= s_ < L:
+                dx[:, s_, :] += dy[:, t, :] @ wk.T
+                dw[k * C:(k + 1) * C] += x[:, s_, :].T @ dy[:, t, :]
+    return dx, dw, dy.sum(axis=(0, 1))
+
+
+def conv_stem_fwd(x, p):
+    """x [B, 2*N, bins] -> [B*N, h]: conv(stride 1) - GELU - conv(stride 2) - GELU + pos[N, h]."""
+    z1 = conv1d_fwd(x, p["w_c1"], p["b_c1"], 1)
+    a1 = gelu(z1)
+    z2 = conv1d_fwd(a1, p["w_c2"], p["b_c2"], 2)
+    y = gelu(z2) + p["pos"][None, :, :]
+    return y.reshape(-1, y.shape[-1]), dict(x=x, z1=z1, a1=a1, z2=z2)
+
+
+def conv_stem_bwd(dy, p, s):
+    g = {}
+    B, N, h = s["z2"].shape
+    dy = dy.reshape(B, N, h)
+    g["pos"] = dy.sum(axis=0)
+    dz2 = dy * gelu_grad(s["z2"])
+    da1, g["w_c2"], g["b_c2"] = conv1d_bwd(s["a1"], p["w_c2"], dz2, 2)
+    dz1 = da1 * gelu_grad(s["z1"])
+    dx, g["w_c1"], g["b_c1"] = conv1d_bwd(s["x"], p["w_c1"], dz1, 1)
+    return dx, g
 
 
 # -------------------------------------------------------------------------- optimizer

@@ -145,6 +145,53 @@ def test_decoder_layer_with_gqa_and_rope_by_finite_differences():
     assert (loss(p, x + 1e-5 * D) - loss(p, x - 1e-5 * D)) / 2e-5 == pytest.approx(float((dx * D).sum()), rel=1e-6, abs=1e-9)
 
 
+# ----------------------------------------------------------- strided-convolution stem
+@pytest.mark.parametrize("stride,L", [(1, 9), (2, 10), (2, 7)])
+def test_conv1d_matches_library_and_finite_differences(stride, L):
+    B, C, Co = 2, 3, 5
+    x = synth.normal(9300, (B, L, C)); w = synth.normal(9301, (3 * C, Co)); b = synth.normal(9302, (Co,))
+    y = O.conv1d_fwd(x, w, b, stride)
+    wt = torch.from_numpy(w.reshape(3, C, Co).transpose(2, 1, 0).copy())          # [Co, C, tap]
+    ref = torch.nn.functional.conv1d(torch.from_numpy(x.transpose(0, 2, 1).copy()), wt, torch.from_numpy(b), stride=stride, padding=1)
+    assert np.allclose(y, ref.numpy().transpose(0, 2, 1), atol=1e-13)
+    R = synth.normal(9303, y.shape)
+    dx, dw, db = O.conv1d_bwd(x, w, R, stride)
+    for arr, grad, seed in ((x, dx, 1), (w, dw, 2), (b, db, 3)):
+        D = synth.normal(9310 + seed, arr.shape)
+        f = lambda e: float((O.conv1d_fwd(x + e * D if arr is x else x, w + e * D if arr is w else w, b + e * D if arr is b else b, stride) * R).sum())
+        assert (f(1e-6) - f(-1e-6)) / 2e-6 == pytest.approx(float((grad * D).sum()), rel=1e-7, abs=1e-8)
+
+
+def test_conv1d_border_taps_written_out():
+    # one channel, identity-like taps: w = [1, 10, 100] picks x[t-1] + 10 x[t] + 100 x[t+1]
+    x = np.arange(1.0, 6.0).reshape(1, 5, 1)
+    w = np.array([[1.0], [10.0], [100.0]])
+    y1 = O.conv1d_fwd(x, w, np.zeros(1), 1)[0, :, 0]
+    assert np.array_equal(y1, [210.0, 321.0, 432.0, 543.0, 54.0])
+    y2 = O.conv1d_fwd(x, w, np.zeros(1), 2)[0, :, 0]
+    assert np.array_equal(y2, [210.0, 432.0, 54.0])                                  # frames 0, 2, 4
+
+
+def test_conv_stem_by_finite_differences():
+    B, N, C, h = 2, 5, 4, 6
+    p = dict(w_c1=synth.normal(9320, (3 * C, h), 0, 0.3), b_c1=synth.normal(9321, (h,), 0, 0.1),
+             w_c2=synth.normal(9322, (3 * h, h), 0, 0.3), b_c2=synth.normal(9323, (h,), 0, 0.1),
+             pos=synth.normal(9324, (N, h), 0, 0.1))
+    x = synth.normal(9325, (B, 2 * N, C))
+    y, s = O.conv_stem_fwd(x, p)
+    assert y.shape == (B * N, h)
+    R = synth.normal(9326, y.shape)
+    dx, g = O.conv_stem_bwd(R, p, s)
+    loss = lambda pp, xx=x: float((O.conv_stem_fwd(xx, pp)[0] * R).sum())
+    for key in p:
+        D = synth.normal(9330 + len(key), p[key].shape)
+        pp, pm = dict(p), dict(p)
+        pp[key] = p[key] + 1e-6 * D; pm[key] = p[key] - 1e-6 * D
+        assert (loss(pp) - loss(pm)) / 2e-6 == pytest.approx(float((g[key] * D).sum()), rel=1e-6, abs=1e-8), key
+    D = synth.normal(9340, x.shape)
+    assert (loss(p, x + 1e-6 * D) - loss(p, x - 1e-6 * D)) / 2e-6 == pytest.approx(float((dx * D).sum()), rel=1e-6, abs=1e-8)
+
+
 # --------------------------------------------------------------------------- AdamW
 def test_adamw_first_step_closed_form():
     # zero moments, step 1: mhat = g, vhat = g^2, so p' = p - lr (g/(|g|+eps) + wd p)
