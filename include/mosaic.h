@@ -47,7 +47,7 @@ enum {
 
 enum { MOSAIC_F32 = 0, MOSAIC_BF16 = 1 };
 enum { MOSAIC_ENCODER = 0, MOSAIC_DECODER = 1, MOSAIC_PROJECTOR = 2,
-       MOSAIC_PATCH_STEM = 3, MOSAIC_TEXT_STEM = 4 };
+       MOSAIC_PATCH_STEM = 3, MOSAIC_TEXT_STEM = 4, MOSAIC_CONV_STEM = 5 };
 enum { MOSAIC_NORM_NONE = 0, MOSAIC_LAYERNORM = 1, MOSAIC_RMSNORM = 2 };
 enum { MOSAIC_GELU = 0, MOSAIC_SWIGLU = 1,
        MOSAIC_GELU_TANH = 2 };  /* tanh form of GELU: a layer variant, not used by the workloads */
@@ -114,7 +114,11 @@ mosaic_status mosaic_probe_placement(const mosaic_stream* stream, int32_t n, int
  * + learned position table [seq,hidden]; in_dim = 3*patch*patch; for audio frames use
  * patch = 0 and x = [T,in_dim]), TEXT_STEM (rows [0,n_img) of each sample copied from
  * x = [batch*n_img, hidden], rows [n_img,seq) gathered from an embedding table
- * [vocab,hidden] by int32 ids bound with mosaic_module_bind_ids). */
+ * [vocab,hidden] by int32 ids bound with mosaic_module_bind_ids), CONV_STEM (a layer variant:
+ * the two-convolution audio stem of speech encoders; x = [batch, 2*seq, in_dim] frames-major ->
+ * Conv1d(in_dim->hidden, k=3, stride 1, pad 1), GELU, Conv1d(hidden->hidden, k=3, stride 2,
+ * pad 1), GELU, + learned position table [seq,hidden]; convolution weights are stored
+ * [3*C_in, C_out] with row index tap*C_in + channel). */
 typedef struct {
   int32_t kind, dtype;
   int32_t layers, hidden, heads, mlp, batch, seq;

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmosaic.so")
 
 OK, EINVAL, EQUOTA, ENOMEM, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-ENCODER, DECODER, PROJECTOR, PATCH_STEM, TEXT_STEM = 0, 1, 2, 3, 4
+ENCODER, DECODER, PROJECTOR, PATCH_STEM, TEXT_STEM, CONV_STEM = 0, 1, 2, 3, 4, 5
 NORM_NONE, LAYERNORM, RMSNORM = 0, 1, 2
 GELU, SWIGLU = 0, 1
 STRIPED, XCD_ALIGNED = 0, 1
@@ -25,7 +25,7 @@ COLOCATED, TIME_SLICED, CHAINED = 0, 1, 2
 MAX_STAGE_MODULES = 8
 
 _KIND = {"encoder": ENCODER, "decoder": DECODER, "projector": PROJECTOR,
-         "patch_stem": PATCH_STEM, "text_stem": TEXT_STEM}
+         "patch_stem": PATCH_STEM, "text_stem": TEXT_STEM, "conv_stem": CONV_STEM}
 _NORM = {"none": NORM_NONE, "layernorm": LAYERNORM, "rmsnorm": RMSNORM}
 GELU_TANH = 2
 _ACT = {"gelu": GELU, "swiglu": SWIGLU, "gelu_tanh": GELU_TANH}

@@ -57,6 +57,12 @@ mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int
 mosaic_status launch_adamw(hipStream_t s, int quota, int dtype, int64_t n, void* p, const void* g,
                            float* m, float* v, float* master, float lr, float beta1, float beta2,
                            float eps, float weight_decay, int64_t step);
+// k=3, pad=1 convolution over frames-major [B, L, C] as gather + GEMM: out [B*Lo, 3*C] with
+// column index tap*C + channel; col2im1d is the transposed gather (one owner per element)
+mosaic_status launch_im2col1d(hipStream_t s, int quota, int dtype, int64_t B, int L, int Lo, int C,
+                              int stride, const void* x, void* out);
+mosaic_status launch_col2im1d(hipStream_t s, int quota, int dtype, int64_t B, int L, int Lo, int C,
+                              int stride, const void* dP, void* dx);
 size_t mse_scratch_bytes();
 mosaic_status launch_mse(hipStream_t s, int quota, int dtype, int64_t n, const void* y,
                          const void* target, void* dy, float* loss, void* scratch);

@@ -44,6 +44,7 @@ struct mosaic_module {
   size_t s_dA, s_dZ, s_dU, s_dX1, s_dO, s_dQKV, s_delta, s_g0, s_g1, s_norm, s_colsum, s_mse, s_dyloss, s_splitk;
   size_t s_patches;
   size_t s_rope = 0;     // (cos, sin) table of the rotary embedding, when on
+  size_t c_p1 = 0, c_z1 = 0, c_a1 = 0, c_p2 = 0, c_z2 = 0, c_dz2 = 0, c_dp2 = 0, c_da1 = 0, c_dz1 = 0, c_dp1 = 0;   // conv stem
   // bound buffers
   char* params = nullptr;
   char* grads = nullptr;
@@ -105,6 +106,10 @@ mosaic_status validate(const mosaic_module_desc& d) {
       }
       break;
     }
+    case MOSAIC_CONV_STEM:
+      if (d.in_dim <= 0 || d.hidden <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "conv stem needs in_dim and hidden");
+      if (d.in_dim % vn || d.hidden % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "in_dim and hidden must be multiples of %d", vn);
+      break;
     case MOSAIC_TEXT_STEM:
       if (d.hidden <= 0 || d.vocab <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "text stem needs hidden and vocab");
       if (d.n_img < 0 || d.n_img > d.seq) MOSAIC_FAIL(MOSAIC_EINVAL, "n_img must lie in [0, seq]");
@@ -214,6 +219,27 @@ void build_layout(mosaic_module* m) {
     m->s_patches = take(&cur, T * d.in_dim * es);
     m->s_colsum = take(&cur, colsum_scratch_bytes(h));
     m->s_splitk = take(&cur, gemm_splitk_scratch_bytes(d.in_dim, h, T));
+  } else if (d.kind == MOSAIC_CONV_STEM) {
+    LayerParams q;
+    const int64_t C = d.in_dim, Tin = 2 * T;            // input frames = 2 * seq per sample
+    q.w_1 = add_tensor(m, "w_c1", 3 * C, h);
+    q.b_1 = add_tensor(m, "b_c1", 1, h);
+    q.w_2 = add_tensor(m, "w_c2", 3 * h, h);
+    q.b_2 = add_tensor(m, "b_c2", 1, h);
+    q.w_o = add_tensor(m, "pos", d.seq, h);
+    m->lp.push_back(q);
+    m->c_p1 = take(&cur, Tin * 3 * C * es);
+    m->c_z1 = take(&cur, Tin * h * es);
+    m->c_a1 = take(&cur, Tin * h * es);
+    m->c_p2 = take(&cur, T * 3 * h * es);
+    m->c_z2 = take(&cur, T * h * es);
+    m->c_dz2 = take(&cur, T * h * es);
+    m->c_dp2 = take(&cur, T * 3 * h * es);
+    m->c_da1 = take(&cur, Tin * h * es);
+    m->c_dz1 = take(&cur, Tin * h * es);
+    m->c_dp1 = take(&cur, Tin * 3 * C * es);
+    m->s_colsum = take(&cur, colsum_scratch_bytes(h));
+    m->s_splitk = take(&cur, std::max(gemm_splitk_scratch_bytes(3 * C, h, Tin), gemm_splitk_scratch_bytes(3 * h, h, T)));
   } else {  // TEXT_STEM
     LayerParams q;
     q.w_1 = add_tensor(m, "table", d.vocab, h);
@@ -373,6 +399,44 @@ mosaic_status patch_stem_backward(mosaic_module* m, hipStream_t s, int q, const 
   return MOSAIC_OK;
 }
 
+// conv stem: each convolution is a three-tap gather followed by a linear layer
+mosaic_status conv_stem_forward(mosaic_module* m, hipStream_t s, int q, const void* x, void* y) {
+  const mosaic_module_desc& d = m->d;
+  const LayerParams& p = m->lp[0];
+  const int dt = d.dtype, C = d.in_dim, h = d.hidden, Lo = d.seq, L = 2 * d.seq;
+  const int64_t T = m->T, Tin = 2 * T;
+  MOSAIC_TRY(launch_im2col1d(s, q, dt, d.batch, L, L, C, 1, x, W(m, m->c_p1)));
+  MOSAIC_TRY(launch_gemm(s, q, dt, true, false, Tin, h, 3 * C, W(m, m->c_p1), 3 * C, P(m, p.w_1), h, W(m, m->c_z1), h, P(m, p.b_1), nullptr));
+  MOSAIC_TRY(launch_gelu_fwd(s, q, dt, Tin * h, W(m, m->c_z1), W(m, m->c_a1)));
+  MOSAIC_TRY(launch_im2col1d(s, q, dt, d.batch, L, Lo, h, 2, W(m, m->c_a1), W(m, m->c_p2)));
+  MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, 3 * h, W(m, m->c_p2), 3 * h, P(m, p.w_2), h, W(m, m->c_z2), h, P(m, p.b_2), nullptr));
+  MOSAIC_TRY(launch_gelu_fwd(s, q, dt, T * h, W(m, m->c_z2), y));
+  MOSAIC_TRY(launch_add_pos(s, q, dt, d.batch, Lo, h, P(m, p.w_o), y));
+  return MOSAIC_OK;
+}
+
+mosaic_status conv_stem_backward(mosaic_module* m, hipStream_t s, int q, const void* dy, void* dx) {
+  const mosaic_module_desc& d = m->d;
+  const LayerParams& p = m->lp[0];
+  const int dt = d.dtype, C = d.in_dim, h = d.hidden, Lo = d.seq, L = 2 * d.seq;
+  const int64_t T = m->T, Tin = 2 * T;
+  void* csc = W(m, m->s_colsum); void* sk = W(m, m->s_splitk);
+  MOSAIC_TRY(launch_pos_grad(s, q, dt, d.batch, Lo, h, dy, G(m, p.w_o)));
+  MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * h, W(m, m->c_z2), dy, W(m, m->c_dz2)));
+  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, 3 * h, h, T, W(m, m->c_p2), 3 * h, W(m, m->c_dz2), h, G(m, p.w_2), h, nullptr, nullptr, sk));
+  MOSAIC_TRY(launch_colsum(s, q, dt, T, h, W(m, m->c_dz2), G(m, p.b_2), csc));
+  MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, 3 * h, h, W(m, m->c_dz2), h, P(m, p.w_2), h, W(m, m->c_dp2), 3 * h, nullptr, nullptr));
+  MOSAIC_TRY(launch_col2im1d(s, q, dt, d.batch, L, Lo, h, 2, W(m, m->c_dp2), W(m, m->c_da1)));
+  MOSAIC_TRY(launch_gelu_bwd(s, q, dt, Tin * h, W(m, m->c_z1), W(m, m->c_da1), W(m, m->c_dz1)));
+  MOSAIC_TRY(launch_gemm(s, q, dt, false, false, 3 * C, h, Tin, W(m, m->c_p1), 3 * C, W(m, m->c_dz1), h, G(m, p.w_1), h, nullptr, nullptr, sk));
+  MOSAIC_TRY(launch_colsum(s, q, dt, Tin, h, W(m, m->c_dz1), G(m, p.b_1), csc));
+  if (dx) {
+    MOSAIC_TRY(launch_gemm(s, q, dt, true, true, Tin, 3 * C, h, W(m, m->c_dz1), h, P(m, p.w_1), h, W(m, m->c_dp1), 3 * C, nullptr, nullptr));
+    MOSAIC_TRY(launch_col2im1d(s, q, dt, d.batch, L, L, C, 1, W(m, m->c_dp1), dx));
+  }
+  return MOSAIC_OK;
+}
+
 }  // namespace
 
 // ================================================================== C ABI: modules
@@ -408,6 +472,7 @@ size_t mosaic_module_input_elems(const mosaic_module* m) {
     case MOSAIC_PROJECTOR: return (size_t)m->T * d.in_dim;
     case MOSAIC_PATCH_STEM: return (size_t)m->T * d.in_dim;   // unfolding permutes, never drops, pixels
     case MOSAIC_TEXT_STEM: return (size_t)d.batch * d.n_img * d.hidden;
+    case MOSAIC_CONV_STEM: return (size_t)2 * m->T * d.in_dim;   // twice as many input frames as output tokens
     default: return (size_t)m->T * d.hidden;
   }
 }
@@ -472,6 +537,7 @@ mosaic_status mosaic_module_forward(mosaic_module* m, int32_t quota, const mosai
     case MOSAIC_DECODER: st = layers_forward(m, s, q, x, y); break;
     case MOSAIC_PROJECTOR: st = projector_forward(m, s, q, x, y); break;
     case MOSAIC_PATCH_STEM: st = patch_stem_forward(m, s, q, x, y); break;
+    case MOSAIC_CONV_STEM: st = conv_stem_forward(m, s, q, x, y); break;
     default:
       if (!m->ids) MOSAIC_FAIL(MOSAIC_EINVAL, "text stem has no token ids bound");
       st = launch_text_stem_fwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, x, m->ids, P(m, m->lp[0].w_1), y);
@@ -492,6 +558,7 @@ mosaic_status mosaic_module_backward(mosaic_module* m, int32_t quota, const mosa
     case MOSAIC_DECODER: return layers_backward(m, s, q, dy, dx);
     case MOSAIC_PROJECTOR: return projector_backward(m, s, q, dy, dx);
     case MOSAIC_PATCH_STEM: return patch_stem_backward(m, s, q, dy, dx);
+    case MOSAIC_CONV_STEM: return conv_stem_backward(m, s, q, dy, dx);
     default:
       return launch_text_stem_bwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, dy, m->ids, dx, G(m, m->lp[0].w_1));
   }

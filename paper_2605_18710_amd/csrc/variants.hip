@@ -113,7 +113,89 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(T* __restrict__ p, cons
   }
 }
 
+// Gathers the three taps of a k=3, pad=1 convolution over frames-major x [B, L, C]:
+// out[(b*Lo + t), k*C + c] = x[b, t*stride - 1 + k, c], zero outside [0, L).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void im2col1d_kernel(const T* __restrict__ x, T* __restrict__ out, int64_t B, int L,
+                                                            int Lo, int C, int stride) {
+  constexpr int VN = Vec16<T>::N;
+  const int cv = C / VN;
+  const int64_t nvec = B * Lo * 3 * cv;
+  for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * kThreads) {
+    const int c = (int)(v % cv) * VN;
+    const int k = (int)((v / cv) % 3);
+    const int64_t row = v / (3 * cv);
+    const int t = (int)(row % Lo);
+    const int64_t b = row / Lo;
+    const int src = t * stride - 1 + k;
+    Vec16<T> val;
+    if (src >= 0 && src < L) val.load(x + (b * L + src) * C + c);
+    else {
+#pragma unroll
+      for (int e = 0; e < VN; ++e) val.set(e, 0.f);
+    }
+    val.store(out + row * 3 * (int64_t)C + (int64_t)k * C + c);
+  }
+}
+
+// The transpose of the gather: dx[b, s, c] = sum over taps k (ascending) of
+// dP[(b*Lo + t), k*C + c] with t*stride - 1 + k == s; one owner per element, fixed order.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void col2im1d_kernel(const T* __restrict__ dP, T* __restrict__ dx, int64_t B, int L,
+                                                            int Lo, int C, int stride) {
+  constexpr int VN = Vec16<T>::N;
+  const int cv = C / VN;
+  const int64_t nvec = B * L * cv;
+  for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * kThreads) {
+    const int c = (int)(v % cv) * VN;
+    const int64_t fr = v / cv;
+    const int s_ = (int)(fr % L);
+    const int64_t b = fr / L;
+    float acc[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[e] = 0.f;
+    for (int k = 0; k < 3; ++k) {
+      const int num = s_ + 1 - k;
+      if (num < 0 || num % stride) continue;
+      const int t = num / stride;
+      if (t >= Lo) continue;
+      Vec16<T> val;
+      val.load(dP + (b * Lo + t) * 3 * (int64_t)C + (int64_t)k * C + c);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) acc[e] += val.get(e);
+    }
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) o.set(e, acc[e]);
+    o.store(dx + fr * C + c);
+  }
+}
+
 }  // namespace
+
+mosaic_status launch_im2col1d(hipStream_t s, int quota, int dtype, int64_t B, int L, int Lo, int C, int stride,
+                              const void* x, void* out) {
+  const int vn = dtype == MOSAIC_BF16 ? 8 : 4;
+  if (C % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "channel count %d is not a multiple of %d", C, vn);
+  if (B <= 0 || L <= 0 || Lo <= 0) return MOSAIC_OK;
+  const int grid = grid_for(quota, 8, ceil_div(B * Lo * 3 * (C / vn), kThreads));
+  if (dtype == MOSAIC_BF16) im2col1d_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)x, (bf16*)out, B, L, Lo, C, stride);
+  else im2col1d_kernel<float><<<grid, kThreads, 0, s>>>((const float*)x, (float*)out, B, L, Lo, C, stride);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_col2im1d(hipStream_t s, int quota, int dtype, int64_t B, int L, int Lo, int C, int stride,
+                              const void* dP, void* dx) {
+  const int vn = dtype == MOSAIC_BF16 ? 8 : 4;
+  if (C % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "channel count %d is not a multiple of %d", C, vn);
+  if (B <= 0 || L <= 0 || Lo <= 0) return MOSAIC_OK;
+  const int grid = grid_for(quota, 8, ceil_div(B * L * (C / vn), kThreads));
+  if (dtype == MOSAIC_BF16) col2im1d_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dP, (bf16*)dx, B, L, Lo, C, stride);
+  else col2im1d_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dP, (float*)dx, B, L, Lo, C, stride);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
 
 mosaic_status launch_gelu_tanh_fwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, void* a) {
   const int vn = dtype == MOSAIC_BF16 ? 8 : 4;

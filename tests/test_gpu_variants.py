@@ -155,6 +155,39 @@ def test_stack_with_variants_matches_oracle_and_is_quota_invariant(mb, dtype, cf
     m.destroy()
 
 
+@pytest.mark.parametrize("dtype,B,N,C,h", [("f32", 2, 10, 8, 32), ("bf16", 2, 150, 80, 256), ("bf16", 1, 333, 80, 128)])
+def test_conv_stem_matches_oracle_and_is_quota_invariant(mb, dtype, B, N, C, h):
+    p = dict(w_c1=synth.normal(3700, (3 * C, h), 0, 0.05), b_c1=synth.normal(3701, (h,), 0, 0.02),
+             w_c2=synth.normal(3702, (3 * h, h), 0, 0.05), b_c2=synth.normal(3703, (h,), 0, 0.02),
+             pos=synth.normal(3704, (N, h), 0, 0.02))
+    p = quantize_tree(p, dtype)
+    x = quantize(synth.normal(3705, (B, 2 * N, C)), dtype)
+    dy = quantize(synth.normal(3706, (B * N, h)), dtype)
+    y_ref, saved = O.conv_stem_fwd(x, p)
+    dx_ref, g_ref = O.conv_stem_bwd(dy, p, saved)
+    cfg = dict(kind="conv_stem", batch=B, seq=N, hidden=h, in_dim=C, layers=1)
+    m = mb.Module(cfg, dtype)
+    for k, v in p.items():
+        m.set_tensor(k, v)
+    x_, dy_ = to_dev(x.reshape(-1), dtype), to_dev(dy, dtype)
+    first = None
+    for q in (256, 40):
+        y = torch.empty_like(dy_); dx = torch.empty_like(x_)
+        m.grads.zero_()
+        m.step(q, None, x_, y, dy=dy_, dx=dx)
+        torch.cuda.synchronize()
+        snap = [bits(y), bits(dx), bits(m.grads)]
+        if first is None:
+            first = snap
+            assert rel_l2(from_dev(y), y_ref) <= tol(dtype)
+            assert rel_l2(from_dev(dx), dx_ref.reshape(-1)) <= tol(dtype)
+            for k in g_ref:
+                assert rel_l2(m.get_tensor(k, grads=True).reshape(g_ref[k].shape), g_ref[k]) <= tol(dtype), k
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(snap, first))
+    m.destroy()
+
+
 @pytest.mark.parametrize("dtype,n,master", [("f32", 4 * 1031, False), ("bf16", 8 * 4099, False), ("bf16", 8 * 4099, True)])
 def test_adamw_steps(mb, dtype, n, master):
     hp = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.05)
