@@ -96,18 +96,31 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(T* __restrict__ p, cons
     Vec16<T> pv, gv;
     pv.load(p + i * VN);
     gv.load(g + i * VN);
+    // fp32 state moves as 16-byte vectors as well (VN is 4 or 8: one or two float4 per array)
+    float mv[VN], vv[VN], ms[VN];
+#pragma unroll
+    for (int k = 0; k < VN; k += 4) {
+      *reinterpret_cast<float4*>(mv + k) = *reinterpret_cast<const float4*>(m + i * VN + k);
+      *reinterpret_cast<float4*>(vv + k) = *reinterpret_cast<const float4*>(v + i * VN + k);
+      if (master) *reinterpret_cast<float4*>(ms + k) = *reinterpret_cast<const float4*>(master + i * VN + k);
+    }
 #pragma unroll
     for (int k = 0; k < VN; ++k) {
-      const int64_t e = i * VN + k;
       const float gk = gv.get(k);
-      const float pk = master ? master[e] : pv.get(k);
-      const float mk = b1 * m[e] + (1.0f - b1) * gk;
-      const float vk = b2 * v[e] + (1.0f - b2) * gk * gk;
-      m[e] = mk; v[e] = vk;
+      const float pk = master ? ms[k] : pv.get(k);
+      const float mk = b1 * mv[k] + (1.0f - b1) * gk;
+      const float vk = b2 * vv[k] + (1.0f - b2) * gk * gk;
+      mv[k] = mk; vv[k] = vk;
       const float upd = (mk * inv_bc1) / (sqrtf(vk * inv_bc2) + eps) + wd * pk;
       const float np_ = pk - lr * upd;
-      if (master) master[e] = np_;
+      ms[k] = np_;
       pv.set(k, np_);
+    }
+#pragma unroll
+    for (int k = 0; k < VN; k += 4) {
+      *reinterpret_cast<float4*>(m + i * VN + k) = *reinterpret_cast<const float4*>(mv + k);
+      *reinterpret_cast<float4*>(v + i * VN + k) = *reinterpret_cast<const float4*>(vv + k);
+      if (master) *reinterpret_cast<float4*>(master + i * VN + k) = *reinterpret_cast<const float4*>(ms + k);
     }
     pv.store(p + i * VN);
   }
@@ -252,6 +265,7 @@ mosaic_status launch_adamw(hipStream_t s, int quota, int dtype, int64_t n, void*
   const int vn = dtype == MOSAIC_BF16 ? 8 : 4;
   if (n % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "element count %lld is not a multiple of %d", (long long)n, vn);
   if (step < 1) MOSAIC_FAIL(MOSAIC_EINVAL, "step counts from 1");
+  if (((uintptr_t)p | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v | (uintptr_t)master) & 15) MOSAIC_FAIL(MOSAIC_EINVAL, "AdamW buffers must be 16-byte aligned");
   if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f)) MOSAIC_FAIL(MOSAIC_EINVAL, "betas must lie in [0,1)");
   if (n == 0) return MOSAIC_OK;
   // bias corrections in double on the host: 1 - beta^t loses digits in float for small t
