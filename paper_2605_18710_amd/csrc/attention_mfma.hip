@@ -581,13 +581,22 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
             if ((gi >= N) || (j >= N) || (causal && j > gi)) sacc[r] = -INFINITY;
           }
         }
+        // registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}: their statistics
+        // are four consecutive floats, one 16-byte LDS read each
         float pv[16], ds[16];
+        const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
+        const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int il = acc_row(r, hb);
-          const float p = fast_exp2(fmaf(sacc[r], scale_log2, -sl[il] * kLog2e));
-          pv[r] = p;
-          ds[r] = p * (pacc[r] - sd[il]);
+        for (int g = 0; g < 4; ++g) {
+          const float4 l4 = sl4[2 * g], d4 = sd4[2 * g];
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            const float p = fast_exp2(fmaf(sacc[r], scale_log2, -lv[e] * kLog2e));
+            pv[r] = p;
+            ds[r] = p * (pacc[r] - dv4[e]);
+          }
         }
         const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
 #pragma unroll
