@@ -68,9 +68,11 @@ struct LdsTile {
     else return (((r >> 1) & 1) << 2) | (((r >> 3) & 1) << 1) | ((r >> 2) & 1);
   }
 
-  int rrow[NI], rcol[NI];   // row inside the tile and first column of this lane's chunk, per instruction
+  // per wave instruction: byte offset of this lane's 16-byte chunk inside a matrix whose
+  // rows are rs_bytes apart (row of the tile times the stride, plus the swizzled column)
+  unsigned loff[NI];
   int wave_base;
-  __device__ __forceinline__ void init() {
+  __device__ __forceinline__ void init(unsigned rs_bytes) {
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     wave_base = w * NI * 1024;
@@ -78,16 +80,17 @@ struct LdsTile {
     for (int j = 0; j < NI; ++j) {
       const int byte = 16 * lane;
       const int row = (w * NI + j) * RPI + byte / ROWB, pos = (byte % ROWB) >> 4;
-      rrow[j] = row;
-      rcol[j] = (pos ^ swz(row)) * 8;
+      loff[j] = (unsigned)row * rs_bytes + (unsigned)((pos ^ swz(row)) * 16);
     }
   }
-  // rows row0 .. row0+RS-1 of the matrix described by `desc` (row stride rs_bytes) -> LDS
-  // byte address dst; rows beyond the descriptor's range arrive as zeros.
-  __device__ __forceinline__ void issue(i32x4 desc, unsigned rs_bytes, int row0, unsigned dst, unsigned col_bytes = 0u) const {
+  // rows row0 .. row0+RS-1 of the matrix described by `desc` -> LDS byte address dst, where
+  // base = row0 * row stride + byte offset of the first column (uniform over the workgroup);
+  // rows beyond the descriptor's range arrive as zeros.  The whole offset travels in the
+  // vector operand: the scalar offset field of the instruction is not range-checked.
+  __device__ __forceinline__ void issue(i32x4 desc, unsigned base, unsigned dst) const {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const unsigned off = (unsigned)(row0 + rrow[j]) * rs_bytes + (unsigned)rcol[j] * 2u + col_bytes;
+      const unsigned off = loff[j] + base;
       // m0 = LDS address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Assembly, so that
       // the compiler's wait-count pass does not put a vmcnt(0) in front of every LDS read;
       // completion is waited for by hand before the barrier that publishes the tile.
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
   const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   L ld;
-  ld.init();
+  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
@@ -218,8 +221,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
     auto request = [&](int tile) {         // tiles past the last one point outside the slice
       const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
       const int row0 = tile < ntiles ? tile * RS : N;
-      ld.issue(dk_, rsb, row0, nb);
-      ld.issue(dv_, rsb, row0, nb + L::BYTES);
+      const unsigned at = (unsigned)row0 * rsb;
+      ld.issue(dk_, at, nb);
+      ld.issue(dv_, at, nb + L::BYTES);
     };
     __syncthreads();                      // previous item's readers are done with every stage
 #pragma unroll
@@ -362,7 +366,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
   const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   L ld;
-  ld.init();
+  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
@@ -402,8 +406,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
     auto request = [&](int tile) {
       const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
       const int row0 = tile < ntiles ? tile * RS : N;
-      ld.issue(dk_, rsb, row0, nb);
-      ld.issue(dv_, rsb, row0, nb + L::BYTES);
+      const unsigned at = (unsigned)row0 * rsb;
+      ld.issue(dk_, at, nb);
+      ld.issue(dv_, at, nb + L::BYTES);
     };
     __syncthreads();
 #pragma unroll
@@ -482,8 +487,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   typedef LdsTile<KT, D, NW> LV;
   const lds_byte* vblk = smem + NST * STAGE;
   const float* stat = reinterpret_cast<const float*>(smem_raw + NST * STAGE + LV::BYTES);  // [NST][2][64]: lse, delta
-  L ld;
-  ld.init();
+  L ld, ldo;           // lane offsets for the two row strides: q rows and dO rows
+  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
+  ldo.init((unsigned)(H * D * 2));
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, hb = lane >> 5;
   // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
@@ -541,14 +547,14 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       const int g = tile / ntq, tq = tile - g * ntq;
       const int row0 = tile < ntiles ? q_begin + tq * RS : N;
       const unsigned col = tile < ntiles ? (unsigned)(g * D * 2) : 0u;
-      ld.issue(dq_, rsb, row0, nb, col);
-      ld.issue(do_, hsb, row0, nb + L::BYTES, col);
+      ld.issue(dq_, (unsigned)row0 * rsb + col, nb);
+      ldo.issue(do_, (unsigned)row0 * hsb + col, nb + L::BYTES);
     };
     __syncthreads();
     {
       LV ldv;            // built here so that its per-lane offsets do not live across the tile loop
-      ldv.init();
-      ldv.issue(slice_desc(rowb + vo + kvh * D, N, rs, D), rsb, k0, lds0 + NST * STAGE);
+      ldv.init(rsb);
+      ldv.issue(slice_desc(rowb + vo + kvh * D, N, rs, D), (unsigned)k0 * rsb, lds0 + NST * STAGE);
     }
 #pragma unroll
     for (int u = 0; u < PD; ++u) { request(u); stage_stats(u); }
