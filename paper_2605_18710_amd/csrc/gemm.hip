@@ -194,7 +194,7 @@ struct WorkItem {
 // the first tiles of the next item are already in LDS while the epilogue of the current one
 // runs (the other wave on the SIMD keeps the matrix cores busy meanwhile).
 template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK>
-__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
+__global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
     const bf16* __restrict__ bias, const bf16* __restrict__ R, int M, int N, int K,
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
@@ -362,11 +362,15 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     int ln = lane;
     asm volatile("" : "+v"(ln));
     const int elr = ln & 31, ehb = ln >> 5;
+    // Blocks leave in the order b = i * TN + j (row block i outer, column block j inner):
+    // the two 64-byte halves of a 128-byte line of C belong to column blocks j, j+1 of the
+    // same rows and are stored back to back, so they meet in the L2 before the line is
+    // written out.
     // byte offset in C (and in the residual) of the 8 columns this lane writes back for row
     // half q of block b; rows past M fall outside the descriptor's range
     auto out_off = [&](int b, int q) -> unsigned {
-      const int row = it.m0 + wm + 32 * (b % TM) + (ln >> 2) + 16 * q;
-      const int col = it.n0 + wn + 32 * (b / TM) + 8 * (ln & 3);
+      const int row = it.m0 + wm + 32 * (b / TN) + (ln >> 2) + 16 * q;
+      const int col = it.n0 + wn + 32 * (b % TN) + 8 * (ln & 3);
       return (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
     };
     // bias for the 8 columns this lane writes back in column block j (same for every row block)
@@ -387,8 +391,10 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(0, q), 0, 0);
     }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int b = 0; b < TM * TN; ++b) {
+      const int i = b / TN, j = b % TN;
       const int cb = it.n0 + wn + 32 * j;                 // first column of the block
+      const int rb0 = it.m0 + wm + 32 * i;                // first row of the block
       float bvals[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) bvals[e] = 0.f;
@@ -397,10 +403,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) bvals[e] = (float)bv[e];
       }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int b = j * TM + i;
-        const int rb0 = it.m0 + wm + 32 * i;              // first row of the block
+      {
         // accumulator layout -> LDS: row lr, column group cg = 2g + hb (4 columns each)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -434,7 +437,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
             if (b + 1 < TM * TN) {
 #pragma unroll
               for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(b + 1, q), 0, 0);
-              if ((b + 1) % TM == 0) bnext = bias_req((b + 1) / TM);
+              bnext = bias_req((b + 1) % TN);
             }
           }
 #pragma unroll
@@ -467,6 +470,75 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     __syncthreads();               // the patch lives in the stage the next step overwrites
   };
+  // Plain and bias variants when the wave tile is 64 columns wide: the two column blocks of
+  // a row block are rounded to bf16 in accumulator layout (bias added in fp32 first) and
+  // pass through the patch together as 32 rows of 128 bytes, 16-byte chunks XOR-swizzled
+  // by (row/2)%8; they leave as whole 128-byte lines, 8 rows per store instruction.
+  auto finish_rows = [&](const WorkItem& it, int free_stage, auto mode_) {
+    constexpr int MODE = decltype(mode_)::value;
+    static_assert(TN == 2, "row-wide epilogue needs a 64-column wave tile");
+    unsigned char* patch = smem + free_stage + wave * 4096;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int elr = ln & 31, ehb = ln >> 5;
+    // bias of the columns this lane holds in accumulator layout: block j, group g -> 4 values
+    u32x2 braw[MODE == EPI_BIAS ? 2 * 4 : 1] = {};
+    if constexpr (MODE == EPI_BIAS) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = it.n0 + wn + 32 * j + 8 * g + 4 * ehb;
+          braw[4 * j + g] = __builtin_amdgcn_raw_buffer_load_b64(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
+        }
+    }
+    const int wr = elr * 128 + ehb * 8, wsx = (elr >> 1) & 7;
+    const int c16 = ln & 7;
+    const int ocol = it.n0 + wn + 8 * c16;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
+          bf16x4 bv = {};
+          if constexpr (MODE == EPI_BIAS) bv = __builtin_bit_cast(bf16x4, braw[4 * j + g]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float v = acc[i][j][4 * g + e];
+            if constexpr (MODE == EPI_BIAS) v += (float)bv[e];
+            o[e] = (bf16)v;
+          }
+          *reinterpret_cast<bf16x4*>(patch + wr + (((4 * j + g) ^ wsx) << 4)) = o;
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      u32x4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = (ln >> 3) + 8 * q;
+        v[q] = *reinterpret_cast<const u32x4*>(patch + r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = it.m0 + wm + 32 * i + (ln >> 3) + 8 * q;
+        const unsigned off = (ocol < N) ? (unsigned)(((int64_t)row * ldc + ocol) * 2) : kOob;
+        __builtin_amdgcn_raw_buffer_store_b128(v[q], rc, (int)off, 0, 0);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    __syncthreads();               // the patch lives in the stage the next step overwrites
+  };
   // Only the forward form meets a bias without a residual often enough to hold a variant for
   // it; elsewhere such a call takes EPI_RES, whose empty residual descriptor reads zeros.
   constexpr bool BIAS_VARIANT = A_KC && !B_KC;
@@ -478,9 +550,9 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     } else {
       if (epi_mode == EPI_RES) { finish_impl(it, free_stage, std::integral_constant<int, EPI_RES>{}); return; }
       if constexpr (BIAS_VARIANT) {
-        if (epi_mode == EPI_BIAS) { finish_impl(it, free_stage, std::integral_constant<int, EPI_BIAS>{}); return; }
+        if (epi_mode == EPI_BIAS) { finish_rows(it, free_stage, std::integral_constant<int, EPI_BIAS>{}); return; }
       }
-      finish_impl(it, free_stage, std::integral_constant<int, EPI_PLAIN>{});
+      finish_rows(it, free_stage, std::integral_constant<int, EPI_PLAIN>{});
     }
   };
 
