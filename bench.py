@@ -203,6 +203,8 @@ def main():
     ap.add_argument("--roofline-only", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--layer-split", action="store_true",
+                    help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
     ap.add_argument("--no-pool-bench", action="store_true",
                     help="skip the create/destroy microbenchmark of masked streams (the profiler's queue interception does not survive it)")
     args = ap.parse_args()
@@ -307,6 +309,33 @@ def main():
     def util(fl, ms, q):
         return fl / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12 * q / cus)
 
+    # Two-stage alternative: the decoder cut after layer k, layers [0, k) colocated with the
+    # other groups, layers [k, L) alone on all CUs.  (plan, k) is picked from the colocated
+    # module times already measured (a decoder's time is linear in its layers), then measured.
+    split = None
+    stage_destroyed = False
+    L = llm["layers"]
+    if args.layer_split and L >= 2 and ngroups >= 2:
+        from paper_2605_18710_amd.workload import SplitStage
+        dec_g = [gi for gi, g in enumerate(stage.groups) if llm["name"] in g][0]
+        cands = []
+        for r in results:
+            g_ms = [sum(r["module_ms"][i] for i, n in enumerate(stage.names) if n in g) for g in stage.groups]
+            others = max(v for gi, v in enumerate(g_ms) if gi != dec_g)
+            for k in range(1, L):
+                cands.append((max(others, g_ms[dec_g] * k / L) + group_ms_full[dec_g] * (L - k) / L, r["plan"], k))
+        pred, sp_plan, sp_k = min(cands)
+        stage.destroy()
+        stage_destroyed = True
+        ss = SplitStage(args.config, sp_k)
+        ss.run(sp_plan)
+        rs = [ss.run(sp_plan) for _ in range(5)]
+        it = statistics.median(r["iteration_ms"] for r in rs)
+        split = {"cut_after_layer": sp_k, "plan_cus": sp_plan, "predicted_ms": round(pred, 4), "iteration_ms": round(it, 4),
+                 "stage_ms": [round(statistics.median(r["stage_ms"][j] for r in rs), 4) for j in range(2)],
+                 "samples_per_s": round(B / (it * 1e-3), 2), "speedup_vs_time_sliced": round(ts["stage_ms"] / it, 4)}
+        ss.destroy()
+
     group_ms_co = [sum(best["module_ms"][i] for i, n in enumerate(stage.names) if n in g) for g in stage.groups]
     dominant = max(gms, key=lambda k: gms[k])       # the slowest of the three forms bounds the step
     line = {
@@ -326,7 +355,8 @@ def main():
                       "aggregate_mfma_util": round(sum(gflop) / (best["stage_ms"] * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
                       "plans": [dict(plan=r["plan"], stage_ms=round(r["stage_ms"], 4)) for r in results],
                       "chosen_from_curves": {"plan": chosen, "predicted_ms": round(predicted, 4),
-                                             "cu_grid": grid, "group_ms": [[round(v, 4) for v in row] for row in curves]}},
+                                             "cu_grid": grid, "group_ms": [[round(v, 4) for v in row] for row in curves]},
+                      "decoder_cut_in_time": split},
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel 256x256x32 {dominant} T={Tl} k={hl} n={2 * fl}",
                      "achieved": round(gflops / gms[dominant] / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gflops / gms[dominant] / 1e9 / PEAK_BF16_TFLOPS, 4),
@@ -345,7 +375,8 @@ def main():
                                                    (ms_per_step + ngroups * pool["on_demand_create_destroy_ms"]), 4)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
-    stage.destroy()
+    if not stage_destroyed:
+        stage.destroy()
     print(json.dumps(line))
 
 

@@ -124,3 +124,71 @@ class StagedStage:
     def destroy(self):
         for m in self.staged:
             m.destroy()
+
+
+class SplitStage:
+    """The same workload with its decoder cut after layer k into two modules that read
+    staged buffers like every other module.  An iteration is two stages (Eq. 1): stage A
+    colocates the other groups with layers [0, k) under the given group quotas, stage B runs
+    layers [k, L) alone on all CUs.  On this GPU quotas come in steps of 32 CUs, too coarse
+    to balance an encoder against a whole decoder of several times its work; cutting the
+    decoder in time restores the balance (the slicing of modules the paper cites as prior
+    work, Sec. 2.3, applied to one module and combined with its spatial sharing)."""
+
+    def __init__(self, config: int, k: int, dtype: str | None = None):
+        wl = synth.WORKLOADS[config]
+        self.dtype = dtype or wl["dtype"]
+        self.groups = [list(g) for g in wl["groups"]]
+        self.first: List[StagedModule] = []      # stage A, in workload order
+        self.first_names: List[str] = []
+        self.second: StagedModule | None = None  # stage B
+        for i, cfg in enumerate(wl["modules"]):
+            seed = synth.tensor_seed(config, 0) + 10000 * (i + 1)
+            if cfg["kind"] != "decoder":
+                self.first.append(StagedModule(dict(cfg), self.dtype, seed, with_target=False))
+                self.first_names.append(cfg["name"])
+                continue
+            if not 0 < k < cfg["layers"]:
+                raise ValueError("cut must leave layers on both sides")
+            a, b = dict(cfg), dict(cfg)
+            a["layers"], b["layers"] = k, cfg["layers"] - k
+            self.first.append(StagedModule(a, self.dtype, seed, with_target=True))
+            self.first_names.append(cfg["name"])
+            self.second = StagedModule(b, self.dtype, seed + 5000, with_target=True)
+        if self.second is None:
+            raise ValueError("workload has no decoder to cut")
+        self.cus = mb.device_cu_count()
+
+    def _group_of(self, name: str) -> int:
+        for g, members in enumerate(self.groups):
+            if name in members:
+                return g
+        raise KeyError(name)
+
+    def run(self, group_quotas) -> dict:
+        offs, o = [], 0
+        for q in group_quotas:
+            offs.append(o)
+            o += q
+        quotas = [group_quotas[self._group_of(n)] for n in self.first_names]
+        offsets = [offs[self._group_of(n)] for n in self.first_names]
+        # a masked stream holds a hardware queue: each stage keeps only its own streams alive
+        mb.pool_clear()
+        for q, off in zip(group_quotas, offs):
+            mb.pool_reserve(q, off, mb.STRIPED)
+        s = self.first
+        ra = mb.stage_run([m.module for m in s], [m.x for m in s], [m.y for m in s], quotas, offsets, mb.STRIPED,
+                          mb.COLOCATED, dy=[m.dy for m in s], target=[m.target for m in s],
+                          dx=[m.dx for m in s], loss=[m.loss for m in s])
+        mb.pool_clear()
+        mb.pool_reserve(self.cus, 0, mb.STRIPED)
+        b = self.second
+        rb = mb.stage_run([b.module], [b.x], [b.y], [self.cus], [0], mb.STRIPED, mb.TIME_SLICED,
+                          dy=[b.dy], target=[b.target], dx=[b.dx], loss=[b.loss])
+        return dict(iteration_ms=ra["stage_ms"] + rb["stage_ms"], stage_ms=[ra["stage_ms"], rb["stage_ms"]],
+                    module_ms=ra["module_ms"] + rb["module_ms"])
+
+    def destroy(self):
+        for m in self.first:
+            m.destroy()
+        self.second.destroy()
