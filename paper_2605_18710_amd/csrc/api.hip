@@ -19,6 +19,13 @@ mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, 
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// The MFMA kernels address one sample's packed q|k|v rows with 32-bit byte offsets (buffer
+// descriptors); a tile may start up to 63 rows past the end.  Longer slices take the plain
+// kernels, which index with 64 bits.
+static bool attn_slice_fits32(int N, int H, int Hkv, int d) {
+  return ((int64_t)N + 64) * ((int64_t)H + 2 * Hkv) * d * 2 < ((int64_t)1 << 32);
+}
+
 static mosaic_status check_attn(int B, int N, int H, int Hkv, int d) {
   if (B <= 0 || N <= 0 || H <= 0 || d <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "attention sizes must be positive");
   if (Hkv <= 0 || H % Hkv) MOSAIC_FAIL(MOSAIC_EINVAL, "key/value heads (%d) must divide the query heads (%d)", Hkv, H);
@@ -29,7 +36,7 @@ static mosaic_status check_attn(int B, int N, int H, int Hkv, int d) {
 mosaic_status launch_attention_fwd(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d, int causal,
                                    const void* qkv, void* O, float* lse) {
   MOSAIC_TRY(check_attn(B, N, H, Hkv, d));
-  if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(O))
+  if (attention_mfma_supported(dtype, d) && attn_slice_fits32(N, H, Hkv, d) && aligned16(qkv) && aligned16(O))
     return launch_attention_fwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, O, lse);
   return launch_attention_fwd_simple(s, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse);
 }
@@ -38,7 +45,7 @@ mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, i
                                    const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
                                    float* delta) {
   MOSAIC_TRY(check_attn(B, N, H, Hkv, d));
-  if (attention_mfma_supported(dtype, d) && aligned16(qkv) && aligned16(dO) && aligned16(dqkv)) {
+  if (attention_mfma_supported(dtype, d) && attn_slice_fits32(N, H, Hkv, d) && aligned16(qkv) && aligned16(dO) && aligned16(dqkv)) {
     MOSAIC_TRY(launch_attention_delta(s, quota, dtype, B, N, H, d, O, dO, delta));
     return launch_attention_bwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, lse, dO, dqkv, delta);
   }

@@ -28,7 +28,7 @@
 //   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
 //     so a lane owns four consecutive output columns per register group; the epilogue
 //     (bias, residual, bf16 rounding) is staged through the free LDS stage into
-//     row-contiguous 16-byte stores.
+//     row-contiguous 16-byte stores that fill whole 128-byte lines of the output.
 //   * tiles are handed out so that the workgroups running on one XCD at the same time
 //     form a 4 x 8 patch of the tile grid and share operand panels in that XCD's L2.
 //
@@ -339,20 +339,22 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
 
   // Epilogue of one work item.  acc[i][j][4g+e] is output (row m0+wm+32i+lr, column
   // n0+wn+32j+8g+4hb+e): a lane holds 4-column pieces of 32 different rows, which would
-  // reach memory as 16-byte fragments.  Each 32x32 block therefore passes through a 4 KB
-  // per-wave patch of the LDS stage that is free between two pipeline steps (fp32, XOR
-  // swizzled) and leaves row-contiguous: 64-byte runs of bf16 (bias and residual added in
-  // fp32, one rounding) or full 128-byte lines of fp32 pieces.
+  // reach memory as 8-byte fragments.  The accumulators therefore pass through a 4 KB
+  // per-wave patch of the LDS stage that is free between two pipeline steps (XOR swizzled)
+  // and leave row-contiguous.
   // Three variants, chosen by a uniform branch, so that each holds no request it does not
   // need.  The compiler's wait before a use of a loaded value counts every request of the
   // wave in issue order, stores included: a bias or residual request issued between two
   // stores makes the block that uses it wait until all earlier blocks' stores have been
   // acknowledged.
-  //   EPI_PLAIN: no bias, no residual - stores only, nothing waits.
-  //   EPI_BIAS:  every bias value is requested before the first store.
+  //   EPI_PLAIN: no bias, no residual - stores only, nothing waits        (finish_rows)
+  //   EPI_BIAS:  every bias value is requested before the first store     (finish_rows)
   //   EPI_RES:   residual (and bias, if any: a null bias reads zeros through its empty
   //              descriptor); the requests for block b+1 are issued before block b is stored,
-  //              so a wait never covers the newest stores.
+  //              so a wait never covers the newest stores                 (finish_impl)
+  // finish_impl moves one 32x32 block at a time in fp32 and adds bias and residual in
+  // row-contiguous layout (fp32, one rounding); split-K pieces take the same path and leave
+  // as fp32.
   constexpr int EPI_PLAIN = 0, EPI_BIAS = 1, EPI_RES = 2;
   auto finish_impl = [&](const WorkItem& it, int free_stage, auto mode_) {
     constexpr int MODE = decltype(mode_)::value;
