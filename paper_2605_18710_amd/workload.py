@@ -142,21 +142,22 @@ class SplitStage:
         self.first: List[StagedModule] = []      # stage A, in workload order
         self.first_names: List[str] = []
         self.second: StagedModule | None = None  # stage B
+        decoders = [m for m in wl["modules"] if m["kind"] == "decoder"]
+        if len(decoders) != 1:
+            raise ValueError("workload needs exactly one decoder to cut")
+        if not 0 < k < decoders[0]["layers"]:
+            raise ValueError("cut must leave layers on both sides")
         for i, cfg in enumerate(wl["modules"]):
             seed = synth.tensor_seed(config, 0) + 10000 * (i + 1)
             if cfg["kind"] != "decoder":
                 self.first.append(StagedModule(dict(cfg), self.dtype, seed, with_target=False))
                 self.first_names.append(cfg["name"])
                 continue
-            if not 0 < k < cfg["layers"]:
-                raise ValueError("cut must leave layers on both sides")
             a, b = dict(cfg), dict(cfg)
             a["layers"], b["layers"] = k, cfg["layers"] - k
             self.first.append(StagedModule(a, self.dtype, seed, with_target=True))
             self.first_names.append(cfg["name"])
             self.second = StagedModule(b, self.dtype, seed + 5000, with_target=True)
-        if self.second is None:
-            raise ValueError("workload has no decoder to cut")
         self.cus = mb.device_cu_count()
 
     def _group_of(self, name: str) -> int:

@@ -107,3 +107,23 @@ def test_stage_modes_agree_and_pool_is_used(mb):
     assert e.value.status == mb.EQUOTA
     for m in mods:
         m.destroy()
+
+
+def test_decoder_cut_in_time_runs_two_stages(mb):
+    """Two-stage plan: layers [0, k) of the decoder colocated with the vision group, layers
+    [k, L) alone on all CUs.  Both stages must run, and the iteration is their sum (Eq. 1)."""
+    from paper_2605_18710_amd.workload import SplitStage
+    with pytest.raises(ValueError):
+        SplitStage(0, 1)                        # the tiny workload's decoder has one layer: nothing to cut
+    st = SplitStage(1, 2)
+    try:
+        r = st.run([32, 224])
+        assert len(r["stage_ms"]) == 2 and all(t > 0 for t in r["stage_ms"])
+        assert r["iteration_ms"] == pytest.approx(sum(r["stage_ms"]), rel=1e-6)
+        assert len(r["module_ms"]) == len(st.first) + 1
+        for m in st.first + [st.second]:
+            assert torch.isfinite(m.y.float()).all()
+        assert torch.isfinite(st.second.loss).all() and float(st.second.loss) > 0
+    finally:
+        st.destroy()
+        mb.pool_clear()
