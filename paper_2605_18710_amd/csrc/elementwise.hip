@@ -135,6 +135,121 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_dx_kernel(
   }
 }
 
+// dx and the dgamma / dbeta partial sums in one pass over x and dy.  Work item = row
+// partition p (rp rows; rp depends on the row count alone).  Wave w of the workgroup takes
+// rows r0+w, r0+w+4, ... in ascending order, holds the row of x and dy in registers, writes
+// dx and adds dy*xhat (and dy) into per-lane column accumulators.  The four waves'
+// accumulators are added in wave order through LDS, one 64-lane column slab at a time, and
+// land in scratch[p][2][h]; reduce_partials_kernel adds the partitions in a fixed order.
+template <typename T, int NORM, int NV>
+__global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
+    const T* __restrict__ dy, const T* __restrict__ R, T* __restrict__ dx, float* __restrict__ scratch,
+    int64_t rows, int h, int rp, int np) {
+  constexpr int VN = Vec16<T>::N;
+  constexpr int NSUM = (NORM == MOSAIC_LAYERNORM) ? 2 : 1;
+  __shared__ float red[kWaves - 1][NSUM][64 * VN];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_h = 1.0f / (float)h;
+  Vec16<T> g[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = (j * 64 + lane) * VN;
+    if (c < h) g[j].load(gamma + c);
+  }
+  for (int p = blockIdx.x; p < np; p += gridDim.x) {
+    float ag[NV][VN], ab[NSUM == 2 ? NV : 1][VN];
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+      for (int i = 0; i < VN; ++i) { ag[j][i] = 0.f; if (NSUM == 2) ab[j][i] = 0.f; }
+    const int64_t r0 = (int64_t)p * rp;
+    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
+    for (int64_t row = r0 + wave; row < r1; row += kWaves) {
+      const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+      Vec16<T> xv[NV], dv[NV];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+          xv[j].load(x + row * h + c);
+          dv[j].load(dy + row * h + c);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) {
+            const float d = dv[j].get(i);
+            const float t = d * g[j].get(i);
+            if (NORM == MOSAIC_LAYERNORM) {
+              const float xh = (xv[j].get(i) - mean) * rstd;
+              s1 += t; s2 += t * xh;
+              ag[j][i] += d * xh; ab[NSUM == 2 ? j : 0][i] += d;
+            } else {
+              s2 += t * xv[j].get(i);
+              ag[j][i] += d * xv[j].get(i) * rstd;
+            }
+          }
+        }
+      }
+      if (NORM == MOSAIC_LAYERNORM) s1 = wave_sum(s1) * inv_h;
+      s2 = wave_sum(s2) * inv_h;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+          Vec16<T> o, rv;
+          if (R) rv.load(R + row * h + c);
+#pragma unroll
+          for (int i = 0; i < VN; ++i) {
+            const float xr = xv[j].get(i);
+            const float t = dv[j].get(i) * g[j].get(i);
+            float r;
+            if (NORM == MOSAIC_LAYERNORM) r = (t - s1 - (xr - mean) * rstd * s2) * rstd;
+            else r = rstd * t - rstd * rstd * rstd * xr * s2;
+            if (R) r += rv.get(i);
+            o.set(i, r);
+          }
+          o.store(dx + row * h + c);
+        }
+      }
+    }
+    // waves 1..3 hand their sums to wave 0, slab by slab; every wave passes every barrier
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          red[wave - 1][0][i * 64 + lane] = ag[j][i];
+          if (NSUM == 2) red[wave - 1][NSUM - 1][i * 64 + lane] = ab[NSUM == 2 ? j : 0][i];
+        }
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const int c = (j * 64 + lane) * VN;
+        if (c < h) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) {
+            float a = ag[j][i], b = (NSUM == 2) ? ab[NSUM == 2 ? j : 0][i] : 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves - 1; ++w) {
+              a += red[w][0][i * 64 + lane];
+              if (NSUM == 2) b += red[w][NSUM - 1][i * 64 + lane];
+            }
+            scratch[((int64_t)p * 2 + 0) * h + c + i] = a;
+            if (NSUM == 2) scratch[((int64_t)p * 2 + 1) * h + c + i] = b;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
 // dgamma / dbeta partial column sums: work item = (row partition p, tile of 256 column
 // vectors); a thread owns VN columns and walks the partition's rows in ascending order.
 // scratch[p][2][h]; the partitions are added in a fixed order by reduce_partials_kernel.
@@ -357,6 +472,8 @@ __global__ __launch_bounds__(kThreads) void mse_final_kernel(const float* __rest
 
 // ------------------------------------------------------------------------------ colsum
 constexpr int kColsumMaxParts = 256;
+// widest row (in 16-byte vectors per lane) whose column accumulators the fused norm backward keeps in registers
+constexpr int kNormFusedMaxNV = 8;   // LayerNorm; RMSNorm (one sum per column) also fits at 10
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __restrict__ X, float* __restrict__ partial,
@@ -550,6 +667,36 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   const int nv = pick_nv((int)ceil_div(h, 64 * VN));
   if (nv < 0) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld too large", (long long)h);
   if (rows == 0) return MOSAIC_OK;
+  int rp, np;
+  col_partition(rows, &rp, &np);
+  const int g2 = grid_for(quota, 8, ceil_div(2 * h, 32));
+  if (nv <= kNormFusedMaxNV || norm == MOSAIC_RMSNORM) {
+    // one pass: x and dy are read once for dx and for the column sums
+    const int gf = grid_for(quota, 8, np);
+#define LF(NVC)                                                                                       \
+    if (norm == MOSAIC_LAYERNORM)                                                                     \
+      norm_bwd_fused_kernel<T, MOSAIC_LAYERNORM, NVC><<<gf, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np); \
+    else                                                                                              \
+      norm_bwd_fused_kernel<T, MOSAIC_RMSNORM, NVC><<<gf, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np)
+    switch (nv) {
+      case 1: LF(1); break;
+      case 2: LF(2); break;
+      case 3: LF(3); break;
+      case 4: LF(4); break;
+      case 5: LF(5); break;
+      case 6: LF(6); break;
+      case 8: LF(8); break;
+      default:
+        norm_bwd_fused_kernel<T, MOSAIC_RMSNORM, 10><<<gf, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np);
+        break;
+    }
+#undef LF
+    MOSAIC_LAUNCH_CHECK();
+    reduce_partials_kernel<T><<<g2, kThreads, 0, s>>>(scratch, np, 2 * h, 2 * h, h, dgamma,
+                                                      norm == MOSAIC_LAYERNORM ? dbeta : (T*)nullptr);
+    MOSAIC_LAUNCH_CHECK();
+    return MOSAIC_OK;
+  }
   const int grid = grid_for(quota, 8, ceil_div(rows, kWaves));
 #define L(NVC)                                                                                        \
   if (norm == MOSAIC_LAYERNORM)                                                                       \
@@ -559,8 +706,6 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   DISPATCH_NV(nv, L);
 #undef L
   MOSAIC_LAUNCH_CHECK();
-  int rp, np;
-  col_partition(rows, &rp, &np);
   const int ctiles = (int)ceil_div(h, (int64_t)kThreads * VN);
   const int g1 = grid_for(quota, 8, (int64_t)np * ctiles);
   if (norm == MOSAIC_LAYERNORM)
@@ -568,7 +713,6 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   else
     norm_colgrad_partial_kernel<T, MOSAIC_RMSNORM><<<g1, kThreads, 0, s>>>(x, stats, dy, scratch, rows, (int)h, rp, np, ctiles);
   MOSAIC_LAUNCH_CHECK();
-  const int g2 = grid_for(quota, 8, ceil_div(2 * h, 32));
   reduce_partials_kernel<T><<<g2, kThreads, 0, s>>>(scratch, np, 2 * h, 2 * h, h, dgamma,
                                                     norm == MOSAIC_LAYERNORM ? dbeta : (T*)nullptr);
   MOSAIC_LAUNCH_CHECK();
