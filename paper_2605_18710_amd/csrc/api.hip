@@ -14,8 +14,8 @@ bool attention_mfma_supported(int dtype, int d);
 mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
                                         const void* qkv, void* O, float* lse);
 mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
-                                        const void* qkv, const float* lse, const void* dO, void* dqkv,
-                                        const float* delta);
+                                        const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+                                        float* delta);
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -45,9 +45,8 @@ mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, i
                                    const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
                                    float* delta) {
   MOSAIC_TRY(check_attn(B, N, H, Hkv, d));
-  if (attention_mfma_supported(dtype, d) && attn_slice_fits32(N, H, Hkv, d) && aligned16(qkv) && aligned16(dO) && aligned16(dqkv)) {
-    MOSAIC_TRY(launch_attention_delta(s, quota, dtype, B, N, H, d, O, dO, delta));
-    return launch_attention_bwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, lse, dO, dqkv, delta);
+  if (attention_mfma_supported(dtype, d) && attn_slice_fits32(N, H, Hkv, d) && aligned16(qkv) && aligned16(O) && aligned16(dO) && aligned16(dqkv)) {
+    return launch_attention_bwd_mfma(s, quota, B, N, H, Hkv, d, causal, qkv, O, lse, dO, dqkv, delta);
   }
   return launch_attention_bwd_simple(s, quota, dtype, B, N, H, Hkv, d, causal, qkv, O, lse, dO, dqkv, delta);
 }

@@ -354,8 +354,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
 
 // ------------------------------------------------------------------------------- dQ
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
-                                                        const float* __restrict__ lse, const float* __restrict__ delta,
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+                                                        const bf16* __restrict__ dO,
+                                                        const float* __restrict__ lse, float* __restrict__ delta,
                                                         bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
                                                         float scale, int qtiles) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
@@ -382,18 +383,27 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
     const bf16* base = rowb + hd * D;
     const int kvh = hd / GQ;
     const bf16* dob = dO + (int64_t)b * N * h + hd * D;
+    const bf16* ob = O + (int64_t)b * N * h + hd * D;
     bf16x8 qf[NS], dof[NS];
+    // delta_i = sum_c dO[i][c] * O[i][c] of this wave's rows is formed here, from the dO
+    // fragments the wave holds anyway (a lane covers half of the columns, the other half
+    // sits 32 lanes away), and stored for the dK/dV kernel, which runs after this one
+    float dlt = 0.f;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       if (i < N) {
         qf[s] = *reinterpret_cast<const bf16x8*>(base + (int64_t)i * rs + 16 * s + 8 * hb);
         dof[s] = *reinterpret_cast<const bf16x8*>(dob + (int64_t)i * h + 16 * s + 8 * hb);
+        const bf16x8 of = *reinterpret_cast<const bf16x8*>(ob + (int64_t)i * h + 16 * s + 8 * hb);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dlt = fmaf((float)dof[s][e], (float)of[e], dlt);
       } else {
         for (int e = 0; e < 8; ++e) { qf[s][e] = (bf16)0.f; dof[s][e] = (bf16)0.f; }
       }
     }
+    dlt += __shfl_xor(dlt, 32, 64);
+    if (i < N && hb == 0) delta[((int64_t)b * H + hd) * N + i] = dlt;
     const float lse2 = (i < N) ? lse[((int64_t)b * H + hd) * N + i] * kLog2e : 0.f;
-    const float dlt = (i < N) ? delta[((int64_t)b * H + hd) * N + i] : 0.f;
     f32x16 dq[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c)
@@ -657,25 +667,26 @@ mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
 }
 
 template <int D, int NW>
-mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, const float* lse,
-                    const bf16* dO, bf16* dqkv, const float* delta) {
+mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, const bf16* O,
+                    const float* lse, const bf16* dO, bf16* dqkv, float* delta) {
   const int tiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * tiles;
   const float scale = 1.0f / sqrtf((float)D);
   const int grid = grid_for(quota, 8 / NW, items);
+  {
+    // dQ first: it also writes the per-row delta that the dK/dV kernel reads
+    constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
+    static bool once = false;
+    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
+    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
+    MOSAIC_LAUNCH_CHECK();
+  }
   {
     constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<32, D, NW>::BYTES + LdsTile<32 * NW, D, NW>::BYTES +
                             (size_t)Ring<NW>::NST * 2 * 64 * sizeof(float);
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D, NW>, smem)); once = true; }
     attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
-    MOSAIC_LAUNCH_CHECK();
-  }
-  {
-    constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
-    static bool once = false;
-    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
-    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
@@ -692,8 +703,8 @@ mosaic_status launch_attention_fwd_mfma(hipStream_t s, int quota, int B, int N, 
 }
 
 mosaic_status launch_attention_bwd_mfma(hipStream_t s, int quota, int B, int N, int H, int Hkv, int d, int causal,
-                                        const void* qkv, const float* lse, const void* dO, void* dqkv,
-                                        const float* delta) {
-  if (d == 64) return bwd_t<64, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
-  return bwd_t<128, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+                                        const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+                                        float* delta) {
+  if (d == 64) return bwd_t<64, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, delta);
+  return bwd_t<128, 4>(s, quota, B, N, H, Hkv, causal, (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, delta);
 }

@@ -140,7 +140,7 @@ WORKLOADS = {
                      _enc("audio", 8, 1500, 1280, 20, 5120, 8, stem_in=80),
                      _dec("llm", 8, 4096, 4096, 32, 11008, 4)],
             groups=[["vit"], ["audio"], ["llm"]],
-            plans=[[32, 32, 192], [32, 64, 160], [64, 64, 128], [32, 96, 128], [16, 48, 192]],
+            plans=[[32, 32, 192], [32, 64, 160], [64, 64, 128], [32, 96, 128], [64, 32, 160]],
             image=(8, 3, 336, 336), patch=14),
 }
 
