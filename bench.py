@@ -202,6 +202,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the workload list (1 = CLIP-B / small-LM scale)")
     ap.add_argument("--roofline-only", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
+    ap.add_argument("--bandwidth-only", action="store_true", help="only the bandwidth-bound kernels at the decoder's shapes (for rocprofv3)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--layer-split", action="store_true",
                     help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
@@ -227,6 +228,15 @@ def main():
 
     if args.attention_only:
         print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20)))
+        return
+    if args.bandwidth_only:
+        # plus a plain device copy of known size, so that HBM byte counters of the same run can be scaled
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"shape": {"T": Tl, "h": hl, "f": fl}, "gbs": bandwidth_kernels(mb, Tl, hl, fl, reps=20)}))
         return
     gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=20)
     if args.roofline_only:
