@@ -91,38 +91,35 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(T* __restrict__ p, cons
                                                          float* __restrict__ v, float* __restrict__ master, int64_t nvec,
                                                          float lr, float b1, float b2, float eps, float wd,
                                                          float inv_bc1, float inv_bc2) {
-  constexpr int VN = Vec16<T>::N;
+  // Four elements per thread for either type: the fp32 state moves as one 16-byte vector, a
+  // bf16 parameter and gradient as one 8-byte vector, so that every instruction of a wave
+  // covers one contiguous run (1 KB, or 512 bytes) and each line is written whole by one
+  // instruction.
+  typedef __attribute__((ext_vector_type(4))) T vec4;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
-    Vec16<T> pv, gv;
-    pv.load(p + i * VN);
-    gv.load(g + i * VN);
-    // fp32 state moves as 16-byte vectors as well (VN is 4 or 8: one or two float4 per array)
-    float mv[VN], vv[VN], ms[VN];
+    vec4 pv = *reinterpret_cast<const vec4*>(p + i * 4);
+    const vec4 gv = *reinterpret_cast<const vec4*>(g + i * 4);
+    float4 mv = *reinterpret_cast<const float4*>(m + i * 4);
+    float4 vv = *reinterpret_cast<const float4*>(v + i * 4);
+    float4 ms = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (master) ms = *reinterpret_cast<const float4*>(master + i * 4);
+    float* mp = &mv.x; float* vp = &vv.x; float* sp = &ms.x;
 #pragma unroll
-    for (int k = 0; k < VN; k += 4) {
-      *reinterpret_cast<float4*>(mv + k) = *reinterpret_cast<const float4*>(m + i * VN + k);
-      *reinterpret_cast<float4*>(vv + k) = *reinterpret_cast<const float4*>(v + i * VN + k);
-      if (master) *reinterpret_cast<float4*>(ms + k) = *reinterpret_cast<const float4*>(master + i * VN + k);
-    }
-#pragma unroll
-    for (int k = 0; k < VN; ++k) {
-      const float gk = gv.get(k);
-      const float pk = master ? ms[k] : pv.get(k);
-      const float mk = b1 * mv[k] + (1.0f - b1) * gk;
-      const float vk = b2 * vv[k] + (1.0f - b2) * gk * gk;
-      mv[k] = mk; vv[k] = vk;
+    for (int k = 0; k < 4; ++k) {
+      const float gk = (float)gv[k];
+      const float pk = master ? sp[k] : (float)pv[k];
+      const float mk = b1 * mp[k] + (1.0f - b1) * gk;
+      const float vk = b2 * vp[k] + (1.0f - b2) * gk * gk;
+      mp[k] = mk; vp[k] = vk;
       const float upd = (mk * inv_bc1) / (sqrtf(vk * inv_bc2) + eps) + wd * pk;
       const float np_ = pk - lr * upd;
-      ms[k] = np_;
-      pv.set(k, np_);
+      sp[k] = np_;
+      pv[k] = (T)np_;
     }
-#pragma unroll
-    for (int k = 0; k < VN; k += 4) {
-      *reinterpret_cast<float4*>(m + i * VN + k) = *reinterpret_cast<const float4*>(mv + k);
-      *reinterpret_cast<float4*>(v + i * VN + k) = *reinterpret_cast<const float4*>(vv + k);
-      if (master) *reinterpret_cast<float4*>(master + i * VN + k) = *reinterpret_cast<const float4*>(ms + k);
-    }
-    pv.store(p + i * VN);
+    *reinterpret_cast<float4*>(m + i * 4) = mv;
+    *reinterpret_cast<float4*>(v + i * 4) = vv;
+    if (master) *reinterpret_cast<float4*>(master + i * 4) = ms;
+    *reinterpret_cast<vec4*>(p + i * 4) = pv;
   }
 }
 
@@ -262,7 +259,7 @@ mosaic_status launch_rope(hipStream_t s, int quota, int dtype, int B, int N, int
 
 mosaic_status launch_adamw(hipStream_t s, int quota, int dtype, int64_t n, void* p, const void* g, float* m, float* v,
                            float* master, float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step) {
-  const int vn = dtype == MOSAIC_BF16 ? 8 : 4;
+  const int vn = 4;
   if (n % vn) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "element count %lld is not a multiple of %d", (long long)n, vn);
   if (step < 1) MOSAIC_FAIL(MOSAIC_EINVAL, "step counts from 1");
   if (((uintptr_t)p | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v | (uintptr_t)master) & 15) MOSAIC_FAIL(MOSAIC_EINVAL, "AdamW buffers must be 16-byte aligned");
