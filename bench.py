@@ -26,13 +26,27 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
-def time_kernel(fn, reps, warm=3):
+def time_kernel(fn, reps, warm=3, settle_ms=0.0):
     """Average duration in ms of `reps` launches of fn on the default stream (HIP events
-    recorded on that same stream)."""
+    recorded on that same stream).  settle_ms > 0: after the warm-up calls, fn is launched
+    untimed for about that long first.  From idle the board runs the first ~1.5 ms of heavy
+    work above its sustained clock, then the power controller clamps below it and settles
+    over the next ~15 ms; a training step sees the settled rate, so that is what is timed."""
     import torch
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
+    if settle_ms > 0.0:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        est = max(e0.elapsed_time(e1) / 3.0, 1e-3)
+        for _ in range(int(settle_ms / est) + 1):
+            fn()
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
@@ -56,12 +70,10 @@ def profiled_traffic(form):
     return None
 
 
-def roofline_gemm(mb, T, k, n, reps, warm):
+def roofline_gemm(mb, T, k, n, reps, settle_ms):
     """The dominant kernel: the bf16 MFMA GEMM at the decoder's gate/up projection shape,
-    forward, input-gradient and weight-gradient forms, on all CUs.  `warm` untimed calls come
-    first: from idle the board runs the first few calls above its sustained clock, then the
-    power controller clamps below it and settles over the next ~10 ms; a training step sees
-    the settled rate, so that is what is timed."""
+    forward, input-gradient and weight-gradient forms, on all CUs, each timed after
+    settle_ms of untimed calls (see time_kernel)."""
     import torch
     bf = torch.bfloat16
     X = torch.randn(T, k, device="cuda", dtype=bf)
@@ -74,9 +86,9 @@ def roofline_gemm(mb, T, k, n, reps, warm):
     q = mb.device_cu_count()
     flops = 2.0 * T * k * n
     out = {}
-    out["fprop"] = time_kernel(lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y), reps, warm)
-    out["dgrad"] = time_kernel(lambda: mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY, W, None, dX), reps, warm)
-    out["wgrad"] = time_kernel(lambda: mb.op_linear_wgrad(None, q, "bf16", T, k, n, X, dY, dW, None, ws), reps, warm)
+    out["fprop"] = time_kernel(lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y), reps, 3, settle_ms)
+    out["dgrad"] = time_kernel(lambda: mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY, W, None, dX), reps, 3, settle_ms)
+    out["wgrad"] = time_kernel(lambda: mb.op_linear_wgrad(None, q, "bf16", T, k, n, X, dY, dW, None, ws), reps, 3, settle_ms)
     return flops, out
 
 
@@ -129,8 +141,8 @@ def attention_kernels(mb, B, N, H, d, causal, reps):
     O = torch.empty(B * N, h, device="cuda", dtype=bf); dO = torch.randn(B * N, h, device="cuda", dtype=bf)
     lse = torch.empty(B * H * N, device="cuda", dtype=torch.float32); delta = torch.empty_like(lse)
     dqkv = torch.empty_like(qkv)
-    tf = time_kernel(lambda: mb.op_attention_fwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse), reps)
-    tb = time_kernel(lambda: mb.op_attention_bwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta), reps)
+    tf = time_kernel(lambda: mb.op_attention_fwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse), reps, 3, 40.0)
+    tb = time_kernel(lambda: mb.op_attention_bwd(None, q, "bf16", B, N, H, d, causal, qkv, O, lse, dO, dqkv, delta), reps, 3, 40.0)
     fl = 4.0 * B * N * N * h * (0.5 if causal else 1.0)
     return dict(shape=dict(B=B, N=N, H=H, d=d, causal=causal), fwd_ms=round(tf, 4), bwd_ms=round(tb, 4),
                 fwd_tflops=round(fl / tf / 1e9, 1), bwd_tflops=round(2.0 * fl / tb / 1e9, 1))
@@ -230,7 +242,7 @@ def main():
     cus = mb.device_cu_count()
 
     if args.attention_only:
-        print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20)))
+        print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=50)))
         return
     if args.bandwidth_only:
         # plus a plain device copy of known size, so that HBM byte counters of the same run can be scaled
@@ -241,7 +253,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"shape": {"T": Tl, "h": hl, "f": fl}, "gbs": bandwidth_kernels(mb, Tl, hl, fl, reps=20)}))
         return
-    gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=50, warm=50)
+    gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=50, settle_ms=40.0)
     if args.roofline_only:
         # a plain device copy of known size, so that HBM byte counters of the same run can
         # be scaled: 1 GiB read + 1 GiB written per launch
@@ -254,7 +266,7 @@ def main():
                           "tflops": {k: gflops / v / 1e9 for k, v in gms.items()}}))
         return
     bw = bandwidth_kernels(mb, Tl, hl, fl, reps=20)
-    attn = attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20)
+    attn = attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=50)
     pool = None if args.no_pool_bench else stream_pool_latency(mb, cus)
 
     stage = StagedStage(args.config)
