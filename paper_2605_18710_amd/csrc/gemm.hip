@@ -58,9 +58,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-#ifndef GEMM_RPM2
-#define GEMM_RPM2 1
-#endif
 constexpr int NS = 5;             // LDS stages
 constexpr int AHEAD = 4;          // K-tiles between the load cursor and the compute cursor
 
@@ -570,11 +567,10 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     mfmas(fa0, fb0);
     frags(fa0, fb0, nx, 0);              // k-step 0 of the next K-tile
     mfmas(fa1, fb1);
-#ifndef GEMM_NO_SCHED_GROUPS
     {
       constexpr int NM = TM * TN;
       constexpr int NR = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);   // LDS reads per batch
-      constexpr int RPM = (NR + NM - 1) / NM, RPM2 = GEMM_RPM2 * RPM;
+      constexpr int RPM = (NR + NM - 1) / NM;
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -584,10 +580,9 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
 #pragma unroll
       for (int q = 0; q < NM; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q * RPM2 < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM2, 0);   // early: they must land before the barrier
+        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // early: they must land before the barrier
       }
     }
-#endif
     wait_loads(std::integral_constant<int, 2 * NLOADS>{});
     __syncthreads();
     si = si + 1 >= NS ? 0 : si + 1;
