@@ -404,7 +404,9 @@ mosaic_status mosaic_op_rope(void* stream, int32_t quota, int32_t dtype, int32_t
 /* AdamW over n elements: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2;
  * p -= lr * ( (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps) + weight_decay * p ).
  * params, grads in `dtype`; m, v and master (may be NULL) fp32; master, when given, is the
- * value that is updated and params receives its rounding. */
+ * value that is updated and params receives its rounding.  n must be a multiple of 4 and
+ * all buffers 16-byte aligned (MOSAIC_EUNSUPPORTED / MOSAIC_EINVAL otherwise); step counts
+ * from 1. */
 mosaic_status mosaic_op_adamw(void* stream, int32_t quota, int32_t dtype, int64_t n, void* params,
                               const void* grads, float* m, float* v, float* master, float lr,
                               float beta1, float beta2, float eps, float weight_decay,

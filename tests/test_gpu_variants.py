@@ -188,7 +188,7 @@ def test_conv_stem_matches_oracle_and_is_quota_invariant(mb, dtype, B, N, C, h):
     m.destroy()
 
 
-@pytest.mark.parametrize("dtype,n,master", [("f32", 4 * 1031, False), ("bf16", 8 * 4099, False), ("bf16", 8 * 4099, True)])
+@pytest.mark.parametrize("dtype,n,master", [("f32", 4 * 1031, False), ("bf16", 8 * 4099, False), ("bf16", 8 * 4099, True), ("bf16", 4 * 4099, True)])
 def test_adamw_steps(mb, dtype, n, master):
     hp = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.05)
     p0 = quantize(synth.normal(3500, (n,), 0.0, 0.02), dtype)
