@@ -669,7 +669,9 @@ template <int D, int NW>
 mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, bf16* O, float* lse) {
   const int qtiles = (int)ceil_div(N, 32 * NW);
   const int64_t items = (int64_t)B * H * qtiles;
-  const int grid = grid_for(quota, 8 / NW, items);
+  // resident workgroups per CU: two by registers at head size 128; at 64 the forward and dQ
+  // kernels need ~150 registers, so three fit (measured: forward 151 -> 130 us at B8 N1500 H20)
+  const int grid = grid_for(quota, (D == 64 && NW == 4) ? 3 : 8 / NW, items);
   constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
   static bool once = false;
   if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
@@ -690,7 +692,8 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
     constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
     static bool once = false;
     if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
-    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
+    const int gq = grid_for(quota, (D == 64 && NW == 4) ? 3 : 8 / NW, items);   // as in the forward kernel
+    attn_bwd_dq_mfma<D, NW><<<gq, 64 * NW, smem, s>>>(qkv, O, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
     MOSAIC_LAUNCH_CHECK();
   }
   {
