@@ -471,7 +471,10 @@ __global__ __launch_bounds__(kThreads) void mse_final_kernel(const float* __rest
 }
 
 // ------------------------------------------------------------------------------ colsum
-constexpr int kColsumMaxParts = 256;
+// row partitions of a column reduction (a function of the row count alone).  512: two
+// workgroups per CU for the one-pass norm backward (5.1 TB/s at the decoder shape against 4.8
+// with 256; 1024 partitions make the partial sums too much traffic: 4.1)
+constexpr int kColsumMaxParts = 512;
 // widest row (in 16-byte vectors per lane) whose column accumulators the fused norm backward keeps in registers
 constexpr int kNormFusedMaxNV = 8;   // LayerNorm; RMSNorm (one sum per column) also fits at 10
 
