@@ -70,6 +70,26 @@ def test_linear_fwd_dgrad_wgrad(mb, dtype, T, k, n):
             assert np.array_equal(a, b0), "result depends on the quota"
 
 
+@pytest.mark.parametrize("T,k,n", [(2100, 1304, 520), (4096, 2048, 1536), (1000, 520, 4104)])
+def test_linear_dgrad_without_residual_partial_round(mb, T, k, n):
+    """Input gradient with nothing added in the epilogue (the plain store path), at quotas that
+    leave a partial round of large tiles to the quarter-tile launch (ragged edges in the first
+    shape, a long contraction over few tiles in the last); bits must not depend on the quota."""
+    W = quantize(synth.normal(21, (k, n), 0, 0.05), "bf16"); dY = quantize(synth.normal(22, (T, n)), "bf16")
+    W_, dY_ = to_dev(W, "bf16"), to_dev(dY, "bf16")
+    ref_dx, _, _ = O.linear_bwd(np.zeros((T, k)), W, dY)
+    outs = []
+    for q in (256, 24, 40, 8):
+        dX = empty((T, k), "bf16")
+        mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY_, W_, None, dX)
+        torch.cuda.synchronize()
+        outs.append(bits(dX))
+        if q == 256:
+            assert rel_l2(from_dev(dX), ref_dx) <= 2e-2
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0]), "result depends on the quota"
+
+
 def test_linear_without_bias_and_residual_and_empty(mb):
     T, k, n = 70, 64, 72
     X = quantize(synth.normal(7, (T, k)), "bf16"); W = quantize(synth.normal(8, (k, n), 0, 0.05), "bf16")
