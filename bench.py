@@ -150,6 +150,66 @@ def attention_kernels(mb, B, N, H, d, causal, reps):
                 fwd_tflops=round(fl / tf / 1e9, 1), bwd_tflops=round(2.0 * fl / tb / 1e9, 1))
 
 
+def power_probe(mb, seconds=4.0):
+    """Board power and shader clock while the forward GEMM of a 7B-shaped gate/up projection
+    (T=32768, k=4096, n=22016) runs in a loop, on N(0,1) inputs and on constant inputs (no bit
+    toggling in the operands).  Power and clock are read from the driver's sysfs files every
+    0.1 s by a host thread; missing files give nulls."""
+    import glob
+    import threading
+    import torch
+    bf = torch.bfloat16
+    q = mb.device_cu_count()
+    T, k, n = 32768, 4096, 22016
+    X = torch.randn(T, k, device="cuda", dtype=bf)
+    W = (torch.randn(k, n, device="cuda", dtype=torch.float32) * 0.02).to(bf)
+    Y = torch.empty(T, n, device="cuda", dtype=bf)
+    pw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+    cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+    clk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+
+    def read_w(paths):
+        try:
+            return int(open(paths[0]).read()) / 1e6
+        except (OSError, ValueError, IndexError):
+            return None
+
+    def read_mhz():
+        try:
+            for line in open(clk[0]).read().splitlines():
+                if line.strip().endswith("*"):
+                    return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            pass
+        return None
+
+    out = {"shape": [T, k, n], "power_cap_w": read_w(cap)}
+    for label in ("normal", "constant"):
+        if label == "constant":
+            X.fill_(1.0); W.fill_(0.5)
+        watts, mhz, stop = [], [], []
+
+        def poll():
+            while not stop:
+                watts.append(read_w(pw)); mhz.append(read_mhz())
+                time.sleep(0.1)
+        th = threading.Thread(target=poll)
+        th.start()
+        rates = []
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            rates.append(2.0 * T * k * n / time_kernel(lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y), 20, 0) / 1e9)
+        stop.append(1)
+        th.join()
+        half = len(watts) // 2           # the second half of the loop: the controller has settled
+        ws = [w for w in watts[half:] if w is not None]
+        ms = [m for m in mhz[half:] if m is not None]
+        out[label] = {"tflops": round(statistics.median(rates[len(rates) // 2:]), 1),
+                      "power_w": round(statistics.median(ws), 1) if ws else None,
+                      "sclk_mhz": round(statistics.median(ms), 1) if ms else None}
+    return out
+
+
 def stream_pool_latency(mb, cus, repeats=30):
     """Analogue of the paper's stream-pool experiment (Sec. 5.3.1): latency of creating and
     destroying a quota'd stream on demand, for quotas 0.1 .. 0.9 of the device, against
@@ -222,6 +282,7 @@ def main():
     ap.add_argument("--roofline-only", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
     ap.add_argument("--bandwidth-only", action="store_true", help="only the bandwidth-bound kernels at the decoder's shapes (for rocprofv3)")
+    ap.add_argument("--power-only", action="store_true", help="board power and clock under the 7B-shaped forward GEMM, random against constant inputs")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--layer-split", action="store_true",
                     help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
@@ -247,6 +308,9 @@ def main():
 
     if args.attention_only:
         print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=50)))
+        return
+    if args.power_only:
+        print(json.dumps(power_probe(mb)))
         return
     if args.bandwidth_only:
         # plus a plain device copy of known size, so that HBM byte counters of the same run can be scaled
