@@ -120,22 +120,30 @@ struct DmaLoader {
 
   // K-tile kt (absolute index) of tile tl -> operand area `dst` of a stage; zeros when
   // !valid, at or past kt_lim, or outside the matrix (rows past the end fall outside the
-  // descriptor's range)
+  // descriptor's range).  prep() holds what the NI requests of one K-tile share; issue_j()
+  // makes request j, so that the caller can spread the requests over its instruction stream.
+  struct Prep { bool oob; unsigned base; };
+  __device__ __forceinline__ Prep prep(const Tile& tl, int kt, int K, int kt_lim, bool valid) const {
+    Prep p;
+    p.oob = !valid || kt >= kt_lim;
+    if constexpr (KC) p.oob = p.oob || (kt * BK + kofs) >= K;
+    p.base = tl.org + (unsigned)kt * kstep;
+    return p;
+  }
+  __device__ __forceinline__ void issue_j(i32x4 rsrc, const Tile& tl, const Prep& p, int j, unsigned dst) const {
+    const unsigned off = (p.oob || ((tl.oobmask >> j) & 1)) ? kOob : p.base + rel[j];
+    // m0 = LDS byte address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Written as
+    // assembly so that the compiler's wait-count pass does not see an LDS write and put a
+    // full vmcnt(0) in front of every following LDS read; completion is waited for by
+    // hand (wait_loads in the kernel).  The compiler itself never uses m0 in this file.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(rsrc) : "m0");
+  }
   __device__ __forceinline__ void issue(i32x4 rsrc, const Tile& tl, int kt, int K, int kt_lim,
                                         bool valid, unsigned dst) const {
-    bool oob = !valid || kt >= kt_lim;
-    if constexpr (KC) oob = oob || (kt * BK + kofs) >= K;
-    const unsigned base = tl.org + (unsigned)kt * kstep;
+    const Prep p = prep(tl, kt, K, kt_lim, valid);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const unsigned off = (oob || ((tl.oobmask >> j) & 1)) ? kOob : base + rel[j];
-      // m0 = LDS byte address of lane 0's 16 bytes; lane l lands at m0 + 16*l.  Written as
-      // assembly so that the compiler's wait-count pass does not see an LDS write and put a
-      // full vmcnt(0) in front of every following LDS read; completion is waited for by
-      // hand (wait_loads in the kernel).  The compiler itself never uses m0 in this file.
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(rsrc) : "m0");
-    }
+    for (int j = 0; j < NI; ++j) issue_j(rsrc, tl, p, j, dst);
   }
 };
 
@@ -325,13 +333,6 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[j] = frb.read(lds + stage + BM * 64, j, ks);
   };
-  auto mfmas = [&](const bf16x8* fa, const bf16x8* fb) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-  };
   frags(fa0, fb0, 0, 0);
 
   // Epilogue of one work item.  acc[i][j][4g+e] is output (row m0+wm+32i+lr, column
@@ -475,16 +476,16 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   // by (row/2)%8; they leave as whole 128-byte lines, 8 rows per store instruction.
   auto finish_rows = [&](const WorkItem& it, int free_stage, auto mode_) {
     constexpr int MODE = decltype(mode_)::value;
-    static_assert(TN == 2, "row-wide epilogue needs a 64-column wave tile");
+    static_assert(TN % 2 == 0, "row-wide epilogue moves 64-column halves of the wave tile");
     unsigned char* patch = smem + free_stage + wave * 4096;
     int ln = lane;
     asm volatile("" : "+v"(ln));
     const int elr = ln & 31, ehb = ln >> 5;
     // bias of the columns this lane holds in accumulator layout: block j, group g -> 4 values
-    u32x2 braw[MODE == EPI_BIAS ? 2 * 4 : 1] = {};
+    u32x2 braw[MODE == EPI_BIAS ? TN * 4 : 1] = {};
     if constexpr (MODE == EPI_BIAS) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int col = it.n0 + wn + 32 * j + 8 * g + 4 * ehb;
@@ -493,42 +494,45 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     }
     const int wr = elr * 128 + ehb * 8, wsx = (elr >> 1) & 7;
     const int c16 = ln & 7;
-    const int ocol = it.n0 + wn + 8 * c16;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int h = 0; h < TN / 2; ++h) {         // 64-column halves of the wave tile
+        const int ocol = it.n0 + wn + 64 * h + 8 * c16;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 o;
-          bf16x4 bv = {};
-          if constexpr (MODE == EPI_BIAS) bv = __builtin_bit_cast(bf16x4, braw[4 * j + g]);
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float v = acc[i][j][4 * g + e];
-            if constexpr (MODE == EPI_BIAS) v += (float)bv[e];
-            o[e] = (bf16)v;
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 o;
+            bf16x4 bv = {};
+            if constexpr (MODE == EPI_BIAS) bv = __builtin_bit_cast(bf16x4, braw[4 * (2 * h + j) + g]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float v = acc[i][2 * h + j][4 * g + e];
+              if constexpr (MODE == EPI_BIAS) v += (float)bv[e];
+              o[e] = (bf16)v;
+            }
+            *reinterpret_cast<bf16x4*>(patch + wr + (((4 * j + g) ^ wsx) << 4)) = o;
           }
-          *reinterpret_cast<bf16x4*>(patch + wr + (((4 * j + g) ^ wsx) << 4)) = o;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        u32x4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int r = (ln >> 3) + 8 * q;
+          v[q] = *reinterpret_cast<const u32x4*>(patch + r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4));
         }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      u32x4 v[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r = (ln >> 3) + 8 * q;
-        v[q] = *reinterpret_cast<const u32x4*>(patch + r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4));
+        for (int q = 0; q < 4; ++q) {
+          const int row = it.m0 + wm + 32 * i + (ln >> 3) + 8 * q;
+          const unsigned off = (ocol < N) ? (unsigned)(((int64_t)row * ldc + ocol) * 2) : kOob;
+          __builtin_amdgcn_raw_buffer_store_b128(v[q], rc, (int)off, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = it.m0 + wm + 32 * i + (ln >> 3) + 8 * q;
-        const unsigned off = (ocol < N) ? (unsigned)(((int64_t)row * ldc + ocol) * 2) : kOob;
-        __builtin_amdgcn_raw_buffer_store_b128(v[q], rc, (int)off, 0, 0);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -560,31 +564,54 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   // into the stage that was read last step, the current K-tile is multiplied, and before
   // the barrier every wave waits for its own requests of the K-tile two ahead, so that
   // after the barrier that tile is complete for all waves.
+  // Written slot by slot: one MFMA, then at most a fragment read and a request, then a
+  // scheduling barrier that keeps the compiler from regrouping them.  A wave that is alone
+  // on its SIMD has nobody to cover a clump of requests or a wait for a read it has just
+  // issued, so every fragment is read a whole batch of MFMAs before its first use and the
+  // requests are spread over the first batch.
+  // The barrier is the bare instruction.  What it has to order: (1) requests into the
+  // stage read in this step are issued in the next step, after every wave has passed this
+  // barrier, and all reads of that stage feed MFMAs that precede the barrier in program
+  // order (the scheduling barriers keep them there), so those reads have returned;
+  // (2) each wave has waited for its own requests of the K-tile two ahead before it
+  // arrives, so after the barrier that tile is complete.
+  constexpr int NM = TM * TN, NF = TM + TN;
+  auto read_frag = [&](bf16x8* fa, bf16x8* fb, int stage, int ks, int r) {
+    // fragment order: weight-side block 0, the TM activation-side blocks, the other weight-side blocks
+    if (r == 0) fb[0] = frb.read(lds + stage + BM * 64, 0, ks);
+    else if (r <= TM) fa[r - 1] = fra.read(lds + stage, r - 1, ks);
+    else fb[r - TM] = frb.read(lds + stage + BM * 64, r - TM, ks);
+  };
   auto step = [&]() {
     const int rd = stg(0), nx = stg(1), ldst = stg(AHEAD);
-    frags(fa1, fb1, rd, 1);              // k-step 1 of this K-tile
-    issue(ldst);
-    mfmas(fa0, fb0);
-    frags(fa0, fb0, nx, 0);              // k-step 0 of the next K-tile
-    mfmas(fa1, fb1);
-    {
-      constexpr int NM = TM * TN;
-      constexpr int NR = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);   // LDS reads per batch
-      constexpr int RPM = (NR + NM - 1) / NM;
+    const typename LA::Prep pa = la.prep(lta, lkt, K, lit.kt_end, lit.valid);
+    const typename LB::Prep pb = lb.prep(ltb, lkt, K, lit.kt_end, lit.valid);
+    const unsigned dsta = lds0 + (unsigned)ldst, dstb = dsta + BM * 64;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int q = 0; q < NM; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
-        if (q >= NM - 2) __builtin_amdgcn_sched_group_barrier(0x020, (NLOADS + 1) / 2, 0);
-      }
+    for (int q = 0; q < NM; ++q) {
+      const int i = q % TM, j = q / TM;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[j], fa0[i], acc[i][j], 0, 0, 0);
 #pragma unroll
-      for (int q = 0; q < NM; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (q * RPM < NR) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // early: they must land before the barrier
+      for (int r = (q * NF + NM - 1) / NM; r < ((q + 1) * NF + NM - 1) / NM; ++r) read_frag(fa1, fb1, rd, 1, r);   // k-step 1 of this K-tile
+#pragma unroll
+      for (int l = q * NLOADS / NM; l < (q + 1) * NLOADS / NM; ++l) {
+        if (l < LA::NI) la.issue_j(da, lta, pa, l, dsta);
+        else lb.issue_j(db, ltb, pb, l - LA::NI, dstb);
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < NM; ++q) {
+      const int i = q % TM, j = q / TM;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[j], fa1[i], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int r = (q * NF + NM - 1) / NM; r < ((q + 1) * NF + NM - 1) / NM; ++r) read_frag(fa0, fb0, nx, 0, r);   // k-step 0 of the next K-tile
+      __builtin_amdgcn_sched_barrier(0);
     }
     wait_loads(std::integral_constant<int, 2 * NLOADS>{});
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     si = si + 1 >= NS ? 0 : si + 1;
     ++lkt; ++kt;
   };
