@@ -24,7 +24,8 @@
 //     requests of tile t+2.  The stream of K-tiles runs across output tiles, so a new
 //     output tile starts without a pipeline refill.
 //   * fragments are double-buffered in registers: the reads for the next batch of MFMAs
-//     are issued under the current batch (scheduling group barriers fix the interleaving).
+//     are issued under the current batch, one fragment and one request per MFMA slot
+//     (a scheduling barrier after every slot keeps the written order).
 //   * accumulators are kept transposed (the weight-side fragment is MFMA's first operand),
 //     so a lane owns four consecutive output columns per register group; the epilogue
 //     (bias, residual, bf16 rounding) is staged through the free LDS stage into
