@@ -10,6 +10,8 @@ roofline of the dominant kernel and the CPU checker's time on a bounded sample.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
     python bench.py --roofline-only | --attention-only | --bandwidth-only
                                          # only that kernel loop (the commands profiled in profiles/)
+    python bench.py --power-only | --library-only
+                                         # context: board power and clock under the GEMM; the GEMM beside the vendor library
     python bench.py --layer-split        # also the two-stage plan with the decoder cut in time
 """
 from __future__ import annotations
@@ -150,11 +152,13 @@ def attention_kernels(mb, B, N, H, d, causal, reps):
                 fwd_tflops=round(fl / tf / 1e9, 1), bwd_tflops=round(2.0 * fl / tb / 1e9, 1))
 
 
-def power_probe(mb, seconds=4.0):
-    """Board power and shader clock while the forward GEMM of a 7B-shaped gate/up projection
-    (T=32768, k=4096, n=22016) runs in a loop, on N(0,1) inputs and on constant inputs (no bit
-    toggling in the operands).  Power and clock are read from the driver's sysfs files every
-    0.1 s by a host thread; missing files give nulls."""
+def power_probe(mb, seconds=3.0):
+    """Board power and shader clock while a GEMM of the 7B-shaped gate/up projection
+    (T=32768, k=4096, n=22016) runs in a loop: this build's forward form on N(0,1) inputs and
+    on constant inputs (no bit toggling in the operands), its two gradient forms, and, as
+    context, torch.matmul (the vendor library) with the weight stored k x n ("nn") and
+    n x k ("nt").  Power and clock are read from the driver's sysfs files every 0.1 s by a
+    host thread; missing files give nulls."""
     import glob
     import threading
     import torch
@@ -163,7 +167,12 @@ def power_probe(mb, seconds=4.0):
     T, k, n = 32768, 4096, 22016
     X = torch.randn(T, k, device="cuda", dtype=bf)
     W = (torch.randn(k, n, device="cuda", dtype=torch.float32) * 0.02).to(bf)
+    Wt = W.t().contiguous()
+    dY = torch.randn(T, n, device="cuda", dtype=bf)
     Y = torch.empty(T, n, device="cuda", dtype=bf)
+    dX = torch.empty(T, k, device="cuda", dtype=bf)
+    dW = torch.empty(k, n, device="cuda", dtype=bf)
+    ws = torch.empty(max(mb.linear_wgrad_scratch_bytes(T, k, n), 16), dtype=torch.uint8, device="cuda")
     pw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
     cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
     clk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
@@ -183,8 +192,13 @@ def power_probe(mb, seconds=4.0):
             pass
         return None
 
+    fwd = lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y)
+    cases = (("normal", fwd), ("dgrad", lambda: mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY, W, None, dX)),
+             ("wgrad", lambda: mb.op_linear_wgrad(None, q, "bf16", T, k, n, X, dY, dW, None, ws)),
+             ("library_nn", lambda: torch.matmul(X, W, out=Y)), ("library_nt", lambda: torch.matmul(X, Wt.t(), out=Y)),
+             ("constant", fwd))
     out = {"shape": [T, k, n], "power_cap_w": read_w(cap)}
-    for label in ("normal", "constant"):
+    for label, fn in cases:
         if label == "constant":
             X.fill_(1.0); W.fill_(0.5)
         watts, mhz, stop = [], [], []
@@ -198,16 +212,43 @@ def power_probe(mb, seconds=4.0):
         rates = []
         t0 = time.perf_counter()
         while time.perf_counter() - t0 < seconds:
-            rates.append(2.0 * T * k * n / time_kernel(lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y), 20, 0) / 1e9)
+            rates.append(2.0 * T * k * n / time_kernel(fn, 20, 0) / 1e9)
         stop.append(1)
         th.join()
         half = len(watts) // 2           # the second half of the loop: the controller has settled
-        ws = [w for w in watts[half:] if w is not None]
+        ws_ = [w for w in watts[half:] if w is not None]
         ms = [m for m in mhz[half:] if m is not None]
         out[label] = {"tflops": round(statistics.median(rates[len(rates) // 2:]), 1),
-                      "power_w": round(statistics.median(ws), 1) if ws else None,
+                      "power_w": round(statistics.median(ws_), 1) if ws_ else None,
                       "sclk_mhz": round(statistics.median(ms), 1) if ms else None}
     return out
+
+
+def library_compare(mb, reps=50, settle_ms=40.0):
+    """Context only: the forward GEMM of this build beside torch.matmul (the vendor library)
+    on the same N(0,1) inputs, timed the same way, in TFLOP/s.  "nn": weight stored k x n
+    (this build's layout); "nt": weight stored n x k (a layout the boundary does not use)."""
+    import torch
+    bf = torch.bfloat16
+    q = mb.device_cu_count()
+    rows = []
+    for (T, k, n) in ((8192, 2048, 11264), (8192, 2048, 2048), (8192, 5632, 2048), (32768, 4096, 22016),
+                      (4608, 1024, 4096), (4608, 1024, 1024)):
+        X = torch.randn(T, k, device="cuda", dtype=bf)
+        W = (torch.randn(k, n, device="cuda", dtype=torch.float32) * 0.02).to(bf)
+        Wt = W.t().contiguous()
+        Y = torch.empty(T, n, device="cuda", dtype=bf)
+        Y2 = torch.empty(T, n, device="cuda", dtype=bf)
+        fl = 2.0 * T * k * n
+        row = {"T": T, "k": k, "n": n}
+        for name, fn in (("mosaic_fprop", lambda: mb.op_linear_fwd(None, q, "bf16", T, k, n, X, W, None, None, Y)),
+                         ("library_nn", lambda: torch.matmul(X, W, out=Y2)),
+                         ("library_nt", lambda: torch.matmul(X, Wt.t(), out=Y2))):
+            row[name] = round(fl / time_kernel(fn, reps, 3, settle_ms) / 1e9, 1)
+        row["max_abs_diff"] = float((Y.float() - Y2.float()).abs().max())
+        rows.append(row)
+        del X, W, Wt, Y, Y2
+    return rows
 
 
 def stream_pool_latency(mb, cus, repeats=30):
@@ -282,7 +323,8 @@ def main():
     ap.add_argument("--roofline-only", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
     ap.add_argument("--bandwidth-only", action="store_true", help="only the bandwidth-bound kernels at the decoder's shapes (for rocprofv3)")
-    ap.add_argument("--power-only", action="store_true", help="board power and clock under the 7B-shaped forward GEMM, random against constant inputs")
+    ap.add_argument("--power-only", action="store_true", help="board power and clock under the 7B-shaped GEMM: the three forms, constant inputs, and the vendor library as context")
+    ap.add_argument("--library-only", action="store_true", help="context: the forward GEMM beside torch.matmul (vendor library) at six shapes")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--layer-split", action="store_true",
                     help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
@@ -311,6 +353,9 @@ def main():
         return
     if args.power_only:
         print(json.dumps(power_probe(mb)))
+        return
+    if args.library_only:
+        print(json.dumps(library_compare(mb)))
         return
     if args.bandwidth_only:
         # plus a plain device copy of known size, so that HBM byte counters of the same run can be scaled
