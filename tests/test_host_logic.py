@@ -180,3 +180,27 @@ def test_unbound_module_and_null_arguments_are_errors_not_crashes():
     assert l.mosaic_stage_run(None, None, None) == mb.EINVAL
     assert b"null" in l.mosaic_last_error()
     l.mosaic_module_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The stage is a single-GPU construct: asking bench.py for more exits with a message."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_committed_gemm_traffic_parses_and_is_not_below_the_algorithmic_bytes():
+    """bench.py's roofline.traffic comes from the committed counter summary: every form must
+    parse, and HBM-side bytes cannot be below reading each operand and writing the output once."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    T, k, n = 8192, 2048, 11264                      # the roofline shape of configs[1]
+    algorithmic = 2 * (T * k + k * n + T * n)
+    for form in ("fprop", "dgrad", "wgrad"):
+        t = bench.profiled_traffic(form)
+        assert isinstance(t, int) and algorithmic <= t < 8 * algorithmic, (form, t)
