@@ -437,11 +437,33 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
         f32x16 sacc, pacc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+        // The K and V fragments are read two MFMA pairs ahead of their use (the scheduling
+        // barriers keep that distance): read right in front of the MFMA that consumes it, a
+        // fragment costs the wave a full LDS round trip per pair.
+        constexpr int PF = 2;
+        bf16x8 kfr[NS], vfr[NS];
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+          kfr[s] = L::nat(ks, 32 * sub + lr, s, hb);
+          vfr[s] = L::nat(vs, 32 * sub + lr, s, hb);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, 32 * sub + lr, s, hb), qf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(vs, 32 * sub + lr, s, hb), dof[s], pacc, 0, 0, 0);
+          if (s + PF < NS) {
+            kfr[s + PF] = L::nat(ks, 32 * sub + lr, s + PF, hb);
+            vfr[s + PF] = L::nat(vs, 32 * sub + lr, s + PF, hb);
+          }
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[s], dof[s], pacc, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
+        // the transposed K fragments of the first two dQ column blocks are on their way while
+        // the probabilities are formed
+        bf16x8 ta[NC], tb[NC];
+#pragma unroll
+        for (int c = 0; c < (NC < 2 ? NC : 2); ++c) { ta[c] = L::tr(ks, c, 32 * sub); tb[c] = L::tr(ks, c, 32 * sub + 16); }
+        __builtin_amdgcn_sched_barrier(0);
         // only blocks that touch the diagonal or the end of the sequence need the mask: a
         // masked score becomes -inf, so its recomputed probability is exactly 0
         if ((jb + 32 > N) || (i0 + 32 > N) || (causal && jb + 31 > i0)) {
@@ -455,11 +477,18 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
 #pragma unroll
         for (int r = 0; r < 16; ++r) ds[r] = fast_exp2(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
         const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
+        __builtin_amdgcn_sched_barrier(0);
+        // each accumulator takes its two products in the same order as before (k-half 0, then
+        // k-half 1); the halves of different column blocks alternate, so no MFMA waits for
+        // the one issued just before it
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(ks, c, 32 * sub), d0, dq[c], 0, 0, 0);
-          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(ks, c, 32 * sub + 16), d1, dq[c], 0, 0, 0);
+          if (c + 2 < NC) { ta[c + 2] = L::tr(ks, c + 2, 32 * sub); tb[c + 2] = L::tr(ks, c + 2, 32 * sub + 16); }
+          dq[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta[c], d0, dq[c], 0, 0, 0);
+          if (c > 0) dq[c - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tb[c - 1], d1, dq[c - 1], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
+        dq[NC - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tb[NC - 1], d1, dq[NC - 1], 0, 0, 0);
       }
       wait_requests<(PD - 1) * NREQ>();
       __syncthreads();
