@@ -631,6 +631,211 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   wait_loads(std::integral_constant<int, 0>{});
 }
 
+// Both operands K-contiguous (the input-gradient form), K a multiple of 128: 256x256x64 tile,
+// four waves of 128x128 with the accumulators in the accumulator half of the register file.
+// A row of a K-contiguous operand gives a whole 128-byte line per K-tile of 64, so the path
+// to the L2 carries half the requests of the 32-wide K-tiles of the kernel above.  Operand
+// tiles go global -> registers -> LDS: two register sets are in flight (K-tiles kt+1 and kt+2
+// while kt is multiplied), LDS is double buffered, one barrier per K-tile.  Every output
+// element is still accumulated in ascending k with v_mfma_f32_32x32x16_bf16 in steps of 16
+// and rounded once after the same fp32 additions, so its bits equal the other kernel's.
+//   LDS tile: rows of 128 bytes, 16-byte pieces XOR-swizzled by (row/2)%8; a fragment is one
+//   ds_read_b128 per lane (row = lane%32, piece = 2*kstep + lane/32).
+//   Slots: one MFMA each; the fragment reads of the next k-step sit in slots 0..7 of a
+//   k-step, the LDS writes (each followed at once by the request that refills its
+//   registers) in read-free slots of k-steps 0..2; the barrier comes before k-step 3, whose
+//   slots read the first fragments of the next K-tile from the other LDS stage.
+template <bool HAS_R>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
+    const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C, const bf16* __restrict__ R,
+    int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
+    int tiles_m, int tiles_n, int tile_begin, int tile_count) {
+  constexpr int TBM = 256, TBK = 64, OPB = TBM * TBK * 2, STG = 2 * OPB;
+  extern __shared__ __align__(16) unsigned char smem[];
+  lds_byte* const lds = (lds_byte*)smem;
+  typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+  typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int lr = lane & 31, hb = lane >> 5;
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, a_bytes), rb = make_rsrc(B, b_bytes);
+  const __amdgpu_buffer_rsrc_t rc = make_rsrc(C, c_bytes), rr = make_rsrc(R, HAS_R ? c_bytes : 0u);
+  const int nk = K / TBK;                       // even: K is a multiple of 128
+  // this thread's 8 pieces of an operand tile: piece c = tid + 256*i -> tile row tid/8 + 32*i,
+  // 16 bytes tid%8.  The swizzle term (row/2)%8 is the same for all eight (32*i/2 is a
+  // multiple of 8), so one LDS offset serves with immediates 4096*i; likewise for the
+  // fragment rows lr + 32*i.
+  const int grow0 = tid >> 3, gch = tid & 7;
+  const int lwr0 = grow0 * 128 + ((gch ^ ((grow0 >> 1) & 7)) << 4);
+  const int fro0 = lr * 128, frsw = (lr >> 1) & 7;
+  const int G = gridDim.x;
+  for (int round = 0;; ++round) {
+    // same work order as gemm_bf16_kernel: panel-major tile list, contiguous eighths per XCD
+    const int base = round * G;
+    if (base >= tile_count) break;
+    const int cnt = min(G, tile_count - base);
+    int local;
+    if ((G & 7) == 0) {
+      const int per = (cnt + 7) >> 3;
+      local = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+      if (((int)blockIdx.x >> 3) >= per || local >= cnt) break;
+    } else {
+      local = blockIdx.x;
+      if (local >= cnt) break;
+    }
+    const int tile = tile_begin + base + local;
+    const int panel = tile / (tiles_m * 8), pw = min(8, tiles_n - panel * 8), in_panel = tile - panel * tiles_m * 8;
+    const int m0 = (in_panel / pw) * TBM, n0 = (panel * 8 + in_panel % pw) * TBM;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // byte offsets of this thread's pieces at K-tile 0; rows past the end fall outside the
+    // descriptor's range and read zeros
+    const unsigned oa0 = (unsigned)(((int64_t)(m0 + grow0) * lda) * 2 + gch * 16);
+    const unsigned ob0 = (unsigned)(((int64_t)(n0 + grow0) * ldb) * 2 + gch * 16);
+    const unsigned sa = (unsigned)(32 * lda * 2), sb = (unsigned)(32 * ldb * 2);     // 32 rows further
+    // K-tiles past the end are requested too (their registers are never used): the piece
+    // must not alias a valid row of the next K range, so it is sent out of range
+    auto ga_load = [&](int i, int kt) -> u32x4 {
+      return __builtin_amdgcn_raw_buffer_load_b128(ra, kt < nk ? (int)(oa0 + (unsigned)i * sa + (unsigned)kt * (TBK * 2)) : (int)kOob, 0, 0);
+    };
+    auto gb_load = [&](int i, int kt) -> u32x4 {
+      return __builtin_amdgcn_raw_buffer_load_b128(rb, kt < nk ? (int)(ob0 + (unsigned)i * sb + (unsigned)kt * (TBK * 2)) : (int)kOob, 0, 0);
+    };
+    u32x4 ga0[8], gb0[8], ga1[8], gb1[8];
+    bf16x8 fa[2][4], fb[2][4];
+    // prologue: K-tile 0 -> LDS stage 0, K-tile 1 -> register set 0, K-tile 2 -> register set 1
+    __syncthreads();                    // the previous tile's epilogue is done with the LDS
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { ga0[i] = ga_load(i, 0); gb0[i] = gb_load(i, 0); }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<lds_u32x4*>(lds + lwr0 + 4096 * i) = ga0[i];
+      *reinterpret_cast<lds_u32x4*>(lds + OPB + lwr0 + 4096 * i) = gb0[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { ga0[i] = ga_load(i, 1); gb0[i] = gb_load(i, 1); }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { ga1[i] = ga_load(i, 2); gb1[i] = gb_load(i, 2); }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[0][i] = *reinterpret_cast<const lds_bf16x8*>(lds + wm * 128 + fro0 + 4096 * i + ((hb ^ frsw) << 4));
+      fb[0][i] = *reinterpret_cast<const lds_bf16x8*>(lds + OPB + wn * 128 + fro0 + 4096 * i + ((hb ^ frsw) << 4));
+    }
+    auto body = [&](int kt, auto sel_) {
+      constexpr int SEL = decltype(sel_)::value;
+      const int st = kt & 1;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int cur = ks & 1, nxt = cur ^ 1;
+        // K-tile kt+1 is in LDS for everybody and nobody reads stage st after this k-step
+        if (ks == 3) __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int i = q & 3, j = q >> 2;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+          if (q < 8) {
+            // fragments of the next k-step (of the next K-tile's first k-step when ks == 3)
+            const int rs_ = ks < 3 ? st : st ^ 1, rk = ks < 3 ? ks + 1 : 0;
+            if (q < 4) fa[nxt][q] = *reinterpret_cast<const lds_bf16x8*>(lds + rs_ * STG + wm * 128 + fro0 + 4096 * q + (((2 * rk + hb) ^ frsw) << 4));
+            else fb[nxt][q - 4] = *reinterpret_cast<const lds_bf16x8*>(lds + rs_ * STG + OPB + wn * 128 + fro0 + 4096 * (q - 4) + (((2 * rk + hb) ^ frsw) << 4));
+          }
+          if ((ks < 2 && q >= 8 && q < 14) || (ks == 2 && q >= 8 && q < 12)) {
+            // register set SEL (K-tile kt+1) -> the other LDS stage; the freed registers go
+            // straight back out for K-tile kt+3
+            const int w = ks * 6 + (q - 8), i8 = w >> 1;
+            if ((w & 1) == 0) {
+              u32x4& a_ = SEL ? ga1[i8] : ga0[i8];
+              *reinterpret_cast<lds_u32x4*>(lds + (st ^ 1) * STG + lwr0 + 4096 * i8) = a_;
+              a_ = ga_load(i8, kt + 3);
+            } else {
+              u32x4& b_ = SEL ? gb1[i8] : gb0[i8];
+              *reinterpret_cast<lds_u32x4*>(lds + (st ^ 1) * STG + OPB + lwr0 + 4096 * i8) = b_;
+              b_ = gb_load(i8, kt + 3);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+      body(kt, std::integral_constant<int, 0>{});
+      body(kt + 1, std::integral_constant<int, 1>{});
+    }
+    __syncthreads();                    // every wave is done reading fragments: LDS is free
+
+    // Epilogue, one 32x32 block at a time through a 4 KB fp32 patch per wave (XOR swizzled),
+    // leaving row-contiguous; the residual is added in fp32 in that layout, one rounding.
+    // acc[i][j][4g+e] is output (row m0+wm+32i+lr, column n0+wn+32j+8g+4hb+e).
+    {
+      float* patch = reinterpret_cast<float*>(smem) + wave * 1024;
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int elr = ln & 31, ehb = ln >> 5;
+      auto out_off = [&](int b, int q) -> unsigned {
+        const int row = m0 + wm + 32 * (b >> 2) + (ln >> 2) + 16 * q;
+        const int col = n0 + wn + 32 * (b & 3) + 8 * (ln & 3);
+        return (col < N) ? (unsigned)(((int64_t)row * ldc + col) * 2) : kOob;
+      };
+      u32x4 rnext[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+      if constexpr (HAS_R) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(0, q), 0, 0);
+      }
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        const int i = b >> 2, j = b & 3;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int cg = (2 * g + ehb) ^ ((elr >> 1) & 7);
+          float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+          *reinterpret_cast<float4*>(patch + elr * 32 + cg * 4) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float4 v0[2], v1[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int r = (ln >> 2) + 16 * q, c8 = ln & 3, sx = (r >> 1) & 7;
+          v0[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8) ^ sx) * 4));
+          v1[q] = *reinterpret_cast<const float4*>(patch + r * 32 + (((2 * c8 + 1) ^ sx) * 4));
+        }
+        const u32x4 rcur[2] = {rnext[0], rnext[1]};
+        if constexpr (HAS_R) {
+          if (b + 1 < 16) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) rnext[q] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)out_off(b + 1, q), 0, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const bf16x8 rv = __builtin_bit_cast(bf16x8, rcur[q]);
+          const float vals[8] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w, v1[q].x, v1[q].y, v1[q].z, v1[q].w};
+          bf16x8 o;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float v = vals[e];
+            if constexpr (HAS_R) { v += 0.f; v += (float)rv[e]; }   // value + (absent bias) + residual
+            o[e] = (bf16)v;
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rc, (int)out_off(b, q), 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    }
+  }
+}
+
 // out[row][col] = bf16( P[0] + P[1] + ... ) in ascending piece order
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, bf16* __restrict__ C,
                                                             int64_t M, int64_t N, int64_t ldc, int ksplit) {
@@ -746,6 +951,37 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
   return MOSAIC_OK;
 }
 
+// The four-wave kernel for the K-contiguous x K-contiguous form: whole tiles only (sub = 1).
+mosaic_status launch_kc4w(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda, const bf16* B,
+                          int64_t ldb, bf16* C, int64_t ldc, const bf16* R, uint32_t a_bytes, uint32_t b_bytes,
+                          uint32_t c_bytes, int tile_begin, int tile_count) {
+  constexpr size_t smem = 2 * 2 * 256 * 64 * 2;        // two stages of two 256 x 64 operand tiles
+  static bool attr_set = false;
+  if (!attr_set) {
+    MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  const int tiles_m = (int)ceil_div(M, 256), tiles_n = (int)ceil_div(N, 256);
+  if (tile_count < 0) tile_count = tiles_m * tiles_n - tile_begin;
+  if (tile_count <= 0) return MOSAIC_OK;
+  const int grid = grid_for(quota, 1, tile_count);
+  if (R) gemm_bf16_kc4w_kernel<true><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
+                                                             tiles_m, tiles_n, tile_begin, tile_count);
+  else gemm_bf16_kc4w_kernel<false><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
+                                                            tiles_m, tiles_n, tile_begin, tile_count);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+bool kc4w_enabled() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("MOSAIC_GEMM_KC4W"); v = e ? atoi(e) : 1; }
+  return v != 0;
+}
+
 int forced_tile() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("MOSAIC_GEMM_TILE"); v = e ? atoi(e) : 0; }
@@ -799,11 +1035,18 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   int plan = cost256 <= cost128 ? (cost256 <= cost_mix ? 256 : 0) : (cost128 <= cost_mix ? 128 : 0);
   if (forced_tile() == 128 || forced_tile() == 256) plan = forced_tile();
   if (forced_tile() == 1 && whole > 0 && rest > 0) plan = 0;
-  if (plan == 256) return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  // whole 256x256 tiles of the K-contiguous x K-contiguous form go to the four-wave kernel
+  // (its K-tiles are 64 wide and come in pairs; no bias in its epilogue)
+  const bool kc4w = A_KC && B_KC && !bias && (K % 128 == 0) && kc4w_enabled();
+  if (plan == 256) {
+    if (kc4w) return launch_kc4w(s, quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
+    return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  }
   if (plan == 128) return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
   const int head = (int)(whole * quota);
-  mosaic_status st = launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
-                                                             b_bytes, c_bytes, 1, 0, nullptr, 1, 0, head);
+  mosaic_status st = kc4w ? launch_kc4w(s, quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, head)
+                          : launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
+                                                                    b_bytes, c_bytes, 1, 0, nullptr, 1, 0, head);
   if (st != MOSAIC_OK) return st;
   return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
                                                  c_bytes, 1, 0, nullptr, 2, head, (int)rest);
