@@ -90,6 +90,38 @@ def test_linear_dgrad_without_residual_partial_round(mb, T, k, n):
         assert np.array_equal(o, outs[0]), "result depends on the quota"
 
 
+@pytest.mark.parametrize("T,k,n,with_res", [(1000, 504, 384, False), (1000, 504, 384, True), (2048, 1024, 2304, True),
+                                             (777, 264, 128, False)])
+def test_linear_dgrad_four_wave_kernel_matches_the_other_kernels_bit_for_bit(mb, T, k, n, with_res):
+    """Contractions that are a multiple of 128 long send whole 256x256 tiles of the input
+    gradient to the four-wave kernel; the quotas below make the host pick it for all tiles (8),
+    for the whole rounds only (the rest goes to the quarter-tile kernel), or not at all (plans
+    of 128x128 tiles).  Ragged edges in both output dimensions, with and without the residual
+    added in the epilogue; every element against the oracle, and the bits must not depend on
+    which kernel produced them."""
+    W = quantize(synth.normal(31, (k, n), 0, 0.05), "bf16"); dY = quantize(synth.normal(32, (T, n)), "bf16")
+    R = quantize(synth.normal(33, (T, k)), "bf16") if with_res else None
+    W_, dY_ = to_dev(W, "bf16"), to_dev(dY, "bf16")
+    R_ = to_dev(R, "bf16") if with_res else None
+    ref_dx, _, _ = O.linear_bwd(np.zeros((T, k)), W, dY)
+    if with_res:
+        ref_dx = ref_dx + R
+    outs = []
+    for q in (8, 16, 3, 256, 40):
+        dX = empty((T, k), "bf16")
+        mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY_, W_, R_, dX)
+        torch.cuda.synchronize()
+        outs.append(bits(dX))
+        if q == 8:
+            got = from_dev(dX)
+            assert rel_l2(got, ref_dx) <= 2e-2
+            # element by element: one bf16 rounding of an fp32 sum of n products
+            tol = 2.0 ** -7 * np.abs(ref_dx) + 1e-2 * np.sqrt(n) * 0.05
+            assert np.all(np.abs(got - ref_dx) <= tol)
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0]), "result depends on the quota"
+
+
 def test_linear_without_bias_and_residual_and_empty(mb):
     T, k, n = 70, 64, 72
     X = quantize(synth.normal(7, (T, k)), "bf16"); W = quantize(synth.normal(8, (k, n), 0, 0.05), "bf16")
