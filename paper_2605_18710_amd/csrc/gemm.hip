@@ -1,12 +1,14 @@
 // Linear-layer contractions (forward, input gradient, weight gradient) for gfx950.
 //
-// bf16 path: persistent MFMA kernel.  A workgroup of 8 waves (256x256 tile, 128x64 per
-// wave) or 4 waves (128x128 tile, 64x64 per wave) walks output tiles;
+// bf16 path: persistent MFMA kernels.  gemm_bf16_kernel serves every form: a workgroup of 8
+// waves (256x256 tile, 128x64 per wave) or 4 waves (128x128 tile, 64x64 per wave) walks
+// output tiles; gemm_bf16_kc4w_kernel (described at its definition) takes the whole 256x256
+// tiles of the form with both operands K-contiguous.  In both,
 // the grid is sized to the module's CU quota.  Each output element is produced by exactly
 // one wave that accumulates k in ascending order with v_mfma_f32_32x32x16_bf16, so the
 // bits of the result do not depend on the grid, the tile shape, the tile order or the CU.
 //
-// Data movement
+// Data movement (gemm_bf16_kernel)
 //   * HBM -> LDS directly (buffer_load ... lds): no register staging and no LDS write
 //     instructions.  A wave instruction fills 1 KB of consecutive LDS; each lane chooses
 //     which 16 bytes of the tile it requests, which realises the bank swizzle.  The
