@@ -325,6 +325,8 @@ def main():
     ap.add_argument("--bandwidth-only", action="store_true", help="only the bandwidth-bound kernels at the decoder's shapes (for rocprofv3)")
     ap.add_argument("--power-only", action="store_true", help="board power and clock under the 7B-shaped GEMM: the three forms, constant inputs, and the vendor library as context")
     ap.add_argument("--library-only", action="store_true", help="context: the forward GEMM beside torch.matmul (vendor library) at six shapes")
+    ap.add_argument("--plan", default=None, help="comma-separated CU quotas, one per group: time this plan instead of the best measured one "
+                    "(under rocprofv3 the measured ranking of plans is distorted)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--layer-split", action="store_true",
                     help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
@@ -420,6 +422,9 @@ def main():
     plans = [list(p) for p in wl["plans"]]
     if chosen not in plans:
         plans.append(chosen)
+    forced = [int(x) for x in args.plan.split(",")] if args.plan else None
+    if forced is not None and forced not in plans:
+        plans.append(forced)
     results = []
     for p in plans:
         # Only the streams of the plan under test are alive: every masked stream owns a
@@ -431,6 +436,8 @@ def main():
         r = median_run(p, mb.COLOCATED)
         results.append(dict(plan=p, stage_ms=r["stage_ms"], module_ms=r["module_ms"]))
     best = min(results, key=lambda r: r["stage_ms"])
+    if forced is not None:
+        best = [r for r in results if r["plan"] == forced][0]
     mb.pool_clear()
     stage.reserve(best["plan"])
 
