@@ -60,6 +60,36 @@ def test_random_linear_shapes(mb):
         assert all(np.array_equal(a, b0) for a, b0 in zip(outs[0], outs[1])), info
 
 
+def test_random_input_gradient_shapes_with_contractions_of_whole_128s(mb):
+    """The input gradient has a kernel of its own for contractions that are a multiple of 128
+    long; which tiles it computes depends on the quota.  Random output shapes (ragged in both
+    dimensions), with and without the residual, four quotas each including tiny ones: every
+    element against the CPU checker, bits identical across the quotas."""
+    rng = random.Random(4242)
+    for it in range(12):
+        T = rng.choice([8, 100, 257, 600, 1000, 1568, 2100, 4096]) + 8 * rng.randrange(0, 4)
+        k = 8 * rng.randrange(1, 160); n = 128 * rng.randrange(1, 24)
+        use_r = rng.random() < 0.5
+        W = quantize(synth.normal(200 + it, (k, n), 0, 0.05), "bf16"); dY = quantize(synth.normal(500 + it, (T, n)), "bf16")
+        R = quantize(synth.normal(400 + it, (T, k)), "bf16")
+        W_, dY_, R_ = [to_dev(a, "bf16") for a in (W, dY, R)]
+        ref_dx, _, _ = O.linear_bwd(np.zeros((T, k)), W, dY)
+        if use_r:
+            ref_dx = ref_dx + R
+        outs = []
+        for q in rng.sample(QS + [3, 1], 4):
+            dX = empty((T, k))
+            mb.op_linear_dgrad(None, q, "bf16", T, k, n, dY_, W_, R_ if use_r else None, dX)
+            torch.cuda.synchronize()
+            outs.append(bits(dX))
+        info = (T, k, n, use_r)
+        got = from_dev(dX)
+        assert rel_l2(got, ref_dx) <= 2e-2, info
+        # one bf16 rounding of an fp32 sum of n products of N(0,1) and N(0,0.05^2) values
+        assert np.all(np.abs(got - ref_dx) <= 2.0 ** -7 * np.abs(ref_dx) + 1e-2 * np.sqrt(n) * 0.05), info
+        assert all(np.array_equal(o, outs[0]) for o in outs[1:]), info
+
+
 def test_random_attention_shapes(mb):
     rng = random.Random(18711)
     for it in range(12):
