@@ -1030,16 +1030,18 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
     constexpr double pen = (A_KC && B_KC) ? 1.3 : (!A_KC && !B_KC) ? 1.8 : 1.45;
     return (double)full * 2.0 * pen + (rem == 0 ? 0.0 : rem <= quota ? 1.2 * pen : 2.0 * pen);
   };
+  // whole 256x256 tiles of the K-contiguous x K-contiguous form go to the four-wave kernel
+  // (its K-tiles are 64 wide and come in pairs; no bias in its epilogue); a round of it takes
+  // about 3.7 units where the eight-wave kernel takes 4
+  const bool kc4w = A_KC && B_KC && !bias && (K % 128 == 0) && kc4w_enabled();
+  const double round256 = kc4w ? 3.7 : 4.0;
   const int64_t whole = t256 / quota, rest = t256 % quota;
-  const double cost256 = (double)ceil_div(t256, quota) * 4.0;
+  const double cost256 = (double)ceil_div(t256, quota) * round256;
   const double cost128 = cost_small(t128);
-  const double cost_mix = (whole > 0 && rest > 0) ? (double)whole * 4.0 + cost_small(4 * rest) + 0.15 : 1e30;
+  const double cost_mix = (whole > 0 && rest > 0) ? (double)whole * round256 + cost_small(4 * rest) + 0.15 : 1e30;
   int plan = cost256 <= cost128 ? (cost256 <= cost_mix ? 256 : 0) : (cost128 <= cost_mix ? 128 : 0);
   if (forced_tile() == 128 || forced_tile() == 256) plan = forced_tile();
   if (forced_tile() == 1 && whole > 0 && rest > 0) plan = 0;
-  // whole 256x256 tiles of the K-contiguous x K-contiguous form go to the four-wave kernel
-  // (its K-tiles are 64 wide and come in pairs; no bias in its epilogue)
-  const bool kc4w = A_KC && B_KC && !bias && (K % 128 == 0) && kc4w_enabled();
   if (plan == 256) {
     if (kc4w) return launch_kc4w(s, quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
     return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
