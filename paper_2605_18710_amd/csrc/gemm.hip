@@ -978,12 +978,16 @@ mosaic_status launch_kc4w(hipStream_t s, int quota, int M, int N, int K, const b
   return MOSAIC_OK;
 }
 
+// MOSAIC_GEMM_KC4W=0 sends the input-gradient form back to the eight-wave kernel (for A/B
+// timing; the bits are the same either way).  Read once per process.
 bool kc4w_enabled() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("MOSAIC_GEMM_KC4W"); v = e ? atoi(e) : 1; }
   return v != 0;
 }
 
+// MOSAIC_GEMM_TILE=256 / 128 forces the tile plan, 1 forces the mixed plan where there is a
+// partial round (for A/B timing; the bits are the same for every plan).  Read once per process.
 int forced_tile() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("MOSAIC_GEMM_TILE"); v = e ? atoi(e) : 0; }
