@@ -712,17 +712,18 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
     };
     u32x4 ga0[8], gb0[8], ga1[8], gb1[8];
     bf16x8 fa[2][4], fb[2][4];
-    // prologue: K-tile 0 -> LDS stage 0, K-tile 1 -> register set 0, K-tile 2 -> register set 1
+    // prologue: K-tile 0 -> register set 1 -> LDS stage 0 and K-tile 1 -> register set 0 are
+    // requested together (one round trip, not two), then K-tile 2 -> register set 1
     __syncthreads();                    // the previous tile's epilogue is done with the LDS
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { ga0[i] = ga_load(i, 0); gb0[i] = gb_load(i, 0); }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<lds_u32x4*>(lds + lwr0 + 4096 * i) = ga0[i];
-      *reinterpret_cast<lds_u32x4*>(lds + OPB + lwr0 + 4096 * i) = gb0[i];
-    }
+    for (int i = 0; i < 8; ++i) { ga1[i] = ga_load(i, 0); gb1[i] = gb_load(i, 0); }
 #pragma unroll
     for (int i = 0; i < 8; ++i) { ga0[i] = ga_load(i, 1); gb0[i] = gb_load(i, 1); }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<lds_u32x4*>(lds + lwr0 + 4096 * i) = ga1[i];
+      *reinterpret_cast<lds_u32x4*>(lds + OPB + lwr0 + 4096 * i) = gb1[i];
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) { ga1[i] = ga_load(i, 2); gb1[i] = gb_load(i, 2); }
     __syncthreads();
