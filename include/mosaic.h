@@ -365,6 +365,20 @@ mosaic_status mosaic_op_norm_bwd(void* stream, int32_t quota, int32_t dtype, int
                                  const float* stats, const void* dy, const void* R,
                                  void* dx, void* dgamma, void* dbeta, void* scratch);
 size_t        mosaic_op_norm_bwd_scratch_bytes(int64_t h);
+/* The same operation for callers that cannot allocate device memory or bring a scratch buffer
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * kernels, same bits, but the partial column sums live in a 20 MiB array built into the
+ * library's device code (one copy per GPU, held until the process ends), so the call allocates
+ * nothing.  Rows of up to mosaic_op_norm_bwd_static_max_h() = 5120 elements; wider rows return
+ * MOSAIC_EUNSUPPORTED before anything is launched.  Nothing in the array has to start at zero
+ * (every partial sum that is read has been written by the same call).  All calls on one GPU
+ * share the array: calls that overlap in time on one GPU (different streams) race; calls on one
+ * stream, or otherwise ordered, are safe. */
+mosaic_status mosaic_op_norm_bwd_static(void* stream, int32_t quota, int32_t dtype, int32_t norm,
+                                        int64_t T, int64_t h, const void* x, const void* gamma,
+                                        const float* stats, const void* dy, const void* R,
+                                        void* dx, void* dgamma, void* dbeta);
+size_t        mosaic_op_norm_bwd_static_max_h(void);
 
 /* a = gelu(z) ; dz = da * gelu'(z)   (exact erf form), elementwise over n elements. */
 mosaic_status mosaic_op_gelu_fwd(void* stream, int32_t quota, int32_t dtype, int64_t n,

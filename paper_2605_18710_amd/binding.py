@@ -118,6 +118,8 @@ SIGNATURES = {
     "mosaic_op_norm_fwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _f32, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_norm_bwd_scratch_bytes": (_sz, [_i64]),
     "mosaic_op_norm_bwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mosaic_op_norm_bwd_static": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mosaic_op_norm_bwd_static_max_h": (_sz, []),
     "mosaic_op_gelu_fwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp]),
     "mosaic_op_gelu_bwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp]),
     "mosaic_op_gelu_tanh_fwd": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp]),
@@ -499,6 +501,15 @@ def op_norm_fwd(stream, quota, dtype, norm, T, h, eps, x, gamma, beta, y, stats)
 def op_norm_bwd(stream, quota, dtype, norm, T, h, x, gamma, stats, dy, R, dx, dgamma, dbeta, scratch):
     check(lib().mosaic_op_norm_bwd(stream, quota, _dt(dtype), _NORM[norm], T, h, _ptr(x), _ptr(gamma), _ptr(stats), _ptr(dy),
                                    _ptr(R), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(scratch)))
+
+
+def op_norm_bwd_static(stream, quota, dtype, norm, T, h, x, gamma, stats, dy, R, dx, dgamma, dbeta):
+    check(lib().mosaic_op_norm_bwd_static(stream, quota, _dt(dtype), _NORM[norm], T, h, _ptr(x), _ptr(gamma), _ptr(stats),
+                                          _ptr(dy), _ptr(R), _ptr(dx), _ptr(dgamma), _ptr(dbeta)))
+
+
+def norm_bwd_static_max_h() -> int:
+    return int(lib().mosaic_op_norm_bwd_static_max_h())
 
 
 def op_gelu_fwd(stream, quota, dtype, n, z, a):

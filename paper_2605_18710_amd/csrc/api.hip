@@ -1,5 +1,6 @@
 // C-ABI wrappers of the single operations, and the dispatch between the MFMA attention
 // kernels and the plain FMA ones.
+#include <mutex>
 #include "kernels.h"
 
 mosaic_status launch_attention_fwd_simple(hipStream_t s, int quota, int dtype, int B, int N, int H, int Hkv, int d,
@@ -148,6 +149,49 @@ mosaic_status mosaic_op_norm_bwd(void* stream, int32_t quota, int32_t dtype, int
   if (norm == MOSAIC_LAYERNORM) NONNULL(dbeta);
   if (T < 0 || h <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm sizes");
   return launch_norm_bwd((hipStream_t)stream, quota, dtype, norm, T, h, x, gamma, stats, dy, R, dx, dgamma, dbeta, scratch);
+}
+
+// Scratch of the entry point for callers that cannot allocate: the partial column sums of the
+// norm backward for rows of up to kStaticNormMaxH elements.  Each GPU holds its own copy of the
+// array at its own address; host code never uses the array's name as an address, only the
+// pointer that hipGetSymbolAddress returned with that GPU current.
+constexpr int64_t kStaticNormMaxH = 5120;
+constexpr size_t kStaticScratchBytes = (size_t)512 * 2 * kStaticNormMaxH * sizeof(float);   // 20 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static mosaic_status static_scratch_ptr(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = 0;
+  MOSAIC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "device index %d beyond the %d this table holds", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    MOSAIC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) MOSAIC_FAIL(MOSAIC_EHIP, "hipGetSymbolAddress returned a null address");
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return MOSAIC_OK;
+}
+
+size_t mosaic_op_norm_bwd_static_max_h(void) { return (size_t)kStaticNormMaxH; }
+
+mosaic_status mosaic_op_norm_bwd_static(void* stream, int32_t quota, int32_t dtype, int32_t norm, int64_t T, int64_t h,
+                                        const void* x, const void* gamma, const float* stats, const void* dy,
+                                        const void* R, void* dx, void* dgamma, void* dbeta) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  NONNULL(x); NONNULL(gamma); NONNULL(stats); NONNULL(dy); NONNULL(dx); NONNULL(dgamma);
+  if (norm == MOSAIC_LAYERNORM) NONNULL(dbeta);
+  if (T < 0 || h <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm sizes");
+  if (h > kStaticNormMaxH || norm_bwd_scratch_bytes(h) > kStaticScratchBytes)
+    MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "row width %lld exceeds the %lld elements the built-in scratch covers; "
+                "use mosaic_op_norm_bwd with a caller-provided scratch", (long long)h, (long long)kStaticNormMaxH);
+  void* sc = nullptr;
+  MOSAIC_TRY(static_scratch_ptr(&sc));
+  return launch_norm_bwd((hipStream_t)stream, quota, dtype, norm, T, h, x, gamma, stats, dy, R, dx, dgamma, dbeta, sc);
 }
 
 mosaic_status mosaic_op_gelu_fwd(void* stream, int32_t quota, int32_t dtype, int64_t n, const void* z, void* a) {
