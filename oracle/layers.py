@@ -516,6 +516,34 @@ def split_tokens(d, B, n_img, n_txt):
     return di, dt
 
 
+def concat_tokens_counts(img_tok, txt_rows, B, n_img, N, counts):
+    """Per-sample image-token counts (reading: the workload draws them per sample while the
+    sequence length stays fixed; the paper pads or truncates every module input to a uniform
+    length, Sec. 3.5).  Sample b takes rows [0, counts[b]) from the first counts[b] of its n_img
+    projected image tokens and rows [counts[b], N) from txt_rows, which holds one row per
+    sequence position (the embedding of the id at that position)."""
+    h = img_tok.shape[1]
+    out = np.zeros((B * N, h), dtype=img_tok.dtype)
+    for b in range(B):
+        nb = int(counts[b])
+        out[b * N:b * N + nb] = img_tok[b * n_img:b * n_img + nb]
+        out[b * N + nb:(b + 1) * N] = txt_rows[b * N + nb:(b + 1) * N]
+    return out
+
+
+def split_tokens_counts(d, B, n_img, N, counts):
+    """Transpose of concat_tokens_counts: image tokens that were not used and sequence
+    positions that were filled by image tokens receive zero gradient."""
+    h = d.shape[1]
+    di = np.zeros((B * n_img, h), dtype=d.dtype)
+    dt = np.zeros((B * N, h), dtype=d.dtype)
+    for b in range(B):
+        nb = int(counts[b])
+        di[b * n_img:b * n_img + nb] = d[b * N:b * N + nb]
+        dt[b * N + nb:(b + 1) * N] = d[b * N + nb:(b + 1) * N]
+    return di, dt
+
+
 # ------------------------------------------------------------------------------ chain
 
 

@@ -261,6 +261,27 @@ def test_concat_split_roundtrip():
     assert np.array_equal(a, a2) and np.array_equal(b, b2)
 
 
+def test_concat_split_with_per_sample_image_token_counts():
+    """Written-out case: 2 samples, 3 image tokens each, sequence 5, counts (1, 3)."""
+    n_img, N, h = 3, 5, 2
+    img = np.arange(2 * n_img * h, dtype=np.float64).reshape(2 * n_img, h) + 100.0
+    txt = np.arange(2 * N * h, dtype=np.float64).reshape(2 * N, h) + 500.0       # one row per sequence position
+    c = O.concat_tokens_counts(img, txt, 2, n_img, N, [1, 3])
+    want = np.stack([img[0], txt[1], txt[2], txt[3], txt[4],            # sample 0: one image token, four text rows
+                     img[3], img[4], img[5], txt[8], txt[9]])           # sample 1: three image tokens, two text rows
+    assert np.array_equal(c, want)
+    # with every count at n_img it is the plain concatenation of the image tokens and the last N - n_img positions
+    full = O.concat_tokens_counts(img, txt, 2, n_img, N, [3, 3])
+    plain = O.concat_tokens(img, np.concatenate([txt[3:5], txt[8:10]]), 2, n_img, N - n_img)
+    assert np.array_equal(full, plain)
+    # the split is the transpose: <concat(a, b), d> == <a, di> + <b, dt> for any d
+    d = synth.normal(67, (2 * N, h))
+    di, dt = O.split_tokens_counts(d, 2, n_img, N, [1, 3])
+    assert abs((c * d).sum() - ((img * di).sum() + (txt * dt).sum())) < 1e-9
+    assert not di[1:3].any() and not dt[0].any() and not dt[5:8].any()     # unused image tokens, image positions
+    assert np.array_equal(di[0], d[0]) and np.array_equal(dt[1:5], d[1:5]) and np.array_equal(di[3:6], d[5:8])
+
+
 # ------------------------------------------------------------------- stage semantics
 def test_stage_time_semantics():
     assert O.time_sliced([3.0, 4.5]) == 7.5      # Eq. 1
