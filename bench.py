@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the multiplexed stage on one MI355X.
 
-A step is one forward+backward of every module of the stage (all hot-path kernels) over
-one batch of synthetic input, run colocated under the best measured quota plan.  The
-same stage is also run time-sliced (every module alone on all CUs, one after another);
-the line printed at the end carries both, the per-module MFMA utilisation at quota, the
-roofline of the dominant kernel and the CPU checker's time on a bounded sample.
+A step is one forward+backward of every module of the workload (all hot-path kernels) over
+one batch of synthetic input, run under the best measured plan: stages one after another,
+the modules of a stage side by side on disjoint CU quotas.  The same modules are also run
+time-sliced (every module alone on all CUs, one after another); the line printed at the
+end carries both, every plan that was measured, the per-module MFMA utilisation at quota,
+the roofline of the dominant kernel and the CPU checker's time on a bounded sample.  The
+default workload is the largest one that fits one GPU (vision + audio + 7B-shaped decoder);
+the CLIP-B / small-LM workload is reported beside it under "secondary".
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--secondary 1]
     python bench.py --roofline-only | --attention-only | --bandwidth-only
                                          # only that kernel loop (the commands profiled in profiles/)
     python bench.py --power-only | --library-only
@@ -60,12 +63,18 @@ def time_kernel(fn, reps, warm=3, settle_ms=0.0):
     return e0.elapsed_time(e1) / reps
 
 
-def profiled_traffic(form):
-    """HBM bytes per launch of the roofline kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size); None if the summary is absent."""
-    path = os.path.join(ROOT, "profiles", "gemm_bf16_kernel_roofline_config2.txt")
+PROFILE_OF_SHAPE = {(8192, 2048, 11264): "gemm_bf16_kernel_roofline_config2.txt",
+                    (32768, 4096, 22016): "gemm_bf16_kernel_roofline_7b_shape.txt"}
+
+
+def profiled_traffic(form, shape):
+    """HBM bytes per launch of the roofline kernel, from the committed rocprofv3 --pmc summary of
+    that shape (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size); None if there is none."""
+    name = PROFILE_OF_SHAPE.get(tuple(shape))
+    if name is None:
+        return None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("traffic_bytes_per_launch:"):
                 vals = dict(kv.split("=") for kv in line.split(":", 1)[1].split())
                 return int(vals[form])
@@ -273,12 +282,13 @@ def stream_pool_latency(mb, cus, repeats=30):
                 quotas="0.1..0.9 of the CUs, %d repeats each" % repeats)
 
 
-def cpu_baseline(wl):
+def cpu_baseline(wl, budget_tflop=6.0):
     """The CPU checker as it stands, timed on this host on a bounded sample of the same
-    workload: a few layers of every encoder and decoder at full batch, forward+backward in
-    float64 (about 10 s for the default workload), extrapolated to the whole stage by the
-    layer count.  Reported, not a target."""
-    import numpy as np
+    workload: one layer of every encoder and decoder, forward+backward in float64, at full
+    sequence length and hidden sizes, on as many samples of the batch as fit in about
+    `budget_tflop` of arithmetic per module (all of them for the small modules, one or two for a
+    7B-shaped decoder layer); the stage time is extrapolated as sample time x (batch / sampled
+    batch) x layers.  Reported, not a target."""
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from oracle import layers as O
     from paper_2605_18710_amd import synth
@@ -294,24 +304,238 @@ def cpu_baseline(wl):
         if m["kind"] == "projector":
             continue
         cfg = dict(m)
-        T, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
-        # bounded: at most four layers, and none is started once the module has cost 5 s
-        done, spent = 0, 0.0
+        per_sample = synth.module_flops(dict(cfg, batch=1, layers=1))
+        b = int(max(1, min(cfg["batch"], budget_tflop * 1e12 // per_sample)))
+        cfg["batch"] = b
+        T, h = b * cfg["seq"], cfg["hidden"]
         x = synth.normal(124, (T, h)); dy = synth.normal(125, (T, h))
-        while done < min(m["layers"], 4) and (done == 0 or spent < 5.0):
-            p = layer_params(cfg, 123 + 100 * done, perturb=False)
-            t0 = time.perf_counter()
-            y, saved = O.layer_fwd(x, p, cfg)
-            O.layer_bwd(dy, p, saved, cfg)
-            spent += time.perf_counter() - t0
-            done += 1
-            x = y
-        total += spent * m["layers"] / done
-        parts.append(f"{m['name']}: {done} of {m['layers']} layers at batch {cfg['batch']} in {spent:.2f}s")
+        p = layer_params(cfg, 123, perturb=False)
+        t0 = time.perf_counter()
+        y, saved = O.layer_fwd(x, p, cfg)
+        O.layer_bwd(dy, p, saved, cfg)
+        spent = time.perf_counter() - t0
+        total += spent * (m["batch"] / b) * m["layers"]
+        parts.append(f"{m['name']}: 1 of {m['layers']} layers at batch {b} of {m['batch']} in {spent:.2f}s")
     B = wl["modules"][0]["batch"]
     return dict(value=round(B / total, 5), unit="samples/s", cores=int(cores), kind="oracle",
                 sample="float64 numpy forward+backward; " + "; ".join(parts) +
-                       "; stage time extrapolated as sum(time per sampled layer x layers), projector omitted")
+                       "; stage time extrapolated as sum(sample time x batch/sampled batch x layers), projector omitted")
+
+
+def candidate_quotas(t_full_ms, t_budget_ms, cus, lo=8, step=8, max_points=10):
+    """Quotas at which a module is worth measuring alone: multiples of `step` from the smallest at
+    which it could still finish within t_budget_ms if its time scaled as 1/CUs, up to what the
+    other modules leave; thinned to at most max_points, keeping the ends."""
+    q_min = max(lo, int(t_full_ms * cus / t_budget_ms) // step * step)
+    qs = list(range(q_min, cus, step))
+    if len(qs) > max_points:
+        keep = {qs[0], qs[-1]}
+        stride = (len(qs) - 1) / (max_points - 1)
+        keep |= {qs[int(round(i * stride))] for i in range(max_points)}
+        qs = sorted(keep)
+    return qs
+
+
+def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=False, fine=True):
+    """Builds the staged workload `config`, measures the time-sliced baseline, the time-vs-CU
+    curves, every named plan plus the plans derived from the curves (three-way, two modules
+    sharing a quota, and the planner's stages), then times `steps` iterations of the best one."""
+    import torch
+    from paper_2605_18710_amd.workload import StagedStage
+    wl = synth.WORKLOADS[config]
+    cus = mb.device_cu_count()
+    stage = StagedStage(config)
+    B = stage.batch
+    flops = stage.flops()
+    names = stage.names
+    ngroups = len(stage.groups)
+    gflop = [sum(flops[n] for n in g) for g in stage.groups]
+    gidx = [[i for i, n in enumerate(names) if n in g] for g in stage.groups]
+    s = stage.staged
+    med = statistics.median
+
+    def run_groups(groups, quotas, offsets, mode):
+        """One stage: the modules of `groups` (group indices), group g on (quotas[g], offsets[g])."""
+        idx = [i for g in groups for i in gidx[g]]
+        qs = [quotas[groups.index(stage.group_of(names[i]))] for i in idx]
+        os_ = [offsets[groups.index(stage.group_of(names[i]))] for i in idx]
+        r = mb.stage_run([s[i].module for i in idx], [s[i].x for i in idx], [s[i].y for i in idx], qs, os_, mb.STRIPED, mode,
+                         dy=[s[i].dy for i in idx], target=[s[i].target for i in idx],
+                         dx=[s[i].dx for i in idx], loss=[s[i].loss for i in idx])
+        per_group = [sum(r["module_ms"][k] for k, i in enumerate(idx) if i in gidx[g]) for g in groups]
+        return r["stage_ms"], per_group
+
+    def reserve(plan):
+        """Only the streams of the plan under test are alive: every masked stream owns a hardware
+        queue, the process has few of them, and streams that share one run one after the other."""
+        mb.pool_clear()
+        for st in plan["stages"]:
+            for q, o in set(zip(st["quotas"], st["offsets"])):
+                mb.pool_reserve(q, o, mb.STRIPED)
+
+    def run_plan(plan):
+        """One iteration: the plan's stages one after another (Eq. 1), each colocated (Eq. 4)."""
+        tot, per_group = 0.0, [0.0] * ngroups
+        for st in plan["stages"]:
+            mode = mb.COLOCATED if len(st["groups"]) > 1 else mb.TIME_SLICED
+            ms, pg = run_groups(st["groups"], st["quotas"], st["offsets"], mode)
+            tot += ms
+            for g, v in zip(st["groups"], pg):
+                per_group[g] = v
+        return tot, per_group
+
+    def median_plan(plan, iters):
+        reserve(plan)
+        run_plan(plan)
+        rs = [run_plan(plan) for _ in range(iters)]
+        return med(r[0] for r in rs), [med(r[1][g] for r in rs) for g in range(ngroups)]
+
+    def pack(quotas):
+        """Offsets for quotas that share the device: the largest quota starts at CU 0 (a CU range
+        that starts at a multiple of 32 spreads over an XCD's shader engines in the order the
+        dispatcher fills them, so all of its CUs are used at once; the small quotas at the top
+        of the device are short enough not to care)."""
+        offs, o = [0] * len(quotas), 0
+        for i in sorted(range(len(quotas)), key=lambda i: -quotas[i]):
+            offs[i] = o
+            o += quotas[i]
+        return offs
+
+    def packed(quotas, label):
+        return dict(label=label, stages=[dict(groups=list(range(ngroups)), quotas=list(quotas), offsets=pack(quotas))])
+
+    # time-sliced baseline: every module alone on all CUs, back to back (sum over stages, Eq. 1)
+    ts_plan = dict(label="time-sliced", stages=[dict(groups=[g], quotas=[cus], offsets=[0]) for g in range(ngroups)])
+    ts_ms, group_ms_full = median_plan(ts_plan, 5)
+
+    # time-vs-CU curves on multiples of 8 CUs, each module where it could still be useful
+    grid = list(range(8, cus, 8))
+    curves = [[1e30] * len(grid) for _ in range(ngroups)]
+    for g in range(ngroups):
+        for q in candidate_quotas(group_ms_full[g], 1.25 * ts_ms, cus) if fine else [q for q in range(32, cus, 32)]:
+            one = dict(label="curve", stages=[dict(groups=[g], quotas=[q], offsets=[0])])
+            curves[g][grid.index(q)] = median_plan(one, 2)[0]
+    chosen, predicted = mb.plan_choose(grid, curves, cus)
+
+    plans = [packed(p, "named") for p in wl["plans"]]
+    plans.append(packed(chosen, "chosen from the curves (Eq. 4-5)"))
+    if fine and ngroups == 3:
+        # the two small modules share one quota and run back to back beside the large one
+        best = None
+        for qi, q in enumerate(grid):
+            if curves[0][qi] < 1e29 and curves[1][qi] < 1e29 and curves[2][grid.index(cus - q)] < 1e29 if (cus - q) in grid else False:
+                t = max(curves[0][qi] + curves[1][qi], curves[2][grid.index(cus - q)])
+                if best is None or t < best[0]:
+                    best = (t, q)
+        if best:
+            q = best[1]
+            plans.append(dict(label="small modules share a quota", predicted_ms=round(best[0], 4),
+                              stages=[dict(groups=[0, 1, 2], quotas=[q, q, cus - q], offsets=[cus - q, cus - q, 0])]))
+    if ngroups >= 3:
+        # Alg. 1 on the measured curves: stages of modules that pay to run side by side
+        # (the planner takes up to 16 quota levels: the measured ones, thinned if need be, plus the whole device)
+        lv = sorted({q for row in curves for q, v in zip(grid, row) if v < 1e29})
+        while len(lv) > 15:
+            lv = lv[::2] if lv[-1] == lv[::2][-1] else lv[::2] + [lv[-1]]
+        full = [[row[grid.index(q)] if row[grid.index(q)] < 1e29 else 1e9 for q in lv] + [group_ms_full[g]] for g, row in enumerate(curves)]
+        st_, alloc, t_pred, _ = mb.planner_solve(ngroups, [], lv + [cus], full, cus)
+        if len(st_) > 1:
+            stages = [dict(groups=list(members), quotas=[alloc[m] for m in members], offsets=pack([alloc[m] for m in members]))
+                      for members in st_]
+            plans.append(dict(label="planner stages (Alg. 1)", predicted_ms=round(t_pred, 4), stages=stages))
+    if forced is not None:
+        plans.append(packed(forced, "forced"))
+    results, seen = [], set()
+    for p in plans:
+        key = json.dumps(p["stages"])
+        if key in seen:
+            continue
+        seen.add(key)
+        ms, pg = median_plan(p, 3)
+        results.append(dict(p, iteration_ms=ms, group_ms=pg))
+    best = min(results, key=lambda r: r["iteration_ms"])
+    if forced is not None:
+        best = [r for r in results if r["label"] == "forced"][0]
+
+    # the timed region: K iterations under the best plan, inputs resident in HBM
+    reserve(best)
+    for _ in range(warmup):
+        run_plan(best)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_plan(best)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    def util(fl, ms, q):
+        return fl / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12 * q / cus)
+
+    def quota_of(plan, g):
+        for st in plan["stages"]:
+            if g in st["groups"]:
+                return st["quotas"][st["groups"].index(g)]
+
+    out = {
+        "workload": f"configs[{config}] {wl['name']}: " + ", ".join(
+            f"{m['name']} B{m['batch']} N{m['seq']} h{m['hidden'] or m['out_dim']} L{m['layers']}" for m in wl["modules"]),
+        "dtype": wl["dtype"], "batch": B, "groups": stage.groups, "total_tflop": round(sum(gflop) / 1e12, 3),
+        "value": round(B / (ms_per_step * 1e-3), 2), "ms_per_step": round(ms_per_step, 4),
+        "plan": dict(label=best["label"], stages=best["stages"]),
+        "time_sliced": {"ms_per_step": round(ts_ms, 4), "samples_per_s": round(B / (ts_ms * 1e-3), 2),
+                        "group_ms_at_all_cus": [round(v, 4) for v in group_ms_full],
+                        "mfma_util": [round(util(gflop[g], group_ms_full[g], cus), 4) for g in range(ngroups)],
+                        "aggregate_mfma_util": round(sum(gflop) / (ts_ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4)},
+        "colocated": {"speedup_vs_time_sliced": round(ts_ms / best["iteration_ms"], 4),
+                      "speedup_vs_time_sliced_timed_region": round(ts_ms / ms_per_step, 4),
+                      "group_ms_at_quota": [round(v, 4) for v in best["group_ms"]],
+                      "mfma_util_at_quota": [round(util(gflop[g], best["group_ms"][g], quota_of(best, g)), 4) for g in range(ngroups)],
+                      "aggregate_mfma_util": round(sum(gflop) / (best["iteration_ms"] * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+                      "plans": [dict(label=r["label"], stages=[dict(groups=st["groups"], cus=st["quotas"], offsets=st["offsets"]) for st in r["stages"]],
+                                     iteration_ms=round(r["iteration_ms"], 4), speedup_vs_time_sliced=round(ts_ms / r["iteration_ms"], 4),
+                                     **({"predicted_ms": r["predicted_ms"]} if "predicted_ms" in r else {})) for r in results],
+                      "chosen_from_curves": {"plan": chosen, "predicted_ms": round(predicted, 4), "cu_grid_step": 8,
+                                             "group_ms": [{str(q): round(v, 4) for q, v in zip(grid, row) if v < 1e29} for row in curves]}},
+    }
+    if layer_split and ngroups >= 2:
+        out["colocated"]["decoder_cut_in_time"] = decoder_cut(mb, synth, config, stage, results, group_ms_full, ts_ms)
+    else:
+        stage.destroy()
+    mb.pool_clear()
+    return out
+
+
+def decoder_cut(mb, synth, config, stage, results, group_ms_full, ts_ms):
+    """Two-stage alternative: the decoder cut after layer k, layers [0, k) colocated with the
+    other groups, layers [k, L) alone on all CUs.  (plan, k) is picked from the colocated group
+    times already measured (a decoder's time is linear in its layers), then measured."""
+    from paper_2605_18710_amd.workload import SplitStage
+    wl = synth.WORKLOADS[config]
+    llm = [m for m in wl["modules"] if m["kind"] == "decoder"][0]
+    L = llm["layers"]
+    dec_g = [gi for gi, g in enumerate(stage.groups) if llm["name"] in g][0]
+    cands = []
+    for r in results:
+        if len(r["stages"]) != 1 or len(set(r["stages"][0]["offsets"])) != len(r["stages"][0]["offsets"]):
+            continue
+        g_ms = r["group_ms"]
+        others = max(v for gi, v in enumerate(g_ms) if gi != dec_g)
+        for k in range(1, L):
+            cands.append((max(others, g_ms[dec_g] * k / L) + group_ms_full[dec_g] * (L - k) / L, r["stages"][0]["quotas"], k))
+    B = stage.batch
+    stage.destroy()
+    if not cands:
+        return None
+    pred, sp_plan, sp_k = min(cands)
+    ss = SplitStage(config, sp_k, sp_plan)
+    ss.run()
+    rs = [ss.run() for _ in range(5)]
+    it = statistics.median(r["iteration_ms"] for r in rs)
+    out = {"cut_after_layer": sp_k, "plan_cus": sp_plan, "predicted_ms": round(pred, 4), "iteration_ms": round(it, 4),
+           "stage_ms": [round(statistics.median(r["stage_ms"][j] for r in rs), 4) for j in range(2)],
+           "samples_per_s": round(B / (it * 1e-3), 2), "speedup_vs_time_sliced": round(ts_ms / it, 4)}
+    ss.destroy()
+    return out
 
 
 def main():
@@ -319,7 +543,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="index into the workload list (1 = CLIP-B / small-LM scale)")
+    ap.add_argument("--config", type=int, default=4,
+                    help="index into the workload list (default 4: vision + audio + 7B-shaped decoder, the largest single-GPU workload)")
+    ap.add_argument("--secondary", type=int, default=1, help="a second workload reported in the same line (-1: none)")
     ap.add_argument("--roofline-only", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="only the attention kernels at the decoder's shape (for rocprofv3)")
     ap.add_argument("--bandwidth-only", action="store_true", help="only the bandwidth-bound kernels at the decoder's shapes (for rocprofv3)")
@@ -340,7 +566,6 @@ def main():
 
     import torch
     from paper_2605_18710_amd import binding as mb, synth
-    from paper_2605_18710_amd.workload import StagedStage
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
@@ -368,7 +593,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"shape": {"T": Tl, "h": hl, "f": fl}, "gbs": bandwidth_kernels(mb, Tl, hl, fl, reps=20)}))
         return
-    gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=50, settle_ms=40.0)
+    big = Tl * hl * fl > 1e12                       # calls of several ms: fewer of them
+    gflops, gms = roofline_gemm(mb, Tl, hl, 2 * fl, reps=20 if big else 50, settle_ms=40.0)
     if args.roofline_only:
         # a plain device copy of known size, so that HBM byte counters of the same run can
         # be scaled: 1 GiB read + 1 GiB written per launch
@@ -381,147 +607,48 @@ def main():
                           "tflops": {k: gflops / v / 1e9 for k, v in gms.items()}}))
         return
     bw = bandwidth_kernels(mb, Tl, hl, fl, reps=20)
-    attn = attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=50)
+    attn = attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=20 if big else 50)
     pool = None if args.no_pool_bench else stream_pool_latency(mb, cus)
+    torch.cuda.empty_cache()
 
-    stage = StagedStage(args.config)
-    B = stage.batch
-    flops = stage.flops()
-    ngroups = len(stage.groups)
-    gflop = [sum(flops[n] for n in g) for g in stage.groups]
-    mb.pool_reserve(cus, 0, mb.STRIPED)
-
-    def median_run(quotas, mode, iters=5):
-        stage.run(quotas, mode)
-        rs = [stage.run(quotas, mode) for _ in range(iters)]
-        med = lambda xs: statistics.median(xs)
-        return dict(stage_ms=med([r["stage_ms"] for r in rs]),
-                    module_ms=[med([r["module_ms"][i] for r in rs]) for i in range(len(stage.names))])
-
-    # time-sliced baseline: every module alone on all CUs, back to back (sum over stages)
-    ts = median_run([cus], mb.TIME_SLICED)
-    group_ms_full = [sum(ts["module_ms"][i] for i, n in enumerate(stage.names) if n in g) for g in stage.groups]
-
-    # colocated under every listed plan, plus the plan chosen from the time-vs-CU curves
-    grid = [32, 64, 96, 128, 160, 192, 224]
-    curves = []
-    for gi, g in enumerate(stage.groups):
-        idx = [i for i, n in enumerate(stage.names) if n in g]
-        row = []
-        for q in grid:
-            mb.pool_reserve(q, 0, mb.STRIPED)
-            s = stage.staged
-            run = lambda: mb.stage_run([s[i].module for i in idx], [s[i].x for i in idx], [s[i].y for i in idx],
-                                       [q] * len(idx), [0] * len(idx), mb.STRIPED, mb.TIME_SLICED,
-                                       dy=[s[i].dy for i in idx], target=[s[i].target for i in idx],
-                                       dx=[s[i].dx for i in idx], loss=[s[i].loss for i in idx])
-            run()
-            row.append(statistics.median([run()["stage_ms"] for _ in range(3)]))
-        curves.append(row)
-    chosen, predicted = mb.plan_choose(grid, curves, cus)
-    plans = [list(p) for p in wl["plans"]]
-    if chosen not in plans:
-        plans.append(chosen)
     forced = [int(x) for x in args.plan.split(",")] if args.plan else None
-    if forced is not None and forced not in plans:
-        plans.append(forced)
-    results = []
-    for p in plans:
-        # Only the streams of the plan under test are alive: every masked stream owns a
-        # hardware queue, the process has few of them, and streams that end up sharing one
-        # run one after the other (measured: the same plan 13.6 ms with its two streams
-        # alone, 18.9 ms with the twenty streams of the sweep still alive).
-        mb.pool_clear()
-        stage.reserve(p)
-        r = median_run(p, mb.COLOCATED)
-        results.append(dict(plan=p, stage_ms=r["stage_ms"], module_ms=r["module_ms"]))
-    best = min(results, key=lambda r: r["stage_ms"])
-    if forced is not None:
-        best = [r for r in results if r["plan"] == forced][0]
-    mb.pool_clear()
-    stage.reserve(best["plan"])
+    main_rec = measure_workload(mb, synth, args.config, args.steps, args.warmup, forced, args.layer_split)
+    torch.cuda.empty_cache()
+    second = None
+    if args.secondary >= 0 and args.secondary != args.config and forced is None:
+        second = measure_workload(mb, synth, args.secondary, args.steps, args.warmup)
+        torch.cuda.empty_cache()
 
-    # the timed region: K colocated steps under the best plan, inputs resident in HBM
-    for _ in range(args.warmup):
-        stage.run(best["plan"], mb.COLOCATED)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stage.run(best["plan"], mb.COLOCATED)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    def util(fl, ms, q):
-        return fl / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12 * q / cus)
-
-    # Two-stage alternative: the decoder cut after layer k, layers [0, k) colocated with the
-    # other groups, layers [k, L) alone on all CUs.  (plan, k) is picked from the colocated
-    # module times already measured (a decoder's time is linear in its layers), then measured.
-    split = None
-    stage_destroyed = False
-    L = llm["layers"]
-    if args.layer_split and L >= 2 and ngroups >= 2:
-        from paper_2605_18710_amd.workload import SplitStage
-        dec_g = [gi for gi, g in enumerate(stage.groups) if llm["name"] in g][0]
-        cands = []
-        for r in results:
-            g_ms = [sum(r["module_ms"][i] for i, n in enumerate(stage.names) if n in g) for g in stage.groups]
-            others = max(v for gi, v in enumerate(g_ms) if gi != dec_g)
-            for k in range(1, L):
-                cands.append((max(others, g_ms[dec_g] * k / L) + group_ms_full[dec_g] * (L - k) / L, r["plan"], k))
-        pred, sp_plan, sp_k = min(cands)
-        stage.destroy()
-        stage_destroyed = True
-        ss = SplitStage(args.config, sp_k)
-        ss.run(sp_plan)
-        rs = [ss.run(sp_plan) for _ in range(5)]
-        it = statistics.median(r["iteration_ms"] for r in rs)
-        split = {"cut_after_layer": sp_k, "plan_cus": sp_plan, "predicted_ms": round(pred, 4), "iteration_ms": round(it, 4),
-                 "stage_ms": [round(statistics.median(r["stage_ms"][j] for r in rs), 4) for j in range(2)],
-                 "samples_per_s": round(B / (it * 1e-3), 2), "speedup_vs_time_sliced": round(ts["stage_ms"] / it, 4)}
-        ss.destroy()
-
-    group_ms_co = [sum(best["module_ms"][i] for i, n in enumerate(stage.names) if n in g) for g in stage.groups]
     dominant = max(gms, key=lambda k: gms[k])       # the slowest of the three forms bounds the step
+    ngroups = len(main_rec["groups"])
     line = {
         "metric": "colocated stage samples/sec vs time-sliced at 1 GPU; per-module MFMA util @quota",
-        "value": round(B / (ms_per_step * 1e-3), 2), "unit": "samples/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": main_rec["value"], "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_rec["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl["dtype"], "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {wl['name']}: " + ", ".join(
-            f"{m['name']} B{m['batch']} N{m['seq']} h{m['hidden'] or m['out_dim']} L{m['layers']}" for m in wl["modules"]),
-            "plan_cus": best["plan"], "groups": stage.groups, "mode": "colocated, decoupled staged buffers"},
-        "time_sliced": {"ms_per_step": round(ts["stage_ms"], 4), "samples_per_s": round(B / (ts["stage_ms"] * 1e-3), 2),
-                        "group_ms_at_all_cus": [round(v, 4) for v in group_ms_full],
-                        "mfma_util": [round(util(gflop[g], group_ms_full[g], cus), 4) for g in range(ngroups)]},
-        "colocated": {"speedup_vs_time_sliced": round(ts["stage_ms"] / best["stage_ms"], 4),
-                      "group_ms_at_quota": [round(v, 4) for v in group_ms_co],
-                      "mfma_util_at_quota": [round(util(gflop[g], group_ms_co[g], best["plan"][g]), 4) for g in range(ngroups)],
-                      "aggregate_mfma_util": round(sum(gflop) / (best["stage_ms"] * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
-                      "plans": [dict(plan=r["plan"], stage_ms=round(r["stage_ms"], 4)) for r in results],
-                      "chosen_from_curves": {"plan": chosen, "predicted_ms": round(predicted, 4),
-                                             "cu_grid": grid, "group_ms": [[round(v, 4) for v in row] for row in curves]},
-                      "decoder_cut_in_time": split},
-        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16_kernel 256x256x32 {dominant} T={Tl} k={hl} n={2 * fl}",
+        "config": {"workload": main_rec["workload"], "plan": main_rec["plan"], "groups": main_rec["groups"],
+                   "total_tflop_per_step": main_rec["total_tflop"], "mode": "decoupled staged buffers; stages one after another, modules of a stage colocated"},
+        "time_sliced": main_rec["time_sliced"],
+        "colocated": main_rec["colocated"],
+        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16 {dominant} T={Tl} k={hl} n={2 * fl} (the decoder's gate/up projection)",
                      "achieved": round(gflops / gms[dominant] / 1e9, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gflops / gms[dominant] / 1e9 / PEAK_BF16_TFLOPS, 4),
-                     "traffic": profiled_traffic(dominant) if args.config == 1 else None,
+                     "traffic": profiled_traffic(dominant, (Tl, hl, 2 * fl)),
                      "algorithmic_bytes": 2 * (Tl * hl + hl * 2 * fl + Tl * 2 * fl),
                      "avg_ms": {k: round(v, 4) for k, v in gms.items()},
                      "all_forms_tflops": {k: round(gflops / v / 1e9, 2) for k, v in gms.items()},
                      "hbm_kernels_gbs": bw, "hbm_peak_gbs": PEAK_HBM_GBS},
         "attention": attn,
         "stream_pool": pool,
+        "secondary": second,
         "paper_context": "paper reports up to 1.31x per-iteration speedup on 32x H100-80GB (other hardware, other metric)",
     }
     # what creating the stage's streams on demand would add to every step (one per group)
     if pool is not None:
         pool["share_of_step_if_on_demand"] = round(ngroups * pool["on_demand_create_destroy_ms"] /
-                                                   (ms_per_step + ngroups * pool["on_demand_create_destroy_ms"]), 4)
+                                                   (main_rec["ms_per_step"] + ngroups * pool["on_demand_create_destroy_ms"]), 4)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
-    if not stage_destroyed:
-        stage.destroy()
     print(json.dumps(line))
 
 

@@ -114,7 +114,9 @@ mosaic_status mosaic_probe_placement(const mosaic_stream* stream, int32_t n, int
  * + learned position table [seq,hidden]; in_dim = 3*patch*patch; for audio frames use
  * patch = 0 and x = [T,in_dim]), TEXT_STEM (rows [0,n_img) of each sample copied from
  * x = [batch*n_img, hidden], rows [n_img,seq) gathered from an embedding table
- * [vocab,hidden] by int32 ids bound with mosaic_module_bind_ids), CONV_STEM (a layer variant:
+ * [vocab,hidden] by int32 ids bound with mosaic_module_bind_ids; ids outside the table are
+ * clamped to its first / last row in both passes; per-sample image-token counts:
+ * mosaic_module_bind_image_counts), CONV_STEM (a layer variant:
  * the two-convolution audio stem of speech encoders; x = [batch, 2*seq, in_dim] frames-major ->
  * Conv1d(in_dim->hidden, k=3, stride 1, pad 1), GELU, Conv1d(hidden->hidden, k=3, stride 2,
  * pad 1), GELU, + learned position table [seq,hidden]; convolution weights are stored
@@ -156,6 +158,15 @@ mosaic_status mosaic_module_tensor_info(const mosaic_module*, int32_t i, char* n
 mosaic_status mosaic_module_bind(mosaic_module*, void* params, void* grads,
                                  void* workspace, size_t workspace_bytes);
 mosaic_status mosaic_module_bind_ids(mosaic_module*, const int32_t* ids); /* TEXT_STEM */
+/* TEXT_STEM with a different number of image tokens per sample at a fixed sequence length
+ * (the paper pads or truncates every module input to a uniform length, Sec. 3.5, so shapes
+ * never change): counts is a device int32 [batch]; sample b takes rows [0, counts[b]) from the
+ * first counts[b] of its n_img image tokens in x and rows [counts[b], seq) from the embedding
+ * table (counts are clamped to [0, n_img]).  With counts bound, ids must hold one id per
+ * sequence position, [batch, seq] (read at positions counts[b] .. seq-1); in the backward pass
+ * image tokens a sample did not use get zero gradient.  NULL unbinds: every sample then has
+ * n_img image tokens and ids is [batch, seq - n_img] again. */
+mosaic_status mosaic_module_bind_image_counts(mosaic_module*, const int32_t* counts);
 
 /* Enqueue the forward pass: x [input_elems] -> y [output_elems]; activations needed by
  * the backward pass are kept in the workspace.  quota = number of CUs the persistent
@@ -224,8 +235,16 @@ typedef struct {
   float module_ms[MOSAIC_MAX_STAGE_MODULES];      /* each module's own span */
 } mosaic_timing;
 
-/* Host-only plan validation (what mosaic_stage_run checks first). */
+/* Host-only plan validation (what mosaic_stage_run checks first): quotas and offsets legal
+ * for the mask layout, distinct CU ranges disjoint and inside the device (Eq. 5), and, in
+ * COLOCATED mode, no more distinct streams than the process has hardware queues
+ * (mosaic_device_hw_queues): streams that share a queue run one after the other, which would
+ * silently serialise the stage; such a plan returns MOSAIC_EQUOTA. */
 mosaic_status mosaic_plan_validate(const mosaic_plan*, int32_t cu_total, int32_t n_xcd);
+/* Streams the plan runs side by side: distinct (quota, offset) pairs in COLOCATED mode, else 1. */
+int32_t       mosaic_plan_stream_count(const mosaic_plan*);
+/* Hardware queues a process may hold (the runtime's GPU_MAX_HW_QUEUES setting, default 4). */
+int32_t       mosaic_device_hw_queues(void);
 /* Run one forward+backward of every module of the stage under the plan; blocks until
  * done and fills `out` (may be NULL) from device events. */
 mosaic_status mosaic_stage_run(const mosaic_stage*, const mosaic_plan*, mosaic_timing* out);

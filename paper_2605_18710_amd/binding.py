@@ -98,12 +98,15 @@ SIGNATURES = {
     "mosaic_module_tensor_info": (_i32, [_vp, _i32, C.c_char_p, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64)]),
     "mosaic_module_bind": (_i32, [_vp, _vp, _vp, _vp, _sz]),
     "mosaic_module_bind_ids": (_i32, [_vp, _vp]),
+    "mosaic_module_bind_image_counts": (_i32, [_vp, _vp]),
     "mosaic_module_forward": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "mosaic_module_backward": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "mosaic_module_step": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_module_optimizer_state_bytes": (C.c_size_t, [_vp, _i32]),
     "mosaic_module_adamw_step": (_i32, [_vp, _i32, _vp, _vp, C.c_size_t, _i32, _f32, _f32, _f32, _f32, _f32, _i64]),
     "mosaic_plan_validate": (_i32, [C.POINTER(Plan), _i32, _i32]),
+    "mosaic_plan_stream_count": (_i32, [C.POINTER(Plan)]),
+    "mosaic_device_hw_queues": (_i32, []),
     "mosaic_stage_run": (_i32, [C.POINTER(Stage), C.POINTER(Plan), C.POINTER(Timing)]),
     "mosaic_plan_choose": (_i32, [_i32, _i32, C.POINTER(_i32), C.POINTER(_f32), _i32, C.POINTER(_i32), C.POINTER(_f32)]),
     "mosaic_op_linear_fwd": (_i32, [_vp, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
@@ -302,6 +305,10 @@ class Module:
         self._ids = ids
         check(lib().mosaic_module_bind_ids(self.handle, ids.data_ptr()))
 
+    def bind_image_counts(self, counts) -> None:
+        self._counts = counts
+        check(lib().mosaic_module_bind_image_counts(self.handle, _ptr(counts)))
+
     def forward(self, quota: int, stream: Optional[Stream], x, y) -> None:
         check(lib().mosaic_module_forward(self.handle, quota, stream.handle if stream else None, _ptr(x), _ptr(y)))
 
@@ -354,6 +361,15 @@ def make_plan(quotas: Sequence[int], offsets: Sequence[int], layout: int, mode: 
 def plan_validate(quotas, offsets, layout, mode, cu_total: int, n_xcd: int) -> None:
     p = make_plan(quotas, offsets, layout, mode)
     check(lib().mosaic_plan_validate(C.byref(p), cu_total, n_xcd))
+
+
+def plan_stream_count(quotas, offsets, layout, mode) -> int:
+    p = make_plan(quotas, offsets, layout, mode)
+    return int(lib().mosaic_plan_stream_count(C.byref(p)))
+
+
+def device_hw_queues() -> int:
+    return int(lib().mosaic_device_hw_queues())
 
 
 def stage_run(modules: Sequence[Module], x, y, quotas, offsets, layout=STRIPED, mode=COLOCATED,

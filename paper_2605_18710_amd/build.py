@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmosaic.so")
-SOURCES = ["elementwise.hip", "variants.hip", "gemm.hip", "attention_simple.hip", "attention_mfma.hip", "module.hip", "launcher.hip", "planner.hip", "api.hip"]
+SOURCES = ["elementwise.hip", "variants.hip", "gemm.hip", "attention_simple.hip", "attention_mfma.hip", "module.hip", "launcher.hip", "planner.hip", "api.hip", "queue.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"] + os.environ.get("MOSAIC_EXTRA_FLAGS", "").split()

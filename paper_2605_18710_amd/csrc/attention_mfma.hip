@@ -22,8 +22,12 @@
 // Backward is split in two kernels so that every sum has one owner and a fixed order
 // (bit-identical for any grid): the dK/dV kernel owns 128 or 256 keys and streams query
 // tiles; the dQ kernel owns 128 or 256 queries and streams key tiles.  Both recompute P from the saved
-// row log-sum-exp; D_i = sum_c dO_ic O_ic comes from a small per-row kernel.
+// row log-sum-exp; D_i = sum_c dO_ic O_ic is formed by the dQ kernel, which runs first, from the
+// dO fragments it holds, and read by the dK/dV kernel.
+#include <algorithm>
+#include <mutex>
 #include "kernels.h"
+#include "tile_queue.h"
 
 namespace {
 
@@ -40,6 +44,10 @@ constexpr float kLn2 = 0.6931471805599453f;
 // rescale of the running sums (one multiply per accumulator register) becomes rare instead
 // of happening on almost every block of a long row.
 constexpr float kLazyRescale = 8.0f;
+// The next work item is claimed this many streamed 64-row tiles before the end of the current
+// one: late enough that a workgroup cannot take items from workgroups that have not started,
+// early enough that most of the claim's round trip hides under the item's last tiles.
+constexpr int kClaimTilesAhead = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -153,33 +161,36 @@ __device__ __forceinline__ int acc_row(int r, int hb) { return 8 * (r >> 2) + 4 
 // tiles the same Q and dO rows), so they should run at the same time on the same XCD and
 // meet in its L2: handed out head by head otherwise, 512 resident workgroups stream 512
 // different heads and every tile comes from HBM (the forward kernel then moves ~4.4 GB per
-// millisecond and is bandwidth-bound).  Workgroup w runs on XCD w % 8 (workgroups are dealt
-// round-robin over XCDs); the workgroups of one XCD walk that XCD's heads (head % 8 == XCD)
-// one after another, `tiles` consecutive slots per head.  Tiles cost unequally under a causal
-// mask: when a round covers whole heads the position inside the head is mirrored every
-// other round, so a workgroup that drew a heavy tile next draws a light one.  Grids that are not a multiple of 8 take the
-// same walk over all heads.  Returns false when the workgroup has no item in this round
-// (nor in any later one).
-__device__ __forceinline__ bool attn_item(int round, int heads, int tiles, int* head, int* tile) {
-  const int G = gridDim.x, w = blockIdx.x;
-  const bool by_xcd = (G & 7) == 0;
-  const int nx = by_xcd ? 8 : 1, xcd = by_xcd ? (w & 7) : 0, slot = by_xcd ? (w >> 3) : w, spx = by_xcd ? (G >> 3) : G;
-  const int64_t l = (int64_t)round * spx + slot;
-  const int hs = (int)(l / tiles), pos = (int)(l - (int64_t)hs * tiles);
-  const int hh = hs * nx + xcd;
-  if (hh >= heads) return false;
-  *head = hh;
-  // mirroring is a bijection only when a round covers whole heads; otherwise the position
-  // of a workgroup rotates from round to round by itself
-  *tile = ((round & 1) && spx % tiles == 0) ? tiles - 1 - pos : pos;
-  return true;
+// millisecond and is bandwidth-bound).  Items come from the work queue (tile_queue.h) in blocks
+// of `hb` heads: a block belongs to the list of one XCD and the workgroups of that XCD draw its
+// tiles one after another.  Tiles cost unequally under a causal mask.  Inside a block the
+// items are ordered tile-major, costliest tile position first (heavy_last: the last tile is the
+// costliest), all heads of the block for one position before the next position: drawn in that
+// order by whichever workgroup is free, the light tiles fill the gaps the heavy ones leave
+// (longest-first list scheduling).  The host sizes a block to about two rounds of an XCD's
+// workgroups, so several tiles of every head of the block are in flight together.  Without a
+// mask all tiles cost the same and hb = 1 keeps a head's tiles together.
+// Under static rounds (equal-cost tiles, or too few items for the queue to pay) hb = 1 and
+// `mirror` flips the position inside the head on odd rounds when a round covers whole heads,
+// so that a workgroup that drew a heavy tile next draws a light one.
+__device__ __forceinline__ void attn_item(int item, int heads, int tiles, int hb, bool heavy_last, bool mirror, int* head, int* tile) {
+  if (mirror) heavy_last = !heavy_last;
+  const int per = hb * tiles, blk = item / per, within = item - blk * per;
+  const int h0 = blk * hb, hn = min(hb, heads - h0);        // the last block may hold fewer heads
+  const int pos = within / hn;
+  *head = h0 + within - pos * hn;
+  *tile = heavy_last ? tiles - 1 - pos : pos;
+}
+
+__device__ __forceinline__ bool attn_mirror(const TileQueueArgs& q, const TileQueueCursor& c, int tiles) {
+  return q.mode == TQ_ROUNDS && (c.round & 1) && ((gridDim.x & 7) == 0 ? (gridDim.x >> 3) : gridDim.x) % tiles == 0;
 }
 
 // --------------------------------------------------------------------------- forward
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                      float* __restrict__ lse, int B, int N, int H, int Hkv, int causal,
-                                                     float scale_log2, int qtiles) {
+                                                     float scale_log2, int qtiles, int hblk, TileQueueArgs tq) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // K | V
@@ -194,9 +205,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
   // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
   const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
   const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
-  for (int round = 0;; ++round) {
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
     int head_, qt;
-    if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
+    attn_item(item, B * H, qtiles, hblk, causal != 0, attn_mirror(tq, qc, qtiles), &head_, &qt);
     const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* rowb = qkv + (int64_t)b * N * rs;
@@ -230,10 +244,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
     for (int u = 0; u < PD; ++u) request(u);
     wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
+    unsigned entry = 0;
+    const int claim_at = ntiles > kClaimTilesAhead ? ntiles - kClaimTilesAhead : 0;
     for (int t = 0; t < ntiles; ++t) {
       const lds_byte* ks = smem + (t % NST) * STAGE;
       const lds_byte* vs = ks + L::BYTES;
       request(t + PD);
+      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
       const int j0 = t * RS;
       // A 32-key block is visible to this wave when it starts before the end of the keys and
       // (causal) not after the wave's last query; the second block of a tile is visible only
@@ -349,7 +366,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
         }
       if (hb == 0) lse[((int64_t)b * H + hd) * N + i] = (m + log2f(ltot)) * kLn2;
     }
+    item = tq_next(tq, qc, entry, &mail);
   }
+  tq_done(tq);
 }
 
 // ------------------------------------------------------------------------------- dQ
@@ -358,7 +377,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
                                                         const bf16* __restrict__ dO,
                                                         const float* __restrict__ lse, float* __restrict__ delta,
                                                         bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
-                                                        float scale, int qtiles) {
+                                                        float scale, int qtiles, int hblk, TileQueueArgs tq) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // K | V
@@ -374,9 +393,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
   const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
   const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   const float scale_log2 = scale * kLog2e;
-  for (int round = 0;; ++round) {
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
     int head_, qt;
-    if (!attn_item(round, B * H, qtiles, &head_, &qt)) break;
+    attn_item(item, B * H, qtiles, hblk, causal != 0, attn_mirror(tq, qc, qtiles), &head_, &qt);
     const int hd = head_ % H, b = head_ / H;
     const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
     const bf16* rowb = qkv + (int64_t)b * N * rs;
@@ -425,10 +447,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
     for (int u = 0; u < PD; ++u) request(u);
     wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
+    unsigned entry = 0;
+    const int claim_at = ntiles > kClaimTilesAhead ? ntiles - kClaimTilesAhead : 0;
     for (int t = 0; t < ntiles; ++t) {
       const lds_byte* ks = smem + (t % NST) * STAGE;
       const lds_byte* vs = ks + L::BYTES;
       request(t + PD);
+      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
       const int j0 = t * RS;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
@@ -505,7 +530,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* 
           *reinterpret_cast<bf16x4*>(out + 32 * c + 8 * g + 4 * hb) = v;
         }
     }
+    item = tq_next(tq, qc, entry, &mail);
   }
+  tq_done(tq);
 }
 
 // --------------------------------------------------------------------------- dK, dV
@@ -513,7 +540,7 @@ template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
-                                                         float scale, int ktiles) {
+                                                         float scale, int ktiles, int hblk, TileQueueArgs tq) {
   constexpr int RS = 32, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
@@ -535,9 +562,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
   const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   const float scale_log2 = scale * kLog2e;
-  for (int round = 0;; ++round) {
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
     int head_, kt_i;
-    if (!attn_item(round, B * Hkv, ktiles, &head_, &kt_i)) break;
+    attn_item(item, B * Hkv, ktiles, hblk, false, attn_mirror(tq, qc, ktiles), &head_, &kt_i);      // the first key tile has the most queries
     const int kvh = head_ % Hkv, b = head_ / Hkv;
     const int hd0 = kvh * GQ;                    // first query head of the group
     const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
@@ -599,6 +629,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
     for (int u = 0; u < PD; ++u) { request(u); stage_stats(u); }
     wait_requests<(PD - 1) * NREQ>();
     __syncthreads();
+    unsigned entry = 0;
+    const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : 0;   // tiles of 32 rows here
     for (int t = 0; t < ntiles; ++t) {
       const int slot = t % NST;
       const lds_byte* qs = smem + slot * STAGE;
@@ -607,6 +639,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       const float* sd = stat + (slot * 2 + 1) * 64;
       request(t + PD);
       stage_stats(t + PD);
+      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
       const int ib = q_begin + (t % ntq) * RS;
       if (!(causal && ib + 31 < j0w) && j0w < N) {            // otherwise every (i, j) here is masked
         f32x16 sacc, pacc;
@@ -680,13 +713,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
           *reinterpret_cast<bf16x4*>(out + vo + 32 * c + 8 * g + 4 * hb) = vv;
         }
     }
+    item = tq_next(tq, qc, entry, &mail);
   }
-}
-
-template <typename K>
-mosaic_status set_smem(K kern, size_t bytes) {
-  MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-  return MOSAIC_OK;
+  tq_done(tq);
 }
 
 // Workgroup shape.  The kernels are written for NW waves and a ring of stages; measured on
@@ -694,17 +723,40 @@ mosaic_status set_smem(K kern, size_t bytes) {
 // three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU):
 // the loop is bound by the softmax arithmetic sharing the VALU port with MFMA issue, not by
 // load latency.  Only the 4-wave shape is instantiated.
+template <typename K>
+mosaic_status launch_queued(K kern, std::once_flag& once, hipError_t& once_rc, size_t smem, hipStream_t s, int quota,
+                            int wg_per_cu, int64_t heads, int tiles, int causal, TileQueueArgs* tq, int* grid, int* hb) {
+  std::call_once(once, [&] {
+    once_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  });
+  MOSAIC_HIP(once_rc);
+  // heads per block: about two rounds of an XCD's workgroups under a causal mask, else one head
+  // The queue pays once every workgroup draws several items (tiles of unequal cost under a
+  // causal mask, ragged last tiles, and heads that stay together on an XCD: measured 5-10 %
+  // on the audio encoder's full attention at 32 and 64 CUs, 25-40 % on causal rows of 4096);
+  // with up to three rounds static rounds do as well without the claims.
+  const int64_t resident = (int64_t)tile_queue_sure_cus(quota) * wg_per_cu;
+  const bool prefer_queue = heads * tiles > 3 * resident;
+  const int per_xcd = (int)((resident + 7) / 8);
+  *hb = causal ? (int)std::min<int64_t>(std::max<int64_t>(1, (2 * per_xcd + tiles - 1) / tiles), std::max<int64_t>(1, heads / 8)) : 1;
+  MOSAIC_TRY(tile_queue_plan(s, quota, wg_per_cu, heads * tiles, *hb * tiles, prefer_queue, tq, grid));
+  if (tq->mode == TQ_ROUNDS) *hb = 1;
+  return MOSAIC_OK;
+}
+
 template <int D, int NW>
 mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, bf16* O, float* lse) {
   const int qtiles = (int)ceil_div(N, 32 * NW);
-  const int64_t items = (int64_t)B * H * qtiles;
   // resident workgroups per CU: two by registers at head size 128; at 64 the forward and dQ
   // kernels need ~150 registers, so three fit (measured: forward 151 -> 130 us at B8 N1500 H20)
-  const int grid = grid_for(quota, (D == 64 && NW == 4) ? 3 : 8 / NW, items);
   constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
-  static bool once = false;
-  if (!once) { MOSAIC_TRY(set_smem(attn_fwd_mfma<D, NW>, smem)); once = true; }
-  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles);
+  static std::once_flag once;
+  static hipError_t once_rc = hipSuccess;
+  TileQueueArgs tq;
+  int grid, hb;
+  MOSAIC_TRY(launch_queued(attn_fwd_mfma<D, NW>, once, once_rc, smem, s, quota, (D == 64 && NW == 4) ? 3 : 8 / NW,
+                           (int64_t)B * H, qtiles, causal, &tq, &grid, &hb));
+  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles, hb, tq);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
@@ -713,24 +765,28 @@ template <int D, int NW>
 mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int causal, const bf16* qkv, const bf16* O,
                     const float* lse, const bf16* dO, bf16* dqkv, float* delta) {
   const int tiles = (int)ceil_div(N, 32 * NW);
-  const int64_t items = (int64_t)B * H * tiles;
   const float scale = 1.0f / sqrtf((float)D);
-  const int grid = grid_for(quota, 8 / NW, items);
   {
     // dQ first: it also writes the per-row delta that the dK/dV kernel reads
     constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<64, D, NW>::BYTES;
-    static bool once = false;
-    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dq_mfma<D, NW>, smem)); once = true; }
-    const int gq = grid_for(quota, (D == 64 && NW == 4) ? 3 : 8 / NW, items);   // as in the forward kernel
-    attn_bwd_dq_mfma<D, NW><<<gq, 64 * NW, smem, s>>>(qkv, O, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
+    static std::once_flag once;
+    static hipError_t once_rc = hipSuccess;
+    TileQueueArgs tq;
+    int grid, hb;
+    MOSAIC_TRY(launch_queued(attn_bwd_dq_mfma<D, NW>, once, once_rc, smem, s, quota, (D == 64 && NW == 4) ? 3 : 8 / NW,
+                             (int64_t)B * H, tiles, causal, &tq, &grid, &hb));   // residency as in the forward kernel
+    attn_bwd_dq_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
     MOSAIC_LAUNCH_CHECK();
   }
   {
     constexpr size_t smem = (size_t)Ring<NW>::NST * 2 * LdsTile<32, D, NW>::BYTES + LdsTile<32 * NW, D, NW>::BYTES +
                             (size_t)Ring<NW>::NST * 2 * 64 * sizeof(float);
-    static bool once = false;
-    if (!once) { MOSAIC_TRY(set_smem(attn_bwd_dkv_mfma<D, NW>, smem)); once = true; }
-    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles);
+    static std::once_flag once;
+    static hipError_t once_rc = hipSuccess;
+    TileQueueArgs tq;
+    int grid, hb;
+    MOSAIC_TRY(launch_queued(attn_bwd_dkv_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
+    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;

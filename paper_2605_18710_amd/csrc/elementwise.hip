@@ -549,35 +549,46 @@ __global__ __launch_bounds__(kThreads) void pos_grad_kernel(const T* __restrict_
   }
 }
 
+// Token ids and image-token counts.  Without per-sample counts every sample has n_img image
+// tokens and ids holds the N - n_img text ids of a sample, [B, N - n_img].  With counts
+// (int32 [B], clamped to [0, n_img]) sample b takes its first counts[b] image tokens and ids
+// holds one id per sequence position, [B, N], read at positions counts[b] .. N-1.
+__device__ __forceinline__ int stem_n_img(const int32_t* counts, int b, int n_img) {
+  if (!counts) return n_img;
+  const int c = counts[b];
+  return c < 0 ? 0 : (c > n_img ? n_img : c);
+}
+__device__ __forceinline__ int stem_id(const int32_t* ids, const int32_t* counts, int b, int t, int N, int n_img, int vocab) {
+  // an id outside the table is clamped rather than followed out of bounds (forward and backward alike)
+  const int id = counts ? ids[(int64_t)b * N + t] : ids[(int64_t)b * (N - n_img) + (t - n_img)];
+  return id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void text_stem_fwd_kernel(const T* __restrict__ img_tok, const int32_t* __restrict__ ids,
+                                                                 const int32_t* __restrict__ counts,
                                                                  const T* __restrict__ table, T* __restrict__ out,
                                                                  int B, int N, int n_img, int h, int vocab) {
   const int64_t total = (int64_t)B * N * h;
-  const int n_txt = N - n_img;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
     const int c = (int)(i % h);
     const int64_t row = i / h;
     const int t = (int)(row % N), b = (int)(row / N);
-    if (t < n_img) out[i] = img_tok[((int64_t)b * n_img + t) * h + c];
-    else {
-      // an id outside the table is clamped rather than followed out of bounds
-      int id = ids[(int64_t)b * n_txt + (t - n_img)];
-      id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-      out[i] = table[(int64_t)id * h + c];
-    }
+    if (t < stem_n_img(counts, b, n_img)) out[i] = img_tok[((int64_t)b * n_img + t) * h + c];
+    else out[i] = table[(int64_t)stem_id(ids, counts, b, t, N, n_img, vocab) * h + c];
   }
 }
 
+// gradient of the image tokens: rows the sample did not use get zero
 template <typename T>
-__global__ __launch_bounds__(kThreads) void split_img_kernel(const T* __restrict__ dy, T* __restrict__ d_img,
-                                                             int B, int N, int n_img, int h) {
+__global__ __launch_bounds__(kThreads) void split_img_kernel(const T* __restrict__ dy, const int32_t* __restrict__ counts,
+                                                             T* __restrict__ d_img, int B, int N, int n_img, int h) {
   const int64_t total = (int64_t)B * n_img * h;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
     const int c = (int)(i % h);
     const int64_t row = i / h;
     const int t = (int)(row % n_img), b = (int)(row / n_img);
-    d_img[i] = dy[((int64_t)b * N + t) * h + c];
+    d_img[i] = t < stem_n_img(counts, b, n_img) ? dy[((int64_t)b * N + t) * h + c] : from_f32<T>(0.f);
   }
 }
 
@@ -585,17 +596,15 @@ __global__ __launch_bounds__(kThreads) void split_img_kernel(const T* __restrict
 // rows of every occurrence of v in ascending position, so repeated ids need no atomics.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void embed_grad_kernel(const T* __restrict__ dy, const int32_t* __restrict__ ids,
+                                                              const int32_t* __restrict__ counts,
                                                               T* __restrict__ dtable, int B, int N, int n_img, int h, int vocab) {
-  const int n_txt = N - n_img;
-  const int total = B * n_txt;
   for (int v = blockIdx.x; v < vocab; v += gridDim.x) {
     for (int c0 = 0; c0 < h; c0 += kThreads) {
       const int c = c0 + threadIdx.x;
       float acc = 0.f;
-      for (int r = 0; r < total; ++r) {
-        if (ids[r] == v && c < h) {
-          const int b = r / n_txt, t = r - b * n_txt;
-          acc += to_f32(dy[((int64_t)b * N + n_img + t) * h + c]);
+      for (int b = 0; b < B; ++b) {
+        for (int t = stem_n_img(counts, b, n_img); t < N; ++t) {
+          if (stem_id(ids, counts, b, t, N, n_img, vocab) == v && c < h) acc += to_f32(dy[((int64_t)b * N + t) * h + c]);
         }
       }
       if (c < h) dtable[(int64_t)v * h + c] = from_f32<T>(acc);
@@ -861,28 +870,28 @@ mosaic_status launch_pos_grad(hipStream_t s, int quota, int dtype, int B, int N,
 }
 
 mosaic_status launch_text_stem_fwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img, int h, int vocab,
-                                   const void* img_tok, const int32_t* ids, const void* table, void* out) {
+                                   const void* img_tok, const int32_t* ids, const int32_t* counts, const void* table, void* out) {
   const int64_t total = (int64_t)B * N * h;
-#define ARGS(TT) ((const TT*)img_tok, ids, (const TT*)table, (TT*)out, B, N, n_img, h, vocab)
+#define ARGS(TT) ((const TT*)img_tok, ids, counts, (const TT*)table, (TT*)out, B, N, n_img, h, vocab)
   EW_LAUNCH(text_stem_fwd_kernel, total, ARGS);
 #undef ARGS
 }
 
 mosaic_status launch_text_stem_bwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img, int h, int vocab,
-                                   const void* dy, const int32_t* ids, void* d_img, void* dtable) {
+                                   const void* dy, const int32_t* ids, const int32_t* counts, void* d_img, void* dtable) {
   if (d_img != nullptr && n_img > 0) {
     const int64_t total = (int64_t)B * n_img * h;
     const int grid = grid_for(quota, 8, ceil_div(total, kThreads));
-    if (dtype == MOSAIC_BF16) split_img_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, (bf16*)d_img, B, N, n_img, h);
-    else split_img_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, (float*)d_img, B, N, n_img, h);
+    if (dtype == MOSAIC_BF16) split_img_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, counts, (bf16*)d_img, B, N, n_img, h);
+    else split_img_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, counts, (float*)d_img, B, N, n_img, h);
     MOSAIC_LAUNCH_CHECK();
   }
   if (vocab > 0) {
     const int grid = grid_for(quota, 8, vocab);
     if (dtype == MOSAIC_BF16)
-      embed_grad_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, ids, (bf16*)dtable, B, N, n_img, h, vocab);
+      embed_grad_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, ids, counts, (bf16*)dtable, B, N, n_img, h, vocab);
     else
-      embed_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, ids, (float*)dtable, B, N, n_img, h, vocab);
+      embed_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, ids, counts, (float*)dtable, B, N, n_img, h, vocab);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;

@@ -38,8 +38,10 @@
 // fp32 path (and shapes the MFMA path does not cover): a plain LDS-tiled FMA kernel with
 // arbitrary strides; ascending-k accumulation as well.
 #include <stdlib.h>
+#include <mutex>
 #include <type_traits>
 #include "kernels.h"
+#include "tile_queue.h"
 
 namespace {
 
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     const bf16* __restrict__ bias, const bf16* __restrict__ R, int M, int N, int K,
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
     int tiles_m, int tiles_n, int tile_begin, int tile_count, int sub, int ksplit, int ktiles_per,
-    float* __restrict__ P) {
+    float* __restrict__ P, TileQueueArgs tq) {
   constexpr int NT = 64 * NWM * NWN;
   constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -230,30 +232,16 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   // entries form a 4 x 8 patch that shares operand panels.  This launch covers entries
   // [tile_begin, tile_begin + tile_count) of that list, each as sub*sub tiles of BM x BN
   // (sub = 2: the 128x128 kernel finishing the quarter tiles of the 256x256 tiles that did
-  // not fill a whole round of the large kernel).  Each round hands gridDim items out;
-  // workgroup b runs on XCD b%8 (workgroups are dealt round-robin over XCDs), so XCD x takes
-  // the x-th contiguous eighth of the round and its workgroups reuse each other's panels in
-  // that XCD's L2.  Split pieces are split-major.
+  // not fill a whole round of the large kernel), once per split piece (split-major).  The
+  // flat list of these items is handed out by the work queue (tile_queue.h): a chunk of as
+  // many consecutive items as an XCD has resident workgroups goes to the list of one XCD, so
+  // the workgroups of an XCD work on one patch at a time and reuse each other's panels in
+  // that XCD's L2.
   const int per_split = tile_count * sub * sub;
-  const int nitems = per_split * ksplit;
-  const int G = gridDim.x;
-  const bool by_xcd = (G & 7) == 0;
-  auto get_item = [&](int round) -> WorkItem {
+  auto decode = [&](int item) -> WorkItem {
     WorkItem it;
-    it.valid = false; it.m0 = 0; it.n0 = 0; it.kt0 = 0; it.kt_end = 0; it.split = 0;
-    const int base = round * G;
-    if (base >= nitems) return it;
-    const int cnt = min(G, nitems - base);
-    int local;
-    if (by_xcd) {
-      const int per = (cnt + 7) >> 3;
-      local = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
-      if (((int)blockIdx.x >> 3) >= per || local >= cnt) return it;
-    } else {
-      local = blockIdx.x;
-      if (local >= cnt) return it;
-    }
-    const int item = base + local;
+    it.valid = item >= 0; it.m0 = 0; it.n0 = 0; it.kt0 = 0; it.kt_end = 0; it.split = 0;
+    if (!it.valid) return it;
     it.split = item / per_split;
     const int fine = item - it.split * per_split;
     const int quad = fine % (sub * sub);
@@ -265,12 +253,98 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     const int in_panel = tile - panel * tiles_m * 8;
     it.m0 = ((in_panel / pw) * sub + quad / sub) * BM;
     it.n0 = ((panel * 8 + in_panel % pw) * sub + quad % sub) * BN;
-    it.valid = true;
     return it;
   };
 
-  WorkItem cur = get_item(0);
-  if (!cur.valid) return;          // only the last round is partial, so nothing follows either
+  // stage ring: K-tile number t of the stream lives in stage t % NS
+  int si = 0;                                   // stage of the compute cursor's K-tile
+  auto stg = [&](int ahead) { const int i = si + ahead; return (i >= NS ? i - NS : i) * STAGE; };
+
+  // Drawing items.  Thread 0 talks to the queue and hands the item to the workgroup through
+  // four bytes of the LDS stage that is free between two pipeline steps (the kernel's LDS is
+  // otherwise full).  A draw is a round trip to memory.  The first item is drawn at the start;
+  // the second when the load cursor asks for it (once per workgroup, in mid-pipeline: drawn
+  // earlier, a workgroup that started first would take items from workgroups that have not
+  // started yet); from then on one item is claimed at the start of every epilogue and resolved
+  // at its end, so the round trip hides under the epilogue.  `drawn` holds an item drawn
+  // ahead; `lq` the items the load cursor has entered and the compute cursor has not.
+  TileQueueCursor qc;
+  bool drained = false;
+  int drawn = -1;
+  bool have_drawn = false;
+  // Claiming under the epilogue takes the item after the next, a whole tile before it is needed.
+  // That is harmless while the list is long, but near its end a workgroup a few microseconds
+  // ahead of the others would take two of the last items and leave another workgroup with
+  // none (measured: a launch of exactly two rounds took three).  So an item comes with a
+  // flag: `ahead_ok` says that the list it came from (this XCD's own) still held two rounds of
+  // work after the claim; without it the next item is drawn when the load cursor asks for it.
+  bool ahead_ok = false;
+  auto publish = [&](int v) -> int {           // v is thread 0's (item | flag << 30); returns the item to every thread
+    volatile int* mail = reinterpret_cast<volatile int*>(smem + stg(AHEAD));
+    if (threadIdx.x == 0) *mail = v;
+    __syncthreads();
+    const int r = __builtin_amdgcn_readfirstlane(*mail);
+    __syncthreads();                           // read by all before the stage is filled again
+    if (r < 0) { drained = true; ahead_ok = false; return -1; }
+    ahead_ok = (r >> 30) != 0;
+    return r & 0x3fffffff;
+  };
+  int home_list = -1;                          // thread 0: the list of the XCD this workgroup runs on
+  auto flagged = [&](int item, int left) -> int {
+    if (item < 0) return -1;
+    return item | ((qc.list == home_list && left >= 2 * tq.chunk) ? (1 << 30) : 0);
+  };
+  auto draw_sync = [&]() -> int {
+    if (drained) return -1;
+    if (tq.mode == TQ_ROUNDS) {                // static rounds: every thread computes its item
+      const int r = tq_rounds_item(tq, ++qc.round);
+      if (r < 0) drained = true;
+      return r;
+    }
+    int v = -1;
+    if (threadIdx.x == 0) { int left = 0; const int it = tq_resolve(tq, qc, tq_claim(tq, qc), &left); v = flagged(it, left); }
+    return publish(v);
+  };
+  auto draw_first = [&]() -> int {
+    if (tq.mode == TQ_ROUNDS) {
+      const int r = tq_first_item(tq, qc);
+      if (r < 0) drained = true;
+      return r;
+    }
+    int v = -1;
+    if (threadIdx.x == 0) {
+      qc.init();
+      home_list = qc.list;
+      int left = 0;
+      const int it = tq_resolve(tq, qc, tq_claim(tq, qc), &left);
+      v = flagged(it, left);
+    }
+    const int r = publish(v);
+    if (tq.mode != TQ_QUEUE) drained = true;   // one item per workgroup at most
+    return r;
+  };
+  auto next_drawn = [&]() -> int {             // the next item in draw order
+    if (have_drawn) { have_drawn = false; return drawn; }
+    return draw_sync();
+  };
+  int lq0 = -1, lq1 = -1, lq2 = -1, lq3 = -1, lq4 = -1, lq5 = -1, lqn = 0;
+  auto lq_push = [&](int v) {
+    lq0 = lqn == 0 ? v : lq0; lq1 = lqn == 1 ? v : lq1; lq2 = lqn == 2 ? v : lq2;
+    lq3 = lqn == 3 ? v : lq3; lq4 = lqn == 4 ? v : lq4; lq5 = lqn == 5 ? v : lq5;
+    ++lqn;
+  };
+  auto lq_pop = [&]() -> int {
+    const int v = lq0;
+    lq0 = lq1; lq1 = lq2; lq2 = lq3; lq3 = lq4; lq4 = lq5; lq5 = -1;
+    --lqn;
+    return v;
+  };
+
+  WorkItem cur = decode(draw_first());
+  if (!cur.valid) {                // a workgroup that started after the queue ran dry
+    if (threadIdx.x == 0) tq_leave(tq);
+    return;
+  }
 
   typedef DmaLoader<BM, A_KC, NWM * NWN> LA;
   typedef DmaLoader<BN, B_KC, NWM * NWN> LB;
@@ -280,7 +354,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
 
   // load cursor: the next K-tile to request
   WorkItem lit = cur;
-  int lround = 0, lkt = cur.kt0;
+  int lkt = cur.kt0;
   typename LA::Tile lta = la.tile(lda, lit.m0, M);
   typename LB::Tile ltb = lb.tile(ldb, lit.n0, N);
   // buffer descriptors for the direct-to-LDS requests: base, no stride, size in bytes, raw 32-bit format
@@ -297,7 +371,9 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     lb.issue(db, ltb, lkt, K, lit.kt_end, lit.valid, lds0 + (unsigned)(stage + BM * 64));
   };
   auto load_cursor_next_item = [&]() {
-    lit = get_item(++lround);
+    const int item = next_drawn();
+    if (item >= 0) lq_push(item);
+    lit = decode(item);
     lkt = lit.kt0;
     lta = la.tile(lda, lit.m0, M);
     ltb = lb.tile(ldb, lit.n0, N);
@@ -311,9 +387,6 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // stage ring: K-tile number t of the stream lives in stage t % NS
-  int si = 0;                                   // stage of the compute cursor's K-tile
-  auto stg = [&](int ahead) { const int i = si + ahead; return (i >= NS ? i - NS : i) * STAGE; };
   // vmcnt(n) alone: lgkmcnt and expcnt fields at "no wait"
   auto wait_loads = [](auto n) { constexpr int N = decltype(n)::value; __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14)); };
 
@@ -562,7 +635,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     }
   };
 
-  int round = 0, kt = cur.kt0;
+  int kt = cur.kt0;
   // One pipeline step, straight-line: the K-tile AHEAD of the compute cursor is requested
   // into the stage that was read last step, the current K-tile is multiplied, and before
   // the barrier every wave waits for its own requests of the K-tile two ahead, so that
@@ -624,13 +697,24 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     for (; n > 0; --n) step();
     if (lit.valid && lkt >= lit.kt_end) load_cursor_next_item();
     if (kt >= cur.kt_end) {
+      // an item is claimed under the epilogue when none is drawn ahead
+      const bool claim = tq.mode == TQ_QUEUE && !have_drawn && !drained && ahead_ok;
+      unsigned entry = 0;
+      if (claim && threadIdx.x == 0) entry = tq_claim(tq, qc);
       finish(cur, stg(NS - 1));
-      cur = get_item(++round);
+      if (claim) {
+        int v = -1;
+        if (threadIdx.x == 0) { int left = 0; const int it = tq_resolve(tq, qc, entry, &left); v = flagged(it, left); }
+        drawn = publish(v);
+        have_drawn = drawn >= 0;
+      }
+      if (lqn == 0) break;         // the load cursor has found the queue empty
+      cur = decode(lq_pop());
       kt = cur.kt0;
-      if (!cur.valid) break;
     }
   }
   wait_loads(std::integral_constant<int, 0>{});
+  if (threadIdx.x == 0) tq_leave(tq);
 }
 
 // Both operands K-contiguous (the input-gradient form), K a multiple of 128: 256x256x64 tile,
@@ -651,7 +735,7 @@ template <bool HAS_R>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C, const bf16* __restrict__ R,
     int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
-    int tiles_m, int tiles_n, int tile_begin, int tile_count) {
+    int tiles_m, int tiles_n, int tile_begin, int tile_count, TileQueueArgs tq) {
   constexpr int TBM = 256, TBK = 64, OPB = TBM * TBK * 2, STG = 2 * OPB;
   extern __shared__ __align__(16) unsigned char smem[];
   lds_byte* const lds = (lds_byte*)smem;
@@ -670,22 +754,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
   const int grow0 = tid >> 3, gch = tid & 7;
   const int lwr0 = grow0 * 128 + ((gch ^ ((grow0 >> 1) & 7)) << 4);
   const int fro0 = lr * 128, frsw = (lr >> 1) & 7;
-  const int G = gridDim.x;
-  for (int round = 0;; ++round) {
-    // same work order as gemm_bf16_kernel: panel-major tile list, contiguous eighths per XCD
-    const int base = round * G;
-    if (base >= tile_count) break;
-    const int cnt = min(G, tile_count - base);
-    int local;
-    if ((G & 7) == 0) {
-      const int per = (cnt + 7) >> 3;
-      local = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
-      if (((int)blockIdx.x >> 3) >= per || local >= cnt) break;
-    } else {
-      local = blockIdx.x;
-      if (local >= cnt) break;
-    }
-    const int tile = tile_begin + base + local;
+  // Items come from the work queue (tile_queue.h), in the same panel-major tile list as
+  // gemm_bf16_kernel.  Thread 0 claims the next tile when the K loop is done and resolves the
+  // claim after the epilogue, so the round trip hides under the epilogue.
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
+    const int tile = tile_begin + item;
     const int panel = tile / (tiles_m * 8), pw = min(8, tiles_n - panel * 8), in_panel = tile - panel * tiles_m * 8;
     const int m0 = (in_panel / pw) * TBM, n0 = (panel * 8 + in_panel % pw) * TBM;
 
@@ -773,6 +849,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
       body(kt + 1, std::integral_constant<int, 1>{});
     }
     __syncthreads();                    // every wave is done reading fragments: LDS is free
+    const unsigned entry = tq_claim_ahead(tq, qc);
 
     // Epilogue, one 32x32 block at a time through a 4 KB fp32 patch per wave (XOR swizzled),
     // leaving row-contiguous; the residual is added in fp32 in that layout, one rounding.
@@ -836,7 +913,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
     }
+    item = tq_next(tq, qc, entry, &mail);
   }
+  tq_done(tq);
 }
 
 // out[row][col] = bf16( P[0] + P[1] + ... ) in ascending piece order
@@ -932,19 +1011,23 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
                           int tile_count = -1) {
   constexpr size_t smem = (size_t)NS * (BM + BN) * 64;
   auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK>;
-  static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
-  if (!attr_set) {
-    MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  static std::once_flag attr_once;   // per instantiation; launches come from several host threads
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  });
+  MOSAIC_HIP(attr_rc);
   const int tiles_m = (int)ceil_div(M, BM * sub), tiles_n = (int)ceil_div(N, BN * sub);
   if (tile_count < 0) tile_count = tiles_m * tiles_n - tile_begin;
   if (tile_count <= 0) return MOSAIC_OK;
   const int wg_per_cu = (BM == 256) ? 1 : 2;
-  const int grid = grid_for(quota, wg_per_cu, (int64_t)tile_count * sub * sub * ksplit);
+  const int64_t items = (int64_t)tile_count * sub * sub * ksplit;
+  if (items > INT32_MAX) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "too many output tiles");
+  TileQueueArgs tq;
+  int grid;
+  MOSAIC_TRY(tile_queue_plan(s, quota, wg_per_cu, items, 0, false, &tq, &grid));
   kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P);
+                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq);
   MOSAIC_LAUNCH_CHECK();
   if (SPLITK) {
     const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
@@ -959,41 +1042,49 @@ mosaic_status launch_kc4w(hipStream_t s, int quota, int M, int N, int K, const b
                           int64_t ldb, bf16* C, int64_t ldc, const bf16* R, uint32_t a_bytes, uint32_t b_bytes,
                           uint32_t c_bytes, int tile_begin, int tile_count) {
   constexpr size_t smem = 2 * 2 * 256 * 64 * 2;        // two stages of two 256 x 64 operand tiles
-  static bool attr_set = false;
-  if (!attr_set) {
-    MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    MOSAIC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  static std::once_flag attr_once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (attr_rc == hipSuccess)
+      attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kc4w_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  });
+  MOSAIC_HIP(attr_rc);
   const int tiles_m = (int)ceil_div(M, 256), tiles_n = (int)ceil_div(N, 256);
   if (tile_count < 0) tile_count = tiles_m * tiles_n - tile_begin;
   if (tile_count <= 0) return MOSAIC_OK;
-  const int grid = grid_for(quota, 1, tile_count);
+  TileQueueArgs tq;
+  int grid;
+  MOSAIC_TRY(tile_queue_plan(s, quota, 1, tile_count, 0, false, &tq, &grid));
   if (R) gemm_bf16_kc4w_kernel<true><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                                             tiles_m, tiles_n, tile_begin, tile_count);
+                                                             tiles_m, tiles_n, tile_begin, tile_count, tq);
   else gemm_bf16_kc4w_kernel<false><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                                            tiles_m, tiles_n, tile_begin, tile_count);
+                                                            tiles_m, tiles_n, tile_begin, tile_count, tq);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
 
-// MOSAIC_GEMM_KC4W=0 sends the input-gradient form back to the eight-wave kernel (for A/B
-// timing; the bits are the same either way).  Read once per process.
+// A/B switches for kernel timing, compiled in only with -DMOSAIC_TUNING (never in the library
+// that ships): MOSAIC_GEMM_KC4W=0 sends the input-gradient form back to the eight-wave kernel,
+// MOSAIC_GEMM_TILE=256 / 128 / 1 forces the all-256, all-128 or mixed tile plan.  The bits are
+// the same either way.
+#ifdef MOSAIC_TUNING
 bool kc4w_enabled() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("MOSAIC_GEMM_KC4W"); v = e ? atoi(e) : 1; }
   return v != 0;
 }
-
-// MOSAIC_GEMM_TILE=256 / 128 forces the tile plan, 1 forces the mixed plan where there is a
-// partial round (for A/B timing; the bits are the same for every plan).  Read once per process.
 int forced_tile() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("MOSAIC_GEMM_TILE"); v = e ? atoi(e) : 0; }
   return v;
 }
+#else
+constexpr bool kc4w_enabled() { return true; }
+constexpr int forced_tile() { return 0; }
+#endif
 
 // Split count for the weight-gradient form: when the output has too few 256x256 tiles to
 // occupy the device and the contraction is long, cut K so that there are about as many
@@ -1027,6 +1118,9 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   //   all-128: 128x128 tiles, two workgroups per CU;
   //   mixed:   the whole rounds with the large kernel, then the tiles of the partial round
   //            as quarter tiles with the small kernel.
+  // rounds are counted with the CUs that are certain to run a workgroup at the same time
+  const int launch_quota = quota;
+  quota = tile_queue_sure_cus(quota);
   const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256), t128 = ceil_div(M, 128) * ceil_div(N, 128);
   auto cost_small = [&](int64_t tiles) {       // 128x128 tiles on `quota` CUs
     const int64_t full = tiles / (2 * (int64_t)quota), rem = tiles % (2 * (int64_t)quota);
@@ -1048,16 +1142,16 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   if (forced_tile() == 128 || forced_tile() == 256) plan = forced_tile();
   if (forced_tile() == 1 && whole > 0 && rest > 0) plan = 0;
   if (plan == 256) {
-    if (kc4w) return launch_kc4w(s, quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
-    return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+    if (kc4w) return launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
+    return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
   }
-  if (plan == 128) return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  if (plan == 128) return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
   const int head = (int)(whole * quota);
-  mosaic_status st = kc4w ? launch_kc4w(s, quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, head)
-                          : launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
+  mosaic_status st = kc4w ? launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, head)
+                          : launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
                                                                     b_bytes, c_bytes, 1, 0, nullptr, 1, 0, head);
   if (st != MOSAIC_OK) return st;
-  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
+  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
                                                  c_bytes, 1, 0, nullptr, 2, head, (int)rest);
 }
 

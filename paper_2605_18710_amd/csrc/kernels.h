@@ -80,11 +80,14 @@ mosaic_status launch_add_pos(hipStream_t s, int quota, int dtype, int B, int N, 
 // dpos[t,:] = sum_b dy[b*N+t,:] in ascending b
 mosaic_status launch_pos_grad(hipStream_t s, int quota, int dtype, int B, int N, int h,
                               const void* dy, void* dpos);
-// out rows: per sample b, [0,n_img) from img_tok, [n_img,N) from table[ids]
+// out rows: per sample b, [0,n_b) from img_tok, [n_b,N) from table[ids]; n_b = n_img, or
+// counts[b] (clamped to [0,n_img]) when counts is given; ids is [B, N-n_img] without counts and
+// one id per sequence position, [B, N], with them
 mosaic_status launch_text_stem_fwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img,
                                    int h, int vocab, const void* img_tok, const int32_t* ids,
-                                   const void* table, void* out);
-// d_img rows from dy; dtable[v] = sum over occurrences of v (ascending position)
+                                   const int32_t* counts, const void* table, void* out);
+// d_img rows from dy (zero for image tokens a sample did not use); dtable[v] = sum over
+// occurrences of v (ascending position)
 mosaic_status launch_text_stem_bwd(hipStream_t s, int quota, int dtype, int B, int N, int n_img,
                                    int h, int vocab, const void* dy, const int32_t* ids,
-                                   void* d_img, void* dtable);
+                                   const int32_t* counts, void* d_img, void* dtable);

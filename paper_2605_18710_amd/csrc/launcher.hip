@@ -1,6 +1,7 @@
 // Launcher: CU-mask construction, quota'd streams and their pool (Sec. 3.2), plan
 // validation (Eq. 5), quota choice from measured curves (Eq. 4-5), and stage execution in
 // colocated, time-sliced (Eq. 1) and chained modes.
+#include <stdlib.h>
 #include <string.h>
 #include <atomic>
 #include <mutex>
@@ -9,6 +10,7 @@
 #include <thread>
 #include <vector>
 #include "kernels.h"
+#include "tile_queue.h"
 
 // ------------------------------------------------------------------------------ errors
 static thread_local char g_err[512] = "";
@@ -134,6 +136,9 @@ extern "C" int32_t mosaic_stream_offset(const mosaic_stream* s) { return s ? s->
 extern "C" mosaic_status mosaic_stream_destroy(mosaic_stream* s) {
   if (!s) return MOSAIC_OK;
   if (s->pooled) MOSAIC_FAIL(MOSAIC_EINVAL, "a pooled stream is released with mosaic_pool_clear");
+  // the stream's work queue goes back to the table once nothing can be using it
+  (void)hipStreamSynchronize(s->s);
+  tile_queue_release(s->s);
   hipError_t e = hipStreamDestroy(s->s);
   delete s;
   if (e != hipSuccess) MOSAIC_FAIL(MOSAIC_EHIP, "hipStreamDestroy failed: %s", hipGetErrorString(e));
@@ -176,6 +181,8 @@ extern "C" mosaic_status mosaic_pool_clear(void) {
   std::lock_guard<std::mutex> lk(g_pool_mu);
   mosaic_status rc = MOSAIC_OK;
   for (mosaic_stream* s : g_pool) {
+    (void)hipStreamSynchronize(s->s);
+    tile_queue_release(s->s);
     if (hipStreamDestroy(s->s) != hipSuccess) rc = MOSAIC_EHIP;
     delete s;
   }
@@ -206,6 +213,26 @@ extern "C" mosaic_status mosaic_probe_placement(const mosaic_stream* stream, int
 }
 
 // ------------------------------------------------------------------------------- plans
+extern "C" int32_t mosaic_device_hw_queues(void) {
+  // the runtime's limit on hardware queues per process: its default unless the environment says otherwise
+  const char* e = getenv("GPU_MAX_HW_QUEUES");
+  const int v = e ? atoi(e) : 0;
+  return v > 0 ? v : 4;
+}
+
+extern "C" int32_t mosaic_plan_stream_count(const mosaic_plan* p) {
+  if (!p || !p->cu_quota || !p->cu_offset || p->n <= 0) return 0;
+  if (p->mode != MOSAIC_COLOCATED) return 1;
+  int distinct = 0;
+  for (int i = 0; i < p->n; ++i) {
+    bool first = true;
+    for (int j = 0; j < i; ++j)
+      if (p->cu_quota[j] == p->cu_quota[i] && p->cu_offset[j] == p->cu_offset[i]) first = false;
+    distinct += first;
+  }
+  return distinct;
+}
+
 extern "C" mosaic_status mosaic_plan_validate(const mosaic_plan* p, int32_t cu_total, int32_t n_xcd) {
   if (!p || !p->cu_quota || !p->cu_offset) MOSAIC_FAIL(MOSAIC_EINVAL, "null plan");
   if (p->n <= 0 || p->n > MOSAIC_MAX_STAGE_MODULES) MOSAIC_FAIL(MOSAIC_EINVAL, "plan holds %d modules (1..%d allowed)", p->n, MOSAIC_MAX_STAGE_MODULES);
@@ -232,6 +259,14 @@ extern "C" mosaic_status mosaic_plan_validate(const mosaic_plan* p, int32_t cu_t
       }
     }
     if (total > cu_total) MOSAIC_FAIL(MOSAIC_EQUOTA, "quotas sum to %lld CUs, the device has %d", (long long)total, cu_total);
+    // Every masked stream needs a hardware queue of its own to run beside the others; streams
+    // that end up sharing one run one after the other, which silently turns a colocated stage
+    // into a time-sliced one.
+    const int distinct = mosaic_plan_stream_count(p);
+    const int queues = mosaic_device_hw_queues();
+    if (distinct > queues)
+      MOSAIC_FAIL(MOSAIC_EQUOTA, "the plan needs %d streams side by side, the process has %d hardware queues "
+                  "(GPU_MAX_HW_QUEUES): let modules share quotas, or split the stage", distinct, queues);
   }
   return MOSAIC_OK;
 }
@@ -271,28 +306,51 @@ extern "C" mosaic_status mosaic_plan_choose(int32_t n_modules, int32_t n_points,
 // -------------------------------------------------------------------------- stage run
 namespace {
 
+// Events of one mosaic_stage_run call.  Calls may come from several host threads at once, so
+// every call takes a set of its own from a free list (sets are created on first use and kept:
+// event creation is not on the stage's critical path after the first iterations).
 struct EventSet {
   hipEvent_t start = nullptr;
   hipEvent_t ms[MOSAIC_MAX_STAGE_MODULES] = {};
   hipEvent_t me[MOSAIC_MAX_STAGE_MODULES] = {};
-  bool ok = false;
 };
 
-mosaic_status get_events(EventSet** out) {
-  static EventSet ev;
-  static std::mutex mu;
-  std::lock_guard<std::mutex> lk(mu);
-  if (!ev.ok) {
-    MOSAIC_HIP(hipEventCreate(&ev.start));
-    for (int i = 0; i < MOSAIC_MAX_STAGE_MODULES; ++i) {
-      MOSAIC_HIP(hipEventCreate(&ev.ms[i]));
-      MOSAIC_HIP(hipEventCreate(&ev.me[i]));
-    }
-    ev.ok = true;
+std::mutex g_ev_mu;
+std::vector<EventSet*> g_ev_free;
+
+mosaic_status acquire_events(EventSet** out) {
+  {
+    std::lock_guard<std::mutex> lk(g_ev_mu);
+    if (!g_ev_free.empty()) { *out = g_ev_free.back(); g_ev_free.pop_back(); return MOSAIC_OK; }
   }
-  *out = &ev;
+  EventSet* ev = new (std::nothrow) EventSet();
+  if (!ev) MOSAIC_FAIL(MOSAIC_ENOMEM, "host allocation failed");
+  hipError_t e = hipEventCreate(&ev->start);
+  for (int i = 0; i < MOSAIC_MAX_STAGE_MODULES && e == hipSuccess; ++i) {
+    e = hipEventCreate(&ev->ms[i]);
+    if (e == hipSuccess) e = hipEventCreate(&ev->me[i]);
+  }
+  if (e != hipSuccess) {
+    if (ev->start) (void)hipEventDestroy(ev->start);
+    for (int i = 0; i < MOSAIC_MAX_STAGE_MODULES; ++i) {
+      if (ev->ms[i]) (void)hipEventDestroy(ev->ms[i]);
+      if (ev->me[i]) (void)hipEventDestroy(ev->me[i]);
+    }
+    delete ev;
+    MOSAIC_FAIL(MOSAIC_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e));
+  }
+  *out = ev;
   return MOSAIC_OK;
 }
+
+struct EventLease {           // gives the set back when the call returns, on every path
+  EventSet* ev = nullptr;
+  ~EventLease() {
+    if (!ev) return;
+    std::lock_guard<std::mutex> lk(g_ev_mu);
+    g_ev_free.push_back(ev);
+  }
+};
 
 mosaic_status step_one(const mosaic_stage* st, int i, int quota, const mosaic_stream* s) {
   return mosaic_module_step(st->modules[i], quota, s, st->x[i], st->dy ? st->dy[i] : nullptr,
@@ -318,8 +376,9 @@ extern "C" mosaic_status mosaic_stage_run(const mosaic_stage* st, const mosaic_p
     const int k = (plan->mode == MOSAIC_COLOCATED) ? i : 0;
     MOSAIC_TRY(mosaic_pool_get(plan->cu_quota[k], plan->cu_offset[k], plan->layout, &streams[i]));
   }
-  EventSet* ev;
-  MOSAIC_TRY(get_events(&ev));
+  EventLease lease;
+  MOSAIC_TRY(acquire_events(&lease.ev));
+  EventSet* ev = lease.ev;
   mosaic_timing tm;
   memset(&tm, 0, sizeof(tm));
 

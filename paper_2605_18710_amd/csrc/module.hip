@@ -50,6 +50,7 @@ struct mosaic_module {
   char* grads = nullptr;
   char* ws = nullptr;
   const int32_t* ids = nullptr;
+  const int32_t* img_counts = nullptr;   // TEXT_STEM: per-sample image-token counts, optional
   const void* last_x = nullptr;
   bool forward_done = false;
 };
@@ -514,6 +515,13 @@ mosaic_status mosaic_module_bind_ids(mosaic_module* m, const int32_t* ids) {
   return MOSAIC_OK;
 }
 
+mosaic_status mosaic_module_bind_image_counts(mosaic_module* m, const int32_t* counts) {
+  if (!m) MOSAIC_FAIL(MOSAIC_EINVAL, "null argument");
+  if (m->d.kind != MOSAIC_TEXT_STEM) MOSAIC_FAIL(MOSAIC_EINVAL, "only a text stem takes image-token counts");
+  m->img_counts = counts;        // NULL: back to n_img image tokens for every sample
+  return MOSAIC_OK;
+}
+
 static mosaic_status resolve_quota(int32_t quota, const mosaic_stream* stream, int* q) {
   DeviceInfo di;
   MOSAIC_TRY(mosaic_device_info(&di));
@@ -540,7 +548,7 @@ mosaic_status mosaic_module_forward(mosaic_module* m, int32_t quota, const mosai
     case MOSAIC_CONV_STEM: st = conv_stem_forward(m, s, q, x, y); break;
     default:
       if (!m->ids) MOSAIC_FAIL(MOSAIC_EINVAL, "text stem has no token ids bound");
-      st = launch_text_stem_fwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, x, m->ids, P(m, m->lp[0].w_1), y);
+      st = launch_text_stem_fwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, x, m->ids, m->img_counts, P(m, m->lp[0].w_1), y);
   }
   m->forward_done = (st == MOSAIC_OK);
   return st;
@@ -560,7 +568,7 @@ mosaic_status mosaic_module_backward(mosaic_module* m, int32_t quota, const mosa
     case MOSAIC_PATCH_STEM: return patch_stem_backward(m, s, q, dy, dx);
     case MOSAIC_CONV_STEM: return conv_stem_backward(m, s, q, dy, dx);
     default:
-      return launch_text_stem_bwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, dy, m->ids, dx, G(m, m->lp[0].w_1));
+      return launch_text_stem_bwd(s, q, m->d.dtype, m->d.batch, m->d.seq, m->d.n_img, m->d.hidden, m->d.vocab, dy, m->ids, m->img_counts, dx, G(m, m->lp[0].w_1));
   }
 }
 

@@ -13,6 +13,56 @@ def rel_l2(a, b):
     return float(np.sqrt(((a - b) ** 2).sum()) / nb)
 
 
+def elementwise_excess(got, ref, dtype, roundings=1):
+    """Largest |got - ref| / bound over all elements, where the bound of an element is
+    rel * |ref| + floor * rms(ref): a share of the element's own size for its last rounding and a
+    share of the tensor's typical size for what the roundings before it and the fp32 summation
+    order leave.  `roundings` = bf16 (or fp32) roundings between the inputs and this tensor: 1
+    for a single kernel, more for a whole layer (the floor is 2^-6 per rounding for bf16: four
+    times the half-ulp of a single rounding, because it has to hold for the worst of 10^5 to 10^8
+    elements, not for a typical one).  A value <= 1 passes.  A tensor-wide relative L2
+    norm lets a wrong 32 x 32 block of a 10^8-element tensor through; this does not: a block
+    of wrong values is off by about rms(ref), tens of times the bound."""
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if dtype == "bf16":
+        rel, floor = 2.0 ** -7, 2.0 ** -6 * (1.0 + roundings)
+    else:
+        rel, floor = 1e-5, 2e-5 * (1.0 + roundings)
+    if rms == 0.0:
+        return 0.0          # an all-zero reference: the relative-L2 check (absolute then) is the whole test
+    bound = rel * np.abs(ref) + floor * rms
+    return float((np.abs(got - ref) / bound).max())
+
+
+def assert_close(got, ref, dtype, what="", roundings=1, l2=None):
+    """The stated tolerance (relative L2) and the element-by-element bound, together."""
+    e = rel_l2(got, ref)
+    assert e <= (tol(dtype) if l2 is None else l2), (what, "rel L2", e)
+    x = elementwise_excess(got, ref, dtype, roundings)
+    assert x <= 1.0, (what, "element beyond its bound by a factor of", x)
+
+
+def fast_layer_params(cfg, seed):
+    """Layer parameters for full-size shapes: matrices uniform with standard deviation 0.02 from
+    the bulk generator (the counter-based normal generator needs seconds per 10^7 values on the
+    host; these hold 10^8), gains and biases perturbed like layer_params."""
+    h, f = cfg["hidden"], cfg["mlp"]
+    s = iter(range(seed, seed + 64))
+    a = 0.02 * np.sqrt(3.0)
+    n = lambda shape: synth.bulk_uniform(next(s), shape, -a, a)
+    one = lambda k: 1.0 + synth.normal(next(s), (k,), 0.0, 0.02)
+    zero = lambda k: synth.normal(next(s), (k,), 0.0, 0.02)
+    if cfg["kind"] == "encoder":
+        return dict(ln1_g=one(h), ln1_b=zero(h), w_qkv=n((h, 3 * h)), b_qkv=zero(3 * h),
+                    w_o=n((h, h)), b_o=zero(h), ln2_g=one(h), ln2_b=zero(h),
+                    w_1=n((h, f)), b_1=zero(f), w_2=n((f, h)), b_2=zero(h))
+    return dict(rms1_g=one(h), w_qkv=n((h, 3 * h)), w_o=n((h, h)), rms2_g=one(h),
+                w_gate=n((h, f)), w_up=n((h, f)), w_down=n((f, h)))
+
+
 def layer_params(cfg, seed, perturb=True):
     """N(0,0.02) matrices; norm gains 1 and biases 0, perturbed by N(0,0.02) when asked
     so that their gradients are exercised."""

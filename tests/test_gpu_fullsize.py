@@ -11,7 +11,7 @@ import pytest
 
 from oracle import layers as O
 from paper_2605_18710_amd import synth
-from helpers import rel_l2, quantize, to_dev, from_dev
+from helpers import rel_l2, quantize, to_dev, from_dev, assert_close
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -51,14 +51,18 @@ def test_decoder_gate_up_projection_sampled(mb):
     for a, b in zip(snaps[0], snaps[1]):
         assert np.array_equal(a, b), "full-size result depends on the quota"
     rows = synth.integers(9004, (48,), 0, T)
-    rows[:4] = [0, 255, 256, T - 1]                      # tile edges
+    # tile edges, and rows of the tiles that do not fill a whole round of 256 large tiles: the forward
+    # form's 1408 tiles leave 128 (the last three of its 32 tile rows, in the last panels) to the
+    # quarter-tile launch
+    rows[:10] = [0, 255, 256, T - 1, 7424, 7551, 7552, 7679, 7680, 8063]
     Yh, dXh = from_dev(Y[torch.from_numpy(rows).long().cuda()]), from_dev(dX[torch.from_numpy(rows).long().cuda()])
-    assert rel_l2(Yh, X[rows] @ W) <= 2e-2
-    assert rel_l2(dXh, dY[rows] @ W.T) <= 2e-2
+    assert_close(Yh, X[rows] @ W, "bf16", "Y rows")
+    assert_close(dXh, dY[rows] @ W.T, "bf16", "dX rows")
     cols = synth.integers(9005, (24,), 0, n)
-    cols[:3] = [0, 255, n - 1]
+    # the weight gradient's 352 tiles leave 96 to the quarter-tile launch: the last tile columns
+    cols[:8] = [0, 255, n - 1, 8191, 8192, 9215, 10239, 11135]
     dWh = from_dev(dW[:, torch.from_numpy(cols).long().cuda()])
-    assert rel_l2(dWh, X.T @ dY[:, cols]) <= 2e-2
+    assert_close(dWh, X.T @ dY[:, cols], "bf16", "dW columns")
 
 
 def test_decoder_attention_sampled_heads(mb):
@@ -87,10 +91,10 @@ def test_decoder_attention_sampled_heads(mb):
         qh, kh, vh = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
         o_ref, P = O.attention_head_fwd(qh, kh, vh, 1)
         dq, dk, dv = O.attention_head_bwd(qh, kh, vh, P, dO[rows, c])
-        assert rel_l2(Oh[rows, c], o_ref) <= 2e-2
-        assert rel_l2(dh[rows, t * d:(t + 1) * d], dq) <= 2e-2
-        assert rel_l2(dh[rows, h + t * d:h + (t + 1) * d], dk) <= 2e-2
-        assert rel_l2(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv) <= 2e-2
+        assert_close(Oh[rows, c], o_ref, "bf16", ("O", b, t), roundings=2)
+        assert_close(dh[rows, t * d:(t + 1) * d], dq, "bf16", ("dq", b, t), roundings=8)
+        assert_close(dh[rows, h + t * d:h + (t + 1) * d], dk, "bf16", ("dk", b, t), roundings=8)
+        assert_close(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv, "bf16", ("dv", b, t), roundings=8)
         S = (qh @ kh.T) / np.sqrt(d)
         S = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], -np.inf, S)
         mx = S.max(-1)
@@ -153,12 +157,12 @@ def _check_sampled(T, k, n, seed, X, W, dY, Y, dX, dW, edge_rows, edge_cols):
     rows = synth.integers(seed + 3, (32,), 0, T)
     rows[:len(edge_rows)] = edge_rows
     ridx = torch.from_numpy(rows).long().cuda()
-    assert rel_l2(from_dev(Y[ridx]), X[rows] @ W) <= 2e-2
-    assert rel_l2(from_dev(dX[ridx]), dY[rows] @ W.T) <= 2e-2
+    assert_close(from_dev(Y[ridx]), X[rows] @ W, "bf16", "Y rows")
+    assert_close(from_dev(dX[ridx]), dY[rows] @ W.T, "bf16", "dX rows")
     cols = synth.integers(seed + 4, (16,), 0, n)
     cols[:len(edge_cols)] = edge_cols
     cidx = torch.from_numpy(cols).long().cuda()
-    assert rel_l2(from_dev(dW[:, cidx]), X.T @ dY[:, cols]) <= 2e-2
+    assert_close(from_dev(dW[:, cidx]), X.T @ dY[:, cols], "bf16", "dW columns")
 
 
 def test_config3_decoder_output_projection_sampled(mb):
@@ -205,7 +209,7 @@ def test_config5_audio_attention_sampled_heads(mb):
         qh, kh, vh = qkv[rows, 0:h][:, c], qkv[rows, h:2 * h][:, c], qkv[rows, 2 * h:][:, c]
         o_ref, P = O.attention_head_fwd(qh, kh, vh, 0)
         dq, dk, dv = O.attention_head_bwd(qh, kh, vh, P, dO[rows, c])
-        assert rel_l2(Oh[rows, c], o_ref) <= 2e-2
-        assert rel_l2(dh[rows, t * d:(t + 1) * d], dq) <= 2e-2
-        assert rel_l2(dh[rows, h + t * d:h + (t + 1) * d], dk) <= 2e-2
-        assert rel_l2(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv) <= 2e-2
+        assert_close(Oh[rows, c], o_ref, "bf16", ("O", b, t), roundings=2)
+        assert_close(dh[rows, t * d:(t + 1) * d], dq, "bf16", ("dq", b, t), roundings=8)
+        assert_close(dh[rows, h + t * d:h + (t + 1) * d], dk, "bf16", ("dk", b, t), roundings=8)
+        assert_close(dh[rows, 2 * h + t * d:2 * h + (t + 1) * d], dv, "bf16", ("dv", b, t), roundings=8)

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import layers as O
 from paper_2605_18710_amd import synth
-from helpers import (rel_l2, quantize, quantize_tree, to_dev, from_dev, tol, layer_params, projector_params,
+from helpers import (assert_close, rel_l2, quantize, quantize_tree, to_dev, from_dev, tol, layer_params, projector_params,
                      stem_params, load_layer_params, read_layer_grads, load_flat_params, read_flat_grads)
 
 pytestmark = pytest.mark.gpu
@@ -68,13 +68,14 @@ def test_stack_step_matches_oracle_and_is_quota_invariant(mb, dtype, cfg):
         snap = [bits(y), bits(dx), bits(m.grads), bits(loss)]
         if first is None:
             first = snap
-            assert rel_l2(from_dev(y), y_ref) <= tol(dtype)
+            nl = cfg["layers"]
+            assert_close(from_dev(y), y_ref, dtype, "y", roundings=8 * nl)
             assert abs(loss.item() - loss_ref) <= tol(dtype) * loss_ref
-            assert rel_l2(from_dev(dx), dx_ref) <= tol(dtype)
+            assert_close(from_dev(dx), dx_ref, dtype, "dx", roundings=24 * nl)
             g = read_layer_grads(m, layers)
-            for l in range(cfg["layers"]):
+            for l in range(nl):
                 for k in g_ref[l]:
-                    assert rel_l2(g[l][k], g_ref[l][k]) <= tol(dtype), (l, k)
+                    assert_close(g[l][k], g_ref[l][k], dtype, (l, k), roundings=24 * nl)
         else:
             for a, b in zip(snap, first):
                 assert np.array_equal(a, b), "module step depends on the quota"
@@ -178,3 +179,58 @@ def test_config1_chain_end_to_end(mb):
     assert rel_l2(mods[3].get_tensor("table", grads=True), G["table"]) <= 1e-5
     for m in mods:
         m.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_text_stem_with_per_sample_image_token_counts_chained(mb, dtype):
+    """Fixed sequence length, a different number of image tokens per sample (the mix of the
+    large-encoder / mid-LLM workload at reduced size): text stem -> decoder layer -> loss as a
+    chained stage; output, loss, the gradient of the image tokens (zero rows where a sample did
+    not use a token), the embedding-table gradient and the decoder's gradients against the
+    checker.  One count is 0 and one is n_img; one id lies outside the table (clamped both ways)."""
+    B, n_img, N, h, vocab = 4, 24, 64, 64, 50
+    cl = dec(B, N, h, 2, 96, 1)
+    seed = 880
+    counts = synth.integers(seed, (B,), 6, n_img + 1)
+    counts[0], counts[1] = 0, n_img
+    ids = synth.integers(seed + 1, (B, N), 0, vocab)
+    ids[2, N - 1] = vocab + 7                                   # outside the table: reads and updates the last row
+    ids_ref = np.clip(ids, 0, vocab - 1)
+    table = quantize(synth.normal(seed + 2, (vocab, h), 0, 0.02), dtype)
+    img = quantize(synth.normal(seed + 3, (B * n_img, h)), dtype)
+    target = quantize(synth.normal(seed + 4, (B * N, h)), dtype)
+    layers = quantize_tree([layer_params(cl, seed + 10)], dtype)
+    x_ref = O.concat_tokens_counts(img, O.embedding_fwd(ids_ref, table), B, n_img, N, counts)
+    y_ref, saved = O.stack_fwd(x_ref, layers, cl)
+    loss_ref = O.mse_fwd(y_ref, target)
+    dxl, g_ref = O.stack_bwd(O.mse_bwd(y_ref, target), layers, saved, cl)
+    dimg_ref, dtxt = O.split_tokens_counts(dxl, B, n_img, N, counts)
+    gtab_ref = O.embedding_bwd(ids_ref, dtxt, vocab)
+
+    stem = mb.Module(dict(kind="text_stem", batch=B, seq=N, hidden=h, vocab=vocab, n_img=n_img), dtype)
+    llm = mb.Module(cl, dtype)
+    try:
+        stem.set_tensor("table", table); load_layer_params(llm, layers)
+        ids_ = torch.from_numpy(ids.reshape(-1)).cuda(); counts_ = torch.from_numpy(counts).cuda()
+        stem.bind_ids(ids_); stem.bind_image_counts(counts_)
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        x0 = to_dev(img, dtype)
+        ys = [torch.empty(B * N * h, dtype=td, device="cuda") for _ in range(2)]
+        dxs = [torch.full((B * n_img * h,), 7.0, dtype=td, device="cuda"), torch.empty(B * N * h, dtype=td, device="cuda")]
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        mb.pool_reserve(256, 0, mb.STRIPED)
+        mb.stage_run([stem, llm], [x0, ys[0]], ys, [256, 256], [0, 0], mb.STRIPED, mb.CHAINED, dy=[dxs[1], None],
+                     target=[None, to_dev(target, dtype)], dx=dxs, loss=[None, loss])
+        assert np.array_equal(from_dev(ys[0]).reshape(B * N, h), x_ref), "sequence assembly is a copy: exact"
+        assert rel_l2(from_dev(ys[1]).reshape(B * N, h), y_ref) <= tol(dtype)
+        assert abs(loss.item() - loss_ref) <= tol(dtype) * loss_ref
+        dimg = from_dev(dxs[0]).reshape(B * n_img, h)
+        assert rel_l2(dimg, dimg_ref) <= tol(dtype)
+        for b in range(B):
+            assert not dimg[b * n_img + counts[b]:(b + 1) * n_img].any(), "unused image tokens must get zero gradient"
+        assert rel_l2(stem.get_tensor("table", grads=True), gtab_ref) <= tol(dtype)
+        g = read_layer_grads(llm, layers)[0]
+        for k in g_ref[0]:
+            assert rel_l2(g[k], g_ref[0][k]) <= tol(dtype), k
+    finally:
+        stem.destroy(); llm.destroy()

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import layers as O
 from paper_2605_18710_amd import synth
-from helpers import rel_l2, quantize, to_dev, from_dev, tol
+from helpers import rel_l2, quantize, to_dev, from_dev, tol, assert_close
 
 pytestmark = pytest.mark.gpu
 
@@ -61,10 +61,11 @@ def test_linear_fwd_dgrad_wgrad(mb, dtype, T, k, n):
         torch.cuda.synchronize()
         outs.append([bits(t) for t in (Y, dX, dW, db)])
         if q == QUOTAS[0]:
-            assert rel_l2(from_dev(Y), ref_y) <= tol(dtype)
-            assert rel_l2(from_dev(dX), ref_dx) <= tol(dtype)
-            assert rel_l2(from_dev(dW), ref_dw) <= tol(dtype)
-            assert rel_l2(from_dev(db), ref_db) <= tol(dtype)
+            # the stated relative L2 tolerance and, element by element, one rounding of an fp32 sum
+            assert_close(from_dev(Y), ref_y, dtype, "Y")
+            assert_close(from_dev(dX), ref_dx, dtype, "dX")
+            assert_close(from_dev(dW), ref_dw, dtype, "dW")
+            assert_close(from_dev(db), ref_db, dtype, "db")
     for o in outs[1:]:
         for a, b0 in zip(o, outs[0]):
             assert np.array_equal(a, b0), "result depends on the quota"
@@ -85,7 +86,7 @@ def test_linear_dgrad_without_residual_partial_round(mb, T, k, n):
         torch.cuda.synchronize()
         outs.append(bits(dX))
         if q == 256:
-            assert rel_l2(from_dev(dX), ref_dx) <= 2e-2
+            assert_close(from_dev(dX), ref_dx, "bf16", "dX")
     for o in outs[1:]:
         assert np.array_equal(o, outs[0]), "result depends on the quota"
 
@@ -166,11 +167,14 @@ def test_attention_fwd_bwd(mb, dtype, B, N, H, d, causal):
         torch.cuda.synchronize()
         outs.append([bits(Oo), bits(lse), bits(dqkv)])
         if q == QUOTAS[0]:
-            assert rel_l2(from_dev(Oo), ref_o) <= tol(dtype)
-            assert rel_l2(from_dev(lse), ref_lse) <= (1e-5 if dtype == "f32" else 1e-2)
+            # element by element too: the probabilities and dS are rounded to bf16 before their products, and
+            # dS = P (dP - delta) cancels where a row's probability sits on few keys, so the rounding of O
+            # inside delta shows: the gradients get a wider floor than a chain of plain roundings would
+            assert_close(from_dev(Oo), ref_o, dtype, "O", roundings=2)
+            assert_close(from_dev(lse), ref_lse, dtype, "lse", l2=(1e-5 if dtype == "f32" else 1e-2))
             got = from_dev(dqkv)
             for part in range(3):      # dq, dk, dv separately
-                assert rel_l2(got[:, part * h:(part + 1) * h], ref_d[:, part * h:(part + 1) * h]) <= tol(dtype), part
+                assert_close(got[:, part * h:(part + 1) * h], ref_d[:, part * h:(part + 1) * h], dtype, ("dq", "dk", "dv")[part], roundings=8)
     for o in outs[1:]:
         for a, b0 in zip(o, outs[0]):
             assert np.array_equal(a, b0)
@@ -206,11 +210,11 @@ def test_norm_fwd_bwd(mb, dtype, norm, T, h):
         torch.cuda.synchronize()
         outs.append([bits(y), bits(dx), bits(dg)] + ([bits(db)] if ref_db is not None else []))
         if q == QUOTAS[0]:
-            assert rel_l2(from_dev(y), ref_y) <= tol(dtype)
-            assert rel_l2(from_dev(dx), ref_dx) <= tol(dtype)
-            assert rel_l2(from_dev(dg), ref_dg) <= tol(dtype)
+            assert_close(from_dev(y), ref_y, dtype, "y")
+            assert_close(from_dev(dx), ref_dx, dtype, "dx", roundings=2)
+            assert_close(from_dev(dg), ref_dg, dtype, "dgamma", roundings=2)
             if ref_db is not None:
-                assert rel_l2(from_dev(db), ref_db) <= tol(dtype)
+                assert_close(from_dev(db), ref_db, dtype, "dbeta")
     for o in outs[1:]:
         for a, b0 in zip(o, outs[0]):
             assert np.array_equal(a, b0)

@@ -115,11 +115,16 @@ def test_decoder_cut_in_time_runs_two_stages(mb):
     from paper_2605_18710_amd.workload import SplitStage
     with pytest.raises(ValueError):
         SplitStage(0, 1)                        # the tiny workload's decoder has one layer: nothing to cut
-    st = SplitStage(1, 2)
+    st = SplitStage(1, 2, [32, 224])
     try:
-        r = st.run([32, 224])
+        created = mb.pool_creations()
+        st.run()
+        r = st.run()
+        assert mb.pool_creations() == created, "an iteration created a stream"
         assert len(r["stage_ms"]) == 2 and all(t > 0 for t in r["stage_ms"])
-        assert r["iteration_ms"] == pytest.approx(sum(r["stage_ms"]), rel=1e-6)
+        # the iteration is timed by the host clock across both stages: at least their sum (Eq. 1),
+        # and not much more (the gap between the two calls)
+        assert sum(r["stage_ms"]) <= r["iteration_ms"] <= sum(r["stage_ms"]) + 5.0
         assert len(r["module_ms"]) == len(st.first) + 1
         for m in st.first + [st.second]:
             assert torch.isfinite(m.y.float()).all()

@@ -86,6 +86,24 @@ def test_plan_validation_eq5():
     assert e.value.status == mb.EINVAL
 
 
+def test_plan_needs_a_hardware_queue_per_stream(monkeypatch):
+    """Streams that would have to share a hardware queue run one after the other: a colocated
+    plan with more distinct streams than queues is refused, modules that share a quota count once."""
+    monkeypatch.setenv("GPU_MAX_HW_QUEUES", "4")
+    assert mb.device_hw_queues() == 4
+    five = ([32, 32, 32, 32, 128], [0, 32, 64, 96, 128])
+    assert mb.plan_stream_count(*five, mb.STRIPED, mb.COLOCATED) == 5
+    assert mb.plan_stream_count(*five, mb.STRIPED, mb.TIME_SLICED) == 1
+    with pytest.raises(mb.MosaicError) as e:
+        mb.plan_validate(*five, mb.STRIPED, mb.COLOCATED, 256, 8)
+    assert e.value.status == mb.EQUOTA and "hardware queues" in str(e.value)
+    shared = ([32, 32, 32, 32, 128], [0, 0, 32, 64, 96])          # the first two modules share a stream
+    assert mb.plan_stream_count(*shared, mb.STRIPED, mb.COLOCATED) == 4
+    mb.plan_validate(*shared, mb.STRIPED, mb.COLOCATED, 256, 8)
+    monkeypatch.setenv("GPU_MAX_HW_QUEUES", "8")
+    mb.plan_validate(*five, mb.STRIPED, mb.COLOCATED, 256, 8)
+
+
 def test_plan_choose_matches_exhaustive_oracle():
     pts = [32, 64, 96, 128, 160, 192, 224]
     for seed in range(20):
@@ -199,8 +217,11 @@ def test_committed_gemm_traffic_parses_and_is_not_below_the_algorithmic_bytes():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     sys.path.insert(0, root)
     import bench
-    T, k, n = 8192, 2048, 11264                      # the roofline shape of configs[1]
-    algorithmic = 2 * (T * k + k * n + T * n)
-    for form in ("fprop", "dgrad", "wgrad"):
-        t = bench.profiled_traffic(form)
-        assert isinstance(t, int) and algorithmic <= t < 8 * algorithmic, (form, t)
+    for (T, k, n) in bench.PROFILE_OF_SHAPE:         # the roofline shapes of configs[1] and of the 7B-shaped decoders
+        if not os.path.exists(os.path.join(root, "profiles", bench.PROFILE_OF_SHAPE[(T, k, n)])):
+            continue
+        algorithmic = 2 * (T * k + k * n + T * n)
+        for form in ("fprop", "dgrad", "wgrad"):
+            t = bench.profiled_traffic(form, (T, k, n))
+            assert isinstance(t, int) and algorithmic <= t < 8 * algorithmic, (form, t)
+    assert bench.profiled_traffic("fprop", (8, 8, 8)) is None
