@@ -322,21 +322,25 @@ def cpu_baseline(wl, budget_tflop=6.0):
                        "; stage time extrapolated as sum(sample time x batch/sampled batch x layers), projector omitted")
 
 
-def candidate_quotas(t_full_ms, t_budget_ms, cus, lo=8, step=8, max_points=10):
-    """Quotas at which a module is worth measuring alone: multiples of `step` from the smallest at
-    which it could still finish within t_budget_ms if its time scaled as 1/CUs, up to what the
-    other modules leave; thinned to at most max_points, keeping the ends."""
-    q_min = max(lo, int(t_full_ms * cus / t_budget_ms) // step * step)
-    qs = list(range(q_min, cus, step))
-    if len(qs) > max_points:
-        keep = {qs[0], qs[-1]}
-        stride = (len(qs) - 1) / (max_points - 1)
-        keep |= {qs[int(round(i * stride))] for i in range(max_points)}
-        qs = sorted(keep)
+def candidate_quotas(t_full_ms, t_budget_ms, cus, lo=8, max_points=11):
+    """Quotas at which a module is worth measuring alone.  From the smallest at which it could
+    still finish within t_budget_ms if its time scaled as 1/CUs: steps of 8 CUs below 64 (a
+    quota below 32 CUs, or a multiple of 32, has all its CUs busy at once; any other keeps only
+    the multiple of 32 below it busy, so the fine steps matter for the small modules only), then
+    multiples of 32, plus 240 and 248 to show what the large module gets from the last CUs."""
+    q_min = max(lo, int(t_full_ms * cus / t_budget_ms) // 8 * 8)
+    top = [cus - 16, cus - 8] if q_min >= cus // 2 else []
+    qs = [q for q in list(range(8, 64, 8)) + list(range(64, cus, 32)) + top if q_min <= q < cus]
+    qs = sorted(set(qs))
+    while len(qs) > max_points:          # drop the densest interior point
+        gaps = [(qs[i + 1] - qs[i - 1], i) for i in range(1, len(qs) - 1) if qs[i] % 32]
+        if not gaps:
+            break
+        qs.pop(min(gaps)[1])
     return qs
 
 
-def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=False, fine=True):
+def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=False):
     """Builds the staged workload `config`, measures the time-sliced baseline, the time-vs-CU
     curves, every named plan plus the plans derived from the curves (three-way, two modules
     sharing a quota, and the planner's stages), then times `steps` iterations of the best one."""
@@ -412,25 +416,33 @@ def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=
     grid = list(range(8, cus, 8))
     curves = [[1e30] * len(grid) for _ in range(ngroups)]
     for g in range(ngroups):
-        for q in candidate_quotas(group_ms_full[g], 1.25 * ts_ms, cus) if fine else [q for q in range(32, cus, 32)]:
+        for q in candidate_quotas(group_ms_full[g], 1.25 * ts_ms, cus):
             one = dict(label="curve", stages=[dict(groups=[g], quotas=[q], offsets=[0])])
             curves[g][grid.index(q)] = median_plan(one, 2)[0]
     chosen, predicted = mb.plan_choose(grid, curves, cus)
 
     plans = [packed(p, "named") for p in wl["plans"]]
     plans.append(packed(chosen, "chosen from the curves (Eq. 4-5)"))
-    if fine and ngroups == 3:
+    if ngroups == 3:
         # the two small modules share one quota and run back to back beside the large one
+        big = max(range(ngroups), key=lambda g: group_ms_full[g])
+        small = [g for g in range(ngroups) if g != big]
         best = None
         for qi, q in enumerate(grid):
-            if curves[0][qi] < 1e29 and curves[1][qi] < 1e29 and curves[2][grid.index(cus - q)] < 1e29 if (cus - q) in grid else False:
-                t = max(curves[0][qi] + curves[1][qi], curves[2][grid.index(cus - q)])
+            if (cus - q) not in grid:
+                continue
+            ts_ = [curves[g][qi] for g in small]
+            tb = curves[big][grid.index(cus - q)]
+            if max(ts_) < 1e29 and tb < 1e29:
+                t = max(sum(ts_), tb)
                 if best is None or t < best[0]:
                     best = (t, q)
         if best:
             q = best[1]
+            qs, offs = [q] * ngroups, [cus - q] * ngroups
+            qs[big], offs[big] = cus - q, 0
             plans.append(dict(label="small modules share a quota", predicted_ms=round(best[0], 4),
-                              stages=[dict(groups=[0, 1, 2], quotas=[q, q, cus - q], offsets=[cus - q, cus - q, 0])]))
+                              stages=[dict(groups=list(range(ngroups)), quotas=qs, offsets=offs)]))
     if ngroups >= 3:
         # Alg. 1 on the measured curves: stages of modules that pay to run side by side
         # (the planner takes up to 16 quota levels: the measured ones, thinned if need be, plus the whole device)

@@ -2,8 +2,11 @@
 module's time-vs-CU curve (the scaling surface of Sec. 3.3 restricted to one GPU), derives
 the bandwidth-utilisation proxy, fits the interference coefficients of Eq. 8 from a few
 colocated probe runs, forms stages with Alg. 1 and executes the stages one after another,
-each colocated under its allocation.  Only argument marshalling and bookkeeping happen
-here; every step of the arithmetic runs in the library.
+each colocated under its allocation.  The fit of Eq. 8, StageEval and Alg. 1 run in the
+library; what is formed here, in Python, is bookkeeping around them: the utilisation proxy
+B(m, a) (a module's algorithmic bytes or model FLOPs, from `synth`, divided by its measured
+time and the peak -- a stand-in for the counter reading the paper profiles, not one) and the
+delay observations (differences and ratios of measured times).
 """
 from __future__ import annotations
 
