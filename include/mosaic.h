@@ -414,6 +414,18 @@ mosaic_status mosaic_op_swiglu_fwd(void* stream, int32_t quota, int32_t dtype, i
                                    int64_t f, const void* gu, void* a);
 mosaic_status mosaic_op_swiglu_bwd(void* stream, int32_t quota, int32_t dtype, int64_t T,
                                    int64_t f, const void* gu, const void* da, void* dgu);
+/* A linear layer followed by its activation, as the MLP blocks of the modules use it (the paper
+ * schedules whole modules, Sec. 3.1; the layer arithmetic is this build's): Z[T,n] = X[T,k]
+ * W[k,n] (+ bias[n], may be NULL) and A = act(Z).  act = MOSAIC_GELU or MOSAIC_GELU_TANH: A is
+ * [T,n].  act = MOSAIC_SWIGLU: Z = [gate | up] halves of n/2 columns, A[T,n/2] = silu(gate)*up.
+ * Z is kept because the backward pass needs it.  All pointers are device memory owned by the
+ * caller.  For bf16 operands whose sizes and alignment suit the matrix-core kernel (SwiGLU: n
+ * a multiple of 256) the activation is applied in that kernel's epilogue and no second pass is
+ * launched; otherwise the product is followed by the elementwise kernel.  Both roads give the
+ * same bits.  MOSAIC_EINVAL for an unknown activation, negative sizes or an odd n with SwiGLU. */
+mosaic_status mosaic_op_linear_act_fwd(void* stream, int32_t quota, int32_t dtype, int32_t act,
+                                       int64_t T, int64_t k, int64_t n, const void* X,
+                                       const void* W, const void* bias, void* Z, void* A);
 /* loss = mean((y-target)^2) -> *loss (device f32); dy = 2 (y-target)/n.
  * scratch: at least mosaic_op_mse_scratch_bytes(). */
 mosaic_status mosaic_op_mse(void* stream, int32_t quota, int32_t dtype, int64_t n,

@@ -133,6 +133,7 @@ SIGNATURES = {
     "mosaic_op_adamw": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _f32, _i64]),
     "mosaic_op_swiglu_fwd": (_i32, [_vp, _i32, _i32, _i64, _i64, _vp, _vp]),
     "mosaic_op_swiglu_bwd": (_i32, [_vp, _i32, _i32, _i64, _i64, _vp, _vp, _vp]),
+    "mosaic_op_linear_act_fwd": (_i32, [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_mse": (_i32, [_vp, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp]),
     "mosaic_op_mse_scratch_bytes": (_sz, []),
 }
@@ -563,6 +564,10 @@ def op_adamw(stream, quota, dtype, n, params, grads, m, v, master, lr, beta1, be
 
 def op_swiglu_fwd(stream, quota, dtype, T, f, gu, a):
     check(lib().mosaic_op_swiglu_fwd(stream, quota, _dt(dtype), T, f, _ptr(gu), _ptr(a)))
+
+
+def op_linear_act_fwd(stream, quota, dtype, act, T, k, n, X, W, bias, Z, A):
+    check(lib().mosaic_op_linear_act_fwd(stream, quota, _dt(dtype), act, T, k, n, _ptr(X), _ptr(W), _ptr(bias), _ptr(Z), _ptr(A)))
 
 
 def op_swiglu_bwd(stream, quota, dtype, T, f, gu, da, dgu):

@@ -212,6 +212,14 @@ mosaic_status mosaic_op_swiglu_fwd(void* stream, int32_t quota, int32_t dtype, i
   return launch_swiglu_fwd((hipStream_t)stream, quota, dtype, T, f, gu, a);
 }
 
+mosaic_status mosaic_op_linear_act_fwd(void* stream, int32_t quota, int32_t dtype, int32_t act, int64_t T, int64_t k, int64_t n,
+                                       const void* X, const void* W, const void* bias, void* Z, void* A) {
+  MOSAIC_TRY(check_common(quota, dtype));
+  if (T < 0 || k <= 0 || n < 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad linear shape T=%lld k=%lld n=%lld", (long long)T, (long long)k, (long long)n);
+  NONNULL(X); NONNULL(W); NONNULL(Z); NONNULL(A);
+  return launch_linear_act_fwd((hipStream_t)stream, quota, dtype, act, T, k, n, X, W, bias, Z, A);
+}
+
 mosaic_status mosaic_op_swiglu_bwd(void* stream, int32_t quota, int32_t dtype, int64_t T, int64_t f, const void* gu,
                                    const void* da, void* dgu) {
   MOSAIC_TRY(check_common(quota, dtype));

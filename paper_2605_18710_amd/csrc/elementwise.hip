@@ -5,6 +5,7 @@
 //
 // All reductions run in an order fixed by the problem shape alone: persistent grids only
 // decide which workgroup handles a work item, so results are bit-identical for any quota.
+#include "activations.h"
 #include "kernels.h"
 
 namespace {
@@ -345,11 +346,7 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
 }
 
 // -------------------------------------------------------------------------- activations
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_grad_f(float z) {
-  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * expf(-0.5f * z * z) * 0.39894228040143268f;
-}
-__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
+// gelu_f, gelu_grad_f, sigmoid_f, swiglu_f: activations.h
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const T* __restrict__ z, T* __restrict__ a, int64_t nvec) {
@@ -390,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void swiglu_fwd_kernel(const T* __restric
     g.load(gu + r * 2 * f + c);
     u.load(gu + r * 2 * f + f + c);
 #pragma unroll
-    for (int k = 0; k < VN; ++k) { const float z = g.get(k); o.set(k, z * sigmoid_f(z) * u.get(k)); }
+    for (int k = 0; k < VN; ++k) o.set(k, swiglu_f(g.get(k), u.get(k)));
     o.store(a + r * f + c);
   }
 }

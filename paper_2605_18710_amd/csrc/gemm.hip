@@ -40,6 +40,7 @@
 #include <stdlib.h>
 #include <mutex>
 #include <type_traits>
+#include "activations.h"
 #include "kernels.h"
 #include "tile_queue.h"
 
@@ -73,7 +74,12 @@ constexpr int AHEAD = 4;          // K-tiles between the load cursor and the com
 //     16-byte chunks of row r stored at position chunk ^ (r/4)%4.
 //   K-strided operand: LDS rows of ROWS*2 bytes (one k-row of the tile), the 64-byte chunks
 //     of k-row k stored at position chunk ^ k%4; fragments come out with transposing reads.
-template <int ROWS, bool KC, int NWAVES>
+// GU (K-strided operand only): the tile's columns are not consecutive columns of the matrix.
+// The matrix is [gate | up] halves of gu_f columns each; 32-column group c of the tile is
+// group c/2 of the gate half (c even) or of the up half (c odd), counted from column x0/2,
+// so that a wave's two 32-column accumulator blocks hold a gate column and its up column
+// in the same lane and register.
+template <int ROWS, bool KC, int NWAVES, bool GU = false>
 struct DmaLoader {
   static constexpr int NI = ROWS / 16 / NWAVES;     // wave instructions per wave and K-tile
   static constexpr int ROWB = ROWS * 2;             // strided: bytes per k-row
@@ -86,7 +92,8 @@ struct DmaLoader {
   int xofs[NI];         // strided: first tile column of this lane's chunk
   int wave_base;        // LDS byte offset of this wave's first instruction inside the operand area
 
-  __device__ __forceinline__ void init(int64_t ld) {
+  __device__ __forceinline__ void init(int64_t ld, int gu_f = 0) {
+    static_assert(!(GU && KC), "the gate/up column map exists for the K-strided operand");
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     wave_base = w * NI * 1024;
@@ -105,7 +112,9 @@ struct DmaLoader {
         const int kr = (w * NI + j) * RPI + byte / ROWB, bp = byte % ROWB;
         const int c64 = (bp >> 6) ^ (kr & 3), p = (bp & 63) >> 4;
         xofs[j] = c64 * 32 + p * 8;
-        rel[j] = (unsigned)(((int64_t)kr * ld + xofs[j]) * 2);
+        int64_t gcol = xofs[j];
+        if constexpr (GU) gcol = (c64 >> 1) * 32 + p * 8 + (int64_t)(c64 & 1) * gu_f;
+        rel[j] = (unsigned)(((int64_t)kr * ld + gcol) * 2);
         kstep = (unsigned)(BK * ld * 2);
       }
     }
@@ -115,6 +124,7 @@ struct DmaLoader {
     Tile tl;
     tl.oobmask = 0;
     if constexpr (KC) tl.org = (unsigned)((int64_t)x0 * ld * 2);
+    else if constexpr (GU) tl.org = (unsigned)x0;      // column x0/2 of each half, 2 bytes each; halves are whole tiles wide
     else {
       tl.org = (unsigned)(x0 * 2);
 #pragma unroll
@@ -203,13 +213,30 @@ struct WorkItem {
 // cursor runs AHEAD K-tiles ahead of the compute cursor and crosses item boundaries, so
 // the first tiles of the next item are already in LDS while the epilogue of the current one
 // runs (the other wave on the SIMD keeps the matrix cores busy meanwhile).
-template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK>
+//
+// ACT (forward form only): the epilogue also writes an activation of the output to C2, so the
+// pass that would read the output back is never launched.  ACT_GELU: C2 = gelu(C), same shape.
+// ACT_SWIGLU: C is [gate | up] with gu_f columns each and C2[M, gu_f] = silu(gate) * up; the
+// weight tile's columns are gathered so that a wave holds matching gate and up columns
+// (DmaLoader GU).  The activation is taken of the bf16 value that is stored to C, as the
+// separate pass would.
+constexpr int ACT_NONE = 0, ACT_GELU = 1, ACT_SWIGLU = 2;
+struct ActArgs {
+  int act = ACT_NONE;
+  bf16* C2 = nullptr;
+  int64_t ldc2 = 0;
+  uint32_t c2_bytes = 0;
+  int gu_f = 0;
+};
+
+template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK, int ACT = ACT_NONE>
 __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
     const bf16* __restrict__ bias, const bf16* __restrict__ R, int M, int N, int K,
     int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
     int tiles_m, int tiles_n, int tile_begin, int tile_count, int sub, int ksplit, int ktiles_per,
-    float* __restrict__ P, TileQueueArgs tq) {
+    float* __restrict__ P, TileQueueArgs tq, ActArgs aa) {
+  static_assert(ACT == ACT_NONE || (A_KC && !B_KC && !SPLITK), "activation epilogues exist for the forward form");
   constexpr int NT = 64 * NWM * NWN;
   constexpr int WM = BM / NWM, WN = BN / NWN;   // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -347,9 +374,9 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   }
 
   typedef DmaLoader<BM, A_KC, NWM * NWN> LA;
-  typedef DmaLoader<BN, B_KC, NWM * NWN> LB;
+  typedef DmaLoader<BN, B_KC, NWM * NWN, ACT == ACT_SWIGLU> LB;
   LA la; LB lb;
-  la.init(lda); lb.init(ldb);
+  la.init(lda); lb.init(ldb, aa.gu_f);
   constexpr int NLOADS = LA::NI + LB::NI;      // requests per lane and K-tile
 
   // load cursor: the next K-tile to request
@@ -618,6 +645,105 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     __syncthreads();               // the patch lives in the stage the next step overwrites
   };
+  // Activation variants (forward form, no residual): every row block passes through the patch
+  // twice, first the output itself (bias added in fp32, rounded to bf16) on its way to C, then
+  // the activation of those rounded values on its way to C2.  The bias descriptor of a null
+  // bias is empty and reads zeros.
+  auto finish_act = [&](const WorkItem& it, int free_stage) {
+    static_assert(ACT == ACT_NONE || TN == 2, "a wave holds two 32-column blocks");
+    constexpr bool GU = ACT == ACT_SWIGLU;
+    unsigned char* patch = smem + free_stage + wave * 4096;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int elr = ln & 31, ehb = ln >> 5;
+    const __amdgpu_buffer_rsrc_t rc2 = make_rsrc(aa.C2, aa.c2_bytes);
+    // first column in C of the wave's accumulator block 0 and block 1
+    const int zc0 = GU ? (it.n0 >> 1) + (wn >> 1) : it.n0 + wn;
+    const int zc1 = GU ? zc0 + aa.gu_f : zc0 + 32;
+    u32x2 braw[8];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = (j ? zc1 : zc0) + 8 * g + 4 * ehb;
+        braw[4 * j + g] = __builtin_amdgcn_raw_buffer_load_b64(rbias, col < N ? col * 2 : (int)kOob, 0, 0);
+      }
+    const int wr = elr * 128 + ehb * 8, wsx = (elr >> 1) & 7;
+    const int c16 = ln & 7;
+    // column this lane writes back (16 bytes = 8 columns of patch chunk c16), in C and in C2
+    const int zcol = c16 < 4 ? zc0 + 8 * c16 : zc1 + 8 * (c16 - 4);
+    const int acol = GU ? (c16 < 4 ? zc0 + 8 * c16 : -1) : zcol;
+    const int a_n = GU ? aa.gu_f : N;
+    // the value stored to C for accumulator register (i, j, 4g+e)
+    auto zval = [&](int i, int j, int g, int e) -> float {
+      const bf16x4 bv = __builtin_bit_cast(bf16x4, braw[4 * j + g]);
+      return (float)(bf16)(acc[i][j][4 * g + e] + (float)bv[e]);
+    };
+    auto patch_sync = [&]() {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // patch (32 rows of 128 bytes, chunks XOR-swizzled) -> rows of `rsrc`, 8 rows per instruction
+    auto drain = [&](int i, __amdgpu_buffer_rsrc_t rsrc, int64_t ld, int col, int ncols) {
+      u32x4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = (ln >> 3) + 8 * q;
+        v[q] = *reinterpret_cast<const u32x4*>(patch + r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = it.m0 + wm + 32 * i + (ln >> 3) + 8 * q;
+        const unsigned off = (col >= 0 && col < ncols) ? (unsigned)(((int64_t)row * ld + col) * 2) : kOob;
+        __builtin_amdgcn_raw_buffer_store_b128(v[q], rsrc, (int)off, 0, 0);
+      }
+    };
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)zval(i, j, g, e);
+          *reinterpret_cast<bf16x4*>(patch + wr + (((4 * j + g) ^ wsx) << 4)) = o;
+        }
+      patch_sync();
+      drain(i, rc, ldc, zcol, N);
+      patch_sync();
+      if constexpr (GU) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)swiglu_f(zval(i, 0, g, e), zval(i, 1, g, e));
+          *reinterpret_cast<bf16x4*>(patch + wr + ((g ^ wsx) << 4)) = o;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)gelu_f(zval(i, j, g, e));
+            *reinterpret_cast<bf16x4*>(patch + wr + (((4 * j + g) ^ wsx) << 4)) = o;
+          }
+      }
+      patch_sync();
+      drain(i, rc2, aa.ldc2, acol, a_n);
+      patch_sync();
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    __syncthreads();               // the patch lives in the stage the next step overwrites
+  };
   // Only the forward form meets a bias without a residual often enough to hold a variant for
   // it; elsewhere such a call takes EPI_RES, whose empty residual descriptor reads zeros.
   constexpr bool BIAS_VARIANT = A_KC && !B_KC;
@@ -626,6 +752,8 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   auto finish = [&](const WorkItem& it, int free_stage) {
     if constexpr (SPLITK) {
       finish_impl(it, free_stage, std::integral_constant<int, EPI_PLAIN>{});
+    } else if constexpr (ACT != ACT_NONE) {
+      finish_act(it, free_stage);
     } else {
       if (epi_mode == EPI_RES) { finish_impl(it, free_stage, std::integral_constant<int, EPI_RES>{}); return; }
       if constexpr (BIAS_VARIANT) {
@@ -1003,14 +1131,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 
 // One launch of the MFMA kernel over coarse tiles [tile_begin, tile_begin + tile_count) of the
 // panel-major list of (sub*BM) x (sub*BN) tiles; tile_count < 0 means all of them.
-template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK = false>
+template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK = false, int ACT = ACT_NONE>
 mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda,
                           const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
                           uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, int ksplit = 1,
                           int ktiles_per = 0, float* P = nullptr, int sub = 1, int tile_begin = 0,
-                          int tile_count = -1) {
+                          int tile_count = -1, const ActArgs& aa = ActArgs()) {
   constexpr size_t smem = (size_t)NS * (BM + BN) * 64;
-  auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK>;
+  auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, A_KC, B_KC, SPLITK, ACT>;
   static std::once_flag attr_once;   // per instantiation; launches come from several host threads
   static hipError_t attr_rc = hipSuccess;
   std::call_once(attr_once, [&] {
@@ -1027,7 +1155,7 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
   int grid;
   MOSAIC_TRY(tile_queue_plan(s, quota, wg_per_cu, items, 0, false, &tq, &grid));
   kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq);
+                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq, aa);
   MOSAIC_LAUNCH_CHECK();
   if (SPLITK) {
     const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
@@ -1102,7 +1230,8 @@ int splitk_factor(int64_t M, int64_t N, int64_t K) {
 template <bool A_KC, bool B_KC>
 mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, const bf16* A, int64_t lda,
                                 const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
-                                uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, void* splitk_scratch) {
+                                uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, void* splitk_scratch,
+                                const ActArgs& aa = ActArgs()) {
   if constexpr (!A_KC && !B_KC) {
     const int sk = splitk_factor(M, N, K);
     if (sk > 1 && splitk_scratch && !bias && !R) {
@@ -1141,18 +1270,32 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   int plan = cost256 <= cost128 ? (cost256 <= cost_mix ? 256 : 0) : (cost128 <= cost_mix ? 128 : 0);
   if (forced_tile() == 128 || forced_tile() == 256) plan = forced_tile();
   if (forced_tile() == 1 && whole > 0 && rest > 0) plan = 0;
+  // one launch of the eight-wave (big) or four-wave quarter-tile kernel over coarse tiles
+  // [tile_begin, tile_begin + tile_count) (tile_count < 0: all), with the epilogue `aa` asks for
+  auto launch_tiles = [&](auto big_, int sub, int tile_begin, int tile_count) -> mosaic_status {
+    constexpr bool BIG = decltype(big_)::value;
+    constexpr int TB = BIG ? 256 : 128, WN_ = BIG ? 4 : 2;
+    if constexpr (A_KC && !B_KC) {
+      if (aa.act == ACT_GELU)
+        return launch_mfma<TB, TB, 2, WN_, A_KC, B_KC, false, ACT_GELU>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
+                                                                        c_bytes, 1, 0, nullptr, sub, tile_begin, tile_count, aa);
+      if (aa.act == ACT_SWIGLU)
+        return launch_mfma<TB, TB, 2, WN_, A_KC, B_KC, false, ACT_SWIGLU>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
+                                                                          c_bytes, 1, 0, nullptr, sub, tile_begin, tile_count, aa);
+    }
+    return launch_mfma<TB, TB, 2, WN_, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes, 1, 0,
+                                                   nullptr, sub, tile_begin, tile_count);
+  };
   if (plan == 256) {
     if (kc4w) return launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
-    return launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+    return launch_tiles(std::true_type{}, 1, 0, -1);
   }
-  if (plan == 128) return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes);
+  if (plan == 128) return launch_tiles(std::false_type{}, 1, 0, -1);
   const int head = (int)(whole * quota);
   mosaic_status st = kc4w ? launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, head)
-                          : launch_mfma<256, 256, 2, 4, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
-                                                                    b_bytes, c_bytes, 1, 0, nullptr, 1, 0, head);
+                          : launch_tiles(std::true_type{}, 1, 0, head);
   if (st != MOSAIC_OK) return st;
-  return launch_mfma<128, 128, 2, 2, A_KC, B_KC>(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes,
-                                                 c_bytes, 1, 0, nullptr, 2, head, (int)rest);
+  return launch_tiles(std::false_type{}, 2, head, (int)rest);
 }
 
 }  // namespace
@@ -1162,9 +1305,13 @@ size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K) {
   return sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc, int64_t M, int64_t N,
+// fused != null: a forward-form call that also wants act(C) in C2; *fused says whether the
+// launch took care of it
+static mosaic_status launch_gemm_impl(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc, int64_t M, int64_t N,
                           int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
-                          int64_t ldc, const void* bias, const void* R, void* splitk_scratch) {
+                          int64_t ldc, const void* bias, const void* R, void* splitk_scratch,
+                          int act, void* C2, int64_t ldc2, bool* fused) {
+  if (fused) *fused = false;
   if (M < 0 || N < 0 || K < 0) MOSAIC_FAIL(MOSAIC_EINVAL, "negative GEMM size");
   if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "GEMM dimension too large");
   if (M == 0 || N == 0) return MOSAIC_OK;
@@ -1182,7 +1329,22 @@ mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b
     const uint32_t ab = (uint32_t)a_ext, bb = (uint32_t)b_ext, cb = (uint32_t)c_ext;
     const bf16 *a = (const bf16*)A, *b = (const bf16*)B, *bi = (const bf16*)bias, *r = (const bf16*)R;
     bf16* c = (bf16*)C;
-    if (a_kc && !b_kc) return launch_mfma_shape<true, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
+    if (a_kc && !b_kc) {
+      ActArgs aa;
+      if (fused && C2 && !R && (uintptr_t)C2 % 16 == 0 && ldc2 % 8 == 0) {
+        const int64_t n2 = act == MOSAIC_SWIGLU ? N / 2 : N;
+        const int64_t c2_ext = ((M - 1) * ldc2 + n2) * 2;
+        // gate and up halves must be whole quarter tiles wide: a tile then never straddles the halves
+        const bool ok = c2_ext < lim && (act == MOSAIC_GELU || (act == MOSAIC_SWIGLU && N % 256 == 0));
+        if (ok) {
+          aa.act = act == MOSAIC_GELU ? ACT_GELU : ACT_SWIGLU;
+          aa.C2 = (bf16*)C2; aa.ldc2 = ldc2; aa.c2_bytes = (uint32_t)c2_ext;
+          aa.gu_f = act == MOSAIC_SWIGLU ? (int)(N / 2) : 0;
+          *fused = true;
+        }
+      }
+      return launch_mfma_shape<true, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch, aa);
+    }
     if (a_kc && b_kc) return launch_mfma_shape<true, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
     if (!a_kc && !b_kc) return launch_mfma_shape<false, false>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
     return launch_mfma_shape<false, true>(s, quota, (int)M, (int)N, (int)K, a, lda, b, ldb, c, ldc, bi, r, ab, bb, cb, splitk_scratch);
@@ -1199,4 +1361,24 @@ mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b
                                                     (const float*)R, (int)M, (int)N, (int)K, sam, sak, sbk, sbn, ldc, tiles_m, tiles_n);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
+}
+
+mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b_kc, int64_t M, int64_t N,
+                          int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                          int64_t ldc, const void* bias, const void* R, void* splitk_scratch) {
+  return launch_gemm_impl(s, quota, dtype, a_kc, b_kc, M, N, K, A, lda, B, ldb, C, ldc, bias, R, splitk_scratch, 0, nullptr, 0, nullptr);
+}
+
+mosaic_status launch_linear_act_fwd(hipStream_t s, int quota, int dtype, int act, int64_t T, int64_t k, int64_t n,
+                                    const void* X, const void* W, const void* bias, void* Z, void* Aout) {
+  if (act != MOSAIC_GELU && act != MOSAIC_SWIGLU && act != MOSAIC_GELU_TANH) MOSAIC_FAIL(MOSAIC_EINVAL, "unknown activation %d", act);
+  if (act == MOSAIC_SWIGLU && (n % 2)) MOSAIC_FAIL(MOSAIC_EINVAL, "SwiGLU needs an even output width, got %lld", (long long)n);
+  const int64_t na = act == MOSAIC_SWIGLU ? n / 2 : n;
+  bool fused = false;
+  MOSAIC_TRY(launch_gemm_impl(s, quota, dtype, true, false, T, n, k, X, k, W, n, Z, n, bias, nullptr, nullptr, act, Aout, na,
+                              act == MOSAIC_GELU_TANH ? nullptr : &fused));
+  if (fused || T == 0 || n == 0) return MOSAIC_OK;
+  if (act == MOSAIC_SWIGLU) return launch_swiglu_fwd(s, quota, dtype, T, na, Z, Aout);
+  if (act == MOSAIC_GELU_TANH) return launch_gelu_tanh_fwd(s, quota, dtype, T * n, Z, Aout);
+  return launch_gelu_fwd(s, quota, dtype, T * n, Z, Aout);
 }

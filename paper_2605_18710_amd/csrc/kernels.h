@@ -14,6 +14,12 @@ mosaic_status launch_gemm(hipStream_t s, int quota, int dtype, bool a_kc, bool b
                           int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                           const void* B, int64_t ldb, void* C, int64_t ldc,
                           const void* bias, const void* R, void* splitk_scratch = nullptr);
+// Z[T,n] = X[T,k] W[k,n] (+ bias[n]) and A = act(Z): GELU / tanh GELU give A[T,n]; SwiGLU reads Z
+// as [gate | up] halves and gives A[T,n/2] = silu(gate) * up.  Where the bf16 matrix-core kernel
+// takes the product, the activation is applied in its epilogue (same bits as the separate pass);
+// otherwise the elementwise kernel follows the product.
+mosaic_status launch_linear_act_fwd(hipStream_t s, int quota, int dtype, int act, int64_t T, int64_t k, int64_t n,
+                                    const void* X, const void* W, const void* bias, void* Z, void* A);
 // Bytes of fp32 scratch the weight-gradient form wants for a deterministic split of a long
 // contraction over few output tiles (0 when no split is used for this shape).
 size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K);

@@ -283,10 +283,8 @@ mosaic_status layers_forward(mosaic_module* m, hipStream_t s, int q, const void*
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, h, W(m, sv.o), h, P(m, p.w_o), h, W(m, sv.x1), h, P(m, p.b_o), xin));
     MOSAIC_TRY(launch_norm_fwd(s, q, dt, d.norm, T, h, d.eps, W(m, sv.x1), P(m, p.n2_g), P(m, p.n2_b), W(m, sv.u2), (float*)W(m, sv.st2)));
     const int64_t zf = glu ? 2 * f : f;
-    MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, zf, h, W(m, sv.u2), h, P(m, p.w_1), zf, W(m, sv.z), zf, P(m, p.b_1), nullptr));
-    if (glu) MOSAIC_TRY(launch_swiglu_fwd(s, q, dt, T, f, W(m, sv.z), W(m, sv.a)));
-    else if (d.act == MOSAIC_GELU_TANH) MOSAIC_TRY(launch_gelu_tanh_fwd(s, q, dt, T * f, W(m, sv.z), W(m, sv.a)));
-    else MOSAIC_TRY(launch_gelu_fwd(s, q, dt, T * f, W(m, sv.z), W(m, sv.a)));
+    // up projection and activation in one launch where the matrix-core kernel takes it
+    MOSAIC_TRY(launch_linear_act_fwd(s, q, dt, d.act, T, h, zf, W(m, sv.u2), P(m, p.w_1), P(m, p.b_1), W(m, sv.z), W(m, sv.a)));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, f, W(m, sv.a), f, P(m, p.w_2), h, yout, h, P(m, p.b_2), W(m, sv.x1)));
     xin = yout;
   }
@@ -351,8 +349,7 @@ mosaic_status projector_forward(mosaic_module* m, hipStream_t s, int q, const vo
   const LayerParams& p = m->lp[0];
   const LayerSaved& sv = m->ls[0];
   const int64_t T = m->T;
-  MOSAIC_TRY(launch_gemm(s, q, d.dtype, true, false, T, d.out_dim, d.in_dim, x, d.in_dim, P(m, p.w_1), d.out_dim, W(m, sv.z), d.out_dim, P(m, p.b_1), nullptr));
-  MOSAIC_TRY(launch_gelu_fwd(s, q, d.dtype, T * d.out_dim, W(m, sv.z), W(m, sv.a)));
+  MOSAIC_TRY(launch_linear_act_fwd(s, q, d.dtype, MOSAIC_GELU, T, d.in_dim, d.out_dim, x, P(m, p.w_1), P(m, p.b_1), W(m, sv.z), W(m, sv.a)));
   MOSAIC_TRY(launch_gemm(s, q, d.dtype, true, false, T, d.out_dim, d.out_dim, W(m, sv.a), d.out_dim, P(m, p.w_2), d.out_dim, y, d.out_dim, P(m, p.b_2), nullptr));
   return MOSAIC_OK;
 }
@@ -407,11 +404,9 @@ mosaic_status conv_stem_forward(mosaic_module* m, hipStream_t s, int q, const vo
   const int dt = d.dtype, C = d.in_dim, h = d.hidden, Lo = d.seq, L = 2 * d.seq;
   const int64_t T = m->T, Tin = 2 * T;
   MOSAIC_TRY(launch_im2col1d(s, q, dt, d.batch, L, L, C, 1, x, W(m, m->c_p1)));
-  MOSAIC_TRY(launch_gemm(s, q, dt, true, false, Tin, h, 3 * C, W(m, m->c_p1), 3 * C, P(m, p.w_1), h, W(m, m->c_z1), h, P(m, p.b_1), nullptr));
-  MOSAIC_TRY(launch_gelu_fwd(s, q, dt, Tin * h, W(m, m->c_z1), W(m, m->c_a1)));
+  MOSAIC_TRY(launch_linear_act_fwd(s, q, dt, MOSAIC_GELU, Tin, 3 * C, h, W(m, m->c_p1), P(m, p.w_1), P(m, p.b_1), W(m, m->c_z1), W(m, m->c_a1)));
   MOSAIC_TRY(launch_im2col1d(s, q, dt, d.batch, L, Lo, h, 2, W(m, m->c_a1), W(m, m->c_p2)));
-  MOSAIC_TRY(launch_gemm(s, q, dt, true, false, T, h, 3 * h, W(m, m->c_p2), 3 * h, P(m, p.w_2), h, W(m, m->c_z2), h, P(m, p.b_2), nullptr));
-  MOSAIC_TRY(launch_gelu_fwd(s, q, dt, T * h, W(m, m->c_z2), y));
+  MOSAIC_TRY(launch_linear_act_fwd(s, q, dt, MOSAIC_GELU, T, 3 * h, h, W(m, m->c_p2), P(m, p.w_2), P(m, p.b_2), W(m, m->c_z2), y));
   MOSAIC_TRY(launch_add_pos(s, q, dt, d.batch, Lo, h, P(m, p.w_o), y));
   return MOSAIC_OK;
 }

@@ -235,14 +235,78 @@ def test_activations(mb, dtype, T, f):
         torch.cuda.synchronize()
         outs.append([bits(t) for t in (a, dz, s, dgu)])
         if q == QUOTAS[0]:
-            assert rel_l2(from_dev(a), O.gelu(z)) <= tol(dtype)
-            assert rel_l2(from_dev(dz), da * O.gelu_grad(z)) <= tol(dtype)
-            assert rel_l2(from_dev(s), O.swiglu_fwd(gu[:, :f], gu[:, f:])) <= tol(dtype)
+            assert_close(from_dev(a), O.gelu(z), dtype, "gelu")
+            assert_close(from_dev(dz), da * O.gelu_grad(z), dtype, "gelu grad")
+            assert_close(from_dev(s), O.swiglu_fwd(gu[:, :f], gu[:, f:]), dtype, "swiglu")
             dg, du = O.swiglu_bwd(gu[:, :f], gu[:, f:], da)
-            assert rel_l2(from_dev(dgu), np.concatenate([dg, du], 1)) <= tol(dtype)
+            assert_close(from_dev(dgu), np.concatenate([dg, du], 1), dtype, "swiglu grad")
     for o in outs[1:]:
         for a0, b0 in zip(o, outs[0]):
             assert np.array_equal(a0, b0)
+
+
+LINEAR_ACT_SHAPES = [
+    # (dtype, act, T, k, n, bias)
+    ("bf16", "gelu", 1568, 768, 3072, True),        # ViT MLP up projection: bias + GELU in the epilogue
+    ("bf16", "gelu", 333, 264, 392, True),          # ragged in every dimension
+    ("bf16", "gelu", 2100, 520, 1304, False),       # at 24 CUs: whole rounds of large tiles + quarter-tile tail
+    ("bf16", "gelu_tanh", 300, 128, 256, True),     # no epilogue for this form: the elementwise pass follows
+    ("f32", "gelu", 77, 40, 52, True),
+    ("bf16", "swiglu", 2100, 520, 2560, False),     # gate | up of 1280 columns each: ten quarter tiles per half
+    ("bf16", "swiglu", 512, 256, 11264, False),     # the small decoder's gate/up width
+    ("bf16", "swiglu", 700, 264, 1536, True),       # with a bias, ragged rows
+    ("bf16", "swiglu", 333, 264, 400, False),       # halves that are not whole tiles wide: product, then the elementwise pass
+    ("f32", "swiglu", 64, 40, 104, False),
+]
+
+
+@pytest.mark.parametrize("dtype,act,T,k,n,with_bias", LINEAR_ACT_SHAPES)
+def test_linear_with_activation_in_the_epilogue(mb, dtype, act, T, k, n, with_bias):
+    """Z = X W + b and A = act(Z) from one call: the bits of the product followed by the separate
+    activation pass, for every quota; Z and A against the CPU checker."""
+    code = {"gelu": mb.GELU, "swiglu": mb.SWIGLU, "gelu_tanh": mb.GELU_TANH}[act]
+    na = n // 2 if act == "swiglu" else n
+    X = quantize(synth.normal(61, (T, k)), dtype); W = quantize(synth.normal(62, (k, n), 0, 0.06), dtype)
+    b = quantize(synth.normal(63, (n,), 0, 0.3), dtype) if with_bias else None
+    X_, W_ = to_dev(X, dtype), to_dev(W, dtype)
+    b_ = to_dev(b, dtype) if with_bias else None
+    # separate passes
+    Z0 = empty((T, n), dtype); A0 = empty((T, na), dtype)
+    mb.op_linear_fwd(None, 256, dtype, T, k, n, X_, W_, b_, None, Z0)
+    if act == "swiglu":
+        mb.op_swiglu_fwd(None, 256, dtype, T, na, Z0, A0)
+    elif act == "gelu":
+        mb.op_gelu_fwd(None, 256, dtype, T * n, Z0, A0)
+    else:
+        mb.op_gelu_tanh_fwd(None, 256, dtype, T * n, Z0, A0)
+    torch.cuda.synchronize()
+    ref_z = O.linear_fwd(X, W, b)
+    if act == "swiglu":
+        ref_a = O.swiglu_fwd(ref_z[:, :na], ref_z[:, na:])
+    elif act == "gelu":
+        ref_a = O.gelu(ref_z)
+    else:
+        ref_a = O.gelu_tanh(ref_z)
+    for q in [256, 64, 24, 232]:
+        Z = torch.full((T, n), float("nan"), dtype=Z0.dtype, device="cuda")
+        A = torch.full((T, na), float("nan"), dtype=Z0.dtype, device="cuda")
+        mb.op_linear_act_fwd(None, q, dtype, code, T, k, n, X_, W_, b_, Z, A)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(Z), bits(Z0)), f"Z differs from the separate product at quota {q}"
+        assert np.array_equal(bits(A), bits(A0)), f"A differs from the separate activation pass at quota {q}"
+        if q == 256:
+            assert_close(from_dev(Z), ref_z, dtype, "Z")
+            # the activation is taken of the stored (rounded) Z: one more rounding on its input
+            assert_close(from_dev(A), ref_a, dtype, "A", roundings=4 if act == "swiglu" else 2)
+
+
+def test_linear_with_activation_rejects_bad_arguments(mb):
+    x = empty((8, 8), "bf16")
+    with pytest.raises(mb.MosaicError):
+        mb.op_linear_act_fwd(None, 256, "bf16", 7, 8, 8, 8, x, x, None, x, x)
+    with pytest.raises(mb.MosaicError):
+        mb.op_linear_act_fwd(None, 256, "bf16", mb.SWIGLU, 8, 8, 7, x, x, None, x, x)
+    mb.op_linear_act_fwd(None, 256, "bf16", mb.GELU, 0, 8, 8, x, x, None, x, x)     # nothing to do
 
 
 @pytest.mark.parametrize("dtype,n", [("f32", 2 * 128 * 128), ("bf16", 8192 * 2048), ("bf16", 8), ("f32", 4 * 1031)])
