@@ -186,7 +186,7 @@ mosaic_status mosaic_op_norm_bwd_static(void* stream, int32_t quota, int32_t dty
   NONNULL(x); NONNULL(gamma); NONNULL(stats); NONNULL(dy); NONNULL(dx); NONNULL(dgamma);
   if (norm == MOSAIC_LAYERNORM) NONNULL(dbeta);
   if (T < 0 || h <= 0) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm sizes");
-  if (h > kStaticNormMaxH || norm_bwd_scratch_bytes(h) > kStaticScratchBytes)
+  if (h > kStaticNormMaxH || norm_bwd_scratch_bytes(h, false) > kStaticScratchBytes)
     MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "row width %lld exceeds the %lld elements the built-in scratch covers; "
                 "use mosaic_op_norm_bwd with a caller-provided scratch", (long long)h, (long long)kStaticNormMaxH);
   void* sc = nullptr;

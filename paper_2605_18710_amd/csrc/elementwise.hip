@@ -142,14 +142,18 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_dx_kernel(
 // dx and adds dy*xhat (and dy) into per-lane column accumulators.  The four waves'
 // accumulators are added in wave order through LDS, one 64-lane column slab at a time, and
 // land in scratch[p][2][h]; reduce_partials_kernel adds the partitions in a fixed order.
-template <typename T, int NORM, int NV>
+// CS: the column sums of the values written to dx (as stored, after rounding) are formed the
+// same way in a third slab, scratch[p][3][h]: dx is the output gradient of the linear layer in
+// front of the residual branch, so this is that layer's bias gradient, without another pass.
+template <typename T, int NORM, int NV, bool CS = false>
 __global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
     const T* __restrict__ dy, const T* __restrict__ R, T* __restrict__ dx, float* __restrict__ scratch,
     int64_t rows, int h, int rp, int np) {
   constexpr int VN = Vec16<T>::N;
   constexpr int NSUM = (NORM == MOSAIC_LAYERNORM) ? 2 : 1;
-  __shared__ float red[kWaves - 1][NSUM][64 * VN];
+  constexpr int NSLAB = CS ? 3 : 2;                    // slabs per partition in scratch
+  __shared__ float red[kWaves - 1][NSUM + (CS ? 1 : 0)][64 * VN];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float inv_h = 1.0f / (float)h;
   Vec16<T> g[NV];
@@ -159,11 +163,11 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
     if (c < h) g[j].load(gamma + c);
   }
   for (int p = blockIdx.x; p < np; p += gridDim.x) {
-    float ag[NV][VN], ab[NSUM == 2 ? NV : 1][VN];
+    float ag[NV][VN], ab[NSUM == 2 ? NV : 1][VN], ax[CS ? NV : 1][VN];
 #pragma unroll
     for (int j = 0; j < NV; ++j)
 #pragma unroll
-      for (int i = 0; i < VN; ++i) { ag[j][i] = 0.f; if (NSUM == 2) ab[j][i] = 0.f; }
+      for (int i = 0; i < VN; ++i) { ag[j][i] = 0.f; if (NSUM == 2) ab[j][i] = 0.f; if (CS) ax[j][i] = 0.f; }
     const int64_t r0 = (int64_t)p * rp;
     const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
     for (int64_t row = r0 + wave; row < r1; row += kWaves) {
@@ -214,6 +218,7 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
             else r = rstd * t - rstd * rstd * rstd * xr * s2;
             if (R) r += rv.get(i);
             o.set(i, r);
+            if (CS) ax[CS ? j : 0][i] += o.get(i);
           }
           o.store(dx + row * h + c);
         }
@@ -227,6 +232,7 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
         for (int i = 0; i < VN; ++i) {
           red[wave - 1][0][i * 64 + lane] = ag[j][i];
           if (NSUM == 2) red[wave - 1][NSUM - 1][i * 64 + lane] = ab[NSUM == 2 ? j : 0][i];
+          if (CS) red[wave - 1][NSUM][i * 64 + lane] = ax[CS ? j : 0][i];
         }
       }
       __syncthreads();
@@ -235,14 +241,16 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_fused_kernel(
         if (c < h) {
 #pragma unroll
           for (int i = 0; i < VN; ++i) {
-            float a = ag[j][i], b = (NSUM == 2) ? ab[NSUM == 2 ? j : 0][i] : 0.f;
+            float a = ag[j][i], b = (NSUM == 2) ? ab[NSUM == 2 ? j : 0][i] : 0.f, xs = CS ? ax[CS ? j : 0][i] : 0.f;
 #pragma unroll
             for (int w = 0; w < kWaves - 1; ++w) {
               a += red[w][0][i * 64 + lane];
               if (NSUM == 2) b += red[w][NSUM - 1][i * 64 + lane];
+              if (CS) xs += red[w][NSUM][i * 64 + lane];
             }
-            scratch[((int64_t)p * 2 + 0) * h + c + i] = a;
-            if (NSUM == 2) scratch[((int64_t)p * 2 + 1) * h + c + i] = b;
+            scratch[((int64_t)p * NSLAB + 0) * h + c + i] = a;
+            if (NSUM == 2) scratch[((int64_t)p * NSLAB + 1) * h + c + i] = b;
+            if (CS) scratch[((int64_t)p * NSLAB + 2) * h + c + i] = xs;
           }
         }
       }
@@ -307,11 +315,12 @@ __global__ __launch_bounds__(kThreads) void norm_colgrad_partial_kernel(
 
 // out[col] = sum_p partial[p*ld + col], partitions taken in 8 contiguous slices that are
 // added in slice order: a fixed tree that depends on np only.  Columns [0, split) go to
-// out0, columns [split, ncols) to out1 (skipped when out1 is null).
+// out0, columns [split, split2) to out1, columns [split2, ncols) to out2; a null destination
+// skips its columns.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
     const float* __restrict__ partial, int np, int64_t ld, int64_t ncols, int64_t split,
-    T* __restrict__ out0, T* __restrict__ out1) {
+    T* __restrict__ out0, T* __restrict__ out1, int64_t split2 = INT64_MAX, T* __restrict__ out2 = nullptr) {
   __shared__ float red[8][32];
   const int cl = threadIdx.x & 31, sl = threadIdx.x >> 5;
   const int per = (np + 7) / 8;
@@ -319,7 +328,9 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
   for (int64_t gidx = blockIdx.x; gidx < groups; gidx += gridDim.x) {
     const int64_t col = gidx * 32 + cl;
     float acc = 0.f;
-    if (col < ncols && !(col >= split && out1 == nullptr)) {
+    T* dst = nullptr;
+    if (col < ncols) dst = col < split ? out0 + col : col < split2 ? (out1 ? out1 + (col - split) : nullptr) : (out2 ? out2 + (col - split2) : nullptr);
+    if (dst) {
       const int p1 = (sl + 1) * per < np ? (sl + 1) * per : np;
       int p = sl * per;
       // eight independent requests in flight, added in ascending p as before
@@ -334,12 +345,11 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(
     }
     red[sl][cl] = acc;
     __syncthreads();
-    if (sl == 0 && col < ncols) {
+    if (sl == 0 && dst) {
       float t = 0.f;
 #pragma unroll
       for (int q = 0; q < 8; ++q) t += red[q][cl];
-      if (col < split) out0[col] = from_f32<T>(t);
-      else if (out1) out1[col - split] = from_f32<T>(t);
+      *dst = from_f32<T>(t);
     }
     __syncthreads();
   }
@@ -371,6 +381,49 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const T* __restrict_
 #pragma unroll
     for (int k = 0; k < VN; ++k) o.set(k, d.get(k) * gelu_grad_f(v.get(k)));
     o.store(dz + i * VN);
+  }
+}
+
+// dz = da * gelu'(z) and, in the same pass, the partial column sums of dz as stored (the bias
+// gradient of the linear layer that produced z): work item = (row partition p, tile of 256
+// column vectors); a thread owns VN columns and walks the partition's rows in ascending order,
+// exactly as colsum_partial_kernel does over the stored dz, so the sums have the same bits.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gelu_bwd_colsum_kernel(const T* __restrict__ z, const T* __restrict__ da,
+                                                                   T* __restrict__ dz, float* __restrict__ partial,
+                                                                   int64_t rows, int64_t n, int rp, int np, int ctiles) {
+  constexpr int VN = Vec16<T>::N;
+  const int64_t items = (int64_t)np * ctiles;
+  for (int64_t it = blockIdx.x; it < items; it += gridDim.x) {
+    const int p = (int)(it / ctiles), ct = (int)(it - (int64_t)p * ctiles);
+    const int64_t c = ((int64_t)ct * kThreads + threadIdx.x) * VN;
+    if (c >= n) continue;
+    float acc[VN];
+#pragma unroll
+    for (int k = 0; k < VN; ++k) acc[k] = 0.f;
+    const int64_t r0 = (int64_t)p * rp;
+    const int64_t r1 = (r0 + rp < rows) ? r0 + rp : rows;
+    auto one = [&](const Vec16<T>& zv, const Vec16<T>& dv, int64_t r) {
+      Vec16<T> o;
+#pragma unroll
+      for (int k = 0; k < VN; ++k) { o.set(k, dv.get(k) * gelu_grad_f(zv.get(k))); acc[k] += o.get(k); }
+      o.store(dz + r * n + c);
+    };
+    int64_t r = r0;
+    for (; r + 4 <= r1; r += 4) {          // four rows requested together, taken in ascending order
+      Vec16<T> zv[4], dv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { zv[u].load(z + (r + u) * n + c); dv[u].load(da + (r + u) * n + c); }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) one(zv[u], dv[u], r + u);
+    }
+    for (; r < r1; ++r) {
+      Vec16<T> zv, dv;
+      zv.load(z + r * n + c); dv.load(da + r * n + c);
+      one(zv, dv, r);
+    }
+#pragma unroll
+    for (int k = 0; k < VN; ++k) partial[(int64_t)p * n + c + k] = acc[k];
   }
 }
 
@@ -665,12 +718,14 @@ static inline void col_partition(int64_t T, int* rp, int* np) {
   *np = (int)ceil_div(T, r);
 }
 
-size_t norm_bwd_scratch_bytes(int64_t h) { return (size_t)kColsumMaxParts * 2 * (size_t)h * sizeof(float); }
+size_t norm_bwd_scratch_bytes(int64_t h, bool with_dxsum) { return (size_t)kColsumMaxParts * (with_dxsum ? 3 : 2) * (size_t)h * sizeof(float); }
+// widest row (16-byte vectors per lane) for which the one-pass kernel also keeps the column sums of dx
+constexpr int kNormDxSumMaxNV = 4;
 
 template <typename T>
 static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows, int64_t h, const T* x,
                                 const T* gamma, const float* stats, const T* dy, const T* R, T* dx,
-                                T* dgamma, T* dbeta, float* scratch) {
+                                T* dgamma, T* dbeta, float* scratch, T* dxsum, int dtype) {
   constexpr int VN = Vec16<T>::N;
   if (h % VN) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "norm width %lld is not a multiple of %d", (long long)h, VN);
   const int nv = pick_nv((int)ceil_div(h, 64 * VN));
@@ -679,6 +734,25 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   int rp, np;
   col_partition(rows, &rp, &np);
   const int g2 = grid_for(quota, 8, ceil_div(2 * h, 32));
+  if (dxsum && norm == MOSAIC_LAYERNORM && nv <= kNormDxSumMaxNV) {
+    // one pass that also sums the columns of dx
+    const int gf = grid_for(quota, 8, np);
+#define LC(NVC) norm_bwd_fused_kernel<T, MOSAIC_LAYERNORM, NVC, true><<<gf, kThreads, 0, s>>>(x, gamma, stats, dy, R, dx, scratch, rows, (int)h, rp, np)
+    switch (nv) {
+      case 1: LC(1); break;
+      case 2: LC(2); break;
+      case 3: LC(3); break;
+      default: LC(4); break;
+    }
+#undef LC
+    MOSAIC_LAUNCH_CHECK();
+    const int g3 = grid_for(quota, 8, ceil_div(3 * h, 32));
+    reduce_partials_kernel<T><<<g3, kThreads, 0, s>>>(scratch, np, 3 * h, 3 * h, h, dgamma, dbeta, 2 * h, dxsum);
+    MOSAIC_LAUNCH_CHECK();
+    return MOSAIC_OK;
+  }
+  // no kernel that sums dx on the way for this norm or width: the sums take a pass of their own, afterwards
+  auto sum_dx = [&]() -> mosaic_status { return dxsum ? launch_colsum(s, quota, dtype, rows, h, dx, dxsum, scratch) : MOSAIC_OK; };
   if (nv <= kNormFusedMaxNV || norm == MOSAIC_RMSNORM) {
     // one pass: x and dy are read once for dx and for the column sums
     const int gf = grid_for(quota, 8, np);
@@ -704,7 +778,7 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
     reduce_partials_kernel<T><<<g2, kThreads, 0, s>>>(scratch, np, 2 * h, 2 * h, h, dgamma,
                                                       norm == MOSAIC_LAYERNORM ? dbeta : (T*)nullptr);
     MOSAIC_LAUNCH_CHECK();
-    return MOSAIC_OK;
+    return sum_dx();
   }
   const int grid = grid_for(quota, 8, ceil_div(rows, kWaves));
 #define L(NVC)                                                                                        \
@@ -725,18 +799,18 @@ static mosaic_status norm_bwd_t(hipStream_t s, int quota, int norm, int64_t rows
   reduce_partials_kernel<T><<<g2, kThreads, 0, s>>>(scratch, np, 2 * h, 2 * h, h, dgamma,
                                                     norm == MOSAIC_LAYERNORM ? dbeta : (T*)nullptr);
   MOSAIC_LAUNCH_CHECK();
-  return MOSAIC_OK;
+  return sum_dx();
 }
 
 mosaic_status launch_norm_bwd(hipStream_t s, int quota, int dtype, int norm, int64_t T, int64_t h, const void* x,
                               const void* gamma, const float* stats, const void* dy, const void* R, void* dx,
-                              void* dgamma, void* dbeta, void* scratch) {
+                              void* dgamma, void* dbeta, void* scratch, void* dxsum) {
   if (norm != MOSAIC_LAYERNORM && norm != MOSAIC_RMSNORM) MOSAIC_FAIL(MOSAIC_EINVAL, "bad norm kind %d", norm);
   if (dtype == MOSAIC_BF16)
     return norm_bwd_t<bf16>(s, quota, norm, T, h, (const bf16*)x, (const bf16*)gamma, stats, (const bf16*)dy,
-                            (const bf16*)R, (bf16*)dx, (bf16*)dgamma, (bf16*)dbeta, (float*)scratch);
+                            (const bf16*)R, (bf16*)dx, (bf16*)dgamma, (bf16*)dbeta, (float*)scratch, (bf16*)dxsum, dtype);
   return norm_bwd_t<float>(s, quota, norm, T, h, (const float*)x, (const float*)gamma, stats, (const float*)dy,
-                           (const float*)R, (float*)dx, (float*)dgamma, (float*)dbeta, (float*)scratch);
+                           (const float*)R, (float*)dx, (float*)dgamma, (float*)dbeta, (float*)scratch, (float*)dxsum, dtype);
 }
 
 #define EW_CHECK_VEC(n, dtype)                                                               \
@@ -830,6 +904,30 @@ mosaic_status launch_colsum(hipStream_t s, int quota, int dtype, int64_t T, int6
     reduce_partials_kernel<bf16><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (bf16*)out, (bf16*)nullptr);
   else
     reduce_partials_kernel<float><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (float*)out, (float*)nullptr);
+  MOSAIC_LAUNCH_CHECK();
+  return MOSAIC_OK;
+}
+
+mosaic_status launch_gelu_bwd_colsum(hipStream_t s, int quota, int dtype, int64_t T, int64_t n, const void* z,
+                                     const void* da, void* dz, void* colsum, void* scratch) {
+  EW_CHECK_VEC(n, dtype);
+  if (n == 0) return MOSAIC_OK;
+  int rp, np;
+  col_partition(T, &rp, &np);
+  const int ctiles = (int)ceil_div(n, (int64_t)kThreads * vn__);
+  if (np > 0) {
+    const int grid = grid_for(quota, 8, (int64_t)np * ctiles);
+    if (dtype == MOSAIC_BF16)
+      gelu_bwd_colsum_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)z, (const bf16*)da, (bf16*)dz, (float*)scratch, T, n, rp, np, ctiles);
+    else
+      gelu_bwd_colsum_kernel<float><<<grid, kThreads, 0, s>>>((const float*)z, (const float*)da, (float*)dz, (float*)scratch, T, n, rp, np, ctiles);
+    MOSAIC_LAUNCH_CHECK();
+  }
+  const int g2 = grid_for(quota, 8, ceil_div(n, 32));
+  if (dtype == MOSAIC_BF16)
+    reduce_partials_kernel<bf16><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (bf16*)colsum, (bf16*)nullptr);
+  else
+    reduce_partials_kernel<float><<<g2, kThreads, 0, s>>>((const float*)scratch, np, n, n, n, (float*)colsum, (float*)nullptr);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }

@@ -37,14 +37,22 @@ mosaic_status launch_attention_bwd(hipStream_t s, int quota, int dtype, int B, i
 mosaic_status launch_norm_fwd(hipStream_t s, int quota, int dtype, int norm, int64_t T,
                               int64_t h, float eps, const void* x, const void* gamma,
                               const void* beta, void* y, float* stats);
-size_t norm_bwd_scratch_bytes(int64_t h);
+// scratch of launch_norm_bwd: two slabs of partial sums per row partition, a third when dxsum is asked for
+size_t norm_bwd_scratch_bytes(int64_t h, bool with_dxsum = true);
 mosaic_status launch_norm_bwd(hipStream_t s, int quota, int dtype, int norm, int64_t T,
                               int64_t h, const void* x, const void* gamma, const float* stats,
                               const void* dy, const void* R, void* dx, void* dgamma,
-                              void* dbeta, void* scratch);
+                              void* dbeta, void* scratch, void* dxsum = nullptr);
+// dxsum (may be null): receives the column sums of dx[T,h] as stored, in the fixed two-level
+// order of launch_colsum's partitions; formed inside the norm kernel where it has a variant
+// for that (LayerNorm rows of up to 2048 bf16 / 1024 fp32 elements), by a pass over dx otherwise.
 mosaic_status launch_gelu_fwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z, void* a);
 mosaic_status launch_gelu_bwd(hipStream_t s, int quota, int dtype, int64_t n, const void* z,
                               const void* da, void* dz);
+// dz = da * gelu'(z) and colsum[n] = column sums of dz[T,n] as stored (same bits as launch_colsum
+// over dz); scratch: colsum_scratch_bytes(n)
+mosaic_status launch_gelu_bwd_colsum(hipStream_t s, int quota, int dtype, int64_t T, int64_t n, const void* z,
+                                     const void* da, void* dz, void* colsum, void* scratch);
 mosaic_status launch_swiglu_fwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f,
                                 const void* gu, void* a);
 mosaic_status launch_swiglu_bwd(hipStream_t s, int quota, int dtype, int64_t T, int64_t f,

@@ -311,21 +311,27 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     // MLP down projection
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, f, h, gin, h, P(m, p.w_2), h, dA, f, nullptr, nullptr));
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, f, h, T, W(m, sv.a), f, gin, h, G(m, p.w_2), h, nullptr, nullptr, W(m, m->s_splitk)));
-    if (p.b_2 >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, gin, G(m, p.b_2), csc));
+    // Bias gradients are column sums of a layer's output gradient.  Each is formed by the kernel
+    // that writes that gradient where there is one of ours: the first norm's backward of the
+    // layer above (this layer's incoming gradient), the GELU backward, the second norm's
+    // backward.  Only the top layer's incoming gradient and dQKV take a pass of their own.
+    if (p.b_2 >= 0 && l == d.layers - 1) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, gin, G(m, p.b_2), csc));
     // activation
+    bool b1_done = false;
     if (glu) MOSAIC_TRY(launch_swiglu_bwd(s, q, dt, T, f, W(m, sv.z), dA, dZ));
     else if (d.act == MOSAIC_GELU_TANH) MOSAIC_TRY(launch_gelu_tanh_bwd(s, q, dt, T * f, W(m, sv.z), dA, dZ));
+    else if (p.b_1 >= 0) { MOSAIC_TRY(launch_gelu_bwd_colsum(s, q, dt, T, f, W(m, sv.z), dA, dZ, G(m, p.b_1), csc)); b1_done = true; }
     else MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * f, W(m, sv.z), dA, dZ));
     // MLP up projection
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, zf, T, W(m, sv.u2), h, dZ, zf, G(m, p.w_1), zf, nullptr, nullptr, W(m, m->s_splitk)));
-    if (p.b_1 >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, zf, dZ, G(m, p.b_1), csc));
+    if (p.b_1 >= 0 && !b1_done) MOSAIC_TRY(launch_colsum(s, q, dt, T, zf, dZ, G(m, p.b_1), csc));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, zf, dZ, zf, P(m, p.w_1), zf, dU, h, nullptr, nullptr));
     // second norm; residual branch adds the incoming gradient
-    MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, W(m, sv.x1), P(m, p.n2_g), (const float*)W(m, sv.st2), dU, gin, dX1, G(m, p.n2_g), G(m, p.n2_b), nsc));
+    MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, W(m, sv.x1), P(m, p.n2_g), (const float*)W(m, sv.st2), dU, gin, dX1, G(m, p.n2_g), G(m, p.n2_b), nsc,
+                               G(m, p.b_o)));   // dX1 is the output gradient of the attention output projection
     // attention output projection
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, h, dX1, h, P(m, p.w_o), h, dO, h, nullptr, nullptr));
     MOSAIC_TRY(launch_gemm(s, q, dt, false, false, h, h, T, W(m, sv.o), h, dX1, h, G(m, p.w_o), h, nullptr, nullptr, W(m, m->s_splitk)));
-    if (p.b_o >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, h, dX1, G(m, p.b_o), csc));
     // attention
     MOSAIC_TRY(launch_attention_bwd(s, q, dt, d.batch, d.seq, d.heads, kvh, (int)(h / d.heads), d.causal, W(m, sv.qkv), W(m, sv.o),
                                     (const float*)W(m, sv.lse), dO, dQKV, (float*)W(m, m->s_delta)));
@@ -337,7 +343,8 @@ mosaic_status layers_backward(mosaic_module* m, hipStream_t s, int q, const void
     if (p.b_qkv >= 0) MOSAIC_TRY(launch_colsum(s, q, dt, T, qw, dQKV, G(m, p.b_qkv), csc));
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, h, qw, dQKV, qw, P(m, p.w_qkv), qw, dU, h, nullptr, nullptr));
     // first norm
-    MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, xin, P(m, p.n1_g), (const float*)W(m, sv.st1), dU, dX1, gout, G(m, p.n1_g), G(m, p.n1_b), nsc));
+    MOSAIC_TRY(launch_norm_bwd(s, q, dt, d.norm, T, h, xin, P(m, p.n1_g), (const float*)W(m, sv.st1), dU, dX1, gout, G(m, p.n1_g), G(m, p.n1_b), nsc,
+                               l > 0 ? G(m, m->lp[l - 1].b_2) : nullptr));   // gout is the incoming gradient of the layer below
     gin = gout;
   }
   return MOSAIC_OK;
@@ -364,9 +371,8 @@ mosaic_status projector_backward(mosaic_module* m, hipStream_t s, int q, const v
   MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, no, no, dy, no, P(m, p.w_2), no, dA, no, nullptr, nullptr));
   MOSAIC_TRY(launch_gemm(s, q, dt, false, false, no, no, T, W(m, sv.a), no, dy, no, G(m, p.w_2), no, nullptr, nullptr, W(m, m->s_splitk)));
   MOSAIC_TRY(launch_colsum(s, q, dt, T, no, dy, G(m, p.b_2), csc));
-  MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * no, W(m, sv.z), dA, dZ));
+  MOSAIC_TRY(launch_gelu_bwd_colsum(s, q, dt, T, no, W(m, sv.z), dA, dZ, G(m, p.b_1), csc));
   MOSAIC_TRY(launch_gemm(s, q, dt, false, false, ni, no, T, m->last_x, ni, dZ, no, G(m, p.w_1), no, nullptr, nullptr, W(m, m->s_splitk)));
-  MOSAIC_TRY(launch_colsum(s, q, dt, T, no, dZ, G(m, p.b_1), csc));
   if (dx) MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, ni, no, dZ, no, P(m, p.w_1), no, dx, ni, nullptr, nullptr));
   return MOSAIC_OK;
 }
@@ -418,14 +424,12 @@ mosaic_status conv_stem_backward(mosaic_module* m, hipStream_t s, int q, const v
   const int64_t T = m->T, Tin = 2 * T;
   void* csc = W(m, m->s_colsum); void* sk = W(m, m->s_splitk);
   MOSAIC_TRY(launch_pos_grad(s, q, dt, d.batch, Lo, h, dy, G(m, p.w_o)));
-  MOSAIC_TRY(launch_gelu_bwd(s, q, dt, T * h, W(m, m->c_z2), dy, W(m, m->c_dz2)));
+  MOSAIC_TRY(launch_gelu_bwd_colsum(s, q, dt, T, h, W(m, m->c_z2), dy, W(m, m->c_dz2), G(m, p.b_2), csc));
   MOSAIC_TRY(launch_gemm(s, q, dt, false, false, 3 * h, h, T, W(m, m->c_p2), 3 * h, W(m, m->c_dz2), h, G(m, p.w_2), h, nullptr, nullptr, sk));
-  MOSAIC_TRY(launch_colsum(s, q, dt, T, h, W(m, m->c_dz2), G(m, p.b_2), csc));
   MOSAIC_TRY(launch_gemm(s, q, dt, true, true, T, 3 * h, h, W(m, m->c_dz2), h, P(m, p.w_2), h, W(m, m->c_dp2), 3 * h, nullptr, nullptr));
   MOSAIC_TRY(launch_col2im1d(s, q, dt, d.batch, L, Lo, h, 2, W(m, m->c_dp2), W(m, m->c_da1)));
-  MOSAIC_TRY(launch_gelu_bwd(s, q, dt, Tin * h, W(m, m->c_z1), W(m, m->c_da1), W(m, m->c_dz1)));
+  MOSAIC_TRY(launch_gelu_bwd_colsum(s, q, dt, Tin, h, W(m, m->c_z1), W(m, m->c_da1), W(m, m->c_dz1), G(m, p.b_1), csc));
   MOSAIC_TRY(launch_gemm(s, q, dt, false, false, 3 * C, h, Tin, W(m, m->c_p1), 3 * C, W(m, m->c_dz1), h, G(m, p.w_1), h, nullptr, nullptr, sk));
-  MOSAIC_TRY(launch_colsum(s, q, dt, Tin, h, W(m, m->c_dz1), G(m, p.b_1), csc));
   if (dx) {
     MOSAIC_TRY(launch_gemm(s, q, dt, true, true, Tin, 3 * C, h, W(m, m->c_dz1), h, P(m, p.w_1), h, W(m, m->c_dp1), 3 * C, nullptr, nullptr));
     MOSAIC_TRY(launch_col2im1d(s, q, dt, d.batch, L, L, C, 1, W(m, m->c_dp1), dx));
