@@ -44,6 +44,10 @@ constexpr float kLn2 = 0.6931471805599453f;
 // rescale of the running sums (one multiply per accumulator register) becomes rare instead
 // of happening on almost every block of a long row.
 constexpr float kLazyRescale = 8.0f;
+// In the forward kernel's steady state a block's probabilities are formed before anyone has
+// looked at its maximum; a block whose 16 probabilities per lane add up to more than this (or
+// to NaN / infinity) is done again after the reference has been moved.  Far inside bf16 and fp32.
+constexpr float kOptimisticSum = 1048576.0f;      // 2^20: some probability above 2^16
 // The next work item is claimed this many streamed 64-row tiles before the end of the current
 // one: late enough that a workgroup cannot take items from workgroups that have not started,
 // early enough that most of the claim's round trip hides under the item's last tiles.
@@ -187,16 +191,39 @@ __device__ __forceinline__ bool attn_mirror(const TileQueueArgs& q, const TileQu
 }
 
 // --------------------------------------------------------------------------- forward
+// value of the other half-wave's lane (lane ^ 32) combined with this lane's: one cross-half swap,
+// no LDS round trip
+__device__ __forceinline__ float xhalf_max(float v) {
+  typedef __attribute__((ext_vector_type(2))) unsigned u32x2_;
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  const u32x2_ r = __builtin_amdgcn_permlane32_swap(x, x, false, false);   // r[0] = lower half's value, r[1] = upper half's, in every lane
+  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
+// The key blocks of 32 are taken through a software pipeline that is skewed by one block, so
+// that the three things a block needs run at the same time for three consecutive blocks:
+// in slot i the matrix cores compute the scores of block i+1 (S = K Q^T) and add block i-1 to
+// the output (O^T += V^T P^T) while the vector ALU turns the scores of block i into
+// probabilities.  Inside one wave instructions issue in order, and a matrix instruction holds
+// the matrix pipe for 32 cycles during which only instructions that follow it in program order
+// can issue: the slot is therefore written, and pinned with scheduling barriers, as one matrix
+// instruction, the read of an operand a few instructions ahead, a few vector instructions, and
+// so on.  The arithmetic per block is that of the plain loop: scores, reference, probabilities,
+// output, block by block in ascending order.
+//
+// LDS: a step covers two slots and reads the K rows of tile u+1 and the V rows of tile u (64
+// keys each); these share a stage, two stages alternate, and the next step's rows are
+// requested at the start of a step (their stage was last read in the step before).
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                      float* __restrict__ lse, int B, int N, int H, int Hkv, int causal,
                                                      float scale_log2, int qtiles, int hblk, TileQueueArgs tq) {
   constexpr int RS = 64, NS = D / 16, NC = D / 32;
   typedef LdsTile<RS, D, NW> L;
-  constexpr int STAGE = 2 * L::BYTES;                      // K | V
-  constexpr int NST = Ring<NW>::NST, PD = Ring<NW>::PD, QT = 32 * NW, NREQ = 2 * L::NI;
+  constexpr int STAGE = 2 * L::BYTES;                      // K rows of one tile | V rows of the tile before
+  constexpr int QT = 32 * NW;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [2][STAGE]
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   L ld;
   ld.init((unsigned)((H + 2 * Hkv) * D * 2));
@@ -229,55 +256,53 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
       for (int e = 0; e < 16; ++e) o[c][e] = 0.f;
     float m = -INFINITY, lsum = 0.f;
     const int kv_end = causal ? min(N, q0 + QT) : N;
-    const int ntiles = (kv_end + RS - 1) / RS;
+    const int nt = (kv_end + RS - 1) / RS;                 // key tiles the workgroup streams
+    // key blocks this wave multiplies: up to the end of the keys and, under a causal mask, up
+    // to the block that holds its own diagonal; only the last of them can need the mask
+    int nb = (kv_end + 31) / 32;
+    if (causal) nb = min(nb, i0 / 32 + 1);
     const i32x4 dk_ = slice_desc(rowb + ko + kvh * D, N, rs, D), dv_ = slice_desc(rowb + vo + kvh * D, N, rs, D);
     const unsigned rsb = (unsigned)(rs * 2);
-    auto request = [&](int tile) {         // tiles past the last one point outside the slice
-      const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
-      const int row0 = tile < ntiles ? tile * RS : N;
-      const unsigned at = (unsigned)row0 * rsb;
-      ld.issue(dk_, at, nb);
-      ld.issue(dv_, at, nb + L::BYTES);
+    auto request = [&](int u) {            // step u: K rows of tile u+1, V rows of tile u; tiles that do not exist point outside the slice
+      const unsigned nbuf = lds0 + (unsigned)(((u + 1) & 1) * STAGE);
+      const int krow = (u + 1 < nt) ? (u + 1) * RS : N;
+      const int vrow = (u >= 0 && u < nt) ? u * RS : N;
+      ld.issue(dk_, (unsigned)krow * rsb, nbuf);
+      ld.issue(dv_, (unsigned)vrow * rsb, nbuf + L::BYTES);
     };
-    __syncthreads();                      // previous item's readers are done with every stage
-#pragma unroll
-    for (int u = 0; u < PD; ++u) request(u);
-    wait_requests<(PD - 1) * NREQ>();
+    __syncthreads();                      // previous item's readers are done with both stages
+    request(-1);
+    wait_requests<0>();
     __syncthreads();
     unsigned entry = 0;
-    const int claim_at = ntiles > kClaimTilesAhead ? ntiles - kClaimTilesAhead : 0;
-    for (int t = 0; t < ntiles; ++t) {
-      const lds_byte* ks = smem + (t % NST) * STAGE;
+    const int claim_at = nt > kClaimTilesAhead ? nt - kClaimTilesAhead : -1;
+    f32x16 sc;                            // raw scores of the block whose probabilities are formed next
+    bf16x8 pk0, pk1;                      // probabilities of the block whose output product is pending
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { pk0[e] = (bf16)0.f; pk1[e] = (bf16)0.f; }
+    for (int u = -1; u < nt; ++u) {
+      const lds_byte* ks = smem + ((u + 1) & 1) * STAGE;
       const lds_byte* vs = ks + L::BYTES;
-      request(t + PD);
-      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
-      const int j0 = t * RS;
-      // A 32-key block is visible to this wave when it starts before the end of the keys and
-      // (causal) not after the wave's last query; the second block of a tile is visible only
-      // if the first is.
-      auto visible = [&](int jb) { return jb < kv_end && !(causal && jb > i0 + 31); };
-      // online-softmax update with one block of scores (raw dot products, this lane's query
-      // against 16 keys): returns the probabilities as two B-operands
-      auto softmax_block = [&](const f32x16& sacc, int jb, bf16x8& p0, bf16x8& p1) {
-        float sv[16];
-        float mx = -INFINITY;
-        // only blocks that touch the diagonal or the end of the sequence need the mask
-        const bool need_mask = (jb + 32 > N) || (causal && jb + 31 > i0);
-        if (need_mask) {
+      request(u + 1);
+      if (u == claim_at) entry = tq_claim_ahead(tq, qc);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = jb + acc_row(r, hb);
-            const bool masked = (j >= N) || (causal && j > i);
-            sv[r] = masked ? -INFINITY : sacc[r];
-            mx = fmaxf(mx, sv[r]);
+      for (int half = 0; half < 2; ++half) {
+        const int bi = 2 * u + 1 + half;                  // the block whose probabilities this slot forms
+        const bool do_s = bi + 1 < nb, do_x = bi >= 0 && bi < nb, do_pv = bi >= 1 && bi - 1 < nb;
+        const int krow = 32 * half + lr, vrow = 32 * half;
+        // o += V^T P^T for the pending block, one instruction after the other
+        auto add_pv_now = [&]() {
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, vrow), pk0, o[c], 0, 0, 0);
+            o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(vs, c, vrow + 16), pk1, o[c], 0, 0, 0);
           }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { sv[r] = sacc[r]; mx = fmaxf(mx, sv[r]); }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;       // scale > 0: max commutes with it
-        const float mn = fmaxf(m, mx);
-        if (__any(mx > m + kLazyRescale)) {
+        };
+        // moves the reference of the running sums to the new row maximum
+        auto rescale = [&](float mx) {
+          const float mn = fmaxf(m, mx);
           const float mref0 = (mn == -INFINITY) ? 0.f : mn;
           const float corr = fast_exp2(m - mref0);               // m = -inf -> 0
           lsum *= corr;
@@ -286,69 +311,115 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[c][e] *= corr;
           m = mn;
+        };
+        if (bi >= 1 && bi + 1 < nb) {
+          // steady state: all three present, block bi is not the last one, so nothing is masked.
+          // The probabilities are formed against the reference the row already has, without
+          // looking at the block's maximum first; the reference is moved afterwards, and the
+          // block's probabilities formed again, only if their sum shows that they have grown
+          // beyond kOptimisticSum (rare: the reference then lags the row maximum by more than
+          // sixteen powers of two).
+          const float mref = (m == -INFINITY) ? 0.f : m;
+          // Slot by slot: the matrix instruction, the read of the operand PFD slots ahead, and a
+          // share of the vector work, which runs while the matrix instruction holds its pipe.
+          // Score and output products alternate, so no instruction waits for the one just issued.
+          constexpr int NM = NS + 2 * NC, PFD = 3, XPS = 16 / NM;   // NS == 2 * NC for both head sizes
+          static_assert(NS == 2 * NC && 16 % NM == 0, "slots alternate score and output products");
+          auto operand = [&](int k) -> bf16x8 {                  // k even: K fragment k/2; k odd: V fragment of output block k/4, key half (k/2)%2
+            const int q = k >> 1;
+            return (k & 1) ? L::tr(vs, q >> 1, vrow + 16 * (q & 1)) : L::nat(ks, krow, q, hb);
+          };
+          bf16x8 opb[PFD + 1];
+#pragma unroll
+          for (int k = 0; k < PFD; ++k) opb[k] = operand(k);
+          f32x16 sn;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sn[e] = 0.f;
+          float sv[16];
+          float ps = 0.f;
+          bf16x8 pn0, pn1;
+          // the first operands are on their way: the vector work of the first slots runs now,
+          // under their latency, instead of under matrix instructions that cannot start yet
+          auto prob = [&](int k) {
+#pragma unroll
+            for (int x = 0; x < XPS; ++x) {
+              const int r = k * XPS + x;
+              sv[r] = fast_exp2(fmaf(sc[r], scale_log2, -mref));
+              ps += sv[r];
+            }
+          };
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int k = 0; k < PFD; ++k) prob(k);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int k = 0; k < NM; ++k) {
+            if (k + PFD < NM) opb[(k + PFD) % (PFD + 1)] = operand(k + PFD);
+            const bf16x8 a = opb[k % (PFD + 1)];
+            const int q = k >> 1;
+            if (k & 1) o[q >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, (q & 1) ? pk1 : pk0, o[q >> 1], 0, 0, 0);
+            else sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[q], sn, 0, 0, 0);
+            if (k + PFD < NM) prob(k + PFD);
+            if ((k + PFD + 1) * XPS == 8) pn0 = pack8(sv);
+            if (k + PFD == NM - 1) pn1 = pack8(sv + 8);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (__any(!(ps <= kOptimisticSum))) {
+            // o holds every block before bi now (the pending product has just been added)
+            float mx = fmaxf(sc[0], sc[1]);
+#pragma unroll
+            for (int r = 2; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+            rescale(xhalf_max(mx) * scale_log2);
+            ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(fmaf(sc[r], scale_log2, -m)); ps += sv[r]; }
+            pn0 = pack8(sv); pn1 = pack8(sv + 8);
+          }
+          lsum += ps;
+          sc = sn; pk0 = pn0; pk1 = pn1;
+        } else if (do_s || do_x || do_pv) {
+          // first and last slots of the wave: whatever of the three exists, one after the other
+          const int jb = 32 * bi;
+          float sv[16];
+          bool pv_done = !do_pv;
+          if (do_x) {
+            float mx = -INFINITY;
+            if ((jb + 32 > N) || (causal && jb + 31 > i0)) {     // block touches the diagonal or the end of the keys
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int j = jb + acc_row(r, hb);
+                const bool masked = (j >= N) || (causal && j > i);
+                sv[r] = masked ? -INFINITY : sc[r];
+                mx = fmaxf(mx, sv[r]);
+              }
+            } else {
+#pragma unroll
+              for (int r = 0; r < 16; ++r) { sv[r] = sc[r]; mx = fmaxf(mx, sv[r]); }
+            }
+            mx = xhalf_max(mx) * scale_log2;                     // scale > 0: max commutes with it
+            if (__any(mx > m + kLazyRescale)) {
+              if (!pv_done) { add_pv_now(); pv_done = true; }   // o must hold every block before bi when it is rescaled
+              rescale(mx);
+            }
+          }
+          if (!pv_done) add_pv_now();
+          if (do_x) {
+            const float mref = (m == -INFINITY) ? 0.f : m;       // row with nothing visible yet
+            float ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(fmaf(sv[r], scale_log2, -mref)); ps += sv[r]; }
+            lsum += ps;
+            pk0 = pack8(sv); pk1 = pack8(sv + 8);
+          }
+          if (do_s) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(ks, krow, s, hb), qf[s], sc, 0, 0, 0);
+          }
         }
-        const float mref = (m == -INFINITY) ? 0.f : m;           // row with nothing visible yet
-        float ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(fmaf(sv[r], scale_log2, -mref)); ps += sv[r]; }
-        lsum += ps;
-        p0 = pack8(sv); p1 = pack8(sv + 8);
-      };
-      auto scores = [&](const bf16x8* kfr) {
-        f32x16 sacc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
-        return sacc;
-      };
-      auto add_pv = [&](const bf16x8 (*vfr)[2], const bf16x8& p0, const bf16x8& p1) {
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][0], p0, o[c], 0, 0, 0);
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][1], p1, o[c], 0, 0, 0);
-        }
-      };
-      if (visible(j0) && visible(j0 + 32)) {
-        // Both blocks: the scores of the second block are on the matrix cores while the
-        // first block's softmax runs on the vector ALU, and the first block's P V product
-        // runs under the second block's softmax.  Fragment reads are issued a phase ahead.
-        bf16x8 kfa[NS], kfb[NS];
-#pragma unroll
-        for (int s = 0; s < NS; ++s) kfa[s] = L::nat(ks, lr, s, hb);
-#pragma unroll
-        for (int s = 0; s < NS; ++s) kfb[s] = L::nat(ks, 32 + lr, s, hb);
-        __builtin_amdgcn_sched_barrier(0);
-        const f32x16 sa = scores(kfa);
-        const f32x16 sb = scores(kfb);
-        bf16x8 vfa[NC][2];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) { vfa[c][0] = L::tr(vs, c, 0); vfa[c][1] = L::tr(vs, c, 16); }
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 p0, p1;
-        softmax_block(sa, j0, p0, p1);
-        bf16x8 vfb[NC][2];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) { vfb[c][0] = L::tr(vs, c, 32); vfb[c][1] = L::tr(vs, c, 48); }
-        add_pv(vfa, p0, p1);
-        __builtin_amdgcn_sched_barrier(0);
-        softmax_block(sb, j0 + 32, p0, p1);
-        add_pv(vfb, p0, p1);
-      } else if (visible(j0)) {
-        bf16x8 kfr[NS];
-#pragma unroll
-        for (int s = 0; s < NS; ++s) kfr[s] = L::nat(ks, lr, s, hb);
-        __builtin_amdgcn_sched_barrier(0);
-        const f32x16 sa = scores(kfr);
-        bf16x8 vfr[NC][2];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) { vfr[c][0] = L::tr(vs, c, 0); vfr[c][1] = L::tr(vs, c, 16); }
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 p0, p1;
-        softmax_block(sa, j0, p0, p1);
-        add_pv(vfr, p0, p1);
       }
-      wait_requests<(PD - 1) * NREQ>();    // this wave's share of the next tile has landed
+      wait_requests<0>();                  // this wave's share of the next step's rows has landed
       __syncthreads();
     }
     const float ltot = lsum + __shfl_xor(lsum, 32, 64);
@@ -754,7 +825,7 @@ mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
   static hipError_t once_rc = hipSuccess;
   TileQueueArgs tq;
   int grid, hb;
-  MOSAIC_TRY(launch_queued(attn_fwd_mfma<D, NW>, once, once_rc, smem, s, quota, (D == 64 && NW == 4) ? 3 : 8 / NW,
+  MOSAIC_TRY(launch_queued(attn_fwd_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW,
                            (int64_t)B * H, qtiles, causal, &tq, &grid, &hb));
   attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles, hb, tq);
   MOSAIC_LAUNCH_CHECK();
