@@ -442,6 +442,196 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_mfma(const bf16* __r
   tq_done(tq);
 }
 
+// Forward kernel for head size 64, one key tile of 64 at a time: with four matrix instructions
+// per score block the loop is bound by the vector ALU, not by the matrix cores, and three
+// resident workgroups per CU (about 155 registers) serve it better than the skewed pipeline
+// above, which needs about 190 (measured: 149 against 159 us at B8 N1500 H20, 25.6 against
+// 27.7 us at B8 N576 H16).  Both blocks of a tile are multiplied before the first block's
+// probabilities are formed, so the second block's scores are on the matrix cores meanwhile.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ O,
+                                                     float* __restrict__ lse, int B, int N, int H, int Hkv, int causal,
+                                                     float scale_log2, int qtiles, int hblk, TileQueueArgs tq) {
+  constexpr int RS = 64, NS = D / 16, NC = D / 32;
+  typedef LdsTile<RS, D, NW> L;
+  constexpr int STAGE = 2 * L::BYTES;                      // K | V
+  constexpr int NST = Ring<NW>::NST, PD = Ring<NW>::PD, QT = 32 * NW, NREQ = 2 * L::NI;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE]
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  L ld;
+  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 31, hb = lane >> 5;
+  // rows are [q (H heads) | k (Hkv heads) | v (Hkv heads)]; query head t uses key/value head t / (H/Hkv)
+  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
+    int head_, qt;
+    attn_item(item, B * H, qtiles, hblk, causal != 0, attn_mirror(tq, qc, qtiles), &head_, &qt);
+    const int hd = head_ % H, b = head_ / H;
+    const int q0 = qt * QT, i0 = q0 + 32 * wave, i = i0 + lr;
+    const bf16* rowb = qkv + (int64_t)b * N * rs;
+    const bf16* base = rowb + hd * D;
+    const int kvh = hd / GQ;
+    bf16x8 qf[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if (i < N) qf[s] = *reinterpret_cast<const bf16x8*>(base + (int64_t)i * rs + 16 * s + 8 * hb);
+      else { for (int e = 0; e < 8; ++e) qf[s][e] = (bf16)0.f; }
+    }
+    f32x16 o[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[c][e] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+    const int kv_end = causal ? min(N, q0 + QT) : N;
+    const int ntiles = (kv_end + RS - 1) / RS;
+    const i32x4 dk_ = slice_desc(rowb + ko + kvh * D, N, rs, D), dv_ = slice_desc(rowb + vo + kvh * D, N, rs, D);
+    const unsigned rsb = (unsigned)(rs * 2);
+    auto request = [&](int tile) {         // tiles past the last one point outside the slice
+      const unsigned nb = lds0 + (unsigned)((tile % NST) * STAGE);
+      const int row0 = tile < ntiles ? tile * RS : N;
+      const unsigned at = (unsigned)row0 * rsb;
+      ld.issue(dk_, at, nb);
+      ld.issue(dv_, at, nb + L::BYTES);
+    };
+    __syncthreads();                      // previous item's readers are done with every stage
+#pragma unroll
+    for (int u = 0; u < PD; ++u) request(u);
+    wait_requests<(PD - 1) * NREQ>();
+    __syncthreads();
+    unsigned entry = 0;
+    const int claim_at = ntiles > kClaimTilesAhead ? ntiles - kClaimTilesAhead : 0;
+    for (int t = 0; t < ntiles; ++t) {
+      const lds_byte* ks = smem + (t % NST) * STAGE;
+      const lds_byte* vs = ks + L::BYTES;
+      request(t + PD);
+      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
+      const int j0 = t * RS;
+      // A 32-key block is visible to this wave when it starts before the end of the keys and
+      // (causal) not after the wave's last query; the second block of a tile is visible only
+      // if the first is.
+      auto visible = [&](int jb) { return jb < kv_end && !(causal && jb > i0 + 31); };
+      // online-softmax update with one block of scores (raw dot products, this lane's query
+      // against 16 keys): returns the probabilities as two B-operands
+      auto softmax_block = [&](const f32x16& sacc, int jb, bf16x8& p0, bf16x8& p1) {
+        float sv[16];
+        float mx = -INFINITY;
+        // only blocks that touch the diagonal or the end of the sequence need the mask
+        const bool need_mask = (jb + 32 > N) || (causal && jb + 31 > i0);
+        if (need_mask) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int j = jb + acc_row(r, hb);
+            const bool masked = (j >= N) || (causal && j > i);
+            sv[r] = masked ? -INFINITY : sacc[r];
+            mx = fmaxf(mx, sv[r]);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sv[r] = sacc[r]; mx = fmaxf(mx, sv[r]); }
+        }
+        mx = xhalf_max(mx) * scale_log2;                           // scale > 0: max commutes with it
+        const float mn = fmaxf(m, mx);
+        if (__any(mx > m + kLazyRescale)) {
+          const float mref0 = (mn == -INFINITY) ? 0.f : mn;
+          const float corr = fast_exp2(m - mref0);               // m = -inf -> 0
+          lsum *= corr;
+#pragma unroll
+          for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[c][e] *= corr;
+          m = mn;
+        }
+        const float mref = (m == -INFINITY) ? 0.f : m;           // row with nothing visible yet
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(fmaf(sv[r], scale_log2, -mref)); ps += sv[r]; }
+        lsum += ps;
+        p0 = pack8(sv); p1 = pack8(sv + 8);
+      };
+      auto scores = [&](const bf16x8* kfr) {
+        f32x16 sacc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sacc, 0, 0, 0);
+        return sacc;
+      };
+      auto add_pv = [&](const bf16x8 (*vfr)[2], const bf16x8& p0, const bf16x8& p1) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][0], p0, o[c], 0, 0, 0);
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[c][1], p1, o[c], 0, 0, 0);
+        }
+      };
+      if (visible(j0) && visible(j0 + 32)) {
+        // Both blocks: the scores of the second block are on the matrix cores while the
+        // first block's softmax runs on the vector ALU, and the first block's P V product
+        // runs under the second block's softmax.  Fragment reads are issued a phase ahead.
+        bf16x8 kfa[NS], kfb[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfa[s] = L::nat(ks, lr, s, hb);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfb[s] = L::nat(ks, 32 + lr, s, hb);
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 sa = scores(kfa);
+        const f32x16 sb = scores(kfb);
+        bf16x8 vfa[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfa[c][0] = L::tr(vs, c, 0); vfa[c][1] = L::tr(vs, c, 16); }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 p0, p1;
+        softmax_block(sa, j0, p0, p1);
+        bf16x8 vfb[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfb[c][0] = L::tr(vs, c, 32); vfb[c][1] = L::tr(vs, c, 48); }
+        add_pv(vfa, p0, p1);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_block(sb, j0 + 32, p0, p1);
+        add_pv(vfb, p0, p1);
+      } else if (visible(j0)) {
+        bf16x8 kfr[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) kfr[s] = L::nat(ks, lr, s, hb);
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 sa = scores(kfr);
+        bf16x8 vfr[NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { vfr[c][0] = L::tr(vs, c, 0); vfr[c][1] = L::tr(vs, c, 16); }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 p0, p1;
+        softmax_block(sa, j0, p0, p1);
+        add_pv(vfr, p0, p1);
+      }
+      wait_requests<(PD - 1) * NREQ>();    // this wave's share of the next tile has landed
+      __syncthreads();
+    }
+    const float ltot = lsum + __shfl_xor(lsum, 32, 64);
+    if (i < N) {
+      const float inv = 1.0f / ltot;
+      bf16* orow = O + ((int64_t)b * N + i) * h + hd * D;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[c][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4*>(orow + 32 * c + 8 * g + 4 * hb) = v;
+        }
+      if (hb == 0) lse[((int64_t)b * H + hd) * N + i] = (m + log2f(ltot)) * kLn2;
+    }
+    item = tq_next(tq, qc, entry, &mail);
+  }
+  tq_done(tq);
+}
+
 // ------------------------------------------------------------------------------- dQ
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
@@ -825,9 +1015,13 @@ mosaic_status fwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
   static hipError_t once_rc = hipSuccess;
   TileQueueArgs tq;
   int grid, hb;
-  MOSAIC_TRY(launch_queued(attn_fwd_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW,
+  // head size 128: the skewed pipeline, two workgroups per CU by registers; head size 64: the
+  // tile-at-a-time kernel, three per CU
+  constexpr bool PIPE = D == 128;
+  auto kern = [] { if constexpr (PIPE) return attn_fwd_mfma<D, NW>; else return attn_fwd_tile_mfma<D, NW>; }();
+  MOSAIC_TRY(launch_queued(kern, once, once_rc, smem, s, quota, (!PIPE && NW == 4) ? 3 : 8 / NW,
                            (int64_t)B * H, qtiles, causal, &tq, &grid, &hb));
-  attn_fwd_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles, hb, tq);
+  kern<<<grid, 64 * NW, smem, s>>>(qkv, O, lse, B, N, H, Hkv, causal, kLog2e / sqrtf((float)D), qtiles, hb, tq);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
