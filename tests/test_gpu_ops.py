@@ -180,6 +180,46 @@ def test_attention_fwd_bwd(mb, dtype, B, N, H, d, causal):
             assert np.array_equal(a, b0)
 
 
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("kind", ["rising", "steep", "falling", "spike"])
+def test_attention_forward_when_the_row_maximum_moves_late(mb, kind, causal):
+    """The forward kernel at head size 128 forms a block's probabilities against the reference
+    its row already has and repairs the block when they come out too large.  Scores that keep
+    rising along the keys by more than sixteen powers of two per block of 32 send every block
+    through that repair; falling scores and a single late spike take the other roads."""
+    B, N, H, d = 2, 416, 2, 128          # 13 key blocks, ragged last query tile
+    h = H * d
+    rng = np.random.default_rng(77)
+    q = np.ones((B * N, h)) + 0.05 * rng.standard_normal((B * N, h))
+    j = np.tile(np.arange(N), B)[:, None].astype(np.float64)
+    if kind == "rising":
+        k = (0.06 * j) * np.ones((1, h))                  # score rises by 0.06 * 128 / sqrt(128) * 32 = 21.7 nats per block
+    elif kind == "steep":
+        k = (0.3 * j) * np.ones((1, h))                   # 156 powers of two per block: the first attempt overflows to infinity
+    elif kind == "falling":
+        k = (0.06 * (N - j)) * np.ones((1, h))
+    else:
+        k = 0.02 * rng.standard_normal((B * N, h))
+        k[(np.arange(B * N) % N) == 300] = 1.5           # one key far above the rest, in the tenth block
+    k = k + 0.02 * rng.standard_normal((B * N, h))
+    v = rng.standard_normal((B * N, h))
+    qkv = quantize(np.concatenate([q, k, v], 1), "bf16")
+    ref_o = O.attention_fwd(qkv, B, N, H, causal)
+    ref_lse = O.attention_lse(qkv, B, N, H, causal)
+    qkv_ = to_dev(qkv, "bf16")
+    outs = []
+    for quota in (256, 24):
+        Oo = empty((B * N, h), "bf16"); lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        mb.op_attention_fwd(None, quota, "bf16", B, N, H, d, causal, qkv_, Oo, lse)
+        torch.cuda.synchronize()
+        outs.append([bits(Oo), bits(lse)])
+    assert np.isfinite(from_dev(Oo)).all() and np.isfinite(from_dev(lse)).all()
+    assert_close(from_dev(Oo), ref_o, "bf16", "O", roundings=2)
+    assert np.abs(from_dev(lse) - ref_lse).max() <= 1e-3 * max(1.0, np.abs(ref_lse).max())
+    for a, b0 in zip(outs[1], outs[0]):
+        assert np.array_equal(a, b0)
+
+
 NORM_SHAPES = [("f32", "layernorm", 32, 128), ("f32", "rmsnorm", 256, 128), ("bf16", "layernorm", 1568, 768),
                ("bf16", "rmsnorm", 1000, 2048), ("bf16", "rmsnorm", 130, 5120), ("bf16", "layernorm", 3, 3200),
                ("f32", "layernorm", 5, 24)]
