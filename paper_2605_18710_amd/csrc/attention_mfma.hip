@@ -903,47 +903,136 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
       if (t == claim_at) entry = tq_claim_ahead(tq, qc);
       const int ib = q_begin + (t % ntq) * RS;
       if (!(causal && ib + 31 < j0w) && j0w < N) {            // otherwise every (i, j) here is masked
-        f32x16 sacc, pacc;
+        if constexpr (D == 128) {
+          // at head size 128 the accumulators (128 registers), the K fragments (32) and the two
+          // score blocks leave no room for operand buffers: reads stay next to their use and the
+          // other wave of the SIMD covers their latency (with a lookahead the kernel spilled
+          // into scratch inside this loop and ran 9 % slower)
+          f32x16 sacc, pacc;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+          for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
-        }
-        // only blocks that touch the diagonal or the end of the sequence need the mask: a
-        // masked score becomes -inf, so its recomputed probability is exactly 0
-        if ((ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib)) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int gi = ib + acc_row(r, hb);
-            if ((gi >= N) || (j >= N) || (causal && j > gi)) sacc[r] = -INFINITY;
+          for (int s = 0; s < NS; ++s) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
+            pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
           }
-        }
-        // registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}: their statistics
-        // are four consecutive floats, one 16-byte LDS read each
-        float pv[16], ds[16];
-        const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
-        const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
+          // only blocks that touch the diagonal or the end of the sequence need the mask: a
+          // masked score becomes -inf, so its recomputed probability is exactly 0
+          if ((ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib)) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 l4 = sl4[2 * g], d4 = sd4[2 * g];
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            const float p = fast_exp2(fmaf(sacc[r], scale_log2, -lv[e] * kLog2e));
-            pv[r] = p;
-            ds[r] = p * (pacc[r] - dv4[e]);
+            for (int r = 0; r < 16; ++r) {
+              const int gi = ib + acc_row(r, hb);
+              if ((gi >= N) || (j >= N) || (causal && j > gi)) sacc[r] = -INFINITY;
+            }
           }
-        }
-        const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+          // registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}: their statistics
+          // are four consecutive floats, one 16-byte LDS read each
+          float pv[16], ds[16];
+          const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
+          const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 0), p0, dv[c], 0, 0, 0);
-          dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 16), p1, dv[c], 0, 0, 0);
-          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 0), d0, dk[c], 0, 0, 0);
-          dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 16), d1, dk[c], 0, 0, 0);
+          for (int g = 0; g < 4; ++g) {
+            const float4 l4 = sl4[2 * g], d4 = sd4[2 * g];
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * g + e;
+              const float p = fast_exp2(fmaf(sacc[r], scale_log2, -lv[e] * kLog2e));
+              pv[r] = p;
+              ds[r] = p * (pacc[r] - dv4[e]);
+            }
+          }
+          const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 0), p0, dv[c], 0, 0, 0);
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 16), p1, dv[c], 0, 0, 0);
+            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 0), d0, dk[c], 0, 0, 0);
+            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 16), d1, dk[c], 0, 0, 0);
+          }
+        } else {
+          // Operands come from LDS a fixed number of matrix instructions ahead of their use (a
+          // read issued right in front of the instruction that needs it costs the wave a whole
+          // LDS round trip per instruction); scheduling barriers keep that distance.
+          constexpr int PF = 2, PFS = 2;
+          f32x16 sacc, pacc;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
+          if constexpr (PFS > 0) {
+            bf16x8 qa[PFS + 1], da[PFS + 1], va[PFS + 1];       // Q, dO and V fragments of contraction step s in slot s % (PFS + 1)
+#pragma unroll
+            for (int s = 0; s < PFS; ++s) {
+              qa[s] = L::nat(qs, lr, s, hb); da[s] = L::nat(dos, lr, s, hb); va[s] = LV::nat(vblk, 32 * wave + lr, s, hb);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+              if (s + PFS < NS) {
+                const int n = (s + PFS) % (PFS + 1);
+                qa[n] = L::nat(qs, lr, s + PFS, hb); da[n] = L::nat(dos, lr, s + PFS, hb); va[n] = LV::nat(vblk, 32 * wave + lr, s + PFS, hb);
+              }
+              sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s % (PFS + 1)], kf[s], sacc, 0, 0, 0);
+              pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[s % (PFS + 1)], va[s % (PFS + 1)], pacc, 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          } else {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+              sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qs, lr, s, hb), kf[s], sacc, 0, 0, 0);
+              pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(dos, lr, s, hb), LV::nat(vblk, 32 * wave + lr, s, hb), pacc, 0, 0, 0);
+            }
+          }
+          // the first transposed fragments of the products below are on their way while the
+          // probabilities are formed.  Product w of 4 * NC: column block w / 4; w % 4 = 0: dV, keys
+          // half 0; 1: dK, half 0; 2: dV, half 1; 3: dK, half 1 (each accumulator takes half 0 first,
+          // and no instruction follows one that writes the same accumulator)
+          auto tr_operand = [&](int w) -> bf16x8 {
+            const int c = w >> 2, part = w & 3;
+            return L::tr((part & 1) ? qs : dos, c, 16 * (part >> 1));
+          };
+          bf16x8 ta[PF + 1];
+#pragma unroll
+          for (int w = 0; w < PF; ++w) ta[w] = tr_operand(w);
+          __builtin_amdgcn_sched_barrier(0);
+          // only blocks that touch the diagonal or the end of the sequence need the mask: a
+          // masked score becomes -inf, so its recomputed probability is exactly 0
+          if ((ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib)) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int gi = ib + acc_row(r, hb);
+              if ((gi >= N) || (j >= N) || (causal && j > gi)) sacc[r] = -INFINITY;
+            }
+          }
+          // registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}: their statistics
+          // are four consecutive floats, one 16-byte LDS read each
+          float pv[16], ds[16];
+          const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
+          const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 l4 = sl4[2 * g], d4 = sd4[2 * g];
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * g + e;
+              const float p = fast_exp2(fmaf(sacc[r], scale_log2, -lv[e] * kLog2e));
+              pv[r] = p;
+              ds[r] = p * (pacc[r] - dv4[e]);
+            }
+          }
+          const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int w = 0; w < 4 * NC; ++w) {
+            if (w + PF < 4 * NC) ta[(w + PF) % (PF + 1)] = tr_operand(w + PF);
+            const int c = w >> 2, part = w & 3;
+            const bf16x8 a = ta[w % (PF + 1)];
+            if (part == 0) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p0, dv[c], 0, 0, 0);
+            else if (part == 1) dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, d0, dk[c], 0, 0, 0);
+            else if (part == 2) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p1, dv[c], 0, 0, 0);
+            else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, d1, dk[c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       }
       wait_requests<(PD - 1) * NREQ>();
