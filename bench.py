@@ -340,6 +340,29 @@ def candidate_quotas(t_full_ms, t_budget_ms, cus, lo=8, max_points=11):
     return qs
 
 
+def module_steps(mb, synth, config, name, steps, warmup):
+    """`warmup + steps` forward+backward steps of one module of the workload alone on all CUs
+    and nothing else: under `rocprofv3 --kernel-trace --stats` the per-kernel totals divided by
+    the number of steps are the kernel mix of one step."""
+    from paper_2605_18710_amd.workload import StagedStage
+    stage = StagedStage(config)
+    if name not in stage.names:
+        raise SystemExit(f"workload {config} has modules {stage.names}, not {name!r}")
+    i = stage.names.index(name)
+    m = stage.staged[i]
+    cus = mb.device_cu_count()
+    mb.pool_reserve(cus, 0, mb.STRIPED)
+    ms = []
+    for k in range(warmup + steps):
+        r = mb.stage_run([m.module], [m.x], [m.y], [cus], [0], mb.STRIPED, mb.TIME_SLICED, dy=[m.dy], target=[m.target], dx=[m.dx], loss=[m.loss])
+        if k >= warmup:
+            ms.append(r["module_ms"][0])
+    stage.destroy()
+    mb.pool_clear()
+    return {"workload": synth.WORKLOADS[config]["name"], "module": name, "steps_run": warmup + steps, "timed": steps,
+            "ms_per_step": round(statistics.median(ms), 4), "min_ms": round(min(ms), 4)}
+
+
 def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=False):
     """Builds the staged workload `config`, measures the time-sliced baseline, the time-vs-CU
     curves, every named plan plus the plans derived from the curves (three-way, two modules
@@ -565,6 +588,8 @@ def main():
     ap.add_argument("--library-only", action="store_true", help="context: the forward GEMM beside torch.matmul (vendor library) at six shapes")
     ap.add_argument("--plan", default=None, help="comma-separated CU quotas, one per group: time this plan instead of the best measured one "
                     "(under rocprofv3 the measured ranking of plans is distorted)")
+    ap.add_argument("--module-only", default=None, metavar="NAME",
+                    help="only steps of one module of the workload (e.g. llm, vit, audio), alone on all CUs: the kernel mix of a step, for rocprofv3 --stats")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--layer-split", action="store_true",
                     help="also measure the two-stage plan that cuts the decoder in time (built after the timed steps)")
@@ -587,6 +612,9 @@ def main():
     Tl, hl, fl = llm["batch"] * llm["seq"], llm["hidden"], llm["mlp"]
     cus = mb.device_cu_count()
 
+    if args.module_only:
+        print(json.dumps(module_steps(mb, synth, args.config, args.module_only, args.steps, args.warmup)))
+        return
     if args.attention_only:
         print(json.dumps(attention_kernels(mb, llm["batch"], llm["seq"], llm["heads"], hl // llm["heads"], 1, reps=50)))
         return
