@@ -176,55 +176,71 @@ struct Planner {
     return ev;
   }
 
-  // stage graph: edge a -> b when a module of stage a feeds a module of stage b
-  std::vector<std::vector<int>> stage_adj(const std::vector<uint32_t>& stages) const {
-    std::vector<int> where(P.n, -1);
-    for (size_t i = 0; i < stages.size(); ++i)
-      for (int m = 0; m < P.n; ++m) if (stages[i] >> m & 1) where[m] = (int)i;
-    std::vector<std::vector<int>> adj(stages.size());
-    for (auto& ed : P.edges)
-      if (where[ed.first] != where[ed.second]) adj[where[ed.first]].push_back(where[ed.second]);
-    return adj;
-  }
-  static bool reachable(const std::vector<std::vector<int>>& adj, int src, int dst) {
-    std::vector<char> seen(adj.size(), 0);
-    std::vector<int> stack{src};
-    while (!stack.empty()) {
-      const int v = stack.back(); stack.pop_back();
-      for (int w : adj[v]) {
-        if (w == dst) return true;
-        if (!seen[w]) { seen[w] = 1; stack.push_back(w); }
-      }
-    }
-    return false;
-  }
-  static int lowest(uint32_t mask) { return __builtin_ctz(mask); }
+  // ---- the stage list and its order -------------------------------------------------------
+  // A plan in the making is a list of disjoint module sets (bit masks) kept in an execution
+  // order.  Everything the search needs to know about the order is one word per stage:
+  // after[i] = the stages that must run after stage i, i.e. the transitive closure of "a module
+  // of i feeds a module of j".  Two stages may be merged exactly when neither is in the
+  // other's word (otherwise a third stage, or an edge between the two, would end up both
+  // before and after the merged stage).
+  struct StageList {
+    std::vector<uint32_t> mask;      // modules of each stage, in execution order
+    std::vector<uint32_t> after;     // bit j: stage j depends, directly or not, on stage i
+  };
 
-  // Kahn's algorithm; among ready stages the one holding the smallest module index first
-  bool topo(std::vector<uint32_t>* stages) const {
-    auto adj = stage_adj(*stages);
-    const size_t S = stages->size();
-    std::vector<int> indeg(S, 0);
-    for (size_t a = 0; a < S; ++a) for (int b : adj[a]) ++indeg[b];
-    std::vector<uint32_t> out;
-    std::vector<char> done(S, 0);
-    for (size_t step = 0; step < S; ++step) {
+  // direct successors of every stage, as bit masks over stage indices
+  std::vector<uint32_t> successors(const std::vector<uint32_t>& mask) const {
+    std::vector<int> where(P.n, -1);
+    for (size_t i = 0; i < mask.size(); ++i)
+      for (int m = 0; m < P.n; ++m) if (mask[i] >> m & 1) where[m] = (int)i;
+    std::vector<uint32_t> succ(mask.size(), 0);
+    for (auto& ed : P.edges)
+      if (where[ed.first] != where[ed.second]) succ[where[ed.first]] |= 1u << where[ed.second];
+    return succ;
+  }
+
+  // Puts the stages into the order Kahn's algorithm gives when, among the stages whose
+  // predecessors are all placed, the one holding the smallest module index goes first, and
+  // fills `after`.  False when the stage graph has a cycle.
+  bool order(StageList* L) const {
+    const size_t S = L->mask.size();
+    const std::vector<uint32_t> succ = successors(L->mask);
+    std::vector<int> waiting(S, 0);
+    for (size_t a = 0; a < S; ++a)
+      for (size_t b = 0; b < S; ++b) if (succ[a] >> b & 1) ++waiting[b];
+    std::vector<int> perm;                       // perm[k] = old index of the stage placed k-th
+    uint32_t placed = 0;
+    while (perm.size() < S) {
       int pick = -1;
-      for (size_t i = 0; i < S; ++i)
-        if (!done[i] && indeg[i] == 0 && (pick < 0 || lowest((*stages)[i]) < lowest((*stages)[pick]))) pick = (int)i;
-      if (pick < 0) return false;            // cycle
-      done[pick] = 1;
-      out.push_back((*stages)[pick]);
-      for (int b : adj[pick]) --indeg[b];
+      for (size_t i = 0; i < S; ++i) {
+        if ((placed >> i & 1) || waiting[i] != 0) continue;
+        if (pick < 0 || __builtin_ctz(L->mask[i]) < __builtin_ctz(L->mask[pick])) pick = (int)i;
+      }
+      if (pick < 0) return false;
+      placed |= 1u << pick;
+      perm.push_back(pick);
+      for (size_t b = 0; b < S; ++b) if (succ[pick] >> b & 1) --waiting[b];
     }
-    *stages = out;
+    std::vector<int> new_index(S);
+    for (size_t k = 0; k < S; ++k) new_index[perm[k]] = (int)k;
+    StageList out;
+    out.mask.resize(S); out.after.assign(S, 0);
+    for (size_t k = 0; k < S; ++k) out.mask[k] = L->mask[perm[k]];
+    // closure from the back of the order: a stage's word is its successors plus theirs
+    for (int k = (int)S - 1; k >= 0; --k) {
+      uint32_t w = 0;
+      for (size_t b = 0; b < S; ++b)
+        if (succ[perm[k]] >> b & 1) w |= (1u << new_index[b]) | out.after[new_index[b]];
+      out.after[k] = w;
+    }
+    *L = out;
     return true;
   }
 
-  // Early pruning: the merge can only beat best_gain if T_xy < T_x + T_y - best_gain, so every
-  // module of the merged stage needs at least one level whose own time is below that bound
+  // Early pruning: the merge can only beat `bound` = T_x + T_y - (best saving so far) if every
+  // module of the merged stage has at least one level whose own time is below that bound
   // (a delay term can only be trusted not to shorten a time when its coefficients are >= 0).
-  bool prune(uint32_t merged, double bound) const {
+  bool hopeless(uint32_t merged, double bound) const {
     if (P.rect && (P.e[0] < 0 || P.e[1] < 0 || P.e[2] < 0)) return false;
     for (int m = 0; m < P.n; ++m) {
       if (!(merged >> m & 1)) continue;
@@ -235,40 +251,51 @@ struct Planner {
     return false;
   }
 
-  bool run(std::vector<uint32_t>* stages_out, std::vector<Eval>* evals_out) {
-    std::vector<uint32_t> stages;
-    for (int m = 0; m < P.n; ++m) stages.push_back(1u << m);
-    if (!topo(&stages)) return false;
-    std::map<uint32_t, Eval> cur;              // evaluations of the stages in the list
-    for (uint32_t s : stages) cur[s] = eval(s);
-    while (stages.size() > 1) {
-      ++st.rounds;
-      double best_gain = 0.0;
-      int bx = -1, by = -1;
-      Eval best_ev{};
-      auto adj = stage_adj(stages);
-      for (size_t x = 0; x < stages.size(); ++x)
-        for (size_t y = x + 1; y < stages.size(); ++y) {
-          if (reachable(adj, (int)x, (int)y) || reachable(adj, (int)y, (int)x)) continue;
-          const uint32_t u = stages[x] | stages[y];
-          const double tx = cur[stages[x]].t, ty = cur[stages[y]].t;
-          if ((flags & MOSAIC_PLANNER_EARLY_PRUNE) && prune(u, tx + ty - best_gain)) { ++st.pruned; continue; }
-          const Eval ev = eval(u);
-          const double gain = tx + ty - ev.t;
-          if (gain > best_gain) { best_gain = gain; bx = (int)x; by = (int)y; best_ev = ev; }
-        }
-      if (bx < 0) break;
-      const uint32_t u = stages[bx] | stages[by];
-      std::vector<uint32_t> next;
-      for (size_t i = 0; i < stages.size(); ++i) if ((int)i != bx && (int)i != by) next.push_back(stages[i]);
-      next.push_back(u);
-      cur[u] = best_ev;
-      stages = next;
-      if (!topo(&stages)) return false;
+  // One merge proposal: the two stages (positions in the list), the merged set and what the
+  // merge saves.  best_merge() looks at every pair the order allows, in list order, and keeps
+  // the first one with the largest saving above zero.
+  struct Merge { int x = -1, y = -1; uint32_t mask = 0; double saving = 0.0; Eval ev{}; };
+
+  Merge best_merge(const StageList& L, const std::map<uint32_t, Eval>& known) {
+    Merge best;
+    const int S = (int)L.mask.size();
+    for (int x = 0; x < S; ++x) {
+      // stages that neither follow x nor are followed by it; only those behind x in the list
+      uint32_t free_of_x = 0;
+      for (int y = x + 1; y < S; ++y)
+        if (!(L.after[x] >> y & 1) && !(L.after[y] >> x & 1)) free_of_x |= 1u << y;
+      const double tx = known.at(L.mask[x]).t;
+      for (int y = x + 1; y < S; ++y) {
+        if (!(free_of_x >> y & 1)) continue;
+        const uint32_t u = L.mask[x] | L.mask[y];
+        const double apart = tx + known.at(L.mask[y]).t;
+        if ((flags & MOSAIC_PLANNER_EARLY_PRUNE) && hopeless(u, apart - best.saving)) { ++st.pruned; continue; }
+        const Eval ev = eval(u);
+        if (apart - ev.t > best.saving) { best.x = x; best.y = y; best.mask = u; best.saving = apart - ev.t; best.ev = ev; }
+      }
     }
-    *stages_out = stages;
+    return best;
+  }
+
+  // Alg. 1: every module its own stage; merge while some merge saves time.
+  bool run(std::vector<uint32_t>* stages_out, std::vector<Eval>* evals_out) {
+    StageList L;
+    for (int m = 0; m < P.n; ++m) L.mask.push_back(1u << m);
+    if (!order(&L)) return false;
+    std::map<uint32_t, Eval> known;            // evaluations of the stages in the list
+    for (uint32_t s : L.mask) known[s] = eval(s);
+    while (L.mask.size() > 1) {
+      ++st.rounds;
+      const Merge mg = best_merge(L, known);
+      if (mg.x < 0) break;
+      known[mg.mask] = mg.ev;
+      L.mask[mg.x] = mg.mask;                  // the merged stage takes the place of the first
+      L.mask.erase(L.mask.begin() + mg.y);
+      if (!order(&L)) return false;
+    }
+    *stages_out = L.mask;
     evals_out->clear();
-    for (uint32_t s : stages) evals_out->push_back(cur[s]);
+    for (uint32_t s : L.mask) evals_out->push_back(known[s]);
     return true;
   }
 };
