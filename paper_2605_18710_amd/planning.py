@@ -3,13 +3,17 @@ module's time-vs-CU curve (the scaling surface of Sec. 3.3 restricted to one GPU
 the bandwidth-utilisation proxy, fits the interference coefficients of Eq. 8 from a few
 colocated probe runs, forms stages with Alg. 1 and executes the stages one after another,
 each colocated under its allocation.  The fit of Eq. 8, StageEval and Alg. 1 run in the
-library; what is formed here, in Python, is bookkeeping around them: the utilisation proxy
-B(m, a) (a module's algorithmic bytes or model FLOPs, from `synth`, divided by its measured
-time and the peak -- a stand-in for the counter reading the paper profiles, not one) and the
-delay observations (differences and ratios of measured times).
+library; what is formed here, in Python, is bookkeeping around them: the utilisation
+B(m, a) = work of a step / (measured time x peak) and the delay observations (differences
+and ratios of measured times).  The work of a step is, by choice of `proxy`: "counters", the
+HBM-side bytes that the L2's fabric counters read for one step of the module (a table under
+profiles/, written from rocprofv3 runs; Sec. 3.3 profiles memory-bandwidth utilisation);
+"bandwidth", the algorithmic bytes from `synth` where no counter reading exists; "compute",
+the model FLOPs.
 """
 from __future__ import annotations
 
+import os
 import statistics
 from typing import Dict, List, Sequence, Tuple
 
@@ -19,6 +23,27 @@ from .workload import StagedModule
 
 PEAK_HBM_BYTES_PER_S = 8.0e12
 PEAK_BF16_FLOPS = 2.5e15
+STEP_BYTES_TABLE = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles", "module_step_hbm_bytes.txt")
+
+
+def shape_signature(cfg: dict) -> str:
+    """The key of a module in the table of measured step bytes."""
+    if cfg["kind"] == "projector":
+        return f"projector B{cfg['batch']} N{cfg['seq']} in{cfg['in_dim']} out{cfg['out_dim']}"
+    return f"{cfg['kind']} B{cfg['batch']} N{cfg['seq']} h{cfg['hidden']} f{cfg['mlp']} L{cfg['layers']}"
+
+
+def measured_step_bytes(path: str = STEP_BYTES_TABLE) -> Dict[str, float]:
+    """shape signature -> HBM-side bytes (fetched + written) of one step, from the counter
+    table; empty when the table is missing."""
+    out: Dict[str, float] = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) >= 6 and cells[0] == "bytes":
+            out[cells[3]] = float(cells[4]) + float(cells[5])
+    return out
 
 
 class PlannedJob:
@@ -63,17 +88,26 @@ class PlannedJob:
         return [[self._run([m], [q], iters)["stage_ms"] for q in grid] for m in range(len(self.staged))]
 
     def bandwidth_table(self, times: List[List[float]], proxy: str = "bandwidth") -> List[List[float]]:
-        """B(m, a) in [0,1], the utilisation proxy of Eq. 8.  "bandwidth" (the paper's): algorithmic
-        bytes of a step over the time it took, against the HBM peak.  "compute": model FLOPs
+        """B(m, a) in [0,1], the utilisation of Eq. 8.  "counters": the bytes the HBM-side
+        counters read for one step of the module (measured once per shape on all CUs; the
+        re-reads that make up most of them belong to the kernels, not to the quota), over the
+        time the step took at quota a, against the HBM peak.  "bandwidth": the same with algorithmic
+        bytes.  "compute": model FLOPs
         over the time, against the bf16 matrix peak -- on this GPU co-runners contend for the
         board's power budget before they contend for bandwidth, and matrix-core utilisation is
         the better stand-in for a module's share of that budget."""
         out = []
+        table = measured_step_bytes() if proxy == "counters" else {}
         for cfg, row in zip(self.cfgs, times):
-            if proxy == "bandwidth":
+            if proxy == "counters":
+                # a module whose shape was never profiled falls back to its algorithmic bytes
+                w, peak = table.get(shape_signature(cfg), synth.module_bytes(cfg, self.elem)), PEAK_HBM_BYTES_PER_S
+            elif proxy == "bandwidth":
                 w, peak = synth.module_bytes(cfg, self.elem), PEAK_HBM_BYTES_PER_S
-            else:
+            elif proxy == "compute":
                 w, peak = synth.module_flops(cfg), PEAK_BF16_FLOPS
+            else:
+                raise ValueError(f"unknown proxy {proxy!r}")
             out.append([min(1.0, w / (t * 1e-3) / peak) for t in row])
         return out
 

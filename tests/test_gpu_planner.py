@@ -31,6 +31,10 @@ def test_clip_like_job_is_planned_and_run(mb):
         assert all(t > 0 for row in times for t in row)
         bw = job.bandwidth_table(times)
         assert all(0.0 <= b <= 1.0 for row in bw for b in row)
+        # shapes nobody profiled: the counter-based table falls back to the algorithmic bytes
+        assert job.bandwidth_table(times, proxy="counters") == bw
+        with pytest.raises(ValueError):
+            job.bandwidth_table(times, proxy="nonsense")
         fit = job.fit_interference(grid, times, bw, [{0: 128, 1: 128}, {0: 64, 1: 192}, {0: 192, 1: 64}, {2: 128, 3: 128},
                                                       {0: 32, 1: 192}, {2: 64, 3: 192}], iters=2)
         assert fit["n_obs"] == 12 and np.isfinite(fit["r2"]) and fit["r2"] >= fit["r2_additive"] - 1e-9

@@ -225,3 +225,19 @@ def test_committed_gemm_traffic_parses_and_is_not_below_the_algorithmic_bytes():
             t = bench.profiled_traffic(form, (T, k, n))
             assert isinstance(t, int) and algorithmic <= t < 8 * algorithmic, (form, t)
     assert bench.profiled_traffic("fprop", (8, 8, 8)) is None
+
+
+def test_measured_step_bytes_cover_the_benchmarked_modules_and_are_not_below_the_model():
+    """The counter-based utilisation proxy of the planner reads a committed table: every module
+    of the two benchmarked workloads has a row, and no row claims fewer bytes than the
+    algorithmic count (every operand read once, every result written once)."""
+    from paper_2605_18710_amd import planning, synth
+    table = planning.measured_step_bytes()
+    assert table, "profiles/module_step_hbm_bytes.txt is missing or empty"
+    for config in (4, 1):
+        for m in synth.WORKLOADS[config]["modules"]:
+            key = planning.shape_signature(m)
+            assert key in table, key
+            assert table[key] >= synth.module_bytes(m, 2), key
+            assert table[key] <= 8.0 * synth.module_bytes(m, 2), key     # a re-read factor beyond this would be a parsing slip
+    assert planning.measured_step_bytes("/nonexistent/table.txt") == {}
