@@ -444,8 +444,29 @@ def measure_workload(mb, synth, config, steps, warmup, forced=None, layer_split=
             curves[g][grid.index(q)] = median_plan(one, 2)[0]
     chosen, predicted = mb.plan_choose(grid, curves, cus)
 
+    # the paper's granularity (Sec. 3.4: quotas in steps of 10 % of the device): curves on the
+    # multiples of 8 CUs nearest to the deciles, and the split chosen from those alone
+    deciles = sorted({int(round(cus * d / 10.0 / 8.0)) * 8 for d in range(1, 10)})
+    dcurves = [[1e30] * len(deciles) for _ in range(ngroups)]
+    for g in range(ngroups):
+        q_min = group_ms_full[g] * cus / (1.25 * ts_ms)
+        for i, q in enumerate(deciles):
+            if q < q_min:
+                continue
+            if q in grid and curves[g][grid.index(q)] < 1e29:
+                dcurves[g][i] = curves[g][grid.index(q)]
+            else:
+                one = dict(label="curve", stages=[dict(groups=[g], quotas=[q], offsets=[0])])
+                dcurves[g][i] = median_plan(one, 2)[0]
+    try:
+        dchosen, dpredicted = mb.plan_choose(deciles, dcurves, cus)
+    except mb.MosaicError:
+        dchosen, dpredicted = None, None          # no decile split fits every module
+
     plans = [packed(p, "named") for p in wl["plans"]]
     plans.append(packed(chosen, "chosen from the curves (Eq. 4-5)"))
+    if dchosen is not None and dpredicted < 1e29:
+        plans.append(dict(packed(dchosen, "chosen from curves on the decile grid (Sec. 3.4 granularity)"), predicted_ms=round(dpredicted, 4)))
     if ngroups == 3:
         # the two small modules share one quota and run back to back beside the large one
         big = max(range(ngroups), key=lambda g: group_ms_full[g])
