@@ -65,6 +65,38 @@ def test_decoder_gate_up_projection_sampled(mb):
     assert_close(dWh, X.T @ dY[:, cols], "bf16", "dW columns")
 
 
+def test_gate_up_projection_with_swiglu_epilogue_at_the_7b_shape_sampled(mb):
+    """T=32768, k=4096, n=22016: the dominant product of configs[2] and configs[4], with silu(gate)*up
+    written by the epilogue.  Sampled rows of [gate | up] and of the activation against the checker
+    (rows at tile edges, and in the tiles of the last, partial round, which the quarter-tile launch
+    takes); the activation must equal, bit for bit, the separate pass over the stored product."""
+    T, k, f = 32768, 4096, 11008
+    n = 2 * f
+    X_ = torch.from_numpy(synth.bulk_uniform(9101, (T, k), -1.0, 1.0)).to(torch.bfloat16).cuda()
+    W_ = torch.from_numpy(synth.bulk_uniform(9102, (k, n), -0.03, 0.03)).to(torch.bfloat16).cuda()
+    Z = torch.empty((T, n), dtype=torch.bfloat16, device="cuda")
+    A = torch.empty((T, f), dtype=torch.bfloat16, device="cuda")
+    A2 = torch.empty((T, f), dtype=torch.bfloat16, device="cuda")
+    snaps = []
+    for q in (256, 224):
+        Z.fill_(float("nan")); A.fill_(float("nan"))
+        mb.op_linear_act_fwd(None, q, "bf16", mb.SWIGLU, T, k, n, X_, W_, None, Z, A)
+        torch.cuda.synchronize()
+        snaps.append([bits(Z[::97]), bits(A[::97])])
+    for a, b in zip(snaps[0], snaps[1]):
+        assert np.array_equal(a, b), "full-size result depends on the quota"
+    mb.op_swiglu_fwd(None, 256, "bf16", T, f, Z, A2)
+    torch.cuda.synchronize()
+    assert torch.equal(A.view(torch.int16), A2.view(torch.int16)), "epilogue activation differs from the separate pass"
+    rows = synth.integers(9104, (24,), 0, T)
+    rows[:8] = [0, 255, 256, T - 1, T - 256, T - 257, 16383, 16384]
+    ridx = torch.from_numpy(rows).long().cuda()
+    Xh, Wh = X_[ridx].float().cpu().numpy().astype(np.float64), W_.float().cpu().numpy().astype(np.float64)
+    ref_z = Xh @ Wh
+    assert_close(from_dev(Z[ridx]), ref_z, "bf16", "[gate | up] rows")
+    assert_close(from_dev(A[ridx]), O.swiglu_fwd(ref_z[:, :f], ref_z[:, f:]), "bf16", "activation rows", roundings=4)
+
+
 def test_decoder_attention_sampled_heads(mb):
     """B=8, N=1024, 16 heads of 128, causal: sampled (sample, head) problems."""
     B, N, H, d = 8, 1024, 16, 128
