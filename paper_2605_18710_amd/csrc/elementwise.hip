@@ -642,22 +642,63 @@ __global__ __launch_bounds__(kThreads) void split_img_kernel(const T* __restrict
   }
 }
 
-// Owner-computes embedding gradient: a workgroup owns table row v and adds the upstream
-// rows of every occurrence of v in ascending position, so repeated ids need no atomics.
+// Embedding gradient, owner computes: the workgroup that owns table row v walks all token
+// positions once, 256 at a time, and gathers the positions that hold v into a list in LDS in
+// ascending order (waves in order, lanes in order, by ballot and prefix count); whenever the
+// list is nearly full, and at the end, every thread adds the listed rows of dy to the column
+// sums it keeps in registers, in list order.  The sum of a row is therefore taken over its
+// occurrences in ascending position whatever the grid, repeated ids need no atomics, and a
+// row nobody uses costs one pass over the ids and a zero fill.
+constexpr int kEmbedList = 1024;                     // positions gathered before they are summed
+constexpr int kEmbedMaxCols = 32;                    // columns per thread: rows of up to 8192 elements
 template <typename T>
 __global__ __launch_bounds__(kThreads) void embed_grad_kernel(const T* __restrict__ dy, const int32_t* __restrict__ ids,
                                                               const int32_t* __restrict__ counts,
                                                               T* __restrict__ dtable, int B, int N, int n_img, int h, int vocab) {
+  __shared__ int list[kEmbedList];
+  __shared__ int wave_hits[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int total = B * N;
   for (int v = blockIdx.x; v < vocab; v += gridDim.x) {
-    for (int c0 = 0; c0 < h; c0 += kThreads) {
-      const int c = c0 + threadIdx.x;
-      float acc = 0.f;
-      for (int b = 0; b < B; ++b) {
-        for (int t = stem_n_img(counts, b, n_img); t < N; ++t) {
-          if (stem_id(ids, counts, b, t, N, n_img, vocab) == v && c < h) acc += to_f32(dy[((int64_t)b * N + t) * h + c]);
+    float acc[kEmbedMaxCols];
+#pragma unroll
+    for (int j = 0; j < kEmbedMaxCols; ++j) acc[j] = 0.f;
+    int n_list = 0;                                  // the same in every thread
+    auto add_listed = [&]() {
+      for (int e = 0; e < n_list; ++e) {
+        const T* row = dy + (int64_t)list[e] * h;
+#pragma unroll
+        for (int j = 0; j < kEmbedMaxCols; ++j) {
+          const int c = j * kThreads + threadIdx.x;
+          if (c < h) acc[j] += to_f32(row[c]);
         }
       }
-      if (c < h) dtable[(int64_t)v * h + c] = from_f32<T>(acc);
+      __syncthreads();                               // everybody is done with the list
+      n_list = 0;
+    };
+    for (int p0 = 0; p0 < total; p0 += kThreads) {
+      const int p = p0 + threadIdx.x;
+      bool hit = false;
+      if (p < total) {
+        const int b = p / N, t = p - b * N;
+        hit = t >= stem_n_img(counts, b, n_img) && stem_id(ids, counts, b, t, N, n_img, vocab) == v;
+      }
+      const unsigned long long m = __ballot(hit);
+      if (lane == 0) wave_hits[wave] = __popcll(m);
+      __syncthreads();
+      int before = n_list, all = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) { if (w < wave) before += wave_hits[w]; all += wave_hits[w]; }
+      if (hit) list[before + __popcll(m & ((1ull << lane) - 1ull))] = p;
+      n_list += all;
+      __syncthreads();                               // list entries visible; wave_hits free for the next chunk
+      if (n_list > kEmbedList - kThreads) add_listed();
+    }
+    if (n_list > 0) add_listed();
+#pragma unroll
+    for (int j = 0; j < kEmbedMaxCols; ++j) {
+      const int c = j * kThreads + threadIdx.x;
+      if (c < h) dtable[(int64_t)v * h + c] = from_f32<T>(acc[j]);
     }
   }
 }
@@ -982,6 +1023,7 @@ mosaic_status launch_text_stem_bwd(hipStream_t s, int quota, int dtype, int B, i
     MOSAIC_LAUNCH_CHECK();
   }
   if (vocab > 0) {
+    if (h > kEmbedMaxCols * kThreads) MOSAIC_FAIL(MOSAIC_EUNSUPPORTED, "embedding rows of %d elements; the gradient kernel holds up to %d", h, kEmbedMaxCols * kThreads);
     const int grid = grid_for(quota, 8, vocab);
     if (dtype == MOSAIC_BF16)
       embed_grad_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, ids, counts, (bf16*)dtable, B, N, n_img, h, vocab);

@@ -234,3 +234,48 @@ def test_text_stem_with_per_sample_image_token_counts_chained(mb, dtype):
             assert rel_l2(g[k], g_ref[0][k]) <= tol(dtype), k
     finally:
         stem.destroy(); llm.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_embedding_gradient_with_heavily_repeated_ids(mb, dtype):
+    """A table of five rows under 3 x 1096 text positions, two thirds of them the same id: the
+    owner of that row gathers its occurrences through several fills of its position list; one
+    row is never used (zero gradient), ids outside the table count for the nearest row.  Rows
+    of 520 elements span three column blocks, the last one ragged.  Bit-identical across quotas."""
+    B, n_img, N, h, vocab = 3, 4, 1100, 520, 5
+    seed = 990
+    ids = synth.integers(seed, (B, N - n_img), 0, 3)                 # ids 0..2; row 3 stays unused
+    heavy = synth.uniform(seed + 1, (B, N - n_img), 0.0, 1.0) < 0.66
+    ids[heavy] = 2
+    ids[1, 17] = -3; ids[2, 900] = vocab + 11                         # clamped to rows 0 and 4
+    ids_ref = np.clip(ids, 0, vocab - 1)
+    dy = quantize(synth.normal(seed + 2, (B * N, h)), dtype)
+    img = quantize(synth.normal(seed + 3, (B * n_img, h)), dtype)
+    table = quantize(synth.normal(seed + 4, (vocab, h), 0, 0.02), dtype)
+    dimg_ref, dtxt = O.split_tokens(dy, B, n_img, N - n_img)
+    gtab_ref = O.embedding_bwd(ids_ref, dtxt, vocab)
+    assert (ids_ref == 2).sum() > 2 * 1024 and not (ids_ref == 3).any()
+    stem = mb.Module(dict(kind="text_stem", batch=B, seq=N, hidden=h, vocab=vocab, n_img=n_img), dtype)
+    try:
+        stem.set_tensor("table", table)
+        ids_ = torch.from_numpy(ids.reshape(-1).astype(np.int32)).cuda()
+        stem.bind_ids(ids_)
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        y = torch.empty(B * N * h, dtype=td, device="cuda")
+        snaps = []
+        for quota in (256, 24):
+            stem.grads.fill_(float("nan"))
+            dx = torch.full((B * n_img * h,), float("nan"), dtype=td, device="cuda")
+            stem.step(quota, None, to_dev(img, dtype), y, dy=to_dev(dy, dtype), dx=dx)
+            torch.cuda.synchronize()
+            snaps.append((stem.grads.clone(), dx.clone()))
+        got = stem.get_tensor("table", grads=True)
+        # a row's gradient is a sum over up to 2200 rounded rows: rounding of the result plus fp32 accumulation
+        assert_close(got, gtab_ref, dtype, "table gradient", roundings=4)
+        assert not got[3].any(), "a row nobody uses gets a zero gradient"
+        assert np.array_equal(from_dev(snaps[0][1]).reshape(B * n_img, h), dimg_ref), "image-token gradient is a copy: exact"
+        for a, b in zip(snaps[0], snaps[1]):
+            assert torch.equal(a.view(torch.int32 if dtype == "f32" else torch.int16), b.view(torch.int32 if dtype == "f32" else torch.int16))
+    finally:
+        stem.destroy()
+
