@@ -38,6 +38,7 @@
 // fp32 path (and shapes the MFMA path does not cover): a plain LDS-tiled FMA kernel with
 // arbitrary strides; ascending-k accumulation as well.
 #include <stdlib.h>
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 #include "activations.h"
@@ -199,6 +200,41 @@ struct FragReader {
   }
 };
 
+// Position `tile` of the tile list -> (tile row, tile column).  The list is panel-major: panels
+// of 8 tile columns, row-major inside a panel, so 32 consecutive entries form a 4 x 8 patch that
+// shares operand panels in one XCD's L2.  Above that, tile rows are taken in super-blocks of
+// `row_block` rows (all panels of a super-block before the next super-block), sized on the
+// host so that the row operand of a super-block (row_block x 256 rows x K) stays in the
+// last-level cache: it is then re-read from there, not from HBM, once per panel (measured on
+// the 7B-shaped products: +3 % forward, +4 % input gradient; the board is power-bound and HBM
+// reads cost energy).  Both kernels and both launches of a mixed plan use this one order.
+__device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int row_block, int* row, int* col) {
+  const int per_sb = row_block * tiles_n;
+  const int sb = tile / per_sb, rem = tile - sb * per_sb;
+  const int rows_sb = min(row_block, tiles_m - sb * row_block);
+  const int panel = rem / (rows_sb * 8);
+  const int pw = min(8, tiles_n - panel * 8);
+  const int in_panel = rem - panel * rows_sb * 8;
+  *row = sb * row_block + in_panel / pw;
+  *col = panel * 8 + in_panel % pw;
+}
+
+// Tile rows per super-block: the row operand of a super-block (rows x 256 x K bf16) is kept to
+// about half of the 256 MB last-level cache, in whole 4-row patches.  Depends on K alone.
+#ifndef MOSAIC_LLC_ROW_BYTES
+#define MOSAIC_LLC_ROW_BYTES (128 << 20)
+#endif
+// Only products with many tile rows are cut (tiles_m counts 256-row tiles): with 64 rows or
+// fewer, two rounds of 256 tiles already span every row and the plain order re-reads nothing
+// that a cut would save (the weight-gradient form of the 7B shape, 16 tile rows, lost 3 % to a
+// cut of 8 rows).
+static inline int row_block_for(int64_t K, int64_t tiles_m) {
+  if (tiles_m <= 64) return (int)((tiles_m + 3) / 4 * 4);
+  int64_t rb = (int64_t)MOSAIC_LLC_ROW_BYTES / (512 * (K > 0 ? K : 1)) / 4 * 4;
+  if (rb < 4) rb = 4;
+  return (int)std::min<int64_t>(rb, (tiles_m + 3) / 4 * 4);
+}
+
 // One unit of work: an output tile, or (SPLITK) one K-piece of an output tile.
 struct WorkItem {
   int m0, n0, kt0, kt_end, split;
@@ -227,6 +263,7 @@ struct ActArgs {
   int64_t ldc2 = 0;
   uint32_t c2_bytes = 0;
   int gu_f = 0;
+  int row_block = 1 << 20;   // tile rows per super-block of the tile order (set by the launcher)
 };
 
 template <int BM, int BN, int NWM, int NWN, bool A_KC, bool B_KC, bool SPLITK, int ACT = ACT_NONE>
@@ -275,11 +312,10 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
     const int tile = tile_begin + fine / (sub * sub);
     it.kt0 = it.split * ktiles_per;
     it.kt_end = SPLITK ? min(nk_all, it.kt0 + ktiles_per) : nk_all;
-    const int panel = tile / (tiles_m * 8);
-    const int pw = min(8, tiles_n - panel * 8);
-    const int in_panel = tile - panel * tiles_m * 8;
-    it.m0 = ((in_panel / pw) * sub + quad / sub) * BM;
-    it.n0 = ((panel * 8 + in_panel % pw) * sub + quad % sub) * BN;
+    int trow, tcol;
+    tile_coords(tile, tiles_m, tiles_n, aa.row_block, &trow, &tcol);
+    it.m0 = (trow * sub + quad / sub) * BM;
+    it.n0 = (tcol * sub + quad % sub) * BN;
     return it;
   };
 
@@ -863,7 +899,7 @@ template <bool HAS_R>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
     const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C, const bf16* __restrict__ R,
     int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes,
-    int tiles_m, int tiles_n, int tile_begin, int tile_count, TileQueueArgs tq) {
+    int tiles_m, int tiles_n, int tile_begin, int tile_count, int row_block, TileQueueArgs tq) {
   constexpr int TBM = 256, TBK = 64, OPB = TBM * TBK * 2, STG = 2 * OPB;
   extern __shared__ __align__(16) unsigned char smem[];
   lds_byte* const lds = (lds_byte*)smem;
@@ -890,8 +926,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
   int item = tq_first(tq, qc, &mail);
   while (item >= 0) {
     const int tile = tile_begin + item;
-    const int panel = tile / (tiles_m * 8), pw = min(8, tiles_n - panel * 8), in_panel = tile - panel * tiles_m * 8;
-    const int m0 = (in_panel / pw) * TBM, n0 = (panel * 8 + in_panel % pw) * TBM;
+    int trow, tcol;
+    tile_coords(tile, tiles_m, tiles_n, row_block, &trow, &tcol);
+    const int m0 = trow * TBM, n0 = tcol * TBM;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -1154,8 +1191,11 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
   TileQueueArgs tq;
   int grid;
   MOSAIC_TRY(tile_queue_plan(s, quota, wg_per_cu, items, 0, false, &tq, &grid));
+  ActArgs ka = aa;
+  // a split product streams 1/ksplit of K per item; coarse tile rows are BM * sub rows high
+  ka.row_block = row_block_for(ceil_div((int64_t)K, ksplit), ceil_div((int64_t)M, 256)) * 256 / (BM * sub);
   kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq, aa);
+                                          tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq, ka);
   MOSAIC_LAUNCH_CHECK();
   if (SPLITK) {
     const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
@@ -1186,10 +1226,11 @@ mosaic_status launch_kc4w(hipStream_t s, int quota, int M, int N, int K, const b
   TileQueueArgs tq;
   int grid;
   MOSAIC_TRY(tile_queue_plan(s, quota, 1, tile_count, 0, false, &tq, &grid));
+  const int rb = row_block_for(K, tiles_m);
   if (R) gemm_bf16_kc4w_kernel<true><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                                             tiles_m, tiles_n, tile_begin, tile_count, tq);
+                                                             tiles_m, tiles_n, tile_begin, tile_count, rb, tq);
   else gemm_bf16_kc4w_kernel<false><<<grid, 256, smem, s>>>(A, B, C, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
-                                                            tiles_m, tiles_n, tile_begin, tile_count, tq);
+                                                            tiles_m, tiles_n, tile_begin, tile_count, rb, tq);
   MOSAIC_LAUNCH_CHECK();
   return MOSAIC_OK;
 }
