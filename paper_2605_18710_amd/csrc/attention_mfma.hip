@@ -1068,6 +1068,259 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   tq_done(tq);
 }
 
+// dK / dV at head size 128 with ONE wave per SIMD.  With two waves per SIMD a wave has 256
+// registers, the dK and dV accumulators take 128 of them, and nothing is left to read operands
+// ahead of their use or to overlap the phases of a block: every matrix instruction waits for
+// the LDS read in front of it.  Here a workgroup is four waves, one per SIMD, each with up to
+// 512 registers (the accumulators go to the accumulator half), and all the overlap is made
+// inside the wave by a software pipeline skewed by one query block: in slot t the matrix
+// cores compute S and dP of query block t+1 and add block t-1 to dV and dK, one instruction
+// at a time and alternating between the four accumulation chains, while the vector ALU turns
+// S and dP of block t into P and dS; operands are read from LDS three instructions ahead.
+// The V fragments of the owned keys live in registers beside the K fragments.  Streamed Q / dO
+// tiles of 32 rows go through a ring of six LDS stages: block t-1 and block t+1 are read in slot
+// t, the row statistics of block t too, and block t+4 is requested at the start of slot t.
+// Per accumulator the products arrive in the same order as in the kernel above: same bits.
+template <int D>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+                                                                const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
+                                                                float scale, int ktiles, int hblk, TileQueueArgs tq) {
+  constexpr int NW = 4, RS = 32, NS = D / 16, NC = D / 32;
+  static_assert(NS == 2 * NC, "slots alternate between four chains of equal length");
+  typedef LdsTile<RS, D, NW> L;
+  constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
+  constexpr int NST = 6, AHEAD = 4, KT = 32 * NW, NREQ = 2 * L::NI + 2;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE], then [NST][2][64] floats: lse, delta
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  const float* stat = reinterpret_cast<const float*>(smem_raw + NST * STAGE);
+  L ld, ldo;           // lane offsets for the two row strides: q rows and dO rows
+  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
+  ldo.init((unsigned)(H * D * 2));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 31, hb = lane >> 5;
+  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
+  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
+  const float scale_log2 = scale * kLog2e;
+  __shared__ int mail;
+  TileQueueCursor qc;
+  int item = tq_first(tq, qc, &mail);
+  while (item >= 0) {
+    int head_, kt_i;
+    attn_item(item, B * Hkv, ktiles, hblk, false, attn_mirror(tq, qc, ktiles), &head_, &kt_i);      // the first key tile has the most queries
+    const int kvh = head_ % Hkv, b = head_ / Hkv;
+    const int hd0 = kvh * GQ;                    // first query head of the group
+    const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
+    const bf16* rowb = qkv + (int64_t)b * N * rs;
+    const bf16* base = rowb + hd0 * D;           // q columns of the group's heads are adjacent
+    const bf16* dob = dO + (int64_t)b * N * h + hd0 * D;
+    const float* lse_b = lse + ((int64_t)b * H + hd0) * N;
+    const float* del_b = delta + ((int64_t)b * H + hd0) * N;
+    bf16x8 kf[NS], vf[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if (j < N) {
+        kf[s] = *reinterpret_cast<const bf16x8*>(rowb + ko + kvh * D + (int64_t)j * rs + 16 * s + 8 * hb);
+        vf[s] = *reinterpret_cast<const bf16x8*>(rowb + vo + kvh * D + (int64_t)j * rs + 16 * s + 8 * hb);
+      } else {
+        for (int e = 0; e < 8; ++e) { kf[s][e] = (bf16)0.f; vf[s][e] = (bf16)0.f; }
+      }
+    }
+    f32x16 dk[NC], dv[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { dk[c][e] = 0.f; dv[c][e] = 0.f; }
+    const int q_begin = causal ? (k0 / RS) * RS : 0;
+    const int ntq = (N - q_begin + RS - 1) / RS;       // query tiles of one head
+    const int ntiles = ntq * GQ;                         // streamed for every query head of the group in turn
+    auto desc_f32 = [&](const float* p) {
+      i32x4 d;
+      d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
+      d.z = GQ * N * 4; d.w = 0x00020000;
+      return d;
+    };
+    const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
+    // tiles outside [0, ntiles) request nothing (they point outside the descriptors); every wave
+    // issues the same number of requests per tile so that the wait counts are constants
+    auto stage_stats = [&](int tile) {
+      const bool real = tile >= 0 && tile < ntiles;
+      const int g = real ? tile / ntq : 0, tq_ = real ? tile - g * ntq : 0;
+      const unsigned off = (real && lane < RS && q_begin + tq_ * RS + lane < N)
+                               ? (unsigned)(g * N + q_begin + tq_ * RS + lane) * 4u : 0xFFFFFFF0u;
+      const unsigned dst = lds0 + (unsigned)(NST * STAGE + ((tile + NST) % NST) * 2 * 64 * 4);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
+    };
+    const i32x4 dq_ = slice_desc(base, N, rs, GQ * D), do_ = slice_desc(dob, N, h, GQ * D);
+    const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
+    auto request = [&](int tile) {
+      const bool real = tile >= 0 && tile < ntiles;
+      const unsigned nb = lds0 + (unsigned)(((tile + NST) % NST) * STAGE);
+      const int g = real ? tile / ntq : 0, tq_ = real ? tile - g * ntq : 0;
+      const int row0 = real ? q_begin + tq_ * RS : N;
+      const unsigned col = real ? (unsigned)(g * D * 2) : 0u;
+      ld.issue(dq_, (unsigned)row0 * rsb + col, nb);
+      ldo.issue(do_, (unsigned)row0 * hsb + col, nb + L::BYTES);
+    };
+    // a query block this wave has something to do with: it exists and is not wholly above the diagonal
+    auto active = [&](int t) -> bool {
+      if (t < 0 || t >= ntiles || j0w >= N) return false;
+      const int ib = q_begin + (t % ntq) * RS;
+      return !(causal && ib + 31 < j0w);
+    };
+    __syncthreads();                    // the previous item's readers are done with every stage
+#pragma unroll
+    for (int u = 0; u < AHEAD - 1; ++u) { request(u); stage_stats(u); }
+    wait_requests<(AHEAD - 2) * NREQ>();                  // tile 0 has landed
+    __syncthreads();
+    unsigned entry = 0;
+    const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : -1;   // tiles of 32 rows here
+    f32x16 sc, pc;                      // S and dP of the block whose P and dS are formed next
+    bf16x8 p0, p1, d0, d1;              // P and dS of the block whose products are pending
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { p0[e] = (bf16)0.f; p1[e] = (bf16)0.f; d0[e] = (bf16)0.f; d1[e] = (bf16)0.f; }
+    for (int t = -1; t <= ntiles; ++t) {
+      request(t + AHEAD);               // into the stage of block t-2, last read in the slot before
+      stage_stats(t + AHEAD);
+      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
+      const lds_byte* qn = smem + ((t + 1 + NST) % NST) * STAGE;      // block t+1: S, dP
+      const lds_byte* don = qn + L::BYTES;
+      const lds_byte* qp = smem + ((t - 1 + NST) % NST) * STAGE;      // block t-1: dV, dK
+      const lds_byte* dop = qp + L::BYTES;
+      const float* sl = stat + (((t + NST) % NST) * 2 + 0) * 64;      // block t: lse, delta
+      const float* sd = stat + (((t + NST) % NST) * 2 + 1) * 64;
+      const bool do_s = active(t + 1), do_x = active(t), do_acc = active(t - 1);
+      const int ib = q_begin + ((t < 0 ? 0 : t) % ntq) * RS;
+      const bool masked = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
+      // P and dS of register r from S, dP and the row statistics; registers 4g .. 4g+3 of a lane
+      // hold query rows 8g + 4*hb + {0..3}: their statistics are four consecutive floats
+      const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
+      const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
+      if (do_s && do_x && do_acc && !masked) {
+        constexpr int NM = 4 * NS, PFD = 3;
+        auto operand = [&](int k) -> bf16x8 {
+          const int jj = k >> 2, part = k & 3;
+          if (part == 0) return L::nat(qn, lr, jj, hb);                // S, contraction step jj
+          if (part == 2) return L::nat(don, lr, jj, hb);               // dP, contraction step jj
+          const int c = jj % NC, half = jj / NC;                       // dV (part 1) / dK (part 3): column block c, key half
+          return L::tr(part == 1 ? dop : qp, c, 16 * half);
+        };
+        bf16x8 opb[PFD + 1];
+#pragma unroll
+        for (int k = 0; k < PFD; ++k) opb[k] = operand(k);
+        float4 l4[4], e4[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) { l4[g] = sl4[2 * g]; e4[g] = sd4[2 * g]; }
+        f32x16 sn, pn;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { sn[e] = 0.f; pn[e] = 0.f; }
+        float pv[16], ds[16];
+        bf16x8 q0, q1, r0, r1;          // P and dS of block t, packed as they complete
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < NM; ++k) {
+          if (k + PFD < NM) opb[(k + PFD) % (PFD + 1)] = operand(k + PFD);
+          const bf16x8 a = opb[k % (PFD + 1)];
+          const int jj = k >> 2, part = k & 3, c = jj % NC, half = jj / NC;
+          if (part == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[jj], sn, 0, 0, 0);
+          else if (part == 2) pn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[jj], pn, 0, 0, 0);
+          else if (part == 1) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? p1 : p0, dv[c], 0, 0, 0);
+          else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? d1 : d0, dk[c], 0, 0, 0);
+          if ((k & 1) == 0) {           // one of the sixteen registers of block t per two slots
+            const int r = k >> 1, g = r >> 2, e = r & 3;
+            const float lv = e == 0 ? l4[g].x : e == 1 ? l4[g].y : e == 2 ? l4[g].z : l4[g].w;
+            const float dl = e == 0 ? e4[g].x : e == 1 ? e4[g].y : e == 2 ? e4[g].z : e4[g].w;
+            const float p = fast_exp2(fmaf(sc[r], scale_log2, -lv * kLog2e));
+            pv[r] = p;
+            ds[r] = p * (pc[r] - dl);
+            if (r == 7) { q0 = pack8(pv); r0 = pack8(ds); }
+            if (r == 15) { q1 = pack8(pv + 8); r1 = pack8(ds + 8); }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        sc = sn; pc = pn; p0 = q0; p1 = q1; d0 = r0; d1 = r1;
+      } else {
+        // first and last slots of a wave and blocks that touch the diagonal or the end of the
+        // sequence: whatever exists of the three, one after the other
+        if (do_acc) {
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dop, c, 0), p0, dv[c], 0, 0, 0);
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dop, c, 16), p1, dv[c], 0, 0, 0);
+            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 0), d0, dk[c], 0, 0, 0);
+            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 16), d1, dk[c], 0, 0, 0);
+          }
+        }
+        if (do_x) {
+          // a masked score becomes -inf, so its recomputed probability is exactly 0
+          if (masked) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int gi = ib + acc_row(r, hb);
+              if ((gi >= N) || (j >= N) || (causal && j > gi)) sc[r] = -INFINITY;
+            }
+          }
+          float pv[16], ds[16];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 l4 = sl4[2 * g], e4 = sd4[2 * g];
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * g + e;
+              const float p = fast_exp2(fmaf(sc[r], scale_log2, -lv[e] * kLog2e));
+              pv[r] = p;
+              ds[r] = p * (pc[r] - dl[e]);
+            }
+          }
+          p0 = pack8(pv); p1 = pack8(pv + 8); d0 = pack8(ds); d1 = pack8(ds + 8);
+        }
+        if (do_s) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
+#pragma unroll
+          for (int s = 0; s < NS; ++s) {
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qn, lr, s, hb), kf[s], sc, 0, 0, 0);
+            pc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(don, lr, s, hb), vf[s], pc, 0, 0, 0);
+          }
+        }
+      }
+      wait_requests<2 * NREQ>();        // everything up to block t+2 has landed; two tiles stay in flight
+      __syncthreads();
+    }
+    if (j < N) {
+      bf16* out = dqkv + ((int64_t)b * N + j) * rs + kvh * D;
+      // dK rows first, then dV rows: the eight 16-byte pieces that make up a 128-byte line
+      // leave in consecutive instructions and meet in the L2 before the line is written out
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 vk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vk[e] = (bf16)(dk[c][4 * g + e] * scale);
+          *reinterpret_cast<bf16x4*>(out + ko + 32 * c + 8 * g + 4 * hb) = vk;
+        }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 vv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vv[e] = (bf16)dv[c][4 * g + e];
+          *reinterpret_cast<bf16x4*>(out + vo + 32 * c + 8 * g + 4 * hb) = vv;
+        }
+    }
+    item = tq_next(tq, qc, entry, &mail);
+  }
+  tq_done(tq);
+}
+
 // Workgroup shape.  The kernels are written for NW waves and a ring of stages; measured on
 // the 8 x 1024 x 16 x 128 causal problem, 8 waves with four stages (one workgroup per CU,
 // three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU):
@@ -1139,8 +1392,15 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
     static hipError_t once_rc = hipSuccess;
     TileQueueArgs tq;
     int grid, hb;
-    MOSAIC_TRY(launch_queued(attn_bwd_dkv_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
-    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
+    if constexpr (D == 128 && NW == 4) {
+      // one wave per SIMD: six stages of Q | dO tiles and their row statistics
+      constexpr size_t smem1 = (size_t)6 * 2 * LdsTile<32, D, NW>::BYTES + (size_t)6 * 2 * 64 * sizeof(float);
+      MOSAIC_TRY(launch_queued(attn_bwd_dkv_pipe_mfma<D>, once, once_rc, smem1, s, quota, 1, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
+      attn_bwd_dkv_pipe_mfma<D><<<grid, 64 * NW, smem1, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
+    } else {
+      MOSAIC_TRY(launch_queued(attn_bwd_dkv_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
+      attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
+    }
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
