@@ -35,6 +35,12 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+#ifndef DKV_PFD
+#define DKV_PFD 6
+#endif
+#ifndef DKV_AHEAD
+#define DKV_AHEAD 5
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // Online softmax keeps, per row, a reference value m and sums of exp2(s - m).  Any m works
@@ -1090,7 +1096,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
   static_assert(NS == 2 * NC, "slots alternate between four chains of equal length");
   typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
-  constexpr int NST = 6, AHEAD = 4, KT = 32 * NW, NREQ = 2 * L::NI + 2;
+  constexpr int AHEAD = DKV_AHEAD, NST = AHEAD + 2, KT = 32 * NW, NREQ = 2 * L::NI + 2;
+  static_assert((AHEAD - 2) * NREQ < 64, "the wait count has six bits");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE], then [NST][2][64] floats: lse, delta
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
@@ -1104,6 +1111,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
   const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
   const float scale_log2 = scale * kLog2e;
   __shared__ int mail;
+  __shared__ unsigned claimed;
   TileQueueCursor qc;
   int item = tq_first(tq, qc, &mail);
   while (item >= 0) {
@@ -1170,12 +1178,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
       const int ib = q_begin + (t % ntq) * RS;
       return !(causal && ib + 31 < j0w);
     };
+    // The K and V fragments have arrived before the first tile request goes out: the compiler
+    // counts only its own loads, so a partial wait further down would leave it unsure about
+    // these and it would wait for every outstanding request inside the loop.
+    wait_requests<0>();
     __syncthreads();                    // the previous item's readers are done with every stage
 #pragma unroll
     for (int u = 0; u < AHEAD - 1; ++u) { request(u); stage_stats(u); }
     wait_requests<(AHEAD - 2) * NREQ>();                  // tile 0 has landed
     __syncthreads();
-    unsigned entry = 0;
     const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : -1;   // tiles of 32 rows here
     f32x16 sc, pc;                      // S and dP of the block whose P and dS are formed next
     bf16x8 p0, p1, d0, d1;              // P and dS of the block whose products are pending
@@ -1186,7 +1197,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
     for (int t = -1; t <= ntiles; ++t) {
       request(t + AHEAD);               // into the stage of block t-2, last read in the slot before
       stage_stats(t + AHEAD);
-      if (t == claim_at) entry = tq_claim_ahead(tq, qc);
+      // The claimed entry goes through LDS, inside the branch: carried in a register across the
+      // loop, the pending atomic would make the compiler wait for every outstanding request,
+      // the tile requests included, in each iteration.
+      if (t == claim_at && threadIdx.x == 0 && tq.mode == TQ_QUEUE) *(volatile unsigned*)&claimed = tq_claim(tq, qc);
       const lds_byte* qn = smem + ((t + 1 + NST) % NST) * STAGE;      // block t+1: S, dP
       const lds_byte* don = qn + L::BYTES;
       const lds_byte* qp = smem + ((t - 1 + NST) % NST) * STAGE;      // block t-1: dV, dK
@@ -1201,7 +1215,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
       const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
       const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
       if (do_s && do_x && do_acc && !masked) {
-        constexpr int NM = 4 * NS, PFD = 3;
+        constexpr int NM = 4 * NS, PFD = DKV_PFD;
         auto operand = [&](int k) -> bf16x8 {
           const int jj = k >> 2, part = k & 3;
           if (part == 0) return L::nat(qn, lr, jj, hb);                // S, contraction step jj
@@ -1289,7 +1303,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
           }
         }
       }
-      wait_requests<2 * NREQ>();        // everything up to block t+2 has landed; two tiles stay in flight
+      wait_requests<(AHEAD - 2) * NREQ>();   // everything up to block t+2 has landed; the later tiles stay in flight
       __syncthreads();
     }
     if (j < N) {
@@ -1316,6 +1330,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
           *reinterpret_cast<bf16x4*>(out + vo + 32 * c + 8 * g + 4 * hb) = vv;
         }
     }
+    const unsigned entry = (threadIdx.x == 0 && tq.mode == TQ_QUEUE) ? *(volatile unsigned*)&claimed : 0u;
     item = tq_next(tq, qc, entry, &mail);
   }
   tq_done(tq);
@@ -1394,7 +1409,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
     int grid, hb;
     if constexpr (D == 128 && NW == 4) {
       // one wave per SIMD: six stages of Q | dO tiles and their row statistics
-      constexpr size_t smem1 = (size_t)6 * 2 * LdsTile<32, D, NW>::BYTES + (size_t)6 * 2 * 64 * sizeof(float);
+      constexpr size_t smem1 = (size_t)(DKV_AHEAD + 2) * 2 * LdsTile<32, D, NW>::BYTES + (size_t)(DKV_AHEAD + 2) * 2 * 64 * sizeof(float);
       MOSAIC_TRY(launch_queued(attn_bwd_dkv_pipe_mfma<D>, once, once_rc, smem1, s, quota, 1, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
       attn_bwd_dkv_pipe_mfma<D><<<grid, 64 * NW, smem1, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
     } else {
