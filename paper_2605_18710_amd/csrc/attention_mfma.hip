@@ -35,6 +35,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+// The one-wave-per-SIMD dK/dV kernel below is an experiment that is not yet faster than the
+// two-wave kernel (measured 1.2x slower at B16 N2048 H32); it is compiled only on request.
+#ifdef MOSAIC_DKV_ONE_WAVE
+constexpr bool kDkvOneWavePerSimd = true;
+#else
+constexpr bool kDkvOneWavePerSimd = false;
+#endif
 #ifndef DKV_PFD
 #define DKV_PFD 6
 #endif
@@ -1150,33 +1157,30 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
       return d;
     };
     const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
-    // tiles outside [0, ntiles) request nothing (they point outside the descriptors); every wave
-    // issues the same number of requests per tile so that the wait counts are constants
-    auto stage_stats = [&](int tile) {
-      const bool real = tile >= 0 && tile < ntiles;
-      const int g = real ? tile / ntq : 0, tq_ = real ? tile - g * ntq : 0;
-      const unsigned off = (real && lane < RS && q_begin + tq_ * RS + lane < N)
-                               ? (unsigned)(g * N + q_begin + tq_ * RS + lane) * 4u : 0xFFFFFFF0u;
-      const unsigned dst = lds0 + (unsigned)(NST * STAGE + ((tile + NST) % NST) * 2 * 64 * 4);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
-    };
     const i32x4 dq_ = slice_desc(base, N, rs, GQ * D), do_ = slice_desc(dob, N, h, GQ * D);
     const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
-    auto request = [&](int tile) {
-      const bool real = tile >= 0 && tile < ntiles;
-      const unsigned nb = lds0 + (unsigned)(((tile + NST) % NST) * STAGE);
-      const int g = real ? tile / ntq : 0, tq_ = real ? tile - g * ntq : 0;
-      const int row0 = real ? q_begin + tq_ * RS : N;
-      const unsigned col = real ? (unsigned)(g * D * 2) : 0u;
+    // Tiles are requested in order, one per slot, and every position below advances by
+    // increments: a wave alone on its SIMD issues one instruction every four cycles, so a
+    // division or a modulo per slot (some forty scalar instructions each) would cost more
+    // issue slots than the matrix instructions of the slot.  Tiles past the last one request
+    // nothing (they point outside the descriptors); every wave issues the same number of
+    // requests per tile so that the wait counts are constants.
+    int rq_t = 0, rq_g = 0, rq_row = q_begin, rq_left = ntq, rq_st = 0;    // next tile: number, head, first row, blocks left in the head, stage
+    auto request_next = [&]() {
+      const bool real = rq_t < ntiles;
+      const unsigned nb = lds0 + (unsigned)(rq_st * STAGE);
+      const int row0 = real ? rq_row : N;
+      const unsigned col = real ? (unsigned)(rq_g * D * 2) : 0u;
       ld.issue(dq_, (unsigned)row0 * rsb + col, nb);
       ldo.issue(do_, (unsigned)row0 * hsb + col, nb + L::BYTES);
-    };
-    // a query block this wave has something to do with: it exists and is not wholly above the diagonal
-    auto active = [&](int t) -> bool {
-      if (t < 0 || t >= ntiles || j0w >= N) return false;
-      const int ib = q_begin + (t % ntq) * RS;
-      return !(causal && ib + 31 < j0w);
+      const unsigned off = (real && lane < RS && rq_row + lane < N) ? (unsigned)(rq_g * N + rq_row + lane) * 4u : 0xFFFFFFF0u;
+      const unsigned dst = lds0 + (unsigned)(NST * STAGE + rq_st * 2 * 64 * 4);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
+      ++rq_t;
+      rq_row += RS;
+      if (--rq_left == 0) { rq_left = ntq; rq_row = q_begin; ++rq_g; }
+      rq_st = rq_st + 1 == NST ? 0 : rq_st + 1;
     };
     // The K and V fragments have arrived before the first tile request goes out: the compiler
     // counts only its own loads, so a partial wait further down would leave it unsure about
@@ -1184,7 +1188,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
     wait_requests<0>();
     __syncthreads();                    // the previous item's readers are done with every stage
 #pragma unroll
-    for (int u = 0; u < AHEAD - 1; ++u) { request(u); stage_stats(u); }
+    for (int u = 0; u < AHEAD - 1; ++u) request_next();
     wait_requests<(AHEAD - 2) * NREQ>();                  // tile 0 has landed
     __syncthreads();
     const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : -1;   // tiles of 32 rows here
@@ -1194,21 +1198,28 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
     for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
 #pragma unroll
     for (int e = 0; e < 8; ++e) { p0[e] = (bf16)0.f; p1[e] = (bf16)0.f; d0[e] = (bf16)0.f; d1[e] = (bf16)0.f; }
+    // block t+1 (S, dP): number, first query row, blocks left in its head; a block is worked on
+    // when it exists and is not wholly above the diagonal.  Block t and block t-1 inherit.
+    const bool wave_live = j0w < N;
+    int s_t = 0, s_ib = q_begin, s_left = ntq, x_ib = q_begin;
+    bool do_x = false, do_acc = false;
+    int st_p = NST - 2, st_x = NST - 1, st_n = 0;        // stages of blocks t-1, t, t+1
     for (int t = -1; t <= ntiles; ++t) {
-      request(t + AHEAD);               // into the stage of block t-2, last read in the slot before
-      stage_stats(t + AHEAD);
+#ifndef DKV_ABL_NOREQ
+      request_next();                   // block t+AHEAD, into the stage of block t-2, last read in the slot before
+#endif
       // The claimed entry goes through LDS, inside the branch: carried in a register across the
       // loop, the pending atomic would make the compiler wait for every outstanding request,
       // the tile requests included, in each iteration.
       if (t == claim_at && threadIdx.x == 0 && tq.mode == TQ_QUEUE) *(volatile unsigned*)&claimed = tq_claim(tq, qc);
-      const lds_byte* qn = smem + ((t + 1 + NST) % NST) * STAGE;      // block t+1: S, dP
+      const lds_byte* qn = smem + st_n * STAGE;           // block t+1: S, dP
       const lds_byte* don = qn + L::BYTES;
-      const lds_byte* qp = smem + ((t - 1 + NST) % NST) * STAGE;      // block t-1: dV, dK
+      const lds_byte* qp = smem + st_p * STAGE;           // block t-1: dV, dK
       const lds_byte* dop = qp + L::BYTES;
-      const float* sl = stat + (((t + NST) % NST) * 2 + 0) * 64;      // block t: lse, delta
-      const float* sd = stat + (((t + NST) % NST) * 2 + 1) * 64;
-      const bool do_s = active(t + 1), do_x = active(t), do_acc = active(t - 1);
-      const int ib = q_begin + ((t < 0 ? 0 : t) % ntq) * RS;
+      const float* sl = stat + (st_x * 2 + 0) * 64;       // block t: lse, delta
+      const float* sd = stat + (st_x * 2 + 1) * 64;
+      const bool do_s = wave_live && s_t < ntiles && !(causal && s_ib + 31 < j0w);
+      const int ib = x_ib;
       const bool masked = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
       // P and dS of register r from S, dP and the row statistics; registers 4g .. 4g+3 of a lane
       // hold query rows 8g + 4*hb + {0..3}: their statistics are four consecutive floats
@@ -1218,6 +1229,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
         constexpr int NM = 4 * NS, PFD = DKV_PFD;
         auto operand = [&](int k) -> bf16x8 {
           const int jj = k >> 2, part = k & 3;
+#ifdef DKV_ABL_NOLDS
+          return kf[jj];
+#endif
           if (part == 0) return L::nat(qn, lr, jj, hb);                // S, contraction step jj
           if (part == 2) return L::nat(don, lr, jj, hb);               // dP, contraction step jj
           const int c = jj % NC, half = jj / NC;                       // dV (part 1) / dK (part 3): column block c, key half
@@ -1248,9 +1262,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
             const int r = k >> 1, g = r >> 2, e = r & 3;
             const float lv = e == 0 ? l4[g].x : e == 1 ? l4[g].y : e == 2 ? l4[g].z : l4[g].w;
             const float dl = e == 0 ? e4[g].x : e == 1 ? e4[g].y : e == 2 ? e4[g].z : e4[g].w;
+#ifdef DKV_ABL_NOX
+            const float p = sc[r];
+            pv[r] = p;
+            ds[r] = pc[r];
+#else
             const float p = fast_exp2(fmaf(sc[r], scale_log2, -lv * kLog2e));
             pv[r] = p;
             ds[r] = p * (pc[r] - dl);
+#endif
             if (r == 7) { q0 = pack8(pv); r0 = pack8(ds); }
             if (r == 15) { q1 = pack8(pv + 8); r1 = pack8(ds + 8); }
           }
@@ -1303,8 +1323,17 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
           }
         }
       }
+      do_acc = do_x; do_x = do_s; x_ib = s_ib;
+      ++s_t;
+      s_ib += RS;
+      if (--s_left == 0) { s_left = ntq; s_ib = q_begin; }
+      st_p = st_x; st_x = st_n; st_n = st_n + 1 == NST ? 0 : st_n + 1;
+#ifndef DKV_ABL_NOWAIT
       wait_requests<(AHEAD - 2) * NREQ>();   // everything up to block t+2 has landed; the later tiles stay in flight
+#endif
+#ifndef DKV_ABL_NOBAR
       __syncthreads();
+#endif
     }
     if (j < N) {
       bf16* out = dqkv + ((int64_t)b * N + j) * rs + kvh * D;
@@ -1407,7 +1436,7 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
     static hipError_t once_rc = hipSuccess;
     TileQueueArgs tq;
     int grid, hb;
-    if constexpr (D == 128 && NW == 4) {
+    if constexpr (kDkvOneWavePerSimd && D == 128 && NW == 4) {
       // one wave per SIMD: six stages of Q | dO tiles and their row statistics
       constexpr size_t smem1 = (size_t)(DKV_AHEAD + 2) * 2 * LdsTile<32, D, NW>::BYTES + (size_t)(DKV_AHEAD + 2) * 2 * 64 * sizeof(float);
       MOSAIC_TRY(launch_queued(attn_bwd_dkv_pipe_mfma<D>, once, once_rc, smem1, s, quota, 1, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
