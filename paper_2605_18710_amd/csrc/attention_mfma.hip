@@ -26,6 +26,7 @@
 // dO fragments it holds, and read by the dK/dV kernel.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 #include "kernels.h"
 #include "tile_queue.h"
 
@@ -42,11 +43,8 @@ constexpr bool kDkvOneWavePerSimd = true;
 #else
 constexpr bool kDkvOneWavePerSimd = false;
 #endif
-#ifndef DKV_PFD
-#define DKV_PFD 6
-#endif
 #ifndef DKV_AHEAD
-#define DKV_AHEAD 5
+#define DKV_AHEAD 6
 #endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -122,6 +120,12 @@ struct LdsTile {
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                    : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(desc) : "m0");
     }
+  }
+  // the j-th of the NI requests of issue() alone
+  __device__ __forceinline__ void issue_one(i32x4 desc, unsigned base, unsigned dst, int j) const {
+    const unsigned off = loff[j] + base;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(desc) : "m0");
   }
   // fragment whose contraction runs along the row: row `row`, columns 16*s + 8*hb .. +7
   __device__ static __forceinline__ bf16x8 nat(const lds_byte* t, int row, int s, int hb) {
@@ -1086,25 +1090,43 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
 // ahead of their use or to overlap the phases of a block: every matrix instruction waits for
 // the LDS read in front of it.  Here a workgroup is four waves, one per SIMD, each with up to
 // 512 registers (the accumulators go to the accumulator half), and all the overlap is made
-// inside the wave by a software pipeline skewed by one query block: in slot t the matrix
-// cores compute S and dP of query block t+1 and add block t-1 to dV and dK, one instruction
-// at a time and alternating between the four accumulation chains, while the vector ALU turns
-// S and dP of block t into P and dS; operands are read from LDS three instructions ahead.
+// inside the wave.  A wave alone on its SIMD issues at most one instruction every four cycles
+// and a 32x32x16 matrix instruction occupies the matrix core for 32: the loop is a stream of
+// slots, one matrix instruction and at most seven others each, and whatever does not fit into
+// a slot (a wait, a burst of address arithmetic, a division) stops the matrix core.
+//   - The stream is a software pipeline skewed by one query block: in iteration t the matrix
+//     core computes S and dP of block t+1 and adds block t-1 to dV and dK, alternating between
+//     the four accumulation chains, while the vector ALU turns S and dP of block t into P and dS,
+//     one of the sixteen registers per two slots.
+//   - Operands are read from LDS seven slots ahead into a ring of eight buffers that runs on
+//     across iterations (the last seven slots read the first operands of the next iteration),
+//     the row statistics of the next block are read in the last slots, the six requests of the
+//     tile that is AHEAD blocks away go out one per odd slot, P and dS are packed into the
+//     operand registers in the slots right after their last use by the previous block.
+//   - Positions advance by increments (no division, no modulo in the loop).
+//   - The first and last iterations of an item, where one of the three blocks does not exist,
+//     take a plain path (one phase after the other).  Blocks on or above the diagonal and at the
+//     end of the sequence go through the stream in a variant that masks: a block wholly above
+//     the diagonal adds zeros (the other waves of the workgroup work on it anyway).
 // The V fragments of the owned keys live in registers beside the K fragments.  Streamed Q / dO
-// tiles of 32 rows go through a ring of six LDS stages: block t-1 and block t+1 are read in slot
-// t, the row statistics of block t too, and block t+4 is requested at the start of slot t.
-// Per accumulator the products arrive in the same order as in the kernel above: same bits.
+// tiles of 32 rows go through a ring of AHEAD+2 LDS stages: iteration t reads blocks t-1, t+1
+// and, for the next iteration's first operands, t and t+2; block t+AHEAD is requested into the
+// stage of block t-2.  Per accumulator the products arrive in the same order as in the kernel
+// above: same bits.
 template <int D>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
                                                                 bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
                                                                 float scale, int ktiles, int hblk, TileQueueArgs tq) {
-  constexpr int NW = 4, RS = 32, NS = D / 16, NC = D / 32;
+  constexpr int NW = 4, RS = 32, NS = D / 16, NC = D / 32, NM = 4 * NS;
+  constexpr int NB = 8, PFD = NB - 1;                      // operand buffers, slots of lookahead
   static_assert(NS == 2 * NC, "slots alternate between four chains of equal length");
+  static_assert(NM % NB == 0, "the operand ring keeps its phase from one iteration to the next");
   typedef LdsTile<RS, D, NW> L;
   constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
   constexpr int AHEAD = DKV_AHEAD, NST = AHEAD + 2, KT = 32 * NW, NREQ = 2 * L::NI + 2;
-  static_assert((AHEAD - 2) * NREQ < 64, "the wait count has six bits");
+  static_assert(AHEAD >= 4 && (AHEAD - 3) * NREQ < 64, "the wait count has six bits");
+  static_assert(2 * NREQ <= NM - 8, "one request per odd slot, before the statistics reads");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE], then [NST][2][64] floats: lse, delta
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
@@ -1159,28 +1181,34 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
     const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
     const i32x4 dq_ = slice_desc(base, N, rs, GQ * D), do_ = slice_desc(dob, N, h, GQ * D);
     const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
-    // Tiles are requested in order, one per slot, and every position below advances by
-    // increments: a wave alone on its SIMD issues one instruction every four cycles, so a
-    // division or a modulo per slot (some forty scalar instructions each) would cost more
-    // issue slots than the matrix instructions of the slot.  Tiles past the last one request
-    // nothing (they point outside the descriptors); every wave issues the same number of
-    // requests per tile so that the wait counts are constants.
+    // Tiles are requested in order, one per iteration.  request_begin() works out where the
+    // next tile comes from and goes to and advances the position; request_piece(i), i < NREQ,
+    // issues its i-th request.  Tiles past the last one fetch nothing (they point outside the
+    // descriptors); every wave issues the same number of requests per tile so that the wait
+    // counts are constants.
     int rq_t = 0, rq_g = 0, rq_row = q_begin, rq_left = ntq, rq_st = 0;    // next tile: number, head, first row, blocks left in the head, stage
-    auto request_next = [&]() {
+    unsigned rq_nb = 0, rq_qoff = 0, rq_dooff = 0, rq_soff = 0, rq_sdst = 0;
+    auto request_begin = [&]() {
       const bool real = rq_t < ntiles;
-      const unsigned nb = lds0 + (unsigned)(rq_st * STAGE);
       const int row0 = real ? rq_row : N;
       const unsigned col = real ? (unsigned)(rq_g * D * 2) : 0u;
-      ld.issue(dq_, (unsigned)row0 * rsb + col, nb);
-      ldo.issue(do_, (unsigned)row0 * hsb + col, nb + L::BYTES);
-      const unsigned off = (real && lane < RS && rq_row + lane < N) ? (unsigned)(rq_g * N + rq_row + lane) * 4u : 0xFFFFFFF0u;
-      const unsigned dst = lds0 + (unsigned)(NST * STAGE + rq_st * 2 * 64 * 4);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(dl_) : "m0");
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(dst + 256u), "v"(off), "s"(dd_) : "m0");
+      rq_nb = lds0 + (unsigned)(rq_st * STAGE);
+      rq_qoff = (unsigned)row0 * rsb + col;
+      rq_dooff = (unsigned)row0 * hsb + col;
+      rq_soff = (real && lane < RS && rq_row + lane < N) ? (unsigned)(rq_g * N + rq_row + lane) * 4u : 0xFFFFFFF0u;
+      rq_sdst = lds0 + (unsigned)(NST * STAGE + rq_st * 2 * 64 * 4);
       ++rq_t;
       rq_row += RS;
       if (--rq_left == 0) { rq_left = ntq; rq_row = q_begin; ++rq_g; }
       rq_st = rq_st + 1 == NST ? 0 : rq_st + 1;
+    };
+    auto request_piece = [&](int i) {
+      if (i < L::NI) ld.issue_one(dq_, rq_qoff, rq_nb, i);
+      else if (i < 2 * L::NI) ldo.issue_one(do_, rq_dooff, rq_nb + L::BYTES, i - L::NI);
+      else if (i == 2 * L::NI)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(rq_sdst), "v"(rq_soff), "s"(dl_) : "m0");
+      else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(rq_sdst + 256u), "v"(rq_soff), "s"(dd_) : "m0");
     };
     // The K and V fragments have arrived before the first tile request goes out: the compiler
     // counts only its own loads, so a partial wait further down would leave it unsure about
@@ -1188,103 +1216,118 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
     wait_requests<0>();
     __syncthreads();                    // the previous item's readers are done with every stage
 #pragma unroll
-    for (int u = 0; u < AHEAD - 1; ++u) request_next();
-    wait_requests<(AHEAD - 2) * NREQ>();                  // tile 0 has landed
+    for (int u = 0; u < AHEAD - 1; ++u) {
+      request_begin();
+#pragma unroll
+      for (int i = 0; i < NREQ; ++i) request_piece(i);
+    }
+    wait_requests<(AHEAD - 3) * NREQ>();                  // tiles 0 and 1 have landed
     __syncthreads();
     const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : -1;   // tiles of 32 rows here
-    f32x16 sc, pc;                      // S and dP of the block whose P and dS are formed next
-    bf16x8 p0, p1, d0, d1;              // P and dS of the block whose products are pending
+    f32x16 sc, pc;                      // S and dP of block t, whose P and dS are formed in iteration t
+    bf16x8 p0, p1, d0, d1;              // P and dS of block t-1, whose products are added in iteration t
+    bf16x8 opb[NB];                     // operand k of the iteration in buffer k % NB
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    f32x4 l4[4], e4[4];                 // lse and delta of block t: registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}
 #pragma unroll
     for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
 #pragma unroll
     for (int e = 0; e < 8; ++e) { p0[e] = (bf16)0.f; p1[e] = (bf16)0.f; d0[e] = (bf16)0.f; d1[e] = (bf16)0.f; }
-    // block t+1 (S, dP): number, first query row, blocks left in its head; a block is worked on
-    // when it exists and is not wholly above the diagonal.  Block t and block t-1 inherit.
+#pragma unroll
+    for (int u = 0; u < NB; ++u) opb[u] = p0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) { l4[g] = f32x4{0.f, 0.f, 0.f, 0.f}; e4[g] = l4[g]; }
     const bool wave_live = j0w < N;
-    int s_t = 0, s_ib = q_begin, s_left = ntq, x_ib = q_begin;
-    bool do_x = false, do_acc = false;
+    int s_ib = q_begin, s_left = ntq, x_ib = q_begin;    // first query row of block t+1 and blocks left in its head; first row of block t
     int st_p = NST - 2, st_x = NST - 1, st_n = 0;        // stages of blocks t-1, t, t+1
     for (int t = -1; t <= ntiles; ++t) {
-#ifndef DKV_ABL_NOREQ
-      request_next();                   // block t+AHEAD, into the stage of block t-2, last read in the slot before
-#endif
+      request_begin();                  // block t+AHEAD, into the stage of block t-2, last read in the iteration before
       // The claimed entry goes through LDS, inside the branch: carried in a register across the
       // loop, the pending atomic would make the compiler wait for every outstanding request,
       // the tile requests included, in each iteration.
       if (t == claim_at && threadIdx.x == 0 && tq.mode == TQ_QUEUE) *(volatile unsigned*)&claimed = tq_claim(tq, qc);
+      const int st_n2 = st_n + 1 == NST ? 0 : st_n + 1;   // stage of block t+2
       const lds_byte* qn = smem + st_n * STAGE;           // block t+1: S, dP
-      const lds_byte* don = qn + L::BYTES;
       const lds_byte* qp = smem + st_p * STAGE;           // block t-1: dV, dK
-      const lds_byte* dop = qp + L::BYTES;
-      const float* sl = stat + (st_x * 2 + 0) * 64;       // block t: lse, delta
-      const float* sd = stat + (st_x * 2 + 1) * 64;
-      const bool do_s = wave_live && s_t < ntiles && !(causal && s_ib + 31 < j0w);
+      const lds_byte* qn2 = smem + st_n2 * STAGE;         // the next iteration's two
+      const lds_byte* qp2 = smem + st_x * STAGE;
+      const f32x4* sl4n = reinterpret_cast<const f32x4*>(stat + (st_n * 2 + 0) * 64 + 4 * hb);   // statistics of block t+1
+      const f32x4* sd4n = reinterpret_cast<const f32x4*>(stat + (st_n * 2 + 1) * 64 + 4 * hb);
+      const bool do_s = wave_live && t + 1 < ntiles, do_x = wave_live && t >= 0 && t < ntiles, do_acc = wave_live && t >= 1;
       const int ib = x_ib;
       const bool masked = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
-      // P and dS of register r from S, dP and the row statistics; registers 4g .. 4g+3 of a lane
-      // hold query rows 8g + 4*hb + {0..3}: their statistics are four consecutive floats
-      const float4* sl4 = reinterpret_cast<const float4*>(sl + 4 * hb);
-      const float4* sd4 = reinterpret_cast<const float4*>(sd + 4 * hb);
-      if (do_s && do_x && do_acc && !masked) {
-        constexpr int NM = 4 * NS, PFD = DKV_PFD;
-        auto operand = [&](int k) -> bf16x8 {
-          const int jj = k >> 2, part = k & 3;
-#ifdef DKV_ABL_NOLDS
-          return kf[jj];
-#endif
-          if (part == 0) return L::nat(qn, lr, jj, hb);                // S, contraction step jj
-          if (part == 2) return L::nat(don, lr, jj, hb);               // dP, contraction step jj
-          const int c = jj % NC, half = jj / NC;                       // dV (part 1) / dK (part 3): column block c, key half
-          return L::tr(part == 1 ? dop : qp, c, 16 * half);
-        };
-        bf16x8 opb[PFD + 1];
-#pragma unroll
-        for (int k = 0; k < PFD; ++k) opb[k] = operand(k);
-        float4 l4[4], e4[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) { l4[g] = sl4[2 * g]; e4[g] = sd4[2 * g]; }
+      // operand k of an iteration whose S / dP block is in stage a and whose dV / dK block is in stage b
+      auto operand = [&](int k, const lds_byte* a, const lds_byte* b_) -> bf16x8 {
+        const int jj = k >> 2, part = k & 3;
+        if (part == 0) return L::nat(a, lr, jj, hb);                 // S, contraction step jj
+        if (part == 2) return L::nat(a + L::BYTES, lr, jj, hb);      // dP, contraction step jj
+        const int c = jj % NC, half = jj / NC;                       // dV (part 1) / dK (part 3): column block c, key half
+        return L::tr(part == 1 ? b_ + L::BYTES : b_, c, 16 * half);
+      };
+      float pv[16], ds[16];
+      if (do_s && do_x && do_acc) {
         f32x16 sn, pn;
+        auto stream = [&](auto mask_tag) {
+          constexpr bool MASK = decltype(mask_tag)::value;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { sn[e] = 0.f; pn[e] = 0.f; }
-        float pv[16], ds[16];
-        bf16x8 q0, q1, r0, r1;          // P and dS of block t, packed as they complete
-        __builtin_amdgcn_sched_barrier(0);
+          for (int e = 0; e < 16; ++e) { sn[e] = 0.f; pn[e] = 0.f; }
 #pragma unroll
-        for (int k = 0; k < NM; ++k) {
-          if (k + PFD < NM) opb[(k + PFD) % (PFD + 1)] = operand(k + PFD);
-          const bf16x8 a = opb[k % (PFD + 1)];
-          const int jj = k >> 2, part = k & 3, c = jj % NC, half = jj / NC;
-          if (part == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[jj], sn, 0, 0, 0);
-          else if (part == 2) pn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[jj], pn, 0, 0, 0);
-          else if (part == 1) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? p1 : p0, dv[c], 0, 0, 0);
-          else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? d1 : d0, dk[c], 0, 0, 0);
-          if ((k & 1) == 0) {           // one of the sixteen registers of block t per two slots
-            const int r = k >> 1, g = r >> 2, e = r & 3;
-            const float lv = e == 0 ? l4[g].x : e == 1 ? l4[g].y : e == 2 ? l4[g].z : l4[g].w;
-            const float dl = e == 0 ? e4[g].x : e == 1 ? e4[g].y : e == 2 ? e4[g].z : e4[g].w;
-#ifdef DKV_ABL_NOX
-            const float p = sc[r];
-            pv[r] = p;
-            ds[r] = pc[r];
-#else
-            const float p = fast_exp2(fmaf(sc[r], scale_log2, -lv * kLog2e));
-            pv[r] = p;
-            ds[r] = p * (pc[r] - dl);
-#endif
-            if (r == 7) { q0 = pack8(pv); r0 = pack8(ds); }
-            if (r == 15) { q1 = pack8(pv + 8); r1 = pack8(ds + 8); }
+          for (int k = 0; k < NM; ++k) {
+            const int kk = k + PFD;
+            opb[kk % NB] = kk < NM ? operand(kk, qn, qp) : operand(kk - NM, qn2, qp2);
+            const bf16x8 a = opb[k % NB];
+            const int jj = k >> 2, part = k & 3, c = jj % NC, half = jj / NC;
+            if (part == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[jj], sn, 0, 0, 0);
+            else if (part == 2) pn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[jj], pn, 0, 0, 0);
+            else if (part == 1) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? p1 : p0, dv[c], 0, 0, 0);
+            else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? d1 : d0, dk[c], 0, 0, 0);
+            if ((k & 1) == 0) {           // one of the sixteen registers of block t per two slots
+              const int r = k >> 1, g = r >> 2, e = r & 3;
+              float sv = sc[r];
+              if constexpr (MASK) {       // a masked score becomes -inf, so its recomputed probability is exactly 0
+                const int gi = ib + acc_row(r, hb);
+                if ((gi >= N) || (j >= N) || (causal && j > gi)) sv = -INFINITY;
+              }
+              const float p = fast_exp2(fmaf(sv, scale_log2, -l4[g][e] * kLog2e));
+              pv[r] = p;
+              ds[r] = p * (pc[r] - e4[g][e]);
+            } else if (k < 2 * NREQ) {
+              request_piece(k >> 1);
+            }
+            // P and dS of block t go into the operand registers in the slots after the previous
+            // block's last use of them: p0 is read by slots 1 .. 4*NC-3, d0 up to 4*NC-1, p1 up to
+            // NM-3, d1 by the last slot
+            if (k >= 4 * NC - 2 && k < 4 * NC + 2) { const int i = k - (4 * NC - 2); p0[2 * i] = (bf16)pv[2 * i]; p0[2 * i + 1] = (bf16)pv[2 * i + 1]; }
+            if (k >= 4 * NC && k < 4 * NC + 4) { const int i = k - 4 * NC; d0[2 * i] = (bf16)ds[2 * i]; d0[2 * i + 1] = (bf16)ds[2 * i + 1]; }
+            if (k >= NM - 2) {
+              const int i = 2 * (k - (NM - 2));
+              p1[2 * i] = (bf16)pv[8 + 2 * i]; p1[2 * i + 1] = (bf16)pv[9 + 2 * i];
+              p1[2 * i + 2] = (bf16)pv[10 + 2 * i]; p1[2 * i + 3] = (bf16)pv[11 + 2 * i];
+            }
+            // the statistics of the next block, each group after the last use of its registers
+            if (k == NM - 8) { l4[0] = sl4n[0]; e4[0] = sd4n[0]; }
+            if (k == NM - 6) { l4[1] = sl4n[2]; e4[1] = sd4n[2]; }
+            if (k == NM - 4) { l4[2] = sl4n[4]; e4[2] = sd4n[4]; }
+            if (k == NM - 1) {
+              l4[3] = sl4n[6]; e4[3] = sd4n[6];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) d1[e] = (bf16)ds[8 + e];
+            }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        sc = sn; pc = pn; p0 = q0; p1 = q1; d0 = r0; d1 = r1;
+        };
+        if (masked) stream(std::true_type{});
+        else stream(std::false_type{});
+        sc = sn; pc = pn;
       } else {
-        // first and last slots of a wave and blocks that touch the diagonal or the end of the
-        // sequence: whatever exists of the three, one after the other
+        // first and last iterations of an item: whatever exists of the three, one after the other
+#pragma unroll
+        for (int i = 0; i < NREQ; ++i) request_piece(i);
         if (do_acc) {
 #pragma unroll
           for (int c = 0; c < NC; ++c) {
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dop, c, 0), p0, dv[c], 0, 0, 0);
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dop, c, 16), p1, dv[c], 0, 0, 0);
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp + L::BYTES, c, 0), p0, dv[c], 0, 0, 0);
+            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp + L::BYTES, c, 16), p1, dv[c], 0, 0, 0);
             dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 0), d0, dk[c], 0, 0, 0);
             dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 16), d1, dk[c], 0, 0, 0);
           }
@@ -1298,18 +1341,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
               if ((gi >= N) || (j >= N) || (causal && j > gi)) sc[r] = -INFINITY;
             }
           }
-          float pv[16], ds[16];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const float4 l4 = sl4[2 * g], e4 = sd4[2 * g];
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {e4.x, e4.y, e4.z, e4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int r = 4 * g + e;
-              const float p = fast_exp2(fmaf(sc[r], scale_log2, -lv[e] * kLog2e));
-              pv[r] = p;
-              ds[r] = p * (pc[r] - dl[e]);
-            }
+          for (int r = 0; r < 16; ++r) {
+            const float p = fast_exp2(fmaf(sc[r], scale_log2, -l4[r >> 2][r & 3] * kLog2e));
+            pv[r] = p;
+            ds[r] = p * (pc[r] - e4[r >> 2][r & 3]);
           }
           p0 = pack8(pv); p1 = pack8(pv + 8); d0 = pack8(ds); d1 = pack8(ds + 8);
         }
@@ -1319,21 +1355,23 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __r
 #pragma unroll
           for (int s = 0; s < NS; ++s) {
             sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qn, lr, s, hb), kf[s], sc, 0, 0, 0);
-            pc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(don, lr, s, hb), vf[s], pc, 0, 0, 0);
+            pc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qn + L::BYTES, lr, s, hb), vf[s], pc, 0, 0, 0);
           }
         }
+        // what the stream leaves behind for the next iteration: its first operands and its statistics
+#pragma unroll
+        for (int k = 0; k < PFD; ++k) opb[k] = operand(k, qn2, qp2);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) { l4[g] = sl4n[2 * g]; e4[g] = sd4n[2 * g]; }
       }
-      do_acc = do_x; do_x = do_s; x_ib = s_ib;
-      ++s_t;
+      x_ib = s_ib;
       s_ib += RS;
       if (--s_left == 0) { s_left = ntq; s_ib = q_begin; }
-      st_p = st_x; st_x = st_n; st_n = st_n + 1 == NST ? 0 : st_n + 1;
-#ifndef DKV_ABL_NOWAIT
-      wait_requests<(AHEAD - 2) * NREQ>();   // everything up to block t+2 has landed; the later tiles stay in flight
-#endif
-#ifndef DKV_ABL_NOBAR
+      st_p = st_x; st_x = st_n; st_n = st_n2;
+      // everything up to block t+3 has landed: the next iteration reads block t+2 and, ahead of
+      // its successor, block t+3; the later tiles stay in flight
+      wait_requests<(AHEAD - 3) * NREQ>();
       __syncthreads();
-#endif
     }
     if (j < N) {
       bf16* out = dqkv + ((int64_t)b * N + j) * rs + kvh * D;
