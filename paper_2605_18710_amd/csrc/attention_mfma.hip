@@ -26,7 +26,6 @@
 // dO fragments it holds, and read by the dK/dV kernel.
 #include <algorithm>
 #include <mutex>
-#include <type_traits>
 #include "kernels.h"
 #include "tile_queue.h"
 
@@ -36,16 +35,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-// The one-wave-per-SIMD dK/dV kernel below is an experiment that is not yet faster than the
-// two-wave kernel (measured 1.2x slower at B16 N2048 H32); it is compiled only on request.
-#ifdef MOSAIC_DKV_ONE_WAVE
-constexpr bool kDkvOneWavePerSimd = true;
-#else
-constexpr bool kDkvOneWavePerSimd = false;
-#endif
-#ifndef DKV_AHEAD
-#define DKV_AHEAD 6
-#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // Online softmax keeps, per row, a reference value m and sums of exp2(s - m).  Any m works
@@ -120,12 +109,6 @@ struct LdsTile {
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                    : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(desc) : "m0");
     }
-  }
-  // the j-th of the NI requests of issue() alone
-  __device__ __forceinline__ void issue_one(i32x4 desc, unsigned base, unsigned dst, int j) const {
-    const unsigned off = loff[j] + base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 : : "s"(dst + (unsigned)(wave_base + j * 1024)), "v"(off), "s"(desc) : "m0");
   }
   // fragment whose contraction runs along the row: row `row`, columns 16*s + 8*hb .. +7
   __device__ static __forceinline__ bf16x8 nat(const lds_byte* t, int row, int s, int hb) {
@@ -1085,324 +1068,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
   tq_done(tq);
 }
 
-// dK / dV at head size 128 with ONE wave per SIMD.  With two waves per SIMD a wave has 256
-// registers, the dK and dV accumulators take 128 of them, and nothing is left to read operands
-// ahead of their use or to overlap the phases of a block: every matrix instruction waits for
-// the LDS read in front of it.  Here a workgroup is four waves, one per SIMD, each with up to
-// 512 registers (the accumulators go to the accumulator half), and all the overlap is made
-// inside the wave.  A wave alone on its SIMD issues at most one instruction every four cycles
-// and a 32x32x16 matrix instruction occupies the matrix core for 32: the loop is a stream of
-// slots, one matrix instruction and at most seven others each, and whatever does not fit into
-// a slot (a wait, a burst of address arithmetic, a division) stops the matrix core.
-//   - The stream is a software pipeline skewed by one query block: in iteration t the matrix
-//     core computes S and dP of block t+1 and adds block t-1 to dV and dK, alternating between
-//     the four accumulation chains, while the vector ALU turns S and dP of block t into P and dS,
-//     one of the sixteen registers per two slots.
-//   - Operands are read from LDS seven slots ahead into a ring of eight buffers that runs on
-//     across iterations (the last seven slots read the first operands of the next iteration),
-//     the row statistics of the next block are read in the last slots, the six requests of the
-//     tile that is AHEAD blocks away go out one per odd slot, P and dS are packed into the
-//     operand registers in the slots right after their last use by the previous block.
-//   - Positions advance by increments (no division, no modulo in the loop).
-//   - The first and last iterations of an item, where one of the three blocks does not exist,
-//     take a plain path (one phase after the other).  Blocks on or above the diagonal and at the
-//     end of the sequence go through the stream in a variant that masks: a block wholly above
-//     the diagonal adds zeros (the other waves of the workgroup work on it anyway).
-// The V fragments of the owned keys live in registers beside the K fragments.  Streamed Q / dO
-// tiles of 32 rows go through a ring of AHEAD+2 LDS stages: iteration t reads blocks t-1, t+1
-// and, for the next iteration's first operands, t and t+2; block t+AHEAD is requested into the
-// stage of block t-2.  Per accumulator the products arrive in the same order as in the kernel
-// above: same bits.
-template <int D>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_pipe_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
-                                                                const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int B, int N, int H, int Hkv, int causal,
-                                                                float scale, int ktiles, int hblk, TileQueueArgs tq) {
-  constexpr int NW = 4, RS = 32, NS = D / 16, NC = D / 32, NM = 4 * NS;
-  constexpr int NB = 8, PFD = NB - 1;                      // operand buffers, slots of lookahead
-  static_assert(NS == 2 * NC, "slots alternate between four chains of equal length");
-  static_assert(NM % NB == 0, "the operand ring keeps its phase from one iteration to the next");
-  typedef LdsTile<RS, D, NW> L;
-  constexpr int STAGE = 2 * L::BYTES;                      // Q | dO
-  constexpr int AHEAD = DKV_AHEAD, NST = AHEAD + 2, KT = 32 * NW, NREQ = 2 * L::NI + 2;
-  static_assert(AHEAD >= 4 && (AHEAD - 3) * NREQ < 64, "the wait count has six bits");
-  static_assert(2 * NREQ <= NM - 8, "one request per odd slot, before the statistics reads");
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  const lds_byte* smem = (const lds_byte*)smem_raw;        // [NST][STAGE], then [NST][2][64] floats: lse, delta
-  const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  const float* stat = reinterpret_cast<const float*>(smem_raw + NST * STAGE);
-  L ld, ldo;           // lane offsets for the two row strides: q rows and dO rows
-  ld.init((unsigned)((H + 2 * Hkv) * D * 2));
-  ldo.init((unsigned)(H * D * 2));
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int lr = lane & 31, hb = lane >> 5;
-  const int h = H * D, ko = H * D, vo = (H + Hkv) * D, GQ = H / Hkv;
-  const int64_t rs = (int64_t)(H + 2 * Hkv) * D;
-  const float scale_log2 = scale * kLog2e;
-  __shared__ int mail;
-  __shared__ unsigned claimed;
-  TileQueueCursor qc;
-  int item = tq_first(tq, qc, &mail);
-  while (item >= 0) {
-    int head_, kt_i;
-    attn_item(item, B * Hkv, ktiles, hblk, false, attn_mirror(tq, qc, ktiles), &head_, &kt_i);      // the first key tile has the most queries
-    const int kvh = head_ % Hkv, b = head_ / Hkv;
-    const int hd0 = kvh * GQ;                    // first query head of the group
-    const int k0 = kt_i * KT, j0w = k0 + 32 * wave, j = j0w + lr;
-    const bf16* rowb = qkv + (int64_t)b * N * rs;
-    const bf16* base = rowb + hd0 * D;           // q columns of the group's heads are adjacent
-    const bf16* dob = dO + (int64_t)b * N * h + hd0 * D;
-    const float* lse_b = lse + ((int64_t)b * H + hd0) * N;
-    const float* del_b = delta + ((int64_t)b * H + hd0) * N;
-    bf16x8 kf[NS], vf[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      if (j < N) {
-        kf[s] = *reinterpret_cast<const bf16x8*>(rowb + ko + kvh * D + (int64_t)j * rs + 16 * s + 8 * hb);
-        vf[s] = *reinterpret_cast<const bf16x8*>(rowb + vo + kvh * D + (int64_t)j * rs + 16 * s + 8 * hb);
-      } else {
-        for (int e = 0; e < 8; ++e) { kf[s][e] = (bf16)0.f; vf[s][e] = (bf16)0.f; }
-      }
-    }
-    f32x16 dk[NC], dv[NC];
-#pragma unroll
-    for (int c = 0; c < NC; ++c)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) { dk[c][e] = 0.f; dv[c][e] = 0.f; }
-    const int q_begin = causal ? (k0 / RS) * RS : 0;
-    const int ntq = (N - q_begin + RS - 1) / RS;       // query tiles of one head
-    const int ntiles = ntq * GQ;                         // streamed for every query head of the group in turn
-    auto desc_f32 = [&](const float* p) {
-      i32x4 d;
-      d.x = (int)(uint32_t)(uintptr_t)p; d.y = (int)((uint32_t)((uintptr_t)p >> 32) & 0xffffu);
-      d.z = GQ * N * 4; d.w = 0x00020000;
-      return d;
-    };
-    const i32x4 dl_ = desc_f32(lse_b), dd_ = desc_f32(del_b);
-    const i32x4 dq_ = slice_desc(base, N, rs, GQ * D), do_ = slice_desc(dob, N, h, GQ * D);
-    const unsigned rsb = (unsigned)(rs * 2), hsb = (unsigned)(h * 2);
-    // Tiles are requested in order, one per iteration.  request_begin() works out where the
-    // next tile comes from and goes to and advances the position; request_piece(i), i < NREQ,
-    // issues its i-th request.  Tiles past the last one fetch nothing (they point outside the
-    // descriptors); every wave issues the same number of requests per tile so that the wait
-    // counts are constants.
-    int rq_t = 0, rq_g = 0, rq_row = q_begin, rq_left = ntq, rq_st = 0;    // next tile: number, head, first row, blocks left in the head, stage
-    unsigned rq_nb = 0, rq_qoff = 0, rq_dooff = 0, rq_soff = 0, rq_sdst = 0;
-    auto request_begin = [&]() {
-      const bool real = rq_t < ntiles;
-      const int row0 = real ? rq_row : N;
-      const unsigned col = real ? (unsigned)(rq_g * D * 2) : 0u;
-      rq_nb = lds0 + (unsigned)(rq_st * STAGE);
-      rq_qoff = (unsigned)row0 * rsb + col;
-      rq_dooff = (unsigned)row0 * hsb + col;
-      rq_soff = (real && lane < RS && rq_row + lane < N) ? (unsigned)(rq_g * N + rq_row + lane) * 4u : 0xFFFFFFF0u;
-      rq_sdst = lds0 + (unsigned)(NST * STAGE + rq_st * 2 * 64 * 4);
-      ++rq_t;
-      rq_row += RS;
-      if (--rq_left == 0) { rq_left = ntq; rq_row = q_begin; ++rq_g; }
-      rq_st = rq_st + 1 == NST ? 0 : rq_st + 1;
-    };
-    auto request_piece = [&](int i) {
-      if (i < L::NI) ld.issue_one(dq_, rq_qoff, rq_nb, i);
-      else if (i < 2 * L::NI) ldo.issue_one(do_, rq_dooff, rq_nb + L::BYTES, i - L::NI);
-      else if (i == 2 * L::NI)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(rq_sdst), "v"(rq_soff), "s"(dl_) : "m0");
-      else
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" : : "s"(rq_sdst + 256u), "v"(rq_soff), "s"(dd_) : "m0");
-    };
-    // The K and V fragments have arrived before the first tile request goes out: the compiler
-    // counts only its own loads, so a partial wait further down would leave it unsure about
-    // these and it would wait for every outstanding request inside the loop.
-    wait_requests<0>();
-    __syncthreads();                    // the previous item's readers are done with every stage
-#pragma unroll
-    for (int u = 0; u < AHEAD - 1; ++u) {
-      request_begin();
-#pragma unroll
-      for (int i = 0; i < NREQ; ++i) request_piece(i);
-    }
-    wait_requests<(AHEAD - 3) * NREQ>();                  // tiles 0 and 1 have landed
-    __syncthreads();
-    const int claim_at = ntiles > 2 * kClaimTilesAhead ? ntiles - 2 * kClaimTilesAhead : -1;   // tiles of 32 rows here
-    f32x16 sc, pc;                      // S and dP of block t, whose P and dS are formed in iteration t
-    bf16x8 p0, p1, d0, d1;              // P and dS of block t-1, whose products are added in iteration t
-    bf16x8 opb[NB];                     // operand k of the iteration in buffer k % NB
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
-    f32x4 l4[4], e4[4];                 // lse and delta of block t: registers 4g .. 4g+3 of a lane hold query rows 8g + 4*hb + {0..3}
-#pragma unroll
-    for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { p0[e] = (bf16)0.f; p1[e] = (bf16)0.f; d0[e] = (bf16)0.f; d1[e] = (bf16)0.f; }
-#pragma unroll
-    for (int u = 0; u < NB; ++u) opb[u] = p0;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) { l4[g] = f32x4{0.f, 0.f, 0.f, 0.f}; e4[g] = l4[g]; }
-    const bool wave_live = j0w < N;
-    int s_ib = q_begin, s_left = ntq, x_ib = q_begin;    // first query row of block t+1 and blocks left in its head; first row of block t
-    int st_p = NST - 2, st_x = NST - 1, st_n = 0;        // stages of blocks t-1, t, t+1
-    for (int t = -1; t <= ntiles; ++t) {
-      request_begin();                  // block t+AHEAD, into the stage of block t-2, last read in the iteration before
-      // The claimed entry goes through LDS, inside the branch: carried in a register across the
-      // loop, the pending atomic would make the compiler wait for every outstanding request,
-      // the tile requests included, in each iteration.
-      if (t == claim_at && threadIdx.x == 0 && tq.mode == TQ_QUEUE) *(volatile unsigned*)&claimed = tq_claim(tq, qc);
-      const int st_n2 = st_n + 1 == NST ? 0 : st_n + 1;   // stage of block t+2
-      const lds_byte* qn = smem + st_n * STAGE;           // block t+1: S, dP
-      const lds_byte* qp = smem + st_p * STAGE;           // block t-1: dV, dK
-      const lds_byte* qn2 = smem + st_n2 * STAGE;         // the next iteration's two
-      const lds_byte* qp2 = smem + st_x * STAGE;
-      const f32x4* sl4n = reinterpret_cast<const f32x4*>(stat + (st_n * 2 + 0) * 64 + 4 * hb);   // statistics of block t+1
-      const f32x4* sd4n = reinterpret_cast<const f32x4*>(stat + (st_n * 2 + 1) * 64 + 4 * hb);
-      const bool do_s = wave_live && t + 1 < ntiles, do_x = wave_live && t >= 0 && t < ntiles, do_acc = wave_live && t >= 1;
-      const int ib = x_ib;
-      const bool masked = (ib + 32 > N) || (j0w + 32 > N) || (causal && j0w + 31 > ib);
-      // operand k of an iteration whose S / dP block is in stage a and whose dV / dK block is in stage b
-      auto operand = [&](int k, const lds_byte* a, const lds_byte* b_) -> bf16x8 {
-        const int jj = k >> 2, part = k & 3;
-        if (part == 0) return L::nat(a, lr, jj, hb);                 // S, contraction step jj
-        if (part == 2) return L::nat(a + L::BYTES, lr, jj, hb);      // dP, contraction step jj
-        const int c = jj % NC, half = jj / NC;                       // dV (part 1) / dK (part 3): column block c, key half
-        return L::tr(part == 1 ? b_ + L::BYTES : b_, c, 16 * half);
-      };
-      float pv[16], ds[16];
-      if (do_s && do_x && do_acc) {
-        f32x16 sn, pn;
-        auto stream = [&](auto mask_tag) {
-          constexpr bool MASK = decltype(mask_tag)::value;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) { sn[e] = 0.f; pn[e] = 0.f; }
-#pragma unroll
-          for (int k = 0; k < NM; ++k) {
-            const int kk = k + PFD;
-            opb[kk % NB] = kk < NM ? operand(kk, qn, qp) : operand(kk - NM, qn2, qp2);
-            const bf16x8 a = opb[k % NB];
-            const int jj = k >> 2, part = k & 3, c = jj % NC, half = jj / NC;
-            if (part == 0) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[jj], sn, 0, 0, 0);
-            else if (part == 2) pn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[jj], pn, 0, 0, 0);
-            else if (part == 1) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? p1 : p0, dv[c], 0, 0, 0);
-            else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, half ? d1 : d0, dk[c], 0, 0, 0);
-            if ((k & 1) == 0) {           // one of the sixteen registers of block t per two slots
-              const int r = k >> 1, g = r >> 2, e = r & 3;
-              float sv = sc[r];
-              if constexpr (MASK) {       // a masked score becomes -inf, so its recomputed probability is exactly 0
-                const int gi = ib + acc_row(r, hb);
-                if ((gi >= N) || (j >= N) || (causal && j > gi)) sv = -INFINITY;
-              }
-              const float p = fast_exp2(fmaf(sv, scale_log2, -l4[g][e] * kLog2e));
-              pv[r] = p;
-              ds[r] = p * (pc[r] - e4[g][e]);
-            } else if (k < 2 * NREQ) {
-              request_piece(k >> 1);
-            }
-            // P and dS of block t go into the operand registers in the slots after the previous
-            // block's last use of them: p0 is read by slots 1 .. 4*NC-3, d0 up to 4*NC-1, p1 up to
-            // NM-3, d1 by the last slot
-            if (k >= 4 * NC - 2 && k < 4 * NC + 2) { const int i = k - (4 * NC - 2); p0[2 * i] = (bf16)pv[2 * i]; p0[2 * i + 1] = (bf16)pv[2 * i + 1]; }
-            if (k >= 4 * NC && k < 4 * NC + 4) { const int i = k - 4 * NC; d0[2 * i] = (bf16)ds[2 * i]; d0[2 * i + 1] = (bf16)ds[2 * i + 1]; }
-            if (k >= NM - 2) {
-              const int i = 2 * (k - (NM - 2));
-              p1[2 * i] = (bf16)pv[8 + 2 * i]; p1[2 * i + 1] = (bf16)pv[9 + 2 * i];
-              p1[2 * i + 2] = (bf16)pv[10 + 2 * i]; p1[2 * i + 3] = (bf16)pv[11 + 2 * i];
-            }
-            // the statistics of the next block, each group after the last use of its registers
-            if (k == NM - 8) { l4[0] = sl4n[0]; e4[0] = sd4n[0]; }
-            if (k == NM - 6) { l4[1] = sl4n[2]; e4[1] = sd4n[2]; }
-            if (k == NM - 4) { l4[2] = sl4n[4]; e4[2] = sd4n[4]; }
-            if (k == NM - 1) {
-              l4[3] = sl4n[6]; e4[3] = sd4n[6];
-#pragma unroll
-              for (int e = 0; e < 8; ++e) d1[e] = (bf16)ds[8 + e];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }
-        };
-        if (masked) stream(std::true_type{});
-        else stream(std::false_type{});
-        sc = sn; pc = pn;
-      } else {
-        // first and last iterations of an item: whatever exists of the three, one after the other
-#pragma unroll
-        for (int i = 0; i < NREQ; ++i) request_piece(i);
-        if (do_acc) {
-#pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp + L::BYTES, c, 0), p0, dv[c], 0, 0, 0);
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp + L::BYTES, c, 16), p1, dv[c], 0, 0, 0);
-            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 0), d0, dk[c], 0, 0, 0);
-            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qp, c, 16), d1, dk[c], 0, 0, 0);
-          }
-        }
-        if (do_x) {
-          // a masked score becomes -inf, so its recomputed probability is exactly 0
-          if (masked) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int gi = ib + acc_row(r, hb);
-              if ((gi >= N) || (j >= N) || (causal && j > gi)) sc[r] = -INFINITY;
-            }
-          }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(fmaf(sc[r], scale_log2, -l4[r >> 2][r & 3] * kLog2e));
-            pv[r] = p;
-            ds[r] = p * (pc[r] - e4[r >> 2][r & 3]);
-          }
-          p0 = pack8(pv); p1 = pack8(pv + 8); d0 = pack8(ds); d1 = pack8(ds + 8);
-        }
-        if (do_s) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) { sc[e] = 0.f; pc[e] = 0.f; }
-#pragma unroll
-          for (int s = 0; s < NS; ++s) {
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qn, lr, s, hb), kf[s], sc, 0, 0, 0);
-            pc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::nat(qn + L::BYTES, lr, s, hb), vf[s], pc, 0, 0, 0);
-          }
-        }
-        // what the stream leaves behind for the next iteration: its first operands and its statistics
-#pragma unroll
-        for (int k = 0; k < PFD; ++k) opb[k] = operand(k, qn2, qp2);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) { l4[g] = sl4n[2 * g]; e4[g] = sd4n[2 * g]; }
-      }
-      x_ib = s_ib;
-      s_ib += RS;
-      if (--s_left == 0) { s_left = ntq; s_ib = q_begin; }
-      st_p = st_x; st_x = st_n; st_n = st_n2;
-      // everything up to block t+3 has landed: the next iteration reads block t+2 and, ahead of
-      // its successor, block t+3; the later tiles stay in flight
-      wait_requests<(AHEAD - 3) * NREQ>();
-      __syncthreads();
-    }
-    if (j < N) {
-      bf16* out = dqkv + ((int64_t)b * N + j) * rs + kvh * D;
-      // dK rows first, then dV rows: the eight 16-byte pieces that make up a 128-byte line
-      // leave in consecutive instructions and meet in the L2 before the line is written out
-#pragma unroll
-      for (int c = 0; c < NC; ++c)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 vk;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) vk[e] = (bf16)(dk[c][4 * g + e] * scale);
-          *reinterpret_cast<bf16x4*>(out + ko + 32 * c + 8 * g + 4 * hb) = vk;
-        }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int c = 0; c < NC; ++c)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 vv;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) vv[e] = (bf16)dv[c][4 * g + e];
-          *reinterpret_cast<bf16x4*>(out + vo + 32 * c + 8 * g + 4 * hb) = vv;
-        }
-    }
-    const unsigned entry = (threadIdx.x == 0 && tq.mode == TQ_QUEUE) ? *(volatile unsigned*)&claimed : 0u;
-    item = tq_next(tq, qc, entry, &mail);
-  }
-  tq_done(tq);
-}
-
 // Workgroup shape.  The kernels are written for NW waves and a ring of stages; measured on
 // the 8 x 1024 x 16 x 128 causal problem, 8 waves with four stages (one workgroup per CU,
 // three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU):
@@ -1474,15 +1139,8 @@ mosaic_status bwd_t(hipStream_t s, int quota, int B, int N, int H, int Hkv, int 
     static hipError_t once_rc = hipSuccess;
     TileQueueArgs tq;
     int grid, hb;
-    if constexpr (kDkvOneWavePerSimd && D == 128 && NW == 4) {
-      // one wave per SIMD: six stages of Q | dO tiles and their row statistics
-      constexpr size_t smem1 = (size_t)(DKV_AHEAD + 2) * 2 * LdsTile<32, D, NW>::BYTES + (size_t)(DKV_AHEAD + 2) * 2 * 64 * sizeof(float);
-      MOSAIC_TRY(launch_queued(attn_bwd_dkv_pipe_mfma<D>, once, once_rc, smem1, s, quota, 1, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
-      attn_bwd_dkv_pipe_mfma<D><<<grid, 64 * NW, smem1, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
-    } else {
-      MOSAIC_TRY(launch_queued(attn_bwd_dkv_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
-      attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
-    }
+    MOSAIC_TRY(launch_queued(attn_bwd_dkv_mfma<D, NW>, once, once_rc, smem, s, quota, 8 / NW, (int64_t)B * Hkv, tiles, causal, &tq, &grid, &hb));
+    attn_bwd_dkv_mfma<D, NW><<<grid, 64 * NW, smem, s>>>(qkv, dO, lse, delta, dqkv, B, N, H, Hkv, causal, scale, tiles, hb, tq);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
