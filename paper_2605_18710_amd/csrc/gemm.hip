@@ -237,13 +237,14 @@ static inline int row_block_for(int64_t K, int64_t tiles_m) {
 
 // One unit of work: an output tile, or (SPLITK) one K-piece of an output tile.
 struct WorkItem {
-  int m0, n0, kt0, kt_end, split;
+  int m0, n0, kt0, kt_end, split, tl;      // tl: position of the item's coarse tile in this launch's range
   bool valid;
 };
 
 // SPLITK: the K range is cut into `ksplit` contiguous pieces of `ktiles_per` K-tiles; piece s
-// of a tile is accumulated by its own workgroup and stored in fp32 to P[s][M][N]; a second
-// kernel adds the pieces in ascending s.  ksplit depends on the problem shape only.
+// of the launch's t-th tile is accumulated by its own workgroup and stored in fp32 to
+// P[s][t][BM][BN]; a second kernel adds the pieces in ascending s.  Which tiles are cut and
+// into how many pieces depends on the problem shape only.
 //
 // A workgroup streams the K-tiles of ALL its work items through one pipeline: a load
 // cursor runs AHEAD K-tiles ahead of the compute cursor and crosses item boundaries, so
@@ -304,12 +305,13 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
   const int per_split = tile_count * sub * sub;
   auto decode = [&](int item) -> WorkItem {
     WorkItem it;
-    it.valid = item >= 0; it.m0 = 0; it.n0 = 0; it.kt0 = 0; it.kt_end = 0; it.split = 0;
+    it.valid = item >= 0; it.m0 = 0; it.n0 = 0; it.kt0 = 0; it.kt_end = 0; it.split = 0; it.tl = 0;
     if (!it.valid) return it;
     it.split = item / per_split;
     const int fine = item - it.split * per_split;
     const int quad = fine % (sub * sub);
-    const int tile = tile_begin + fine / (sub * sub);
+    it.tl = fine / (sub * sub);
+    const int tile = tile_begin + it.tl;
     it.kt0 = it.split * ktiles_per;
     it.kt_end = SPLITK ? min(nk_all, it.kt0 + ktiles_per) : nk_all;
     int trow, tcol;
@@ -554,13 +556,13 @@ __global__ __launch_bounds__(64 * NWM * NWN, 2) void gemm_bf16_kernel(
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         if constexpr (SPLITK) {
-          float* Ps = P + (int64_t)it.split * M * N;
+          float* Ps = P + ((int64_t)it.split * tile_count + it.tl) * (BM * BN);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int r = (ln >> 3) + 8 * q, cgl = ln & 7;
             const float4 v = *reinterpret_cast<const float4*>(patch + r * 32 + ((cgl ^ ((r >> 1) & 7)) * 4));
             const int row = rb0 + r, col = cb + 4 * cgl;
-            if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (int64_t)row * N + col) = v;
+            if (row < M && col < N) *reinterpret_cast<float4*>(Ps + (row - it.m0) * BN + (col - it.n0)) = v;
           }
         } else {
           float4 v0[2], v1[2];
@@ -1083,20 +1085,31 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kc4w_kernel(
   tq_done(tq);
 }
 
-// out[row][col] = bf16( P[0] + P[1] + ... ) in ascending piece order
+// out = bf16( P[0] + P[1] + ... ) in ascending piece order, for the tiles [tile_begin,
+// tile_begin + tile_count) of the 256x256 tile list that the split launch covered.  One block
+// iteration takes four rows of one tile (256 float4), so the tile's place is found once per
+// iteration.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, bf16* __restrict__ C,
-                                                            int64_t M, int64_t N, int64_t ldc, int ksplit) {
-  const int64_t nvec = M * N / 4;
-  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * 256) {
-    float4 a = reinterpret_cast<const float4*>(P)[v];
+                                                            int M, int N, int64_t ldc, int ksplit, int tiles_m,
+                                                            int tiles_n, int tile_begin, int tile_count, int row_block) {
+  const int64_t piece = (int64_t)tile_count * 65536;
+  const int units = tile_count * 64;
+  for (int u = blockIdx.x; u < units; u += gridDim.x) {
+    const int tl = u >> 6;
+    int trow, tcol;
+    tile_coords(tile_begin + tl, tiles_m, tiles_n, row_block, &trow, &tcol);
+    const int r = (u & 63) * 4 + (threadIdx.x >> 6), c = (threadIdx.x & 63) * 4;
+    const int row = trow * 256 + r, col = tcol * 256 + c;
+    if (row >= M || col >= N) continue;
+    const float* src = P + (int64_t)tl * 65536 + r * 256 + c;
+    float4 a = *reinterpret_cast<const float4*>(src);
     for (int s = 1; s < ksplit; ++s) {
-      const float4 b = reinterpret_cast<const float4*>(P + (int64_t)s * M * N)[v];
+      const float4 b = *reinterpret_cast<const float4*>(src + s * piece);
       a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
     }
-    const int64_t e = v * 4, row = e / N, col = e - row * N;
     bf16x4 o;
     o[0] = (bf16)a.x; o[1] = (bf16)a.y; o[2] = (bf16)a.z; o[3] = (bf16)a.w;
-    *reinterpret_cast<bf16x4*>(C + row * ldc + col) = o;
+    *reinterpret_cast<bf16x4*>(C + (int64_t)row * ldc + col) = o;
   }
 }
 
@@ -1192,14 +1205,16 @@ mosaic_status launch_mfma(hipStream_t s, int quota, int M, int N, int K, const b
   int grid;
   MOSAIC_TRY(tile_queue_plan(s, quota, wg_per_cu, items, 0, false, &tq, &grid));
   ActArgs ka = aa;
-  // a split product streams 1/ksplit of K per item; coarse tile rows are BM * sub rows high
-  ka.row_block = row_block_for(ceil_div((int64_t)K, ksplit), ceil_div((int64_t)M, 256)) * 256 / (BM * sub);
+  // coarse tile rows are BM * sub rows high; every launch over one product (whole rounds,
+  // quarter tiles, split tiles) walks the same tile list
+  ka.row_block = row_block_for(K, ceil_div((int64_t)M, 256)) * 256 / (BM * sub);
   kern<<<grid, 64 * NWM * NWN, smem, s>>>(A, B, C, bias, R, M, N, K, lda, ldb, ldc, a_bytes, b_bytes, c_bytes,
                                           tiles_m, tiles_n, tile_begin, tile_count, sub, ksplit, ktiles_per, P, tq, ka);
   MOSAIC_LAUNCH_CHECK();
   if (SPLITK) {
-    const int g2 = grid_for(quota, 8, ceil_div((int64_t)M * N / 4, 256));
-    splitk_reduce_kernel<<<g2, 256, 0, s>>>(P, C, M, N, ldc, ksplit);
+    static_assert(!SPLITK || (BM == 256 && BN == 256), "the reduce kernel walks 256x256 tiles");
+    const int g2 = grid_for(quota, 8, (int64_t)tile_count * 64);
+    splitk_reduce_kernel<<<g2, 256, 0, s>>>(P, C, M, N, ldc, ksplit, tiles_m, tiles_n, tile_begin, tile_count, ka.row_block);
     MOSAIC_LAUNCH_CHECK();
   }
   return MOSAIC_OK;
@@ -1237,8 +1252,9 @@ mosaic_status launch_kc4w(hipStream_t s, int quota, int M, int N, int K, const b
 
 // A/B switches for kernel timing, compiled in only with -DMOSAIC_TUNING (never in the library
 // that ships): MOSAIC_GEMM_KC4W=0 sends the input-gradient form back to the eight-wave kernel,
-// MOSAIC_GEMM_TILE=256 / 128 / 1 forces the all-256, all-128 or mixed tile plan.  The bits are
-// the same either way.
+// MOSAIC_GEMM_TILE=256 / 128 / 1 forces the all-256, all-128 or mixed tile plan (the bits are
+// the same either way); MOSAIC_SPLITK=n forces the piece count of a weight gradient's cut tail
+// (0: no cut; the bits differ with n).
 #ifdef MOSAIC_TUNING
 bool kc4w_enabled() {
   static int v = -1;
@@ -1255,17 +1271,54 @@ constexpr bool kc4w_enabled() { return true; }
 constexpr int forced_tile() { return 0; }
 #endif
 
-// Split count for the weight-gradient form: when the output has too few 256x256 tiles to
-// occupy the device and the contraction is long, cut K so that there are about as many
-// work items as CUs.  A function of the shape alone (256 = CUs of the device the kernels
-// are written for), never of the quota, so the bits stay quota-independent.
-int splitk_factor(int64_t M, int64_t N, int64_t K) {
+// Splitting the weight-gradient form along K.  Its contraction runs over the tokens and is
+// long; its output has few tiles.  Two cases, both decided by the shape alone (256 = CUs of the
+// device the kernels are written for; never the quota, so the bits stay quota-independent):
+//  - up to 128 tiles of 256x256: every tile is cut, into about as many work items as CUs;
+//  - more: the tiles that do not fill a round of 256 (the tail of the tile list) are cut when
+//    the contraction is at least 16384 long and the cut is priced well below the alternatives,
+//    one more round of large tiles or the tail as quarter tiles.  Prices in microseconds on the
+//    whole device: a 256x256 tile takes 25.5 ns per unit of K, a work item 12 us on top
+//    (pipeline fill, fp32 store of its piece), the pass that adds the pieces reads them at
+//    3.5 TB/s after 8 us; two small workgroups per CU take 1.8 quarter units each (as in
+//    launch_mfma_shape).  Measured, pieces forced to 2 .. 8: the gate/up gradient at T=32768
+//    (1376 tiles, 96 in the tail) 4845 us uncut, 4624 in 5 pieces (the plan's choice; 2 and 8
+//    pieces within 15 us of it); the same at T=16384 2405 -> 2315; the down-projection gradient
+//    (688 tiles, 176 in the tail, else a third round of large tiles) 2410 -> 2362 in 4 pieces
+//    and slower in any other count; at T=8192 no cut gains anything (331 us either way for 96
+//    tail tiles, 178 -> 211 and worse for a lone round of 192 tiles): pieces of a few thousand
+//    tokens are mostly fill and drain.
+// *first: first tile of the list that is cut; returns the piece count (1: nothing is cut).
+int splitk_plan(int64_t M, int64_t N, int64_t K, int* first) {
   const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
-  if (t256 > 128 || K < 2048 || (N % 4)) return 1;
-  int64_t s = 256 / t256;
-  if (s > 8) s = 8;
-  while (s > 1 && ceil_div(K, s) < 512) --s;
-  return (int)s;
+  *first = 0;
+  if (N % 4) return 1;
+  if (t256 <= 128) {
+    if (K < 2048) return 1;
+    int64_t s = 256 / t256;
+    if (s > 8) s = 8;
+    while (s > 1 && ceil_div(K, s) < 512) --s;
+    return (int)s;
+  }
+  const int64_t tail = t256 % 256;
+  if (tail == 0 || K < 16384) return 1;
+  const double tile_us = 25.5e-3 * (double)K;
+  int best = 1;
+  double best_us = 1e30;
+  for (int s = 2; s <= 8 && K / s >= 1024; ++s) {
+    const double pieces = (double)(tail * s);
+    const double us = (double)ceil_div(tail * s, 256) * (tile_us / s + 12.0) + pieces * 262144.0 / 3.5e6 + 8.0;
+    if (us < best_us - 1e-9) { best_us = us; best = s; }
+  }
+  const int64_t q = 4 * tail, full = q / 512, rem = q % 512;
+  const double quarter_us = ((double)full * 2.0 * 1.8 + (rem == 0 ? 0.0 : rem <= 256 ? 1.2 * 1.8 : 2.0 * 1.8)) / 4.0 * tile_us;
+  const double other_us = std::min(tile_us, quarter_us);            // one more round of large tiles, or quarter tiles
+#ifdef MOSAIC_TUNING
+  if (const char* e = getenv("MOSAIC_SPLITK")) { const int f = atoi(e); if (f <= 1) return 1; *first = (int)(t256 - tail); return f; }
+#endif
+  if (best == 1 || best_us >= 0.92 * other_us) return 1;
+  *first = (int)(t256 - tail);
+  return best;
 }
 
 template <bool A_KC, bool B_KC>
@@ -1273,13 +1326,23 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
                                 const bf16* B, int64_t ldb, bf16* C, int64_t ldc, const bf16* bias, const bf16* R,
                                 uint32_t a_bytes, uint32_t b_bytes, uint32_t c_bytes, void* splitk_scratch,
                                 const ActArgs& aa = ActArgs()) {
+  // tiles [split_first, t256) of the tile list are cut along K (weight-gradient form only); the
+  // tiles before them are planned below as if they were the whole product
+  int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
+  const int64_t t256_all = t256;
+  int sk = 1, split_first = 0;
   if constexpr (!A_KC && !B_KC) {
-    const int sk = splitk_factor(M, N, K);
-    if (sk > 1 && splitk_scratch && !bias && !R) {
-      const int per = (int)ceil_div(ceil_div(K, BK), sk);
-      return launch_mfma<256, 256, 2, 4, A_KC, B_KC, true>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes,
-                                                           b_bytes, c_bytes, sk, per, (float*)splitk_scratch);
-    }
+    if (splitk_scratch && !bias && !R) sk = splitk_plan(M, N, K, &split_first);
+  }
+  auto launch_split = [&]() -> mosaic_status {
+    const int per = (int)ceil_div(ceil_div(K, BK), sk);
+    return launch_mfma<256, 256, 2, 4, A_KC, B_KC, true>(s, quota, M, N, K, A, lda, B, ldb, C, ldc, bias, R, a_bytes, b_bytes, c_bytes,
+                                                         sk, per, (float*)splitk_scratch, 1, split_first, (int)(t256_all - split_first));
+  };
+  const bool part = sk > 1;          // the plans below cover tiles [0, t256) only
+  if (part) {
+    if (split_first == 0) return launch_split();
+    t256 = split_first;
   }
   // Tile shape only decides which workgroup computes an element, never its bits.  Large
   // tiles halve LDS traffic per MFMA; small tiles fill the CUs when there are few large
@@ -1291,7 +1354,7 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   // rounds are counted with the CUs that are certain to run a workgroup at the same time
   const int launch_quota = quota;
   quota = tile_queue_sure_cus(quota);
-  const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256), t128 = ceil_div(M, 128) * ceil_div(N, 128);
+  const int64_t t128 = part ? 4 * t256 : ceil_div(M, 128) * ceil_div(N, 128);
   auto cost_small = [&](int64_t tiles) {       // 128x128 tiles on `quota` CUs
     const int64_t full = tiles / (2 * (int64_t)quota), rem = tiles % (2 * (int64_t)quota);
     // a CU shared by two workgroups finishes both in about 2 x 1.35 units (more when the
@@ -1329,21 +1392,28 @@ mosaic_status launch_mfma_shape(hipStream_t s, int quota, int M, int N, int K, c
   };
   if (plan == 256) {
     if (kc4w) return launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, -1);
-    return launch_tiles(std::true_type{}, 1, 0, -1);
+    MOSAIC_TRY(launch_tiles(std::true_type{}, 1, 0, part ? (int)t256 : -1));
+    return part ? launch_split() : MOSAIC_OK;
   }
-  if (plan == 128) return launch_tiles(std::false_type{}, 1, 0, -1);
+  if (plan == 128) {
+    MOSAIC_TRY(part ? launch_tiles(std::false_type{}, 2, 0, (int)t256) : launch_tiles(std::false_type{}, 1, 0, -1));
+    return part ? launch_split() : MOSAIC_OK;
+  }
   const int head = (int)(whole * quota);
   mosaic_status st = kc4w ? launch_kc4w(s, launch_quota, M, N, K, A, lda, B, ldb, C, ldc, R, a_bytes, b_bytes, c_bytes, 0, head)
                           : launch_tiles(std::true_type{}, 1, 0, head);
   if (st != MOSAIC_OK) return st;
-  return launch_tiles(std::false_type{}, 2, head, (int)rest);
+  MOSAIC_TRY(launch_tiles(std::false_type{}, 2, head, (int)rest));
+  return part ? launch_split() : MOSAIC_OK;
 }
 
 }  // namespace
 
 size_t gemm_splitk_scratch_bytes(int64_t M, int64_t N, int64_t K) {
-  const int sk = splitk_factor(M, N, K);
-  return sk > 1 ? (size_t)sk * (size_t)M * (size_t)N * sizeof(float) : 0;
+  int first = 0;
+  const int sk = splitk_plan(M, N, K, &first);
+  const int64_t cut = ceil_div(M, 256) * ceil_div(N, 256) - first;      // whole 256x256 tiles, edge tiles too
+  return sk > 1 ? (size_t)sk * (size_t)cut * 65536 * sizeof(float) : 0;
 }
 
 // fused != null: a forward-form call that also wants act(C) in C2; *fused says whether the

@@ -65,6 +65,38 @@ def test_decoder_gate_up_projection_sampled(mb):
     assert_close(dWh, X.T @ dY[:, cols], "bf16", "dW columns")
 
 
+@pytest.mark.parametrize("T,k,n,note", [
+    (16384, 768, 22016, "258 tiles: 256 in one round, the last two cut into pieces"),
+    (16384, 1024, 8448, "132 tiles, more than half a round and less than one, long contraction: all cut into pieces"),
+    (12288, 768, 8704, "102 tiles: the whole product cut into 2 pieces"),
+])
+def test_weight_gradient_with_tiles_cut_along_the_contraction(mb, T, k, n, note):
+    """Weight gradients whose tile count does not fill rounds of 256: the tiles of the partial round
+    are cut along the token dimension, each piece accumulated by its own workgroup, and a second
+    pass adds the pieces.  Which tiles are cut depends on the shape alone: same bits at every quota.
+    Sampled columns (all rows) against the checker, among them columns of the cut tiles (the end
+    of the tile list: the last tile columns) and of uncut ones."""
+    X = quantize(synth.normal(9201, (T, k)), "bf16")
+    dY = quantize(synth.uniform(9202, (T, n), -1.0, 1.0), "bf16")
+    X_, dY_ = to_dev(X, "bf16"), to_dev(dY, "bf16")
+    dW = torch.empty((k, n), dtype=torch.bfloat16, device="cuda")
+    nbytes = mb.linear_wgrad_scratch_bytes(T, k, n)
+    assert nbytes > 4 * 65536 * 2, "this shape is meant to take the split path"
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    snaps = []
+    for q in (256, 200, 64):
+        dW.fill_(float("nan"))
+        mb.op_linear_wgrad(None, q, "bf16", T, k, n, X_, dY_, dW, None, ws)
+        torch.cuda.synchronize()
+        snaps.append(bits(dW))
+    for b in snaps[1:]:
+        assert np.array_equal(snaps[0], b), "result depends on the quota"
+    cols = synth.integers(9203, (32,), 0, n)
+    cols[:10] = [0, 255, 256, n - 1, n - 2, n - 255, n - 256, n - 257, n - 512, n // 2]
+    dWh = from_dev(dW[:, torch.from_numpy(cols).long().cuda()])
+    assert_close(dWh, X.T @ dY[:, cols], "bf16", "dW columns")
+
+
 def test_gate_up_projection_with_swiglu_epilogue_at_the_7b_shape_sampled(mb):
     """T=32768, k=4096, n=22016: the dominant product of configs[2] and configs[4], with silu(gate)*up
     written by the epilogue.  Sampled rows of [gate | up] and of the activation against the checker
