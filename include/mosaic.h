@@ -340,9 +340,10 @@ mosaic_status mosaic_op_linear_dgrad(void* stream, int32_t quota, int32_t dtype,
                                      const void* W, const void* R, void* dX);
 /* dW[k,n] = X[T,k]^T dY[T,n];  db[n] = column sums of dY (db may be NULL).
  * scratch: 16-byte aligned device buffer of at least
- * mosaic_op_linear_wgrad_scratch_bytes(T,k,n); it holds the fp32 pieces of a long
- * contraction that is split (by shape alone) when the output has few tiles, and the
- * partial column sums. */
+ * mosaic_op_linear_wgrad_scratch_bytes(T,k,n); it holds the fp32 pieces of the output
+ * tiles whose long contraction is split (which tiles and into how many pieces depends on
+ * the shape alone: all of them when the output has few tiles, else the tiles that do not
+ * fill a whole round of the device), and the partial column sums. */
 mosaic_status mosaic_op_linear_wgrad(void* stream, int32_t quota, int32_t dtype,
                                      int64_t T, int64_t k, int64_t n, const void* X,
                                      const void* dY, void* dW, void* db, void* scratch);
