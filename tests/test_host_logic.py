@@ -241,3 +241,23 @@ def test_measured_step_bytes_cover_the_benchmarked_modules_and_are_not_below_the
             assert table[key] >= synth.module_bytes(m, 2), key
             assert table[key] <= 8.0 * synth.module_bytes(m, 2), key     # a re-read factor beyond this would be a parsing slip
     assert planning.measured_step_bytes("/nonexistent/table.txt") == {}
+
+
+@pytest.mark.parametrize("T,k,n,pieces,cut_tiles,why", [
+    (32768, 4096, 22016, 5, 96, "1376 tiles: the 96 past five rounds of 256, in 5 pieces"),
+    (32768, 11008, 4096, 4, 176, "688 tiles: the 176 past two rounds, in 4 pieces"),
+    (32768, 4096, 12288, 1, 0, "768 tiles: three whole rounds, nothing to cut"),
+    (8192, 2048, 11264, 1, 0, "352 tiles but only 8192 tokens: pieces would be mostly fill and drain"),
+    (8192, 2048, 2048, 4, 64, "64 tiles: all of them, in 256 / 64 pieces"),
+    (4608, 1024, 1024, 8, 16, "16 tiles: all of them, in at most 8 pieces"),
+    (1568, 768, 768, 1, 0, "9 tiles, 1568 tokens: too short to cut"),
+])
+def test_weight_gradient_split_is_a_function_of_the_shape(T, k, n, pieces, cut_tiles, why):
+    """Which tiles of a weight gradient are cut along the token dimension, and into how many pieces,
+    is decided by (T, k, n) alone (never the quota: the bits must not depend on it).  The scratch a
+    caller must provide makes the decision visible: fp32 pieces of whole 256x256 tiles, then the
+    partial column sums of the bias gradient."""
+    got = mb.linear_wgrad_scratch_bytes(T, k, n)
+    pieces_bytes = pieces * cut_tiles * 256 * 256 * 4 if pieces > 1 else 0
+    aligned = (pieces_bytes + 255) // 256 * 256
+    assert got == aligned + mb.colsum_scratch_bytes(n), why
