@@ -35,6 +35,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+#ifndef DKV_PF
+#define DKV_PF 3
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // Online softmax keeps, per row, a reference value m and sums of exp2(s - m).  Any m works
@@ -945,12 +948,31 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
             }
           }
           const bf16x8 p0 = pack8(pv), p1 = pack8(pv + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+          // From here on S, dP and the unpacked P and dS are dead: their registers hold a ring of
+          // transposed fragments read DKV_PF matrix instructions ahead (left to itself the compiler
+          // reads every fragment into the same four registers right in front of its instruction).
+          // Product w of 4 * NC: column block w / 4; w % 4 = 0: dV, keys half 0; 1: dK, half 0;
+          // 2: dV, half 1; 3: dK, half 1 (each accumulator takes half 0 first, as before).
+          constexpr int PF = DKV_PF;
+          auto tr_operand = [&](int w) -> bf16x8 {
+            const int c = w >> 2, part = w & 3;
+            return L::tr((part & 1) ? qs : dos, c, 16 * (part >> 1));
+          };
+          bf16x8 ta[PF + 1];
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 0), p0, dv[c], 0, 0, 0);
-            dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(dos, c, 16), p1, dv[c], 0, 0, 0);
-            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 0), d0, dk[c], 0, 0, 0);
-            dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L::tr(qs, c, 16), d1, dk[c], 0, 0, 0);
+          for (int w = 0; w < PF; ++w) ta[w] = tr_operand(w);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int w = 0; w < 4 * NC; ++w) {
+            if (w + PF < 4 * NC) ta[(w + PF) % (PF + 1)] = tr_operand(w + PF);
+            const int c = w >> 2, part = w & 3;
+            const bf16x8 a = ta[w % (PF + 1)];
+            if (part == 0) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p0, dv[c], 0, 0, 0);
+            else if (part == 1) dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, d0, dk[c], 0, 0, 0);
+            else if (part == 2) dv[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p1, dv[c], 0, 0, 0);
+            else dk[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, d1, dk[c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
           }
         } else {
           // Operands come from LDS a fixed number of matrix instructions ahead of their use (a
