@@ -69,6 +69,7 @@ def test_decoder_gate_up_projection_sampled(mb):
     (16384, 768, 22016, "258 tiles: 256 in one round, the last two cut into pieces"),
     (16384, 1024, 8448, "132 tiles, more than half a round and less than one, long contraction: all cut into pieces"),
     (12288, 768, 8704, "102 tiles: the whole product cut into 2 pieces"),
+    (16384, 1000, 16904, "268 tiles with ragged last tile row and column: the last panel's 12 tiles are the cut ones"),
 ])
 def test_weight_gradient_with_tiles_cut_along_the_contraction(mb, T, k, n, note):
     """Weight gradients whose tile count does not fill rounds of 256: the tiles of the partial round
