@@ -1096,7 +1096,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bwd_dkv_mfma(const bf16*
 
 // Workgroup shape.  The kernels are written for NW waves and a ring of stages; measured on
 // the 8 x 1024 x 16 x 128 causal problem, 8 waves with four stages (one workgroup per CU,
-// three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU):
+// three tiles in flight) was no faster than 4 waves with two stages (two workgroups per CU;
+// measured again for dK/dV at 16 x 2048 x 32 x 128 and 8 x 4096 x 32 x 128: 6 - 20 % slower):
 // the loop is bound by the softmax arithmetic sharing the VALU port with MFMA issue, not by
 // load latency.  Only the 4-wave shape is instantiated.
 template <typename K>
